@@ -12,6 +12,7 @@ from .generate import (  # noqa: F401
     decode_inputs,
     f32_to_bf16_bits,
     layer_inputs,
+    salient_fraction,
     salient_mask,
     storage_to_f64,
 )
