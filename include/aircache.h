@@ -1,0 +1,159 @@
+/*
+ * aircache.h - C ABI of the AirCache hot path for MI355X (gfx950).
+ *
+ * AirCache (arxiv 2503.23956) compresses the visual part of an LVLM's KV cache once, after
+ * prefill, and decodes over the shorter cache.  This library is the data-parallel part of
+ * that method (Alg.1 and the decode attention of Sec.3.1):
+ *
+ *   air_score          Alg.1 first loop:  elite observation window (Eq.4-5), cross-modal
+ *                      attention (Eq.6-7), importance I_v (Eq.8), strength and skewness
+ *                      (Eq.9-10) of every layer in a range.
+ *   air_budget         Eq.11: per-layer budgets from the strength / skewness of all layers.
+ *   air_select_compact Alg.1 second loop: top-k by importance, gather of K / V rows into
+ *                      the compacted cache.
+ *   air_decode_attn    Eq.2 append + softmax(q K'^T / sqrt(d)) V' over the compacted cache.
+ *
+ * Conventions
+ *   - Every tensor pointer is DEVICE memory unless its comment says "host".  Descriptor
+ *     arrays (air_layer[], air_seq[]) and getter outputs are HOST memory.
+ *   - The caller owns every input tensor and the workspace; the library borrows them for
+ *     the duration of the enqueued work and never allocates or frees device memory.
+ *   - The four stage calls only enqueue work on `stream` (a hipStream_t passed as void*;
+ *     NULL = the default stream).  They do not synchronise.  The getters synchronise.
+ *   - Every call returns an air_status.  Arguments are validated before anything is
+ *     launched, so an error return implies that no device memory was written.
+ *     air_last_error() gives a text for the last failure on that context.
+ *   - Same inputs give bitwise the same outputs (no floating-point atomics anywhere).
+ *   - Token layout of a prompt: [system | visual | text] (Eq.3; the system prompt is never
+ *     scored and always kept).  Query head h reads KV head h / (n_q_heads / n_kv_heads).
+ *   - head_dim is 64 or 128; the innermost (head_dim) axis of every tensor is contiguous.
+ */
+#ifndef AIRCACHE_H
+#define AIRCACHE_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct air_ctx air_ctx; /* opaque */
+
+typedef enum {
+    AIR_OK = 0,
+    AIR_ERR_INVALID_ARG = 1, /* null pointer, bad enum, bad layer range                      */
+    AIR_ERR_SHAPE = 2,       /* shape outside what the kernels support or the config allows */
+    AIR_ERR_WORKSPACE = 3,   /* workspace missing, misaligned or too small                   */
+    AIR_ERR_STATE = 4,       /* stages called out of order, decode capacity exhausted       */
+    AIR_ERR_HIP = 5          /* a HIP runtime call failed; see air_last_error               */
+} air_status;
+
+typedef enum { AIR_F32 = 0, AIR_BF16 = 1 } air_dtype;
+
+/* How Eq.11 weighs the layers (the paper's allocation and its ablations, Tab.5). */
+typedef enum {
+    AIR_BUDGET_STRENGTH_SKEW = 0, /* r_l = (s't + s'k)/2 * r  (Eq.11) */
+    AIR_BUDGET_UNIFORM = 1,
+    AIR_BUDGET_STRENGTH = 2,
+    AIR_BUDGET_SKEW = 3
+} air_budget_mode;
+
+#define AIR_MAX_BATCH 64   /* sequences per context                       */
+#define AIR_MAX_LAYERS 256 /* layers per context                          */
+#define AIR_MAX_TEXT 4096  /* text tokens per sequence (candidate span)   */
+
+typedef struct {
+    int32_t n_layers, n_q_heads, n_kv_heads, head_dim, batch;
+    int32_t max_vis_len;      /* largest visual span in the batch                          */
+    int32_t max_nonvis_len;   /* largest (system + text) token count in the batch          */
+    int32_t max_window;       /* largest candidate span (win_len) in the batch             */
+    int32_t max_decode_steps; /* tokens that air_decode_attn may append per layer          */
+    int32_t dtype;            /* air_dtype of Q, K, V, the compacted cache and the output  */
+    int32_t budget_mode;      /* air_budget_mode                                            */
+    int32_t min_keep;         /* lower bound on kept visual tokens per layer (>= 0)        */
+    double alpha;             /* relevance threshold of Eq.5, in [0,1]; the paper uses 0.9 */
+    double retention;         /* r: fraction of visual tokens kept overall, in (0,1]       */
+} air_config;
+
+/* One prompt.  system = [0, vis_start), visual = [vis_start, vis_start+vis_len),
+ * text = [vis_start+vis_len, seq_len).  [win_start, win_start+win_len) is the candidate
+ * span of Eq.5, inside the text span; its last token is the reference row of Eq.4.
+ * win_len == text length and alpha = 0.9 is the paper's elite window; alpha = 0 turns
+ * the span into a plain continuous observation window (Tab.5). */
+typedef struct {
+    int32_t seq_len, vis_start, vis_len, win_start, win_len;
+} air_seq;
+
+/* One layer's tensors (device pointers). */
+typedef struct {
+    const void *q_text; /* [B][H_q ][text][d]: queries of the text span; row j = text token j */
+    const void *k;      /* [B][H_kv][seq ][d]                                                  */
+    const void *v;      /* [B][H_kv][seq ][d]                                                  */
+} air_layer;
+
+/* Element strides shared by all layers of a call (innermost axis has stride 1). */
+typedef struct {
+    int64_t q_b, q_h, q_t;    /* q_text: batch, head, token */
+    int64_t kv_b, kv_h, kv_t; /* k and v: batch, head, token */
+} air_strides;
+
+/* Bytes of device workspace a context with this config needs (0 on invalid config). */
+size_t air_workspace_bytes(const air_config *cfg);
+
+/* Create a context over a caller-allocated device workspace (256-byte aligned, at least
+ * air_workspace_bytes(cfg)).  Clears its bookkeeping tables on the default stream and
+ * waits for that.  The context itself is a small host object freed by air_destroy. */
+air_status air_create(const air_config *cfg, void *workspace, size_t workspace_bytes, air_ctx **out);
+air_status air_destroy(air_ctx *ctx);
+
+/* Alg.1, first loop (Eq.4-10) for layers [l0, l1).  layers: host array of l1-l0 entries;
+ * seqs: host array of cfg.batch entries, the same for every call on this context (the
+ * first call fixes it).  Fills importance scores and per-layer strength / skewness. */
+air_status air_score(air_ctx *ctx, void *stream, int32_t l0, int32_t l1, const air_layer *layers,
+                     const air_strides *strides, const air_seq *seqs);
+
+/* Eq.11 for every sequence.  All layers must have been scored (else AIR_ERR_STATE). */
+air_status air_budget(air_ctx *ctx, void *stream);
+
+/* Alg.1, second loop for layers [l0, l1): top-k_l visual tokens per (sequence, KV head)
+ * by importance (ties to the lower token index), then K' = [K_sys ; K_v[idx] ; K_t] and
+ * V' likewise into the compacted cache inside the workspace.  Needs air_budget (or
+ * air_set_budgets).  After the enqueued work has run the caller may free the prompt K/V. */
+air_status air_select_compact(air_ctx *ctx, void *stream, int32_t l0, int32_t l1, const air_layer *layers,
+                              const air_strides *strides);
+
+/* One decode step for layers [l0, l1): appends k_new / v_new to each layer's compacted
+ * cache (Eq.2), then out[h] = softmax(q_h K'^T / sqrt(d)) V' over the whole cache
+ * including the new token.  All tensors dense: q_new, out [l1-l0][B][H_q][d];
+ * k_new, v_new [l1-l0][B][H_kv][d].  At most max_decode_steps calls per layer. */
+air_status air_decode_attn(air_ctx *ctx, void *stream, int32_t l0, int32_t l1, const void *q_new,
+                           const void *k_new, const void *v_new, void *out);
+
+/* ---- inspection (tests, debugging): these synchronise the device ---- */
+/* importance scores of layer l: host [B][H_kv][max_vis_len] (entries past vis_len are 0) */
+air_status air_get_scores(air_ctx *ctx, int32_t l, float *host);
+/* elite window of layer l: counts host [B][H_q]; indices host [B][H_q][max_window] (absolute token positions) */
+air_status air_get_elite(air_ctx *ctx, int32_t l, int32_t *counts, int32_t *indices);
+/* per-layer strength and skewness: host [B][L] each */
+air_status air_get_stats(air_ctx *ctx, double *s_t, double *s_k);
+/* budgets k[b][l]: host [B][L] */
+air_status air_get_budgets(air_ctx *ctx, int32_t *host);
+/* replace the budgets (stage-isolated tests); every entry in [0, vis_len of b] */
+air_status air_set_budgets(air_ctx *ctx, const int32_t *host);
+/* kept visual indices of layer l: host [B][H_kv][max_vis_len], ascending, first k[b][l] valid */
+air_status air_get_indices(air_ctx *ctx, int32_t l, int32_t *host);
+/* current cache length (system + kept + text + appended) per (b, l): host [B][L] */
+air_status air_get_lengths(air_ctx *ctx, int32_t *host);
+/* rows [0, length) of the compacted cache of (layer l, sequence b, KV head h) in token
+ * order, element type = cfg.dtype: host [max_rows][d] each; fails if length > max_rows */
+air_status air_get_cache(air_ctx *ctx, int32_t l, int32_t b, int32_t h, void *k_host, void *v_host,
+                         int32_t max_rows);
+
+const char *air_last_error(const air_ctx *ctx);
+const char *air_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* AIRCACHE_H */

@@ -1,0 +1,439 @@
+// C ABI of libaircache.so: context, workspace layout, argument validation, stage sequencing.
+#include <math.h>
+#include <stdio.h>
+#include <string.h>
+
+#include <string>
+#include <vector>
+
+#include "air_internal.h"
+
+namespace air {
+
+static size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+static bool config_ok(const air_config &c) {
+    if (c.n_layers < 1 || c.n_layers > AIR_MAX_LAYERS) return false;
+    if (c.batch < 1 || c.batch > AIR_MAX_BATCH) return false;
+    if (c.n_kv_heads < 1 || c.n_q_heads < c.n_kv_heads || c.n_q_heads % c.n_kv_heads) return false;
+    if (c.n_q_heads / c.n_kv_heads > 16) return false;
+    if (c.head_dim != 64 && c.head_dim != 128) return false;
+    if (c.max_vis_len < 1 || c.max_nonvis_len < 1) return false;
+    if (c.max_window < 1 || c.max_window > AIR_MAX_TEXT || c.max_window > c.max_nonvis_len) return false;
+    if (c.max_decode_steps < 0) return false;
+    if (c.dtype != AIR_F32 && c.dtype != AIR_BF16) return false;
+    if (c.budget_mode < AIR_BUDGET_STRENGTH_SKEW || c.budget_mode > AIR_BUDGET_SKEW) return false;
+    if (c.min_keep < 0) return false;
+    if (!(c.alpha >= 0.0 && c.alpha <= 1.0)) return false;
+    if (!(c.retention > 0.0 && c.retention <= 1.0)) return false;
+    return true;
+}
+
+static int64_t total_budget(const air_config &c, int n_vis) {
+    int64_t k = (int64_t)floor(c.retention * (double)n_vis * (double)c.n_layers + 0.5);
+    const int64_t lo = (int64_t)c.n_layers * (c.min_keep < n_vis ? c.min_keep : n_vis);
+    const int64_t hi = (int64_t)c.n_layers * n_vis;
+    return k < lo ? lo : (k > hi ? hi : k);
+}
+
+WsLayout make_layout(const air_config &c) {
+    WsLayout w;
+    memset(&w, 0, sizeof(w));
+    const size_t L = c.n_layers, B = c.batch, Hq = c.n_q_heads, Hkv = c.n_kv_heads, D = c.head_dim;
+    const size_t W = c.max_window, NV = c.max_vis_len;
+    const size_t esz = c.dtype == AIR_BF16 ? 2 : 4;
+    w.n_chunks = (int32_t)((NV + kChunkKeys - 1) / kChunkKeys);
+    // rows of one (sequence, KV head) pool: every layer's system + text rows, its decode
+    // appends and alignment slack, plus the kept visual rows of all layers together
+    w.pool_rows = (int64_t)L * (c.max_nonvis_len + c.max_decode_steps + kCacheRowAlign - 1) +
+                  total_budget(c, c.max_vis_len);
+    size_t off = 0;
+    auto take = [&](size_t bytes) {
+        size_t o = off;
+        off = align_up(off + bytes, 256);
+        return o;
+    };
+    w.seq_tab = take(B * sizeof(air_seq));
+    w.elite_cnt = take(L * B * Hq * 4);
+    w.elite_idx = take(L * B * Hq * W * 4);
+    w.row_mtext = take(L * B * Hq * W * 4);
+    w.row_ztext = take(L * B * Hq * W * 4);
+    w.row_M = take(L * B * Hq * W * 4);
+    w.row_w = take(L * B * Hq * W * 4);
+    w.part = take(L * B * Hq * W * (size_t)w.n_chunks * 8);
+    w.scores = take(L * B * Hkv * NV * 4);
+    w.unit_st = take(L * B * Hkv * 8);
+    w.unit_sk = take(L * B * Hkv * 8);
+    w.s_t = take(B * L * 8);
+    w.s_k = take(B * L * 8);
+    w.budgets = take(B * L * 4);
+    w.base_len = take(B * L * 4);
+    w.layer_off = take(B * L * 4);
+    w.indices = take(L * B * Hkv * NV * 4);
+    w.kcache = take(B * Hkv * (size_t)w.pool_rows * D * esz);
+    w.vcache = take(B * Hkv * (size_t)w.pool_rows * D * esz);
+    w.dec_o = take(L * B * Hq * kDecodeSplits * D * 4);
+    w.dec_ml = take(L * B * Hq * kDecodeSplits * 8);
+    w.total = off;
+    return w;
+}
+
+}  // namespace air
+
+using namespace air;
+
+struct air_ctx {
+    air_config cfg;
+    WsLayout lay;
+    Dims dm;
+    DevTables tab;
+    char *ws;
+    bool have_seqs;
+    bool budgets_ready;
+    std::vector<air_seq> seqs;
+    std::vector<char> scored, compacted;
+    std::vector<int32_t> appended;
+    std::vector<int32_t> budgets_host;  // valid only after air_set_budgets / air_get_budgets
+    std::string err;
+};
+
+static air_status fail(air_ctx *ctx, air_status st, const std::string &msg) {
+    if (ctx) ctx->err = msg;
+    return st;
+}
+static air_status hip_fail(air_ctx *ctx, hipError_t e, const char *what) {
+    return fail(ctx, AIR_ERR_HIP, std::string(what) + ": " + hipGetErrorString(e));
+}
+
+extern "C" {
+
+const char *air_version(void) { return "aircache-mi355x 0.1"; }
+
+size_t air_workspace_bytes(const air_config *cfg) {
+    if (!cfg || !config_ok(*cfg)) return 0;
+    return make_layout(*cfg).total;
+}
+
+air_status air_create(const air_config *cfg, void *workspace, size_t workspace_bytes, air_ctx **out) {
+    if (!cfg || !out) return AIR_ERR_INVALID_ARG;
+    *out = nullptr;
+    if (!config_ok(*cfg)) return AIR_ERR_SHAPE;
+    WsLayout lay = make_layout(*cfg);
+    if (!workspace || ((uintptr_t)workspace & 255) || workspace_bytes < lay.total) return AIR_ERR_WORKSPACE;
+    air_ctx *c = new air_ctx();
+    c->cfg = *cfg;
+    c->lay = lay;
+    c->ws = (char *)workspace;
+    Dims &d = c->dm;
+    d.L = cfg->n_layers;
+    d.Hq = cfg->n_q_heads;
+    d.Hkv = cfg->n_kv_heads;
+    d.G = d.Hq / d.Hkv;
+    d.D = cfg->head_dim;
+    d.B = cfg->batch;
+    d.max_vis = cfg->max_vis_len;
+    d.max_window = cfg->max_window;
+    d.n_chunks = lay.n_chunks;
+    d.max_steps = cfg->max_decode_steps;
+    d.pool_rows = lay.pool_rows;
+    DevTables &t = c->tab;
+    char *w = c->ws;
+    t.seq_tab = (air_seq *)(w + lay.seq_tab);
+    t.elite_cnt = (int32_t *)(w + lay.elite_cnt);
+    t.elite_idx = (int32_t *)(w + lay.elite_idx);
+    t.row_mtext = (float *)(w + lay.row_mtext);
+    t.row_ztext = (float *)(w + lay.row_ztext);
+    t.row_M = (float *)(w + lay.row_M);
+    t.row_w = (float *)(w + lay.row_w);
+    t.part = (float2 *)(w + lay.part);
+    t.scores = (float *)(w + lay.scores);
+    t.unit_st = (double *)(w + lay.unit_st);
+    t.unit_sk = (double *)(w + lay.unit_sk);
+    t.s_t = (double *)(w + lay.s_t);
+    t.s_k = (double *)(w + lay.s_k);
+    t.budgets = (int32_t *)(w + lay.budgets);
+    t.base_len = (int32_t *)(w + lay.base_len);
+    t.layer_off = (int32_t *)(w + lay.layer_off);
+    t.indices = (int32_t *)(w + lay.indices);
+    t.kcache = (void *)(w + lay.kcache);
+    t.vcache = (void *)(w + lay.vcache);
+    t.dec_o = (float *)(w + lay.dec_o);
+    t.dec_ml = (float2 *)(w + lay.dec_ml);
+    c->have_seqs = false;
+    c->budgets_ready = false;
+    c->scored.assign(d.L, 0);
+    c->compacted.assign(d.L, 0);
+    c->appended.assign(d.L, 0);
+    // scores past a sequence's visual span and the small tables start at zero
+    hipError_t e = hipMemset(w + lay.scores, 0, lay.unit_st - lay.scores);
+    if (e == hipSuccess) e = hipMemset(w + lay.seq_tab, 0, lay.part - lay.seq_tab);
+    if (e == hipSuccess) e = hipMemset(w + lay.unit_st, 0, lay.indices - lay.unit_st);
+    if (e == hipSuccess) e = hipDeviceSynchronize();
+    if (e != hipSuccess) {
+        delete c;
+        return AIR_ERR_HIP;
+    }
+    *out = c;
+    return AIR_OK;
+}
+
+air_status air_destroy(air_ctx *ctx) {
+    if (!ctx) return AIR_ERR_INVALID_ARG;
+    delete ctx;
+    return AIR_OK;
+}
+
+const char *air_last_error(const air_ctx *ctx) { return ctx ? ctx->err.c_str() : "null context"; }
+
+static bool range_ok(const air_ctx *c, int32_t l0, int32_t l1) { return l0 >= 0 && l1 > l0 && l1 <= c->cfg.n_layers; }
+
+static air_status check_strides(air_ctx *ctx, const air_strides *st, const air_layer *layers, int nl, bool need_q) {
+    const int64_t vec = ctx->cfg.dtype == AIR_BF16 ? 8 : 4;  // elements per 16 bytes
+    const int64_t D = ctx->cfg.head_dim;
+    if (st->kv_t < D || st->kv_t % vec || st->kv_b % vec || st->kv_h % vec || st->kv_b < 0 || st->kv_h < 0)
+        return fail(ctx, AIR_ERR_SHAPE, "k/v strides must be non-negative multiples of 16 bytes with token stride >= head_dim");
+    if (need_q && (st->q_t < D || st->q_t % vec || st->q_b % vec || st->q_h % vec || st->q_b < 0 || st->q_h < 0))
+        return fail(ctx, AIR_ERR_SHAPE, "q strides must be non-negative multiples of 16 bytes with token stride >= head_dim");
+    for (int i = 0; i < nl; ++i) {
+        if (!layers[i].k || !layers[i].v || (need_q && !layers[i].q_text))
+            return fail(ctx, AIR_ERR_INVALID_ARG, "null tensor pointer in layers[]");
+        if (((uintptr_t)layers[i].k & 15) || ((uintptr_t)layers[i].v & 15) || (need_q && ((uintptr_t)layers[i].q_text & 15)))
+            return fail(ctx, AIR_ERR_INVALID_ARG, "tensor pointers must be 16-byte aligned");
+    }
+    return AIR_OK;
+}
+
+static air_status check_seqs(air_ctx *ctx, const air_seq *seqs) {
+    const air_config &c = ctx->cfg;
+    for (int b = 0; b < c.batch; ++b) {
+        const air_seq &s = seqs[b];
+        const int text0 = s.vis_start + s.vis_len;
+        if (s.vis_start < 0 || s.vis_len < 1 || s.vis_len > c.max_vis_len || s.seq_len <= text0)
+            return fail(ctx, AIR_ERR_SHAPE, "air_seq: need vis_len in [1, max_vis_len] and at least one text token");
+        if (s.seq_len - s.vis_len > c.max_nonvis_len)
+            return fail(ctx, AIR_ERR_SHAPE, "air_seq: system + text tokens exceed max_nonvis_len");
+        if (s.win_len < 1 || s.win_len > c.max_window || s.win_start < text0 || s.win_start + s.win_len > s.seq_len)
+            return fail(ctx, AIR_ERR_SHAPE, "air_seq: candidate span must lie inside the text span and fit max_window");
+    }
+    return AIR_OK;
+}
+
+air_status air_score(air_ctx *ctx, void *stream, int32_t l0, int32_t l1, const air_layer *layers,
+                     const air_strides *strides, const air_seq *seqs) {
+    if (!ctx) return AIR_ERR_INVALID_ARG;
+    if (!layers || !strides || !seqs) return fail(ctx, AIR_ERR_INVALID_ARG, "air_score: null argument");
+    if (!range_ok(ctx, l0, l1)) return fail(ctx, AIR_ERR_INVALID_ARG, "air_score: bad layer range");
+    air_status st = check_strides(ctx, strides, layers, l1 - l0, true);
+    if (st != AIR_OK) return st;
+    st = check_seqs(ctx, seqs);
+    if (st != AIR_OK) return st;
+    if (ctx->have_seqs && memcmp(ctx->seqs.data(), seqs, sizeof(air_seq) * ctx->cfg.batch) != 0)
+        return fail(ctx, AIR_ERR_STATE, "air_score: seqs differ from the ones this context was first scored with");
+    for (int l = l0; l < l1; ++l)
+        if (ctx->compacted[l]) return fail(ctx, AIR_ERR_STATE, "air_score: layer already compacted");
+    hipStream_t s = (hipStream_t)stream;
+    SeqArgs sa;
+    memset(&sa, 0, sizeof(sa));
+    memcpy(sa.s, seqs, sizeof(air_seq) * ctx->cfg.batch);
+    const int dt = ctx->cfg.dtype;
+    for (int c0 = l0; c0 < l1; c0 += kMaxLayersPerLaunch) {
+        const int nl = (l1 - c0 < kMaxLayersPerLaunch) ? l1 - c0 : kMaxLayersPerLaunch;
+        LaunchLayers ll;
+        memset(&ll, 0, sizeof(ll));
+        for (int i = 0; i < nl; ++i) {
+            ll.p[i].q = layers[c0 - l0 + i].q_text;
+            ll.p[i].k = layers[c0 - l0 + i].k;
+            ll.p[i].v = layers[c0 - l0 + i].v;
+        }
+        hipError_t e = launch_elite(s, ctx->dm, ctx->tab, dt, c0, nl, ll, *strides, sa, ctx->cfg.alpha);
+        if (e == hipSuccess) e = launch_score_pass1(s, ctx->dm, ctx->tab, dt, c0, nl, ll, *strides);
+        if (e == hipSuccess) e = launch_score_rows(s, ctx->dm, ctx->tab, c0, nl);
+        if (e == hipSuccess) e = launch_score_pass2(s, ctx->dm, ctx->tab, dt, c0, nl, ll, *strides);
+        if (e == hipSuccess) e = launch_stats(s, ctx->dm, ctx->tab, c0, nl);
+        if (e != hipSuccess) return hip_fail(ctx, e, "air_score launch");
+    }
+    if (!ctx->have_seqs) {
+        ctx->seqs.assign(seqs, seqs + ctx->cfg.batch);
+        ctx->have_seqs = true;
+    }
+    for (int l = l0; l < l1; ++l) ctx->scored[l] = 1;
+    ctx->budgets_ready = false;
+    return AIR_OK;
+}
+
+air_status air_budget(air_ctx *ctx, void *stream) {
+    if (!ctx) return AIR_ERR_INVALID_ARG;
+    for (int l = 0; l < ctx->cfg.n_layers; ++l)
+        if (!ctx->scored[l]) return fail(ctx, AIR_ERR_STATE, "air_budget: not every layer has been scored");
+    for (int l = 0; l < ctx->cfg.n_layers; ++l)
+        if (ctx->compacted[l]) return fail(ctx, AIR_ERR_STATE, "air_budget: layers already compacted");
+    hipError_t e = launch_budget((hipStream_t)stream, ctx->dm, ctx->tab, ctx->cfg.retention, ctx->cfg.budget_mode,
+                                 ctx->cfg.min_keep, 0);
+    if (e != hipSuccess) return hip_fail(ctx, e, "air_budget launch");
+    ctx->budgets_ready = true;
+    return AIR_OK;
+}
+
+air_status air_select_compact(air_ctx *ctx, void *stream, int32_t l0, int32_t l1, const air_layer *layers,
+                              const air_strides *strides) {
+    if (!ctx) return AIR_ERR_INVALID_ARG;
+    if (!layers || !strides) return fail(ctx, AIR_ERR_INVALID_ARG, "air_select_compact: null argument");
+    if (!range_ok(ctx, l0, l1)) return fail(ctx, AIR_ERR_INVALID_ARG, "air_select_compact: bad layer range");
+    if (!ctx->budgets_ready) return fail(ctx, AIR_ERR_STATE, "air_select_compact: budgets not computed");
+    for (int l = l0; l < l1; ++l)
+        if (ctx->appended[l]) return fail(ctx, AIR_ERR_STATE, "air_select_compact: layer already decoded on");
+    air_status st = check_strides(ctx, strides, layers, l1 - l0, false);
+    if (st != AIR_OK) return st;
+    hipStream_t s = (hipStream_t)stream;
+    for (int c0 = l0; c0 < l1; c0 += kMaxLayersPerLaunch) {
+        const int nl = (l1 - c0 < kMaxLayersPerLaunch) ? l1 - c0 : kMaxLayersPerLaunch;
+        LaunchLayers ll;
+        memset(&ll, 0, sizeof(ll));
+        for (int i = 0; i < nl; ++i) {
+            ll.p[i].k = layers[c0 - l0 + i].k;
+            ll.p[i].v = layers[c0 - l0 + i].v;
+        }
+        hipError_t e = launch_select(s, ctx->dm, ctx->tab, c0, nl);
+        if (e == hipSuccess) e = launch_gather(s, ctx->dm, ctx->tab, ctx->cfg.dtype, c0, nl, ll, *strides);
+        if (e != hipSuccess) return hip_fail(ctx, e, "air_select_compact launch");
+    }
+    for (int l = l0; l < l1; ++l) ctx->compacted[l] = 1;
+    return AIR_OK;
+}
+
+air_status air_decode_attn(air_ctx *ctx, void *stream, int32_t l0, int32_t l1, const void *q_new, const void *k_new,
+                           const void *v_new, void *out) {
+    if (!ctx) return AIR_ERR_INVALID_ARG;
+    if (!q_new || !k_new || !v_new || !out) return fail(ctx, AIR_ERR_INVALID_ARG, "air_decode_attn: null argument");
+    if (((uintptr_t)q_new & 15) || ((uintptr_t)k_new & 15) || ((uintptr_t)v_new & 15) || ((uintptr_t)out & 15))
+        return fail(ctx, AIR_ERR_INVALID_ARG, "air_decode_attn: tensors must be 16-byte aligned");
+    if (!range_ok(ctx, l0, l1)) return fail(ctx, AIR_ERR_INVALID_ARG, "air_decode_attn: bad layer range");
+    for (int l = l0; l < l1; ++l) {
+        if (!ctx->compacted[l]) return fail(ctx, AIR_ERR_STATE, "air_decode_attn: layer not compacted");
+        if (ctx->appended[l] >= ctx->cfg.max_decode_steps)
+            return fail(ctx, AIR_ERR_STATE, "air_decode_attn: max_decode_steps exhausted");
+    }
+    hipStream_t s = (hipStream_t)stream;
+    for (int c0 = l0; c0 < l1; c0 += kMaxLayersPerLaunch) {
+        const int nl = (l1 - c0 < kMaxLayersPerLaunch) ? l1 - c0 : kMaxLayersPerLaunch;
+        LaunchLayers ll;
+        memset(&ll, 0, sizeof(ll));
+        for (int i = 0; i < nl; ++i) ll.appended[i] = ctx->appended[c0 + i];
+        hipError_t e = launch_append(s, ctx->dm, ctx->tab, ctx->cfg.dtype, c0, nl, c0 - l0, ll, k_new, v_new);
+        if (e == hipSuccess) e = launch_decode(s, ctx->dm, ctx->tab, ctx->cfg.dtype, c0, nl, c0 - l0, ll, q_new, out);
+        if (e != hipSuccess) return hip_fail(ctx, e, "air_decode_attn launch");
+    }
+    for (int l = l0; l < l1; ++l) ctx->appended[l] += 1;
+    return AIR_OK;
+}
+
+// ---------------------------------------------------------------------------------------
+// inspection
+// ---------------------------------------------------------------------------------------
+static air_status d2h(air_ctx *ctx, void *dst, const void *src, size_t bytes) {
+    hipError_t e = hipDeviceSynchronize();
+    if (e == hipSuccess) e = hipMemcpy(dst, src, bytes, hipMemcpyDeviceToHost);
+    if (e != hipSuccess) return hip_fail(ctx, e, "device to host copy");
+    return AIR_OK;
+}
+
+air_status air_get_scores(air_ctx *ctx, int32_t l, float *host) {
+    if (!ctx || !host) return AIR_ERR_INVALID_ARG;
+    if (l < 0 || l >= ctx->cfg.n_layers) return fail(ctx, AIR_ERR_INVALID_ARG, "bad layer");
+    if (!ctx->scored[l]) return fail(ctx, AIR_ERR_STATE, "layer not scored");
+    const size_t n = (size_t)ctx->dm.B * ctx->dm.Hkv * ctx->dm.max_vis;
+    return d2h(ctx, host, ctx->tab.scores + (size_t)l * n, n * 4);
+}
+
+air_status air_get_elite(air_ctx *ctx, int32_t l, int32_t *counts, int32_t *indices) {
+    if (!ctx || !counts || !indices) return AIR_ERR_INVALID_ARG;
+    if (l < 0 || l >= ctx->cfg.n_layers) return fail(ctx, AIR_ERR_INVALID_ARG, "bad layer");
+    if (!ctx->scored[l]) return fail(ctx, AIR_ERR_STATE, "layer not scored");
+    const size_t n = (size_t)ctx->dm.B * ctx->dm.Hq;
+    air_status st = d2h(ctx, counts, ctx->tab.elite_cnt + (size_t)l * n, n * 4);
+    if (st != AIR_OK) return st;
+    return d2h(ctx, indices, ctx->tab.elite_idx + (size_t)l * n * ctx->dm.max_window, n * ctx->dm.max_window * 4);
+}
+
+air_status air_get_stats(air_ctx *ctx, double *s_t, double *s_k) {
+    if (!ctx || !s_t || !s_k) return AIR_ERR_INVALID_ARG;
+    if (!ctx->budgets_ready) return fail(ctx, AIR_ERR_STATE, "air_get_stats: run air_budget first");
+    const size_t n = (size_t)ctx->dm.B * ctx->dm.L;
+    air_status st = d2h(ctx, s_t, ctx->tab.s_t, n * 8);
+    if (st != AIR_OK) return st;
+    return d2h(ctx, s_k, ctx->tab.s_k, n * 8);
+}
+
+air_status air_get_budgets(air_ctx *ctx, int32_t *host) {
+    if (!ctx || !host) return AIR_ERR_INVALID_ARG;
+    if (!ctx->budgets_ready) return fail(ctx, AIR_ERR_STATE, "budgets not computed");
+    return d2h(ctx, host, ctx->tab.budgets, (size_t)ctx->dm.B * ctx->dm.L * 4);
+}
+
+air_status air_set_budgets(air_ctx *ctx, const int32_t *host) {
+    if (!ctx || !host) return AIR_ERR_INVALID_ARG;
+    if (!ctx->have_seqs) return fail(ctx, AIR_ERR_STATE, "air_set_budgets: score at least one layer first");
+    for (int l = 0; l < ctx->cfg.n_layers; ++l)
+        if (ctx->compacted[l]) return fail(ctx, AIR_ERR_STATE, "air_set_budgets: layers already compacted");
+    const int L = ctx->dm.L;
+    for (int b = 0; b < ctx->dm.B; ++b) {
+        const air_seq &s = ctx->seqs[b];
+        int64_t rows = 0;
+        for (int l = 0; l < L; ++l) {
+            const int k = host[(size_t)b * L + l];
+            if (k < 0 || k > s.vis_len) return fail(ctx, AIR_ERR_SHAPE, "air_set_budgets: budget outside [0, vis_len]");
+            const int64_t cap = (int64_t)(s.seq_len - s.vis_len) + k + ctx->dm.max_steps;
+            rows += (cap + kCacheRowAlign - 1) / kCacheRowAlign * kCacheRowAlign;
+        }
+        if (rows > ctx->dm.pool_rows) return fail(ctx, AIR_ERR_SHAPE, "air_set_budgets: budgets exceed the cache pool");
+    }
+    hipError_t e = hipDeviceSynchronize();
+    if (e == hipSuccess) e = hipMemcpy(ctx->tab.budgets, host, (size_t)ctx->dm.B * L * 4, hipMemcpyHostToDevice);
+    if (e == hipSuccess) e = launch_budget(nullptr, ctx->dm, ctx->tab, ctx->cfg.retention, ctx->cfg.budget_mode,
+                                           ctx->cfg.min_keep, 1);
+    if (e == hipSuccess) e = hipDeviceSynchronize();
+    if (e != hipSuccess) return hip_fail(ctx, e, "air_set_budgets");
+    ctx->budgets_ready = true;
+    return AIR_OK;
+}
+
+air_status air_get_indices(air_ctx *ctx, int32_t l, int32_t *host) {
+    if (!ctx || !host) return AIR_ERR_INVALID_ARG;
+    if (l < 0 || l >= ctx->cfg.n_layers) return fail(ctx, AIR_ERR_INVALID_ARG, "bad layer");
+    if (!ctx->compacted[l]) return fail(ctx, AIR_ERR_STATE, "layer not compacted");
+    const size_t n = (size_t)ctx->dm.B * ctx->dm.Hkv * ctx->dm.max_vis;
+    return d2h(ctx, host, ctx->tab.indices + (size_t)l * n, n * 4);
+}
+
+air_status air_get_lengths(air_ctx *ctx, int32_t *host) {
+    if (!ctx || !host) return AIR_ERR_INVALID_ARG;
+    if (!ctx->budgets_ready) return fail(ctx, AIR_ERR_STATE, "budgets not computed");
+    const int L = ctx->dm.L;
+    air_status st = d2h(ctx, host, ctx->tab.base_len, (size_t)ctx->dm.B * L * 4);
+    if (st != AIR_OK) return st;
+    for (int b = 0; b < ctx->dm.B; ++b)
+        for (int l = 0; l < L; ++l) host[(size_t)b * L + l] += ctx->appended[l];
+    return AIR_OK;
+}
+
+air_status air_get_cache(air_ctx *ctx, int32_t l, int32_t b, int32_t h, void *k_host, void *v_host, int32_t max_rows) {
+    if (!ctx || !k_host || !v_host) return AIR_ERR_INVALID_ARG;
+    if (l < 0 || l >= ctx->cfg.n_layers || b < 0 || b >= ctx->dm.B || h < 0 || h >= ctx->dm.Hkv)
+        return fail(ctx, AIR_ERR_INVALID_ARG, "bad (layer, sequence, head)");
+    if (!ctx->compacted[l]) return fail(ctx, AIR_ERR_STATE, "layer not compacted");
+    int32_t base = 0, off = 0;
+    air_status st = d2h(ctx, &base, ctx->tab.base_len + (size_t)b * ctx->dm.L + l, 4);
+    if (st != AIR_OK) return st;
+    st = d2h(ctx, &off, ctx->tab.layer_off + (size_t)b * ctx->dm.L + l, 4);
+    if (st != AIR_OK) return st;
+    const int32_t len = base + ctx->appended[l];
+    if (len > max_rows) return fail(ctx, AIR_ERR_SHAPE, "air_get_cache: max_rows too small");
+    const size_t esz = ctx->cfg.dtype == AIR_BF16 ? 2 : 4;
+    const size_t row0 = ((size_t)b * ctx->dm.Hkv + h) * (size_t)ctx->dm.pool_rows + off;
+    const size_t rb = (size_t)ctx->dm.D * esz;
+    st = d2h(ctx, k_host, (char *)ctx->tab.kcache + row0 * rb, (size_t)len * rb);
+    if (st != AIR_OK) return st;
+    return d2h(ctx, v_host, (char *)ctx->tab.vcache + row0 * rb, (size_t)len * rb);
+}
+
+}  // extern "C"

@@ -1,0 +1,84 @@
+// Internal declarations shared by the translation units of libaircache.so.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "aircache.h"
+
+namespace air {
+
+constexpr int kChunkKeys = 256;       // visual keys per workgroup in the score passes
+constexpr int kMaxLayersPerLaunch = 32;
+constexpr int kDecodeSplits = 8;      // split-K factor of the decode attention
+constexpr int kCacheRowAlign = 32;    // layer regions of the compacted cache start on multiples of this
+constexpr int kGatherRows = 32;       // rows copied per workgroup in the compaction gather
+
+struct LayerPtrs {
+    const void *q, *k, *v;
+};
+
+// Kernel-argument block: the per-layer tensor pointers of one launch and the per-layer
+// count of tokens appended so far (decode only).
+struct LaunchLayers {
+    LayerPtrs p[kMaxLayersPerLaunch];
+    int32_t appended[kMaxLayersPerLaunch];
+};
+
+struct SeqArgs {
+    air_seq s[AIR_MAX_BATCH];
+};
+
+// Byte offsets of every table inside the workspace.
+struct WsLayout {
+    size_t seq_tab, elite_cnt, elite_idx, row_mtext, row_ztext, row_M, row_w, part, scores;
+    size_t unit_st, unit_sk, s_t, s_k, budgets, base_len, layer_off, indices;
+    size_t kcache, vcache, dec_o, dec_ml;
+    size_t total;
+    int32_t n_chunks;     // ceil(max_vis_len / kChunkKeys)
+    int64_t pool_rows;    // rows of one (sequence, KV head) cache pool
+};
+
+// Shapes every kernel needs, passed by value.
+struct Dims {
+    int32_t L, Hq, Hkv, G, D, B;
+    int32_t max_vis, max_window, n_chunks, max_steps;
+    int64_t pool_rows;
+};
+
+struct DevTables {
+    air_seq *seq_tab;
+    int32_t *elite_cnt, *elite_idx;
+    float *row_mtext, *row_ztext, *row_M, *row_w;
+    float2 *part;
+    float *scores;
+    double *unit_st, *unit_sk, *s_t, *s_k;
+    int32_t *budgets, *base_len, *layer_off, *indices;
+    void *kcache, *vcache;
+    float *dec_o;
+    float2 *dec_ml;
+};
+
+WsLayout make_layout(const air_config &cfg);
+
+// ---- kernel launchers (each returns the hipError_t of its launch) ----
+hipError_t launch_elite(hipStream_t s, const Dims &dm, const DevTables &t, int dtype, int l0, int nl,
+                        const LaunchLayers &ll, const air_strides &st, const SeqArgs &seqs, double alpha);
+hipError_t launch_score_pass1(hipStream_t s, const Dims &dm, const DevTables &t, int dtype, int l0, int nl,
+                              const LaunchLayers &ll, const air_strides &st);
+hipError_t launch_score_rows(hipStream_t s, const Dims &dm, const DevTables &t, int l0, int nl);
+hipError_t launch_score_pass2(hipStream_t s, const Dims &dm, const DevTables &t, int dtype, int l0, int nl,
+                              const LaunchLayers &ll, const air_strides &st);
+hipError_t launch_stats(hipStream_t s, const Dims &dm, const DevTables &t, int l0, int nl);
+hipError_t launch_budget(hipStream_t s, const Dims &dm, const DevTables &t, double retention, int mode,
+                         int min_keep, int skip_allocation);
+hipError_t launch_select(hipStream_t s, const Dims &dm, const DevTables &t, int l0, int nl);
+hipError_t launch_gather(hipStream_t s, const Dims &dm, const DevTables &t, int dtype, int l0, int nl,
+                         const LaunchLayers &ll, const air_strides &st);
+hipError_t launch_append(hipStream_t s, const Dims &dm, const DevTables &t, int dtype, int l0, int nl, int lbase,
+                         const LaunchLayers &ll, const void *k_new, const void *v_new);
+hipError_t launch_decode(hipStream_t s, const Dims &dm, const DevTables &t, int dtype, int l0, int nl, int lbase,
+                         const LaunchLayers &ll, const void *q_new, void *out);
+
+}  // namespace air

@@ -1,0 +1,148 @@
+// air_select_compact: Alg.1 second loop.
+//
+//   select_kernel  top-k_l of the importance row of one (layer, sequence, KV head): radix
+//                  select on the fp32 bit patterns (importance is non-negative, so unsigned
+//                  integer order is value order), then an ordered compaction that keeps
+//                  everything above the k-th value and the lowest-index ties at it.
+//   gather_kernel  K' = [K_sys ; K_v[idx] ; K_t], V' likewise, as 16-byte vector copies.
+#include "air_device.h"
+#include "air_internal.h"
+
+namespace air {
+
+constexpr int kSelThreads = 512;
+
+__global__ __launch_bounds__(kSelThreads) void select_kernel(Dims dm, DevTables t, int l0) {
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int64_t unit = (int64_t)l0 * dm.B * dm.Hkv + blockIdx.x;
+    const int b = (blockIdx.x / dm.Hkv) % dm.B;
+    const int l = l0 + blockIdx.x / (dm.Hkv * dm.B);
+    const int n = t.seq_tab[b].vis_len;
+    const int k = t.budgets[(int64_t)b * dm.L + l];
+    const uint32_t *key = reinterpret_cast<const uint32_t *>(t.scores + unit * dm.max_vis);
+    int32_t *out = t.indices + unit * dm.max_vis;
+    if (k <= 0) return;
+    if (k >= n) {
+        for (int i = tid; i < n; i += kSelThreads) out[i] = i;
+        return;
+    }
+
+    __shared__ uint32_t hist[256];
+    __shared__ uint32_t s_prefix, s_kk;
+    __shared__ int s_wgt[kSelThreads / 64], s_weq[kSelThreads / 64];
+    uint32_t prefix = 0, mask = 0, kk = (uint32_t)k;
+    for (int pass = 0; pass < 4; ++pass) {
+        const int shift = 24 - 8 * pass;
+        if (tid < 256) hist[tid] = 0;
+        __syncthreads();
+        for (int i = tid; i < n; i += kSelThreads) {
+            const uint32_t v = key[i];
+            if ((v & mask) == prefix) atomicAdd(&hist[(v >> shift) & 255u], 1u);
+        }
+        __syncthreads();
+        if (tid == 0) {
+            uint32_t cum = 0;
+            int bin = 255;
+            for (; bin > 0; --bin) {
+                if (cum + hist[bin] >= kk) break;
+                cum += hist[bin];
+            }
+            s_prefix = prefix | ((uint32_t)bin << shift);
+            s_kk = kk - cum;
+        }
+        __syncthreads();
+        prefix = s_prefix;
+        kk = s_kk;
+        mask |= 255u << shift;
+    }
+    const uint32_t tau = prefix;  // bit pattern of the k-th largest score; kk of the entries equal to it are kept
+
+    int base_gt = 0, base_eq = 0;
+    for (int i0 = 0; i0 < n; i0 += kSelThreads) {
+        const int i = i0 + tid;
+        const uint32_t v = i < n ? key[i] : 0u;
+        const bool gt = i < n && v > tau;
+        const bool eq = i < n && v == tau;
+        const uint64_t bg = __ballot(gt), be = __ballot(eq);
+        const uint64_t below = (1ull << lane) - 1ull;
+        if (lane == 0) {
+            s_wgt[wave] = __popcll(bg);
+            s_weq[wave] = __popcll(be);
+        }
+        __syncthreads();
+        int gt_before = base_gt + __popcll(bg & below), eq_before = base_eq + __popcll(be & below);
+        int tot_gt = 0, tot_eq = 0;
+#pragma unroll
+        for (int w = 0; w < kSelThreads / 64; ++w) {
+            if (w < wave) {
+                gt_before += s_wgt[w];
+                eq_before += s_weq[w];
+            }
+            tot_gt += s_wgt[w];
+            tot_eq += s_weq[w];
+        }
+        if (gt || (eq && eq_before < (int)kk)) out[gt_before + min(eq_before, (int)kk)] = i;
+        base_gt += tot_gt;
+        base_eq += tot_eq;
+        __syncthreads();
+    }
+}
+
+// One workgroup copies kGatherRows rows of K and of V; workgroups stride over the rows of a unit.
+template <typename T, int D>
+__global__ __launch_bounds__(256) void gather_kernel(Dims dm, DevTables t, int l0, LaunchLayers ll, air_strides st) {
+    const int u = blockIdx.y;
+    const int kvh = u % dm.Hkv;
+    const int b = (u / dm.Hkv) % dm.B;
+    const int li = u / (dm.Hkv * dm.B);
+    const int l = l0 + li;
+    const air_seq sq = t.seq_tab[b];
+    const int kl = t.budgets[(int64_t)b * dm.L + l];
+    const int n_rows = sq.seq_len - sq.vis_len + kl;
+    const int64_t unit = ((int64_t)l * dm.B + b) * dm.Hkv + kvh;
+    const int32_t *idx = t.indices + unit * dm.max_vis;
+    const T *ksrc = (const T *)ll.p[li].k + (int64_t)b * st.kv_b + (int64_t)kvh * st.kv_h;
+    const T *vsrc = (const T *)ll.p[li].v + (int64_t)b * st.kv_b + (int64_t)kvh * st.kv_h;
+    const int64_t dst_row0 = ((int64_t)b * dm.Hkv + kvh) * dm.pool_rows + t.layer_off[(int64_t)b * dm.L + l];
+    T *kdst = (T *)t.kcache + dst_row0 * D;
+    T *vdst = (T *)t.vcache + dst_row0 * D;
+    constexpr int kVecPerRow = D * (int)sizeof(T) / 16;
+    constexpr int kElemPerVec = 16 / (int)sizeof(T);
+    for (int r0 = blockIdx.x * kGatherRows; r0 < n_rows; r0 += gridDim.x * kGatherRows) {
+        for (int v = threadIdx.x; v < kGatherRows * kVecPerRow; v += 256) {
+            const int j = r0 + v / kVecPerRow, c = (v % kVecPerRow) * kElemPerVec;
+            if (j >= n_rows) break;
+            int tok;
+            if (j < sq.vis_start) tok = j;
+            else if (j < sq.vis_start + kl) tok = sq.vis_start + idx[j - sq.vis_start];
+            else tok = sq.vis_start + sq.vis_len + (j - sq.vis_start - kl);
+            const uint4 kx = *reinterpret_cast<const uint4 *>(ksrc + (int64_t)tok * st.kv_t + c);
+            const uint4 vx = *reinterpret_cast<const uint4 *>(vsrc + (int64_t)tok * st.kv_t + c);
+            *reinterpret_cast<uint4 *>(kdst + (int64_t)j * D + c) = kx;
+            *reinterpret_cast<uint4 *>(vdst + (int64_t)j * D + c) = vx;
+        }
+    }
+}
+
+hipError_t launch_select(hipStream_t s, const Dims &dm, const DevTables &t, int l0, int nl) {
+    hipLaunchKernelGGL(select_kernel, dim3(nl * dm.B * dm.Hkv), dim3(kSelThreads), 0, s, dm, t, l0);
+    return hipGetLastError();
+}
+
+template <typename T, int D>
+static hipError_t gather_launch(hipStream_t s, const Dims &dm, const DevTables &t, int l0, int nl,
+                                const LaunchLayers &ll, const air_strides &st) {
+    hipLaunchKernelGGL((gather_kernel<T, D>), dim3(32, nl * dm.B * dm.Hkv), dim3(256), 0, s, dm, t, l0, ll, st);
+    return hipGetLastError();
+}
+
+hipError_t launch_gather(hipStream_t s, const Dims &dm, const DevTables &t, int dtype, int l0, int nl,
+                         const LaunchLayers &ll, const air_strides &st) {
+    if (dtype == AIR_BF16)
+        return dm.D == 128 ? gather_launch<bf16_t, 128>(s, dm, t, l0, nl, ll, st)
+                           : gather_launch<bf16_t, 64>(s, dm, t, l0, nl, ll, st);
+    return dm.D == 128 ? gather_launch<float, 128>(s, dm, t, l0, nl, ll, st)
+                       : gather_launch<float, 64>(s, dm, t, l0, nl, ll, st);
+}
+
+}  // namespace air

@@ -1,0 +1,70 @@
+"""The C-ABI library loads and exports every symbol include/aircache.h declares; host-side argument
+validation answers before anything touches a GPU."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _lib():
+    import paper_2503_23956_amd as A
+    from paper_2503_23956_amd import binding
+
+    if not os.path.exists(binding.LIB_PATH):
+        from paper_2503_23956_amd.build import build
+
+        build(verbose=False)
+    return A.load_library()
+
+
+def _declared():
+    text = open(os.path.join(ROOT, "include", "aircache.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(air_[a-z_]+)\s*\(", text)))
+
+
+def test_every_declared_symbol_is_exported():
+    lib = _lib()
+    names = _declared()
+    assert len(names) >= 17
+    for n in names:
+        assert hasattr(lib, n), f"{n} declared in aircache.h but not exported"
+    from paper_2503_23956_amd import binding
+
+    assert sorted(binding.EXPORTS) == names
+    assert lib.air_version().startswith(b"aircache")
+
+
+def test_invalid_configs_are_rejected_on_the_host():
+    import paper_2503_23956_amd as A
+
+    lib = _lib()
+    good = dict(n_layers=2, n_q_heads=4, n_kv_heads=2, head_dim=64, batch=1, max_vis_len=576, max_nonvis_len=80,
+                max_window=16, max_decode_steps=1, dtype=A.AIR_F32)
+    assert lib.air_workspace_bytes(C.byref(A.make_config(**good))) > 0
+    for bad in (dict(head_dim=96), dict(n_q_heads=5), dict(batch=0), dict(batch=65), dict(max_window=100),
+                dict(dtype=7), dict(n_layers=0), dict(max_vis_len=0)):
+        cfg = A.make_config(**{**good, **bad})
+        assert lib.air_workspace_bytes(C.byref(cfg)) == 0, bad
+    for kw in (dict(alpha=1.5), dict(retention=0.0), dict(retention=1.2), dict(min_keep=-1), dict(budget_mode=9)):
+        assert lib.air_workspace_bytes(C.byref(A.make_config(**good, **kw))) == 0, kw
+    h = C.c_void_p()
+    cfg = A.make_config(**good)
+    assert lib.air_create(C.byref(cfg), None, 1 << 30, C.byref(h)) == A.binding.AIR_ERR_WORKSPACE
+    assert lib.air_create(C.byref(cfg), 256, 16, C.byref(h)) == A.binding.AIR_ERR_WORKSPACE
+    assert lib.air_create(C.byref(cfg), 260, 1 << 30, C.byref(h)) == A.binding.AIR_ERR_WORKSPACE  # misaligned
+    assert lib.air_create(C.byref(A.make_config(**{**good, "head_dim": 96})), 256, 1 << 30, C.byref(h)) == A.binding.AIR_ERR_SHAPE
+    assert lib.air_create(None, 256, 1 << 30, C.byref(h)) == A.binding.AIR_ERR_INVALID_ARG
+    assert not h.value
+    assert lib.air_destroy(None) == A.binding.AIR_ERR_INVALID_ARG
+    assert lib.air_budget(None, None) == A.binding.AIR_ERR_INVALID_ARG
+
+
+def test_missing_library_fails_loudly(tmp_path):
+    import paper_2503_23956_amd as A
+
+    with pytest.raises(FileNotFoundError):
+        A.load_library(str(tmp_path / "libaircache.so"))

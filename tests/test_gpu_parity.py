@@ -1,0 +1,200 @@
+"""HIP path vs CPU oracle, stage by stage, on the same seeded inputs (through the C ABI)."""
+import gc
+
+import numpy as np
+import pytest
+
+import synth
+from oracle import aircache_oracle as O
+from tests import parity_util as P
+
+pytestmark = pytest.mark.gpu
+
+
+def _run_case(w, retention, *, alpha=None, steps=2, layer_chunk=None, token_major=False, budget_mode=0,
+              min_keep=1, check_decode_units=None, verbose=True):
+    """Full pipeline on the GPU, checked stage by stage against the oracle.
+
+    Stages after the budget are fed the oracle's budgets when the GPU's differ from them (the
+    difference itself is checked separately), so that every stage is compared on equal inputs.
+    """
+    import torch
+
+    import paper_2503_23956_amd as A
+    from paper_2503_23956_amd.device_inputs import config_for, to_device, to_host
+
+    dev = torch.device("cuda:0")
+    alpha = w.alpha if alpha is None else alpha
+    seqs = w.seqs()
+    L, B, Hkv, G, d = w.n_layers, w.batch, w.n_kv_heads, w.group, w.head_dim
+    cfg = config_for(w, retention, alpha=alpha, budget_mode=budget_mode, min_keep=min_keep, max_decode_steps=max(steps, 1))
+    ac = A.AirCache(cfg, dev)
+    tag = f"[{w.name} r={retention} alpha={alpha}]"
+
+    # ---- inputs: generate layer by layer, upload, run the oracle's first loop on the host copy
+    q_dev, k_dev, v_dev, host_kv = [], [], [], []
+    orc = P.OracleRun()
+    s_t = np.zeros((B, L))
+    s_k = np.zeros((B, L))
+    for l in range(L):
+        li = synth.layer_inputs(w, l, seqs)
+        if token_major:  # [B][T][H][d] memory order, indexed as [B][H][T][d] through strides
+            q_dev.append(to_device(np.ascontiguousarray(li.q_text.transpose(0, 2, 1, 3)), dev).permute(0, 2, 1, 3))
+            k_dev.append(to_device(np.ascontiguousarray(li.k.transpose(0, 2, 1, 3)), dev).permute(0, 2, 1, 3))
+            v_dev.append(to_device(np.ascontiguousarray(li.v.transpose(0, 2, 1, 3)), dev).permute(0, 2, 1, 3))
+        else:
+            q_dev.append(to_device(li.q_text, dev))
+            k_dev.append(to_device(li.k, dev))
+            v_dev.append(to_device(li.v, dev))
+        sc, el, a, c = P.oracle_score_layer(w, li, seqs, alpha)
+        orc.scores.append(sc)
+        orc.elites.append(el)
+        s_t[:, l] = a
+        s_k[:, l] = c
+        host_kv.append((li.k, li.v))
+    orc.s_t, orc.s_k = s_t, s_k
+    orc.budgets = P.oracle_budgets(s_t, s_k, seqs, retention, budget_mode, min_keep)
+
+    # ---- air_score
+    chunk = layer_chunk or L
+    for l0 in range(0, L, chunk):
+        l1 = min(L, l0 + chunk)
+        ac.air_score(l0, l1, q_dev[l0:l1], k_dev[l0:l1], v_dev[l0:l1], seqs)
+    worst = 0.0
+    for l in range(L):
+        cnt, idx = ac.air_get_elite(l)
+        P.check_elite(cnt, idx, orc.elites[l], f"{tag} layer {l}")
+        worst = max(worst, P.check_scores(ac.air_get_scores(l), orc.scores[l], seqs, f"{tag} layer {l}"))
+
+    # ---- air_budget
+    ac.air_budget()
+    g_st, g_sk = ac.air_get_stats()
+    np.testing.assert_allclose(g_st, s_t, rtol=P.STAT_RTOL, err_msg=f"{tag} strength")
+    np.testing.assert_allclose(g_sk, s_k, rtol=P.STAT_RTOL, atol=1e-9, err_msg=f"{tag} skewness")
+    g_bud = ac.air_get_budgets()
+    # integer work is bit-exact given the same statistics
+    same_stats = P.oracle_budgets(g_st, g_sk, seqs, retention, budget_mode, min_keep)
+    assert np.array_equal(g_bud, same_stats), f"{tag} budgets differ from the oracle's allocation of the GPU's own statistics"
+    assert np.array_equal(g_bud.sum(axis=1), orc.budgets.sum(axis=1))
+    budget_moves = int(np.abs(g_bud - orc.budgets).sum())
+    assert np.abs(g_bud - orc.budgets).max() <= 1, f"{tag} budgets off by more than one token: {g_bud - orc.budgets}"
+    if budget_moves:
+        ac.air_set_budgets(orc.budgets)
+    bud = orc.budgets
+
+    # ---- air_select_compact
+    for l0 in range(0, L, chunk):
+        l1 = min(L, l0 + chunk)
+        ac.air_select_compact(l0, l1, k_dev[l0:l1], v_dev[l0:l1])
+    swaps = 0
+    gpu_idx = []
+    for l in range(L):
+        gi = ac.air_get_indices(l)
+        gpu_idx.append(gi)
+        for b in range(B):
+            for h in range(Hkv):
+                swaps += P.check_selection(gi[b, h, : bud[b, l]], orc.scores[l][b][h], int(bud[b, l]),
+                                           f"{tag} layer {l} b={b} kv={h}")
+    lens = ac.air_get_lengths()
+    for b, s in enumerate(seqs):
+        assert np.array_equal(lens[b], (s.seq_len - s.vis_len) + bud[b])
+
+    # compaction: rows bit-identical to the source rows of [system ; kept ; text]
+    units = check_decode_units or [(l, b, h) for l in range(L) for b in range(B) for h in range(Hkv)]
+    caches = {}
+    for (l, b, h) in units:
+        s = seqs[b]
+        rows = O.compact_rows(P.seg_of(s), gpu_idx[l][b, h, : bud[b, l]])
+        kk, vv = ac.air_get_cache(l, b, h, len(rows))
+        hk, hv = host_kv[l]
+        assert np.array_equal(kk, hk[b, h][rows]), f"{tag} K' rows differ at layer {l} b={b} kv={h}"
+        assert np.array_equal(vv, hv[b, h][rows]), f"{tag} V' rows differ at layer {l} b={b} kv={h}"
+        caches[(l, b, h)] = (synth.storage_to_f64(kk), synth.storage_to_f64(vv))
+
+    # ---- air_decode_attn
+    worst_dec = 0.0
+    out = torch.empty((L, B, w.n_q_heads, d), dtype=q_dev[0].dtype, device=dev)
+    for step in range(steps):
+        qs, ks, vs = zip(*[synth.decode_inputs(w, l, step) for l in range(L)])
+        qn, kn, vn = np.stack(qs), np.stack(ks), np.stack(vs)
+        dq, dk, dv = to_device(qn, dev), to_device(kn, dev), to_device(vn, dev)
+        for l0 in range(0, L, chunk):
+            l1 = min(L, l0 + chunk)
+            ac.air_decode_attn(l0, l1, dq[l0:l1], dk[l0:l1], dv[l0:l1], out[l0:l1])
+        got = synth.storage_to_f64(to_host(out))
+        assert not np.any(np.isnan(got))
+        q64, k64, v64 = synth.storage_to_f64(qn), synth.storage_to_f64(kn), synth.storage_to_f64(vn)
+        for (l, b, h) in units:
+            kc, vc = caches[(l, b, h)]
+            kc = np.concatenate([kc, k64[l, b, h][None]])  # Eq.2
+            vc = np.concatenate([vc, v64[l, b, h][None]])
+            caches[(l, b, h)] = (kc, vc)
+            want = O.decode_attn(q64[l, b, h * G:(h + 1) * G], kc, vc)
+            err = np.abs(got[l, b, h * G:(h + 1) * G] - want).max()
+            worst_dec = max(worst_dec, float(err))
+            assert err <= P.DECODE_ATOL[w.dtype], f"{tag} decode step {step} layer {l} b={b} kv={h}: abs err {err:.3g}"
+    if steps:
+        lens2 = ac.air_get_lengths()
+        assert np.array_equal(lens2, lens + steps)
+        (l, b, h) = units[-1]
+        kk, vv = ac.air_get_cache(l, b, h, int(lens2[b, l]))
+        assert np.array_equal(synth.storage_to_f64(kk), caches[(l, b, h)][0]), "appended K rows differ"
+        assert np.array_equal(synth.storage_to_f64(vv), caches[(l, b, h)][1]), "appended V rows differ"
+    if verbose:
+        print(f"{tag} worst score rel err {worst:.2e}; budget moves {budget_moves}; tolerated swaps {swaps}; "
+              f"worst decode abs err {worst_dec:.2e}", flush=True)
+    ac.close()
+    del ac, q_dev, k_dev, v_dev
+    gc.collect()
+    torch.cuda.empty_cache()
+    return dict(score_err=worst, budget_moves=budget_moves, swaps=swaps, decode_err=worst_dec)
+
+
+def test_config1_tiny_fp32_elite_window():
+    _run_case(synth.get_workload(1), 0.10, alpha=0.9, steps=1)
+
+
+def test_config1_tiny_fp32_continuous_window():
+    # the last-16 continuous observation window of Tab.5: alpha = 0 keeps the whole candidate span
+    _run_case(synth.get_workload(1), 0.10, alpha=0.0, steps=1)
+
+
+@pytest.mark.parametrize("retention", [0.01, 0.10, 0.50, 1.00])
+def test_small_bf16_retention_sweep(retention):
+    # several key chunks and a ragged tail (1500 = 5*256 + 220), G = 7, 3 layers
+    w = synth.get_workload(2).scaled(n_layers=3, n_vis=1500, n_text=40, decode_steps=3)
+    _run_case(w, retention, steps=3)
+
+
+def test_small_ragged_batch_token_major_layout():
+    w = synth.get_workload(3).scaled(batch=3, n_layers=2, n_vis=700, n_text=48)
+    _run_case(w, 0.10, steps=2, token_major=True)
+
+
+def test_layer_chunked_calls_match():
+    w = synth.get_workload(2).scaled(n_layers=5, n_vis=600, n_text=32)
+    _run_case(w, 0.25, steps=2, layer_chunk=2)
+
+
+@pytest.mark.parametrize("mode", [1, 2, 3])
+def test_budget_modes(mode):
+    w = synth.get_workload(2).scaled(n_layers=6, n_vis=520, n_text=24)
+    _run_case(w, 0.10, steps=0, budget_mode=mode)
+
+
+def test_all_text_window_alpha_zero():
+    # every text token is a window row (Tab.5 "all text tokens"): many rows per head
+    w = synth.get_workload(2).scaled(n_layers=2, n_vis=520, n_text=24)
+    _run_case(w, 0.10, alpha=0.0, steps=1)
+
+
+def test_degenerate_sizes():
+    # fewer than three visual tokens (skewness 0), one text token, one-token window, min_keep 0
+    w = synth.get_workload(1).scaled(n_vis=2, n_text=1, window=1, n_sys=1)
+    _run_case(w, 0.5, steps=1, min_keep=0)
+    w = synth.get_workload(1).scaled(n_vis=257, n_text=3, window=2, n_sys=0)
+    _run_case(w, 0.02, steps=1)
+
+
+def test_config2_full_size():
+    _run_case(synth.get_workload(2), 0.10, steps=2)
