@@ -66,6 +66,10 @@ def load_library(path: Optional[str] = None):
     if not os.path.exists(p):
         raise FileNotFoundError(
             f"{p} not found: build it with `python -m paper_2503_23956_amd.build` (there is no CPU fallback)")
+    # PyTorch ships its own HIP runtime (soname libamdhip64.so.7).  Import it first so that this
+    # library binds to the same runtime instance that owns the tensors and streams it is handed.
+    import torch  # noqa: F401
+
     lib = C.CDLL(p)
     vp, i32 = C.c_void_p, C.c_int32
     lib.air_version.restype = C.c_char_p
