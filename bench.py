@@ -1,0 +1,240 @@
+#!/usr/bin/env python3
+"""Benchmark of the AirCache hot path on one MI355X.
+
+One "step" is one pass of the whole hot path over one synthetic prompt batch:
+air_score + air_budget + air_select_compact over all layers (one-shot compression after
+prefill), then `decode_steps` calls of air_decode_attn, each over all layers.  Inputs are
+resident in HBM before the timed region starts.  Prints one JSON line.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 2] [--retention r] [--per-layer]
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0  # MI355X HBM3E, published
+METRIC = "compress us/layer + compacted decode attn tokens/s; achieved HBM GB/s vs peak"
+
+
+def _esize(w):
+    return 2 if w.dtype == "bf16" else 4
+
+
+def algorithmic_bytes(w, seqs, budgets, decode_steps):
+    """Bytes the method itself has to move (per step of the benchmark), by stage.
+
+    score   : K_v once + importance written        N_v*H_kv*d*e + 4*H_kv*N_v      per (layer, seq)
+    select  : importance read + indices written    4*H_kv*N_v + 4*H_kv*k_l
+    compact : kept rows of K and V read + written  4*(N_s+k_l+N_t)*H_kv*d*e
+    decode  : K' and V' read once per step         2*T_l*H_kv*d*e, T_l growing by one per step
+    """
+    e, d, hkv = _esize(w), w.head_dim, w.n_kv_heads
+    score = select = compact = 0
+    decode_first = decode_last = decode_total = 0
+    for b, s in enumerate(seqs):
+        nonvis = s.seq_len - s.vis_len
+        for l in range(w.n_layers):
+            k = int(budgets[b][l])
+            score += s.vis_len * hkv * d * e + 4 * hkv * s.vis_len
+            select += 4 * hkv * s.vis_len + 4 * hkv * k
+            compact += 4 * (nonvis + k) * hkv * d * e
+            t0 = nonvis + k + 1
+            decode_first += 2 * t0 * hkv * d * e
+            decode_last += 2 * (t0 + decode_steps - 1) * hkv * d * e
+            decode_total += sum(2 * (t0 + i) * hkv * d * e for i in range(decode_steps))
+    return dict(score=score, select=select, compact=compact, compress=score + select + compact,
+                decode_first=decode_first, decode_last=decode_last, decode_total=decode_total)
+
+
+def cpu_baseline(w, seqs, retention, host_layers, dec_inputs, decode_steps):
+    """The oracle, as it stands, on the host cores: full compression pass, then a sample of decode steps."""
+    import numpy as np
+
+    import synth
+    from oracle import aircache_oracle as O
+
+    try:
+        from threadpoolctl import threadpool_info
+
+        cores = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+    except Exception:
+        cores = 1
+    segs = [O.Segments(s.seq_len, s.vis_start, s.vis_len, s.win_start, s.win_len) for s in seqs]
+    q64 = [[synth.storage_to_f64(li.q_text[b][:, : s.n_text]) for li in host_layers] for b, s in enumerate(seqs)]
+    k64 = [[synth.storage_to_f64(li.k[b][:, : s.seq_len]) for li in host_layers] for b, s in enumerate(seqs)]
+    v64 = [[synth.storage_to_f64(li.v[b][:, : s.seq_len]) for li in host_layers] for b, s in enumerate(seqs)]
+    t0 = time.perf_counter()
+    caches = []
+    for b, seg in enumerate(segs):
+        res = O.compress_sequence(q64[b], k64[b], seg, w.alpha, retention)
+        per_layer = []
+        for l in range(w.n_layers):
+            per_layer.append([O.compact(k64[b][l][h], v64[b][l][h], seg, res.indices[l][h])
+                              for h in range(w.n_kv_heads)])
+        caches.append(per_layer)
+    t_compress = time.perf_counter() - t0
+    n_sample = min(decode_steps, 8)
+    sample = sorted(set(int(round(i * (decode_steps - 1) / max(n_sample - 1, 1))) for i in range(n_sample)))
+    t_dec = 0.0
+    G = w.group
+    for step in sample:
+        qn, kn, vn = dec_inputs[step]
+        q, k, v = synth.storage_to_f64(qn), synth.storage_to_f64(kn), synth.storage_to_f64(vn)
+        t1 = time.perf_counter()
+        for b in range(w.batch):
+            for l in range(w.n_layers):
+                kcs, vcs = [], []
+                for h in range(w.n_kv_heads):
+                    kc, vc = caches[b][l][h]
+                    # cache length of this step: the sample skips steps, so pad with the new token repeated
+                    kcs.append(np.concatenate([kc, np.repeat(k[l, b, h][None], step + 1, axis=0)]))
+                    vcs.append(np.concatenate([vc, np.repeat(v[l, b, h][None], step + 1, axis=0)]))
+                O.decode_layer(q[l, b], kcs, vcs)
+        t_dec += time.perf_counter() - t1
+    t_step = t_dec / len(sample)
+    total = t_compress + t_step * decode_steps
+    return dict(value=w.batch * decode_steps / total, unit="tokens/s", cores=int(cores), kind="oracle",
+                sample=f"full compression pass of all {w.n_layers} layers ({t_compress:.2f} s) + {len(sample)} of "
+                       f"{decode_steps} decode steps at their true cache lengths ({t_step * 1e3:.1f} ms/step), "
+                       f"numpy fp64",
+                compress_us_per_layer=t_compress * 1e6 / w.n_layers, decode_tokens_per_s=w.batch / t_step)
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--config", type=int, default=2)
+    ap.add_argument("--retention", type=float, default=None)
+    ap.add_argument("--decode-steps", type=int, default=None)
+    ap.add_argument("--per-layer", action="store_true", help="one air_decode_attn call per layer instead of one per step")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+
+    import paper_2503_23956_amd as A
+    import synth
+    from paper_2503_23956_amd import binding
+    from paper_2503_23956_amd.device_inputs import config_for, to_device
+
+    if not os.path.exists(binding.LIB_PATH):
+        from paper_2503_23956_amd.build import build
+
+        build()
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    dev = torch.device("cuda:0")
+    w = synth.get_workload(args.config)
+    retention = args.retention if args.retention is not None else (0.10 if 0.10 in w.retention else w.retention[0])
+    n_dec = args.decode_steps if args.decode_steps is not None else w.decode_steps
+    seqs = w.seqs()
+    L = w.n_layers
+
+    host_layers = [synth.layer_inputs(w, l, seqs) for l in range(L)]
+    q = [to_device(li.q_text, dev) for li in host_layers]
+    k = [to_device(li.k, dev) for li in host_layers]
+    v = [to_device(li.v, dev) for li in host_layers]
+    dec_inputs = []
+    for step in range(n_dec):
+        qs, ks, vs = zip(*[synth.decode_inputs(w, l, step) for l in range(L)])
+        dec_inputs.append((np.stack(qs), np.stack(ks), np.stack(vs)))
+    dq = to_device(np.stack([d[0] for d in dec_inputs]), dev)  # [steps][L][B][Hq][d]
+    dk = to_device(np.stack([d[1] for d in dec_inputs]), dev)
+    dv = to_device(np.stack([d[2] for d in dec_inputs]), dev)
+    out = torch.empty((L, w.batch, w.n_q_heads, w.head_dim), dtype=q[0].dtype, device=dev)
+
+    ac = A.AirCache(config_for(w, retention, max_decode_steps=n_dec, seqs=seqs), dev)
+    ev = lambda: torch.cuda.Event(enable_timing=True)  # noqa: E731
+
+    def one_step(events=None):
+        ac.air_reset()
+        if events is not None:
+            events[0].record()
+        ac.air_score(0, L, q, k, v, seqs)
+        if events is not None:
+            events[1].record()
+        ac.air_budget()
+        if events is not None:
+            events[2].record()
+        ac.air_select_compact(0, L, k, v)
+        if events is not None:
+            events[3].record()
+        for t in range(n_dec):
+            if args.per_layer:
+                for l in range(L):
+                    ac.air_decode_attn(l, l + 1, dq[t, l:l + 1], dk[t, l:l + 1], dv[t, l:l + 1], out[l:l + 1])
+            else:
+                ac.air_decode_attn(0, L, dq[t], dk[t], dv[t], out)
+        if events is not None:
+            events[4].record()
+
+    for _ in range(args.warmup):
+        one_step()
+    torch.cuda.synchronize()
+    budgets = ac.air_get_budgets()
+    all_events = [[ev() for _ in range(5)] for _ in range(args.steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        one_step(all_events[i])
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+
+    stage = np.array([[e[i].elapsed_time(e[i + 1]) for i in range(4)] for e in all_events])  # ms
+    score_ms, budget_ms, select_ms, decode_ms = stage.mean(axis=0)
+    compress_ms = score_ms + budget_ms + select_ms
+    ms_per_step = wall * 1e3 / args.steps
+    ab = algorithmic_bytes(w, seqs, budgets, n_dec)
+    n_launch = n_dec * (L if args.per_layer else 1)
+    dec_launch_us = decode_ms * 1e3 / n_launch
+    dec_gbs = ab["decode_total"] / (decode_ms * 1e-3) / 1e9
+    result = {
+        "metric": METRIC,
+        "value": w.batch * n_dec / (ms_per_step * 1e-3),
+        "unit": "tokens/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": ms_per_step,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": w.dtype,
+        "data": "synthetic",
+        "config": {"workload": f"config{w.cfg_id}:{w.name}", "batch": w.batch, "layers": L,
+                   "q_heads": w.n_q_heads, "kv_heads": w.n_kv_heads, "head_dim": w.head_dim,
+                   "tokens": f"{w.n_sys}+{w.n_vis}+{w.n_text}", "retention": retention, "alpha": w.alpha,
+                   "decode_steps": n_dec, "decode_launch": "per-layer" if args.per_layer else "all-layers"},
+        "compress_us_per_layer": compress_ms * 1e3 / L,
+        "decode_tokens_per_s": w.batch * n_dec / (decode_ms * 1e-3),
+        "stage_us": {"score": score_ms * 1e3, "budget": budget_ms * 1e3, "select_compact": select_ms * 1e3,
+                     "decode_per_step": decode_ms * 1e3 / n_dec},
+        "roofline": {"kernel": "air_decode_attn", "bound": "hbm", "achieved": dec_gbs, "peak": HBM_PEAK_GBS,
+                     "unit": "GB/s", "frac": dec_gbs / HBM_PEAK_GBS, "traffic": None,
+                     "bytes_per_launch": ab["decode_total"] / n_launch, "launch_us": dec_launch_us},
+        "roofline_compress": {"kernel": "air_score+air_budget+air_select_compact", "bound": "hbm",
+                              "achieved": ab["compress"] / (compress_ms * 1e-3) / 1e9, "peak": HBM_PEAK_GBS,
+                              "unit": "GB/s", "frac": ab["compress"] / (compress_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
+                              "score_frac": ab["score"] / (score_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
+                              "bytes": ab["compress"]},
+    }
+    if not args.no_cpu_baseline:
+        result["cpu_baseline"] = cpu_baseline(w, seqs, retention, host_layers, dec_inputs, n_dec)
+    print(json.dumps(result))
+
+
+if __name__ == "__main__":
+    main()

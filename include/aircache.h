@@ -107,6 +107,11 @@ size_t air_workspace_bytes(const air_config *cfg);
 air_status air_create(const air_config *cfg, void *workspace, size_t workspace_bytes, air_ctx **out);
 air_status air_destroy(air_ctx *ctx);
 
+/* Forget the prompt: the context returns to its state after air_create (no layer scored,
+ * no budgets, empty caches) so that the next prompt of the same shape can be compressed.
+ * Host bookkeeping only; nothing is enqueued and device memory is left as it is. */
+air_status air_reset(air_ctx *ctx);
+
 /* Alg.1, first loop (Eq.4-10) for layers [l0, l1).  layers: host array of l1-l0 entries;
  * seqs: host array of cfg.batch entries, the same for every call on this context (the
  * first call fixes it).  Fills importance scores and per-layer strength / skewness. */

@@ -48,7 +48,7 @@ class air_strides(C.Structure):
 
 
 EXPORTS = (
-    "air_version", "air_workspace_bytes", "air_create", "air_destroy", "air_score", "air_budget",
+    "air_version", "air_workspace_bytes", "air_create", "air_destroy", "air_reset", "air_score", "air_budget",
     "air_select_compact", "air_decode_attn", "air_get_scores", "air_get_elite", "air_get_stats",
     "air_get_budgets", "air_set_budgets", "air_get_indices", "air_get_lengths", "air_get_cache",
     "air_last_error",
@@ -77,6 +77,7 @@ def load_library(path: Optional[str] = None):
     lib.air_workspace_bytes.argtypes = [C.POINTER(air_config)]
     lib.air_create.argtypes = [C.POINTER(air_config), vp, C.c_size_t, C.POINTER(vp)]
     lib.air_destroy.argtypes = [vp]
+    lib.air_reset.argtypes = [vp]
     lib.air_score.argtypes = [vp, vp, i32, i32, C.POINTER(air_layer), C.POINTER(air_strides), C.POINTER(air_seq)]
     lib.air_budget.argtypes = [vp, vp]
     lib.air_select_compact.argtypes = [vp, vp, i32, i32, C.POINTER(air_layer), C.POINTER(air_strides)]
@@ -185,6 +186,9 @@ class AirCache:
         arr = self._layers(q_text, k, v)
         sq = self.seq_array(seqs)
         self._check(self.lib.air_score(self.handle, self._stream(), l0, l1, arr, C.byref(st), sq))
+
+    def air_reset(self):
+        self._check(self.lib.air_reset(self.handle))
 
     def air_budget(self):
         self._check(self.lib.air_budget(self.handle, self._stream()))

@@ -183,6 +183,17 @@ air_status air_destroy(air_ctx *ctx) {
     return AIR_OK;
 }
 
+air_status air_reset(air_ctx *ctx) {
+    if (!ctx) return AIR_ERR_INVALID_ARG;
+    ctx->have_seqs = false;
+    ctx->budgets_ready = false;
+    ctx->seqs.clear();
+    ctx->scored.assign(ctx->dm.L, 0);
+    ctx->compacted.assign(ctx->dm.L, 0);
+    ctx->appended.assign(ctx->dm.L, 0);
+    return AIR_OK;
+}
+
 const char *air_last_error(const air_ctx *ctx) { return ctx ? ctx->err.c_str() : "null context"; }
 
 static bool range_ok(const air_ctx *c, int32_t l0, int32_t l1) { return l0 >= 0 && l1 > l0 && l1 <= c->cfg.n_layers; }
@@ -342,7 +353,13 @@ air_status air_get_scores(air_ctx *ctx, int32_t l, float *host) {
     if (l < 0 || l >= ctx->cfg.n_layers) return fail(ctx, AIR_ERR_INVALID_ARG, "bad layer");
     if (!ctx->scored[l]) return fail(ctx, AIR_ERR_STATE, "layer not scored");
     const size_t n = (size_t)ctx->dm.B * ctx->dm.Hkv * ctx->dm.max_vis;
-    return d2h(ctx, host, ctx->tab.scores + (size_t)l * n, n * 4);
+    air_status st = d2h(ctx, host, ctx->tab.scores + (size_t)l * n, n * 4);
+    if (st != AIR_OK) return st;
+    for (int b = 0; b < ctx->dm.B; ++b)  // entries past a sequence's visual span read as 0
+        for (int h = 0; h < ctx->dm.Hkv; ++h)
+            for (int i = ctx->seqs[b].vis_len; i < ctx->dm.max_vis; ++i)
+                host[((size_t)b * ctx->dm.Hkv + h) * ctx->dm.max_vis + i] = 0.f;
+    return AIR_OK;
 }
 
 air_status air_get_elite(air_ctx *ctx, int32_t l, int32_t *counts, int32_t *indices) {
