@@ -72,8 +72,8 @@ WsLayout make_layout(const air_config &c) {
     w.indices = take(L * B * Hkv * NV * 4);
     w.kcache = take(B * Hkv * (size_t)w.pool_rows * D * esz);
     w.vcache = take(B * Hkv * (size_t)w.pool_rows * D * esz);
-    w.dec_o = take(L * B * Hq * kDecodeSplits * D * 4);
-    w.dec_ml = take(L * B * Hq * kDecodeSplits * 8);
+    w.dec_o = take(L * B * Hq * kMaxSplits * D * 4);
+    w.dec_ml = take(L * B * Hq * kMaxSplits * 8);
     w.total = off;
     return w;
 }
@@ -312,6 +312,25 @@ air_status air_select_compact(air_ctx *ctx, void *stream, int32_t l0, int32_t l1
     return AIR_OK;
 }
 
+// Split-K factor of one decode launch: enough workgroups to cover the chip a few times, but no
+// split shorter than one 128-key iteration of the kernel at the average cache length.
+static int decode_splits(const air_ctx *ctx, int n_layers_in_launch, int appended) {
+    const air_config &c = ctx->cfg;
+    const int64_t units = (int64_t)n_layers_in_launch * c.batch * c.n_kv_heads;
+    double avg_len = 0.0;
+    for (int b = 0; b < c.batch; ++b) {
+        const air_seq &s = ctx->seqs[b];
+        avg_len += (double)(s.seq_len - s.vis_len) + c.retention * (double)s.vis_len + appended + 1;
+    }
+    avg_len /= c.batch;
+    int64_t by_work = (2048 + units - 1) / units;
+    int64_t by_len = (int64_t)((avg_len + 127.0) / 128.0);
+    int64_t s = by_work < by_len ? by_work : by_len;
+    if (s < 1) s = 1;
+    if (s > kMaxSplits) s = kMaxSplits;
+    return (int)s;
+}
+
 air_status air_decode_attn(air_ctx *ctx, void *stream, int32_t l0, int32_t l1, const void *q_new, const void *k_new,
                            const void *v_new, void *out) {
     if (!ctx) return AIR_ERR_INVALID_ARG;
@@ -331,7 +350,9 @@ air_status air_decode_attn(air_ctx *ctx, void *stream, int32_t l0, int32_t l1, c
         memset(&ll, 0, sizeof(ll));
         for (int i = 0; i < nl; ++i) ll.appended[i] = ctx->appended[c0 + i];
         hipError_t e = launch_append(s, ctx->dm, ctx->tab, ctx->cfg.dtype, c0, nl, c0 - l0, ll, k_new, v_new);
-        if (e == hipSuccess) e = launch_decode(s, ctx->dm, ctx->tab, ctx->cfg.dtype, c0, nl, c0 - l0, ll, q_new, out);
+        if (e == hipSuccess)
+            e = launch_decode(s, ctx->dm, ctx->tab, ctx->cfg.dtype, c0, nl, c0 - l0, ll, q_new, out,
+                              decode_splits(ctx, nl, ctx->appended[c0]));
         if (e != hipSuccess) return hip_fail(ctx, e, "air_decode_attn launch");
     }
     for (int l = l0; l < l1; ++l) ctx->appended[l] += 1;
@@ -450,7 +471,19 @@ air_status air_get_cache(air_ctx *ctx, int32_t l, int32_t b, int32_t h, void *k_
     const size_t rb = (size_t)ctx->dm.D * esz;
     st = d2h(ctx, k_host, (char *)ctx->tab.kcache + row0 * rb, (size_t)len * rb);
     if (st != AIR_OK) return st;
-    return d2h(ctx, v_host, (char *)ctx->tab.vcache + row0 * rb, (size_t)len * rb);
+    if (!v_transposed(ctx->cfg.dtype, ctx->dm.D))
+        return d2h(ctx, v_host, (char *)ctx->tab.vcache + row0 * rb, (size_t)len * rb);
+    // block-transposed V': fetch whole 32-token blocks and put the tokens back in row order
+    const int D = ctx->dm.D;
+    const size_t n_blk = ((size_t)len + 31) / 32;
+    std::vector<uint16_t> raw(n_blk * 32 * D);
+    st = d2h(ctx, raw.data(), (char *)ctx->tab.vcache + row0 * rb, raw.size() * 2);
+    if (st != AIR_OK) return st;
+    uint16_t *vh = (uint16_t *)v_host;
+    for (int r = 0; r < len; ++r)
+        for (int col = 0; col < D; ++col)
+            vh[(size_t)r * D + col] = raw[((size_t)(r / 32) * D + col) * 32 + v_slot(r % 32)];
+    return AIR_OK;
 }
 
 }  // extern "C"

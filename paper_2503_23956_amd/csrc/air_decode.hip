@@ -1,10 +1,11 @@
 // air_decode_attn: Eq.2 append, then softmax(q K'^T / sqrt(d)) V' over the compacted cache.
 //
-//   append_kernel   writes k_new / v_new behind the last row of each (layer, sequence, KV head).
-//   decode_kernel   split-K: workgroup (split, unit) streams its share of K' and V' once and
-//                   leaves an online-softmax partial (max, sum, unnormalised output) for the
-//                   G query heads that share the KV head.
-//   combine_kernel  merges the kDecodeSplits partials and stores the output in the storage dtype.
+//   append_kernel      writes k_new / v_new behind the last row of each (layer, sequence, KV head).
+//   decode_mfma_kernel bf16, head_dim 128: one wavefront per (split, unit).  K' rows and the
+//                      block-transposed V' go from global memory straight into MFMA operands;
+//                      the G query heads of the group are the second MFMA dimension.
+//   decode_kernel      generic fp32-ALU version (fp32 storage, head_dim 64).
+//   combine_kernel     merges the split-K partials and stores the output in the storage dtype.
 #include "air_device.h"
 #include "air_internal.h"
 
@@ -12,28 +13,202 @@ namespace air {
 
 constexpr int kMaxGroup = 16;
 
-template <typename T, int D>
-__global__ __launch_bounds__(64) void append_kernel(Dims dm, DevTables t, int l0, int lbase, LaunchLayers ll,
-                                                    const T *k_new, const T *v_new) {
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(4))) float f32x4;
+
+// key range of one split: ceil(len / splits) rounded up to whole 32-token blocks
+__device__ __forceinline__ void split_range(int len, int splits, int split, int &k0, int &k1) {
+    int cs = (len + splits - 1) / splits;
+    cs = (cs + 31) & ~31;
+    k0 = split * cs;
+    k1 = min(len, k0 + cs);
+}
+
+// ---------------------------------------------------------------------------------------
+// append (Eq.2)
+// ---------------------------------------------------------------------------------------
+template <typename T, int D, bool VT>
+__global__ __launch_bounds__(128) void append_kernel(Dims dm, DevTables t, int l0, int lbase, LaunchLayers ll,
+                                                     const T *k_new, const T *v_new) {
     const int u = blockIdx.x;
     const int kvh = u % dm.Hkv;
     const int b = (u / dm.Hkv) % dm.B;
     const int li = u / (dm.Hkv * dm.B);
     const int l = l0 + li;
     const int row = t.base_len[(int64_t)b * dm.L + l] + ll.appended[li];
-    const int64_t dst_row = ((int64_t)b * dm.Hkv + kvh) * dm.pool_rows + t.layer_off[(int64_t)b * dm.L + l] + row;
+    const int64_t row0 = ((int64_t)b * dm.Hkv + kvh) * dm.pool_rows + t.layer_off[(int64_t)b * dm.L + l];
     const int64_t src = (((int64_t)(lbase + li) * dm.B + b) * dm.Hkv + kvh) * D;
     constexpr int kVec = D * (int)sizeof(T) / 16;
-    if (threadIdx.x < kVec) {
-        const int c = threadIdx.x * (16 / (int)sizeof(T));
-        *reinterpret_cast<uint4 *>((T *)t.kcache + dst_row * D + c) = *reinterpret_cast<const uint4 *>(k_new + src + c);
-        *reinterpret_cast<uint4 *>((T *)t.vcache + dst_row * D + c) = *reinterpret_cast<const uint4 *>(v_new + src + c);
+    const int tid = threadIdx.x;
+    if (tid < kVec) {
+        const int c = tid * (16 / (int)sizeof(T));
+        *reinterpret_cast<uint4 *>((T *)t.kcache + (row0 + row) * D + c) = *reinterpret_cast<const uint4 *>(k_new + src + c);
+        if (!VT)
+            *reinterpret_cast<uint4 *>((T *)t.vcache + (row0 + row) * D + c) = *reinterpret_cast<const uint4 *>(v_new + src + c);
+    }
+    if (VT && tid < D) {
+        // column tid of the transposed block; a token that opens a new block clears the block's row first
+        bf16_t *vrow = (bf16_t *)t.vcache + (row0 + (row & ~31)) * D + (int64_t)tid * 32;
+        const int tok = row & 31;
+        const bf16_t val = ((const bf16_t *)v_new)[src + tid];
+        if (tok == 0) {
+            uint4 z = make_uint4(0, 0, 0, 0);
+            uint4 first = z;
+            first.x = val;  // slot of token 0 is 0
+            reinterpret_cast<uint4 *>(vrow)[0] = first;
+            reinterpret_cast<uint4 *>(vrow)[1] = z;
+            reinterpret_cast<uint4 *>(vrow)[2] = z;
+            reinterpret_cast<uint4 *>(vrow)[3] = z;
+        } else {
+            vrow[v_slot(tok)] = val;
+        }
     }
 }
 
+// ---------------------------------------------------------------------------------------
+// MFMA decode attention.  Lane (n = lane % 16, c = lane / 16).
+//   scores^T tile (16 keys x 16 heads) = K'(16 keys x 128) * q^T: A = key n, elements 8c..8c+7 of
+//   each 32-element slice; B = head n, same elements; the result leaves lane (n = head, c) with
+//   keys 4c..4c+3 of the tile.  Two tiles cover a 32-token block, so that lane holds 8
+//   probabilities of head n: exactly the A operand of P*V for the block when the block's tokens
+//   are stored in v_slot order.  B of P*V = 16 bytes of the transposed V' block per lane, and the
+//   accumulator of output tile j keeps heads 4c..4c+3 of column 16j + n.
+// ---------------------------------------------------------------------------------------
+__global__ __launch_bounds__(64) void decode_mfma_kernel(Dims dm, DevTables t, int l0, int lbase, LaunchLayers ll,
+                                                         const bf16_t *q_new, int splits) {
+    constexpr int D = 128;
+    constexpr int kIter = 128;  // keys per loop iteration
+    const int lane = threadIdx.x, n = lane & 15, c = lane >> 4;
+    const int split = blockIdx.x;
+    const int u = blockIdx.y;
+    const int kvh = u % dm.Hkv;
+    const int b = (u / dm.Hkv) % dm.B;
+    const int li = u / (dm.Hkv * dm.B);
+    const int l = l0 + li;
+    const int G = dm.G;
+    const int len = t.base_len[(int64_t)b * dm.L + l] + ll.appended[li] + 1;
+    int k0, k1;
+    split_range(len, splits, split, k0, k1);
+    const int64_t row0 = ((int64_t)b * dm.Hkv + kvh) * dm.pool_rows + t.layer_off[(int64_t)b * dm.L + l];
+    const bf16_t *kc = (const bf16_t *)t.kcache + row0 * D;
+    const bf16_t *vc = (const bf16_t *)t.vcache + row0 * D;
+    const int64_t unit = ((int64_t)l * dm.B + b) * dm.Hkv + kvh;
+
+    bf16x8 qb[4];
+    {
+        const bf16_t *q = q_new + (((int64_t)(lbase + li) * dm.B + b) * dm.Hq + (int64_t)kvh * G + n) * D;
+#pragma unroll
+        for (int s = 0; s < 4; ++s) {
+            uint4 x = make_uint4(0, 0, 0, 0);
+            if (n < G) x = *reinterpret_cast<const uint4 *>(q + 32 * s + 8 * c);
+            qb[s] = __builtin_bit_cast(bf16x8, x);
+        }
+    }
+    const float scale = 0.08838834764831845f;  // 1/sqrt(128)
+    float m_run = -INFINITY, l_run = 0.f;
+    f32x4 acc[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) acc[j] = (f32x4){0.f, 0.f, 0.f, 0.f};
+
+    for (int kb = k0; kb < k1; kb += kIter) {
+        // ---- scores^T for 8 tiles of 16 keys
+        f32x4 s[8];
+#pragma unroll
+        for (int tile = 0; tile < 8; ++tile) {
+            const int key = kb + 16 * tile + n;
+            s[tile] = (f32x4){0.f, 0.f, 0.f, 0.f};
+            uint4 a[4];
+#pragma unroll
+            for (int sl = 0; sl < 4; ++sl) {
+                a[sl] = make_uint4(0, 0, 0, 0);
+                if (key < k1) a[sl] = *reinterpret_cast<const uint4 *>(kc + (int64_t)key * D + 32 * sl + 8 * c);
+            }
+#pragma unroll
+            for (int sl = 0; sl < 4; ++sl)
+                s[tile] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a[sl]), qb[sl], s[tile], 0, 0, 0);
+        }
+        // ---- V' operands of the 4 token blocks (issued before the softmax arithmetic)
+        uint4 vb[4][8];
+#pragma unroll
+        for (int tb = 0; tb < 4; ++tb) {
+            const int blk0 = kb + 32 * tb;
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                vb[tb][j] = make_uint4(0, 0, 0, 0);
+                if (blk0 < k1)
+                    vb[tb][j] = *reinterpret_cast<const uint4 *>(vc + (int64_t)blk0 * D + (16 * j + n) * 32 + 8 * c);
+            }
+        }
+        // ---- online softmax for head n over the keys this lane holds (4c+i of each tile)
+        float mb = -INFINITY;
+#pragma unroll
+        for (int tile = 0; tile < 8; ++tile)
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const int key = kb + 16 * tile + 4 * c + i;
+                const float v = key < k1 ? s[tile][i] * scale : -INFINITY;
+                s[tile][i] = v;
+                mb = fmaxf(mb, v);
+            }
+        mb = fmaxf(mb, __shfl_xor(mb, 16, 64));
+        mb = fmaxf(mb, __shfl_xor(mb, 32, 64));
+        const float m_new = fmaxf(m_run, mb);
+        const float corr = __expf(m_run - m_new);
+        float lb = 0.f;
+#pragma unroll
+        for (int tile = 0; tile < 8; ++tile)
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const float p = __expf(s[tile][i] - m_new);
+                s[tile][i] = p;
+                lb += p;
+            }
+        lb += __shfl_xor(lb, 16, 64);
+        lb += __shfl_xor(lb, 32, 64);
+        l_run = l_run * corr + lb;
+        m_run = m_new;
+        // accumulator rows are heads 4c..4c+3: fetch their rescale factors from lanes 4c+i
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const float f = __shfl(corr, 4 * c + i, 64);
+#pragma unroll
+            for (int j = 0; j < 8; ++j) acc[j][i] *= f;
+        }
+        // ---- P * V
+#pragma unroll
+        for (int tb = 0; tb < 4; ++tb) {
+            bf16x8 pa;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                pa[i] = (__bf16)s[2 * tb][i];
+                pa[4 + i] = (__bf16)s[2 * tb + 1][i];
+            }
+#pragma unroll
+            for (int j = 0; j < 8; ++j)
+                acc[j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(pa, __builtin_bit_cast(bf16x8, vb[tb][j]), acc[j], 0, 0, 0);
+        }
+    }
+    // ---- partial of this split
+    const int64_t part = unit * kMaxSplits + split;
+    float *po = t.dec_o + part * (int64_t)G * D;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int g = 4 * c + i;
+        if (g < G) {
+#pragma unroll
+            for (int j = 0; j < 8; ++j) po[g * D + 16 * j + n] = acc[j][i];
+        }
+    }
+    if (c == 0 && n < G) t.dec_ml[part * G + n] = make_float2(m_run, l_run);
+}
+
+// ---------------------------------------------------------------------------------------
+// generic decode attention: one workgroup per (split, unit), thread per key for q.K', thread
+// per output column for P.V', online softmax over blocks of 256 keys.
+// ---------------------------------------------------------------------------------------
 template <typename T, int D>
 __global__ __launch_bounds__(256) void decode_kernel(Dims dm, DevTables t, int l0, int lbase, LaunchLayers ll,
-                                                     const T *q_new) {
+                                                     const T *q_new, int splits) {
     constexpr int NP = 256 / D;  // key-parallel parts in the P*V phase
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
     const int split = blockIdx.x;
@@ -44,8 +219,8 @@ __global__ __launch_bounds__(256) void decode_kernel(Dims dm, DevTables t, int l
     const int l = l0 + li;
     const int G = dm.G;
     const int len = t.base_len[(int64_t)b * dm.L + l] + ll.appended[li] + 1;
-    const int cs = (len + kDecodeSplits - 1) / kDecodeSplits;
-    const int k0 = split * cs, k1 = min(len, k0 + cs);
+    int k0, k1;
+    split_range(len, splits, split, k0, k1);
     const int64_t row0 = ((int64_t)b * dm.Hkv + kvh) * dm.pool_rows + t.layer_off[(int64_t)b * dm.L + l];
     const T *kc = (const T *)t.kcache + row0 * D;
     const T *vc = (const T *)t.vcache + row0 * D;
@@ -78,7 +253,7 @@ __global__ __launch_bounds__(256) void decode_kernel(Dims dm, DevTables t, int l
                 float a = 0.f;
                 if (tid < nk) {
 #pragma unroll
-                    for (int c = 0; c < D; ++c) a = fmaf(s_q[g][c], kreg[c], a);
+                    for (int cc = 0; cc < D; ++cc) a = fmaf(s_q[g][cc], kreg[cc], a);
                 }
                 s_p[g][tid] = tid < nk ? a * scale : -INFINITY;
             }
@@ -121,19 +296,20 @@ __global__ __launch_bounds__(256) void decode_kernel(Dims dm, DevTables t, int l
     for (int g = 0; g < kMaxGroup; ++g)
         if (g < G) s_o[part][g][dcol] = acc[g];
     __syncthreads();
-    float *po = t.dec_o + (unit * kDecodeSplits + split) * (int64_t)G * D;
+    const int64_t pidx = unit * kMaxSplits + split;
+    float *po = t.dec_o + pidx * (int64_t)G * D;
     for (int idx = tid; idx < G * D; idx += 256) {
-        const int g = idx / D, c = idx % D;
+        const int g = idx / D, cc = idx % D;
         float o = 0.f;
 #pragma unroll
-        for (int p = 0; p < NP; ++p) o += s_o[p][g][c];
+        for (int p = 0; p < NP; ++p) o += s_o[p][g][cc];
         po[idx] = o;
     }
-    if (tid < G) t.dec_ml[(unit * kDecodeSplits + split) * G + tid] = make_float2(s_m[tid], s_l[tid]);
+    if (tid < G) t.dec_ml[pidx * G + tid] = make_float2(s_m[tid], s_l[tid]);
 }
 
 template <typename T, int D>
-__global__ __launch_bounds__(256) void combine_kernel(Dims dm, DevTables t, int l0, int lbase, T *out) {
+__global__ __launch_bounds__(256) void combine_kernel(Dims dm, DevTables t, int l0, int lbase, T *out, int splits) {
     const int u = blockIdx.x;
     const int kvh = u % dm.Hkv;
     const int b = (u / dm.Hkv) % dm.B;
@@ -141,17 +317,15 @@ __global__ __launch_bounds__(256) void combine_kernel(Dims dm, DevTables t, int 
     const int l = l0 + li;
     const int G = dm.G;
     const int64_t unit = ((int64_t)l * dm.B + b) * dm.Hkv + kvh;
-    const float2 *ml = t.dec_ml + unit * kDecodeSplits * G;
-    const float *po = t.dec_o + unit * kDecodeSplits * (int64_t)G * D;
+    const float2 *ml = t.dec_ml + unit * kMaxSplits * G;
+    const float *po = t.dec_o + unit * kMaxSplits * (int64_t)G * D;
     T *o = out + (((int64_t)(lbase + li) * dm.B + b) * dm.Hq + (int64_t)kvh * G) * D;
     for (int idx = threadIdx.x; idx < G * D; idx += 256) {
         const int g = idx / D;
         float M = -INFINITY;
-#pragma unroll
-        for (int s = 0; s < kDecodeSplits; ++s) M = fmaxf(M, ml[s * G + g].x);
+        for (int s = 0; s < splits; ++s) M = fmaxf(M, ml[s * G + g].x);
         float num = 0.f, den = 0.f;
-#pragma unroll
-        for (int s = 0; s < kDecodeSplits; ++s) {
+        for (int s = 0; s < splits; ++s) {
             const float2 x = ml[s * G + g];
             const float wgt = x.y > 0.f ? expf(x.x - M) : 0.f;
             num = fmaf(wgt, po[(int64_t)s * G * D + idx], num);
@@ -161,10 +335,10 @@ __global__ __launch_bounds__(256) void combine_kernel(Dims dm, DevTables t, int 
     }
 }
 
-template <typename T, int D>
+template <typename T, int D, bool VT>
 static hipError_t append_launch(hipStream_t s, const Dims &dm, const DevTables &t, int l0, int nl, int lbase,
                                 const LaunchLayers &ll, const void *k_new, const void *v_new) {
-    hipLaunchKernelGGL((append_kernel<T, D>), dim3(nl * dm.B * dm.Hkv), dim3(64), 0, s, dm, t, l0, lbase, ll,
+    hipLaunchKernelGGL((append_kernel<T, D, VT>), dim3(nl * dm.B * dm.Hkv), dim3(128), 0, s, dm, t, l0, lbase, ll,
                        (const T *)k_new, (const T *)v_new);
     return hipGetLastError();
 }
@@ -172,30 +346,35 @@ static hipError_t append_launch(hipStream_t s, const Dims &dm, const DevTables &
 hipError_t launch_append(hipStream_t s, const Dims &dm, const DevTables &t, int dtype, int l0, int nl, int lbase,
                          const LaunchLayers &ll, const void *k_new, const void *v_new) {
     if (dtype == AIR_BF16)
-        return dm.D == 128 ? append_launch<bf16_t, 128>(s, dm, t, l0, nl, lbase, ll, k_new, v_new)
-                           : append_launch<bf16_t, 64>(s, dm, t, l0, nl, lbase, ll, k_new, v_new);
-    return dm.D == 128 ? append_launch<float, 128>(s, dm, t, l0, nl, lbase, ll, k_new, v_new)
-                       : append_launch<float, 64>(s, dm, t, l0, nl, lbase, ll, k_new, v_new);
+        return dm.D == 128 ? append_launch<bf16_t, 128, true>(s, dm, t, l0, nl, lbase, ll, k_new, v_new)
+                           : append_launch<bf16_t, 64, false>(s, dm, t, l0, nl, lbase, ll, k_new, v_new);
+    return dm.D == 128 ? append_launch<float, 128, false>(s, dm, t, l0, nl, lbase, ll, k_new, v_new)
+                       : append_launch<float, 64, false>(s, dm, t, l0, nl, lbase, ll, k_new, v_new);
 }
 
 template <typename T, int D>
 static hipError_t decode_launch(hipStream_t s, const Dims &dm, const DevTables &t, int l0, int nl, int lbase,
-                                const LaunchLayers &ll, const void *q_new, void *out) {
-    hipLaunchKernelGGL((decode_kernel<T, D>), dim3(kDecodeSplits, nl * dm.B * dm.Hkv), dim3(256), 0, s, dm, t, l0,
-                       lbase, ll, (const T *)q_new);
+                                const LaunchLayers &ll, const void *q_new, void *out, int splits, bool mfma) {
+    const int units = nl * dm.B * dm.Hkv;
+    if (mfma)
+        hipLaunchKernelGGL(decode_mfma_kernel, dim3(splits, units), dim3(64), 0, s, dm, t, l0, lbase, ll,
+                           (const bf16_t *)q_new, splits);
+    else
+        hipLaunchKernelGGL((decode_kernel<T, D>), dim3(splits, units), dim3(256), 0, s, dm, t, l0, lbase, ll,
+                           (const T *)q_new, splits);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL((combine_kernel<T, D>), dim3(nl * dm.B * dm.Hkv), dim3(256), 0, s, dm, t, l0, lbase, (T *)out);
+    hipLaunchKernelGGL((combine_kernel<T, D>), dim3(units), dim3(256), 0, s, dm, t, l0, lbase, (T *)out, splits);
     return hipGetLastError();
 }
 
 hipError_t launch_decode(hipStream_t s, const Dims &dm, const DevTables &t, int dtype, int l0, int nl, int lbase,
-                         const LaunchLayers &ll, const void *q_new, void *out) {
+                         const LaunchLayers &ll, const void *q_new, void *out, int splits) {
     if (dtype == AIR_BF16)
-        return dm.D == 128 ? decode_launch<bf16_t, 128>(s, dm, t, l0, nl, lbase, ll, q_new, out)
-                           : decode_launch<bf16_t, 64>(s, dm, t, l0, nl, lbase, ll, q_new, out);
-    return dm.D == 128 ? decode_launch<float, 128>(s, dm, t, l0, nl, lbase, ll, q_new, out)
-                       : decode_launch<float, 64>(s, dm, t, l0, nl, lbase, ll, q_new, out);
+        return dm.D == 128 ? decode_launch<bf16_t, 128>(s, dm, t, l0, nl, lbase, ll, q_new, out, splits, true)
+                           : decode_launch<bf16_t, 64>(s, dm, t, l0, nl, lbase, ll, q_new, out, splits, false);
+    return dm.D == 128 ? decode_launch<float, 128>(s, dm, t, l0, nl, lbase, ll, q_new, out, splits, false)
+                       : decode_launch<float, 64>(s, dm, t, l0, nl, lbase, ll, q_new, out, splits, false);
 }
 
 }  // namespace air

@@ -11,7 +11,7 @@ namespace air {
 
 constexpr int kChunkKeys = 256;       // visual keys per workgroup in the score passes
 constexpr int kMaxLayersPerLaunch = 32;
-constexpr int kDecodeSplits = 8;      // split-K factor of the decode attention
+constexpr int kMaxSplits = 16;        // largest split-K factor of the decode attention
 constexpr int kCacheRowAlign = 32;    // layer regions of the compacted cache start on multiples of this
 constexpr int kGatherRows = 32;       // rows copied per workgroup in the compaction gather
 
@@ -79,6 +79,13 @@ hipError_t launch_gather(hipStream_t s, const Dims &dm, const DevTables &t, int 
 hipError_t launch_append(hipStream_t s, const Dims &dm, const DevTables &t, int dtype, int l0, int nl, int lbase,
                          const LaunchLayers &ll, const void *k_new, const void *v_new);
 hipError_t launch_decode(hipStream_t s, const Dims &dm, const DevTables &t, int dtype, int l0, int nl, int lbase,
-                         const LaunchLayers &ll, const void *q_new, void *out);
+                         const LaunchLayers &ll, const void *q_new, void *out, int splits);
+
+// The bf16 / head_dim 128 cache keeps V' transposed in blocks of 32 tokens so that the decode
+// kernel can feed it to MFMA straight from global memory: block [128 columns][32 slots], and
+// token t of the block sits in slot v_slot(t).  With this order the 8 probabilities a lane holds
+// after the two 16-key score tiles of a block are exactly the 8 contraction slots it must supply.
+inline bool v_transposed(int dtype, int head_dim) { return dtype == AIR_BF16 && head_dim == 128; }
+__host__ __device__ inline int v_slot(int t) { return ((t & 15) >> 2) * 8 + (t >> 4) * 4 + (t & 3); }
 
 }  // namespace air

@@ -124,6 +124,57 @@ __global__ __launch_bounds__(256) void gather_kernel(Dims dm, DevTables t, int l
     }
 }
 
+// bf16 / head_dim 128: same K' copy, but V' is written block-transposed (see v_slot): one
+// workgroup stages the 32 gathered V rows of a block in LDS and writes [128 columns][32 slots].
+// Slots of the last block that have no token yet are written as zeros.
+__global__ __launch_bounds__(256) void gather_vt_kernel(Dims dm, DevTables t, int l0, LaunchLayers ll, air_strides st) {
+    constexpr int D = 128;
+    typedef bf16_t T;
+    const int u = blockIdx.y;
+    const int kvh = u % dm.Hkv;
+    const int b = (u / dm.Hkv) % dm.B;
+    const int li = u / (dm.Hkv * dm.B);
+    const int l = l0 + li;
+    const air_seq sq = t.seq_tab[b];
+    const int kl = t.budgets[(int64_t)b * dm.L + l];
+    const int n_rows = sq.seq_len - sq.vis_len + kl;
+    const int64_t unit = ((int64_t)l * dm.B + b) * dm.Hkv + kvh;
+    const int32_t *idx = t.indices + unit * dm.max_vis;
+    const T *ksrc = (const T *)ll.p[li].k + (int64_t)b * st.kv_b + (int64_t)kvh * st.kv_h;
+    const T *vsrc = (const T *)ll.p[li].v + (int64_t)b * st.kv_b + (int64_t)kvh * st.kv_h;
+    const int64_t dst_row0 = ((int64_t)b * dm.Hkv + kvh) * dm.pool_rows + t.layer_off[(int64_t)b * dm.L + l];
+    T *kdst = (T *)t.kcache + dst_row0 * D;
+    T *vdst = (T *)t.vcache + dst_row0 * D;
+    __shared__ bf16_t tile[32][D + 8];  // indexed [slot][column]; +8 keeps the 16-byte row alignment and spreads banks
+    for (int r0 = blockIdx.x * 32; r0 < n_rows; r0 += gridDim.x * 32) {
+        for (int v = threadIdx.x; v < 32 * 16; v += 256) {
+            const int row = v >> 4, c = (v & 15) * 8;
+            const int j = r0 + row;
+            uint4 vx = make_uint4(0, 0, 0, 0);
+            if (j < n_rows) {
+                int tok;
+                if (j < sq.vis_start) tok = j;
+                else if (j < sq.vis_start + kl) tok = sq.vis_start + idx[j - sq.vis_start];
+                else tok = sq.vis_start + sq.vis_len + (j - sq.vis_start - kl);
+                const uint4 kx = *reinterpret_cast<const uint4 *>(ksrc + (int64_t)tok * st.kv_t + c);
+                vx = *reinterpret_cast<const uint4 *>(vsrc + (int64_t)tok * st.kv_t + c);
+                *reinterpret_cast<uint4 *>(kdst + (int64_t)j * D + c) = kx;
+            }
+            *reinterpret_cast<uint4 *>(&tile[v_slot(row)][c]) = vx;
+        }
+        __syncthreads();
+        for (int v = threadIdx.x; v < D * 4; v += 256) {
+            const int col = v >> 2, c = v & 3;
+            uint32_t w[4];
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+                w[j] = (uint32_t)tile[8 * c + 2 * j][col] | ((uint32_t)tile[8 * c + 2 * j + 1][col] << 16);
+            *reinterpret_cast<uint4 *>(vdst + (int64_t)r0 * D + col * 32 + 8 * c) = make_uint4(w[0], w[1], w[2], w[3]);
+        }
+        __syncthreads();
+    }
+}
+
 hipError_t launch_select(hipStream_t s, const Dims &dm, const DevTables &t, int l0, int nl) {
     hipLaunchKernelGGL(select_kernel, dim3(nl * dm.B * dm.Hkv), dim3(kSelThreads), 0, s, dm, t, l0);
     return hipGetLastError();
@@ -138,6 +189,10 @@ static hipError_t gather_launch(hipStream_t s, const Dims &dm, const DevTables &
 
 hipError_t launch_gather(hipStream_t s, const Dims &dm, const DevTables &t, int dtype, int l0, int nl,
                          const LaunchLayers &ll, const air_strides &st) {
+    if (v_transposed(dtype, dm.D)) {
+        hipLaunchKernelGGL(gather_vt_kernel, dim3(32, nl * dm.B * dm.Hkv), dim3(256), 0, s, dm, t, l0, ll, st);
+        return hipGetLastError();
+    }
     if (dtype == AIR_BF16)
         return dm.D == 128 ? gather_launch<bf16_t, 128>(s, dm, t, l0, nl, ll, st)
                            : gather_launch<bf16_t, 64>(s, dm, t, l0, nl, ll, st);

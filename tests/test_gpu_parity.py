@@ -196,5 +196,16 @@ def test_degenerate_sizes():
     _run_case(w, 0.02, steps=1)
 
 
+def test_decode_many_steps_cross_token_blocks():
+    # appended tokens cross several 32-token block boundaries of the cache
+    w = synth.get_workload(2).scaled(n_layers=2, n_vis=300, n_text=21, decode_steps=70)
+    _run_case(w, 0.10, steps=70)
+
+
+def test_decode_long_cache_multiple_iterations_per_split():
+    w = synth.get_workload(2).scaled(n_layers=2, n_vis=3000, n_text=40, decode_steps=2)
+    _run_case(w, 1.00, steps=2)
+
+
 def test_config2_full_size():
     _run_case(synth.get_workload(2), 0.10, steps=2)
