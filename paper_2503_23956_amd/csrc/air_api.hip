@@ -1,6 +1,7 @@
 // C ABI of libaircache.so: context, workspace layout, argument validation, stage sequencing.
 #include <math.h>
 #include <stdio.h>
+#include <stdlib.h>
 #include <string.h>
 
 #include <string>
@@ -69,10 +70,11 @@ WsLayout make_layout(const air_config &c) {
     w.budgets = take(B * L * 4);
     w.base_len = take(B * L * 4);
     w.layer_off = take(B * L * 4);
+    w.dec_cnt = take(L * B * Hkv * 4);
     w.indices = take(L * B * Hkv * NV * 4);
     w.kcache = take(B * Hkv * (size_t)w.pool_rows * D * esz);
     w.vcache = take(B * Hkv * (size_t)w.pool_rows * D * esz);
-    w.dec_o = take(L * B * Hq * kMaxSplits * D * 4);
+    w.dec_o = take(L * B * Hkv * kMaxSplits * 16 * D * 4);  // per (unit, split): 16 head rows x D
     w.dec_ml = take(L * B * Hq * kMaxSplits * 8);
     w.total = off;
     return w;
@@ -93,7 +95,7 @@ struct air_ctx {
     std::vector<air_seq> seqs;
     std::vector<char> scored, compacted;
     std::vector<int32_t> appended;
-    std::vector<int32_t> budgets_host;  // valid only after air_set_budgets / air_get_budgets
+    int force_splits, force_waves;  // AIR_DECODE_SPLITS / AIR_DECODE_WAVES, 0 = automatic
     std::string err;
 };
 
@@ -154,6 +156,7 @@ air_status air_create(const air_config *cfg, void *workspace, size_t workspace_b
     t.budgets = (int32_t *)(w + lay.budgets);
     t.base_len = (int32_t *)(w + lay.base_len);
     t.layer_off = (int32_t *)(w + lay.layer_off);
+    t.dec_cnt = (int32_t *)(w + lay.dec_cnt);
     t.indices = (int32_t *)(w + lay.indices);
     t.kcache = (void *)(w + lay.kcache);
     t.vcache = (void *)(w + lay.vcache);
@@ -161,6 +164,15 @@ air_status air_create(const air_config *cfg, void *workspace, size_t workspace_b
     t.dec_ml = (float2 *)(w + lay.dec_ml);
     c->have_seqs = false;
     c->budgets_ready = false;
+    c->force_splits = c->force_waves = 0;
+    if (const char *e = getenv("AIR_DECODE_SPLITS")) {
+        const int v = atoi(e);
+        if (v == 1 || v == 2 || v == 4 || v == 8 || v == 16) c->force_splits = v;
+    }
+    if (const char *e = getenv("AIR_DECODE_WAVES")) {
+        const int v = atoi(e);
+        if (v == 1 || v == 2 || v == 4 || v == 8) c->force_waves = v;
+    }
     c->scored.assign(d.L, 0);
     c->compacted.assign(d.L, 0);
     c->appended.assign(d.L, 0);
@@ -312,9 +324,13 @@ air_status air_select_compact(air_ctx *ctx, void *stream, int32_t l0, int32_t l1
     return AIR_OK;
 }
 
-// Split-K factor of one decode launch: enough workgroups to cover the chip a few times, but no
-// split shorter than one 128-key iteration of the kernel at the average cache length.
-static int decode_splits(const air_ctx *ctx, int n_layers_in_launch, int appended) {
+// Shape of one decode launch: `splits` workgroups of `waves` wavefronts per (layer, sequence, KV
+// head).  A wave works in 128-key iterations, so at the average cache length a unit has
+// ceil(len / 128) wave-iterations.  Up to 8 of them go to the waves of one workgroup (merged
+// through LDS, no exchange through memory); more splits are used only when the units alone
+// cannot fill the chip or a workgroup would loop many times.  AIR_DECODE_SPLITS / AIR_DECODE_WAVES
+// override the choice (tuning aid).
+static void decode_shape(const air_ctx *ctx, int n_layers_in_launch, int appended, int *splits, int *waves) {
     const air_config &c = ctx->cfg;
     const int64_t units = (int64_t)n_layers_in_launch * c.batch * c.n_kv_heads;
     double avg_len = 0.0;
@@ -323,12 +339,16 @@ static int decode_splits(const air_ctx *ctx, int n_layers_in_launch, int appende
         avg_len += (double)(s.seq_len - s.vis_len) + c.retention * (double)s.vis_len + appended + 1;
     }
     avg_len /= c.batch;
-    int64_t by_work = (2048 + units - 1) / units;
-    int64_t by_len = (int64_t)((avg_len + 127.0) / 128.0);
-    int64_t s = by_work < by_len ? by_work : by_len;
-    if (s < 1) s = 1;
-    if (s > kMaxSplits) s = kMaxSplits;
-    return (int)s;
+    const int64_t iters = (int64_t)((avg_len + 127.0) / 128.0);
+    int w = 1;
+    while (w < 8 && w < iters) w *= 2;
+    int64_t s = 1;
+    while (s < kMaxSplits && units * s < 256 && iters > (int64_t)w * s) s *= 2;   // fill the chip
+    while (s < kMaxSplits && iters > (int64_t)w * s * 4 && units * s < 2048) s *= 2;  // bound the loop length
+    if (ctx->force_splits > 0) s = ctx->force_splits;
+    if (ctx->force_waves > 0) w = ctx->force_waves;
+    *splits = (int)s;
+    *waves = w;
 }
 
 air_status air_decode_attn(air_ctx *ctx, void *stream, int32_t l0, int32_t l1, const void *q_new, const void *k_new,
@@ -349,10 +369,10 @@ air_status air_decode_attn(air_ctx *ctx, void *stream, int32_t l0, int32_t l1, c
         LaunchLayers ll;
         memset(&ll, 0, sizeof(ll));
         for (int i = 0; i < nl; ++i) ll.appended[i] = ctx->appended[c0 + i];
-        hipError_t e = launch_append(s, ctx->dm, ctx->tab, ctx->cfg.dtype, c0, nl, c0 - l0, ll, k_new, v_new);
-        if (e == hipSuccess)
-            e = launch_decode(s, ctx->dm, ctx->tab, ctx->cfg.dtype, c0, nl, c0 - l0, ll, q_new, out,
-                              decode_splits(ctx, nl, ctx->appended[c0]));
+        int splits = 1, waves = 1;
+        decode_shape(ctx, nl, ctx->appended[c0], &splits, &waves);
+        hipError_t e = launch_decode(s, ctx->dm, ctx->tab, ctx->cfg.dtype, c0, nl, c0 - l0, ll, q_new, k_new, v_new,
+                                     out, splits, waves);
         if (e != hipSuccess) return hip_fail(ctx, e, "air_decode_attn launch");
     }
     for (int l = l0; l < l1; ++l) ctx->appended[l] += 1;

@@ -1,11 +1,13 @@
 // air_decode_attn: Eq.2 append, then softmax(q K'^T / sqrt(d)) V' over the compacted cache.
 //
-//   append_kernel      writes k_new / v_new behind the last row of each (layer, sequence, KV head).
-//   decode_mfma_kernel bf16, head_dim 128: one wavefront per (split, unit).  K' rows and the
-//                      block-transposed V' go from global memory straight into MFMA operands;
-//                      the G query heads of the group are the second MFMA dimension.
-//   decode_kernel      generic fp32-ALU version (fp32 storage, head_dim 64).
-//   combine_kernel     merges the split-K partials and stores the output in the storage dtype.
+//   decode_mfma_kernel bf16, head_dim 128, ONE launch per call: one wavefront per (split, unit).
+//                      K' rows and the block-transposed V' go from global memory straight into
+//                      MFMA operands; the G query heads of the group are the second MFMA
+//                      dimension.  The wave whose key range holds the new token takes it from
+//                      k_new / v_new and stores it into the cache (Eq.2); the wave of a unit that
+//                      finishes last merges the unit's split-K partials.
+//   append_kernel, decode_kernel, combine_kernel
+//                      generic fp32-ALU path (fp32 storage, head_dim 64): three launches.
 #include "air_device.h"
 #include "air_internal.h"
 
@@ -15,6 +17,8 @@ constexpr int kMaxGroup = 16;
 
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(4))) float f32x4;
+typedef __attribute__((ext_vector_type(4))) unsigned int u32x4;
+constexpr int kSysScope = 17;  // buffer cache policy sc0 | sc1: write through / read past the L2 of this XCD
 
 // key range of one split: ceil(len / splits) rounded up to whole 32-token blocks
 __device__ __forceinline__ void split_range(int len, int splits, int split, int &k0, int &k1) {
@@ -66,19 +70,25 @@ __global__ __launch_bounds__(128) void append_kernel(Dims dm, DevTables t, int l
 }
 
 // ---------------------------------------------------------------------------------------
-// MFMA decode attention.  Lane (n = lane % 16, c = lane / 16).
+// MFMA decode attention.  Workgroup (split, unit) of NW waves; wave w takes the 128-key chunks
+// w, w+NW, ... of the split's key range.  Lane (n = lane % 16, c = lane / 16).
 //   scores^T tile (16 keys x 16 heads) = K'(16 keys x 128) * q^T: A = key n, elements 8c..8c+7 of
 //   each 32-element slice; B = head n, same elements; the result leaves lane (n = head, c) with
 //   keys 4c..4c+3 of the tile.  Two tiles cover a 32-token block, so that lane holds 8
 //   probabilities of head n: exactly the A operand of P*V for the block when the block's tokens
 //   are stored in v_slot order.  B of P*V = 16 bytes of the transposed V' block per lane, and the
 //   accumulator of output tile j keeps heads 4c..4c+3 of column 16j + n.
+// The waves of a workgroup merge through LDS.  With more than one split per unit the
+// workgroups exchange partials through memory and the one that finishes last merges them.
 // ---------------------------------------------------------------------------------------
-__global__ __launch_bounds__(64) void decode_mfma_kernel(Dims dm, DevTables t, int l0, int lbase, LaunchLayers ll,
-                                                         const bf16_t *q_new, int splits) {
+template <int NW>
+__global__ __launch_bounds__(64 * NW) void decode_mfma_kernel(Dims dm, DevTables t, int l0, int lbase,
+                                                              LaunchLayers ll, const bf16_t *q_new,
+                                                              const bf16_t *k_new, const bf16_t *v_new, bf16_t *out,
+                                                              int splits) {
     constexpr int D = 128;
-    constexpr int kIter = 128;  // keys per loop iteration
-    const int lane = threadIdx.x, n = lane & 15, c = lane >> 4;
+    constexpr int kIter = 128;  // keys per loop iteration of one wave
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, n = lane & 15, c = lane >> 4;
     const int split = blockIdx.x;
     const int u = blockIdx.y;
     const int kvh = u % dm.Hkv;
@@ -87,12 +97,15 @@ __global__ __launch_bounds__(64) void decode_mfma_kernel(Dims dm, DevTables t, i
     const int l = l0 + li;
     const int G = dm.G;
     const int len = t.base_len[(int64_t)b * dm.L + l] + ll.appended[li] + 1;
+    const int newrow = len - 1;  // the token appended by this call (Eq.2): read from k_new / v_new, stored to the cache
     int k0, k1;
     split_range(len, splits, split, k0, k1);
     const int64_t row0 = ((int64_t)b * dm.Hkv + kvh) * dm.pool_rows + t.layer_off[(int64_t)b * dm.L + l];
-    const bf16_t *kc = (const bf16_t *)t.kcache + row0 * D;
-    const bf16_t *vc = (const bf16_t *)t.vcache + row0 * D;
+    bf16_t *kc = (bf16_t *)t.kcache + row0 * D;
+    bf16_t *vc = (bf16_t *)t.vcache + row0 * D;
     const int64_t unit = ((int64_t)l * dm.B + b) * dm.Hkv + kvh;
+    const int64_t new_src = (((int64_t)(lbase + li) * dm.B + b) * dm.Hkv + kvh) * D;
+    bf16_t *o_unit = out + (((int64_t)(lbase + li) * dm.B + b) * dm.Hq + (int64_t)kvh * G) * D;
 
     bf16x8 qb[4];
     {
@@ -110,18 +123,24 @@ __global__ __launch_bounds__(64) void decode_mfma_kernel(Dims dm, DevTables t, i
 #pragma unroll
     for (int j = 0; j < 8; ++j) acc[j] = (f32x4){0.f, 0.f, 0.f, 0.f};
 
-    for (int kb = k0; kb < k1; kb += kIter) {
+    for (int kb = k0 + wave * kIter; kb < k1; kb += NW * kIter) {
         // ---- scores^T for 8 tiles of 16 keys
         f32x4 s[8];
 #pragma unroll
         for (int tile = 0; tile < 8; ++tile) {
             const int key = kb + 16 * tile + n;
             s[tile] = (f32x4){0.f, 0.f, 0.f, 0.f};
+            const bool is_new = key == newrow && key < k1;  // only the split that owns the row
+            const bf16_t *src = is_new ? k_new + new_src : kc + (int64_t)key * D;
             uint4 a[4];
 #pragma unroll
             for (int sl = 0; sl < 4; ++sl) {
                 a[sl] = make_uint4(0, 0, 0, 0);
-                if (key < k1) a[sl] = *reinterpret_cast<const uint4 *>(kc + (int64_t)key * D + 32 * sl + 8 * c);
+                if (key < k1) a[sl] = *reinterpret_cast<const uint4 *>(src + 32 * sl + 8 * c);
+            }
+            if (is_new) {
+#pragma unroll
+                for (int sl = 0; sl < 4; ++sl) *reinterpret_cast<uint4 *>(kc + (int64_t)key * D + 32 * sl + 8 * c) = a[sl];
             }
 #pragma unroll
             for (int sl = 0; sl < 4; ++sl)
@@ -137,6 +156,27 @@ __global__ __launch_bounds__(64) void decode_mfma_kernel(Dims dm, DevTables t, i
                 vb[tb][j] = make_uint4(0, 0, 0, 0);
                 if (blk0 < k1)
                     vb[tb][j] = *reinterpret_cast<const uint4 *>(vc + (int64_t)blk0 * D + (16 * j + n) * 32 + 8 * c);
+            }
+            if (blk0 < k1 && blk0 <= newrow && newrow < blk0 + 32) {
+                // the block that receives the new token: put v_new into its slot; a token that opens a
+                // block also clears the block's other slots.  The patched operands go back to the cache.
+                const int tok = newrow - blk0, slot = v_slot(tok);
+                const bool fresh = tok == 0, mine = c == (slot >> 3);
+#pragma unroll
+                for (int j = 0; j < 8; ++j) {
+                    uint4 x = fresh ? make_uint4(0, 0, 0, 0) : vb[tb][j];
+                    if (mine) {
+                        const uint32_t val = v_new[new_src + 16 * j + n];
+                        uint32_t w[4] = {x.x, x.y, x.z, x.w};
+                        const int e = slot & 7;
+#pragma unroll
+                        for (int q4 = 0; q4 < 4; ++q4)
+                            if ((e >> 1) == q4) w[q4] = (e & 1) ? ((w[q4] & 0x0000ffffu) | (val << 16)) : ((w[q4] & 0xffff0000u) | val);
+                        x = make_uint4(w[0], w[1], w[2], w[3]);
+                    }
+                    vb[tb][j] = x;
+                    if (fresh || mine) *reinterpret_cast<uint4 *>(vc + (int64_t)blk0 * D + (16 * j + n) * 32 + 8 * c) = x;
+                }
             }
         }
         // ---- online softmax for head n over the keys this lane holds (4c+i of each tile)
@@ -188,18 +228,166 @@ __global__ __launch_bounds__(64) void decode_mfma_kernel(Dims dm, DevTables t, i
                 acc[j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(pa, __builtin_bit_cast(bf16x8, vb[tb][j]), acc[j], 0, 0, 0);
         }
     }
-    // ---- partial of this split
+
+    // ---- merge the NW waves of the workgroup through LDS: wave w ends up with output tiles
+    // w, w+NW, ... (heads 4c..4c+3, column 16j+n) summed over all waves, plus the merged (max, sum)
+    __shared__ f32x4 s_acc[NW][8][64];
+    __shared__ float s_mw[NW][kMaxGroup], s_lw[NW][kMaxGroup];
+    __shared__ int s_prev;
+    float mrg_m[4], mrg_l[4];  // merged max / sum of heads 4c+i
+    if (NW > 1) {
+#pragma unroll
+        for (int j = 0; j < 8; ++j) s_acc[wave][j][lane] = acc[j];
+        if (c == 0) {
+            s_mw[wave][n] = m_run;
+            s_lw[wave][n] = l_run;
+        }
+        __syncthreads();
+        float wgt[NW][4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int g = 4 * c + i;
+            float M = -INFINITY;
+#pragma unroll
+            for (int w = 0; w < NW; ++w) M = fmaxf(M, s_mw[w][g]);
+            float Lsum = 0.f;
+#pragma unroll
+            for (int w = 0; w < NW; ++w) {
+                const float lw = s_lw[w][g];
+                wgt[w][i] = lw > 0.f ? __expf(s_mw[w][g] - M) : 0.f;
+                Lsum = fmaf(wgt[w][i], lw, Lsum);
+            }
+            mrg_m[i] = M;
+            mrg_l[i] = Lsum;
+        }
+#pragma unroll
+        for (int jj = 0; jj < 8 / NW; ++jj) {
+            const int j = wave + NW * jj;
+            f32x4 sum = (f32x4){0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int w = 0; w < NW; ++w) {
+                const f32x4 x = s_acc[w][j][lane];
+#pragma unroll
+                for (int i = 0; i < 4; ++i) sum[i] = fmaf(wgt[w][i], x[i], sum[i]);
+            }
+            acc[jj] = sum;  // tile wave + NW*jj
+        }
+    } else {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            mrg_m[i] = __shfl(m_run, 4 * c + i, 64);
+            mrg_l[i] = __shfl(l_run, 4 * c + i, 64);
+        }
+    }
+    constexpr int kTiles = 8 / NW;  // output tiles this wave owns after the merge: j = wave + NW*jj
+
+    if (splits == 1) {  // no partials: normalise and store
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int g = 4 * c + i;
+            if (g < G) {
+                const float inv = 1.0f / mrg_l[i];
+#pragma unroll
+                for (int jj = 0; jj < kTiles; ++jj)
+                    o_unit[g * D + 16 * (wave + NW * jj) + n] = float_to_bf16_bits(acc[jj][i] * inv);
+            }
+        }
+        return;
+    }
+    // ---- partial of this split.  Partials are exchanged between workgroups of one launch, which
+    // may run on different XCDs (separate L2s).  They are written and read with system-scope
+    // (write-through / L2-bypassing) 16-byte accesses in the accumulators' own lane layout, the
+    // writers wait for their stores to complete before the workgroup counts itself, and the
+    // workgroup that counts last reads them.  This keeps the exchange off the whole-L2 write-back
+    // that a release fence would cost.  Layout of one partial: [tile j][lane][4] floats.
     const int64_t part = unit * kMaxSplits + split;
-    float *po = t.dec_o + part * (int64_t)G * D;
+    float *pu = t.dec_o + unit * kMaxSplits * (int64_t)kMaxGroup * D;
+    const __amdgpu_buffer_rsrc_t prs = __builtin_amdgcn_make_buffer_rsrc(pu, 0, kMaxSplits * kMaxGroup * D * 4, 0x00020000);
+    if (4 * c < G) {
+#pragma unroll
+        for (int jj = 0; jj < kTiles; ++jj)
+            __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4, acc[jj]), prs,
+                                                   (split * kMaxGroup * D + ((wave + NW * jj) * 64 + lane) * 4) * 4, 0,
+                                                   kSysScope);
+    }
+    if (wave == 0 && n == 0) {  // lane (0, c) holds the merged stats of heads 4c..4c+3
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int g = 4 * c + i;
+            if (g < G) {
+                float *mlp = reinterpret_cast<float *>(t.dec_ml + part * G + g);
+                __hip_atomic_store(mlp, mrg_m[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                __hip_atomic_store(mlp + 1, mrg_l[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            }
+        }
+    }
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();
+    if (threadIdx.x == 0) s_prev = __hip_atomic_fetch_add(&t.dec_cnt[unit], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    __syncthreads();
+    if (s_prev != splits - 1) return;
+    if (threadIdx.x == 0) __hip_atomic_store(&t.dec_cnt[unit], 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);  // next launch
+
+    // merge of the splits: every wave loads the partial tiles it owns (one round of loads), the
+    // (max, sum) pairs go through LDS
+    __shared__ float s_m[kMaxSplits][kMaxGroup], s_l[kMaxSplits][kMaxGroup], s_w[kMaxSplits][kMaxGroup];
+    __shared__ float s_inv[kMaxGroup];
+    const float *ml = reinterpret_cast<const float *>(t.dec_ml + unit * kMaxSplits * G);
+    f32x4 num[kTiles];
+#pragma unroll
+    for (int jj = 0; jj < kTiles; ++jj) num[jj] = (f32x4){0.f, 0.f, 0.f, 0.f};
+    for (int p = threadIdx.x; p < splits * G; p += 64 * NW) {
+        s_m[p / G][p % G] = __hip_atomic_load(ml + 2 * p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        s_l[p / G][p % G] = __hip_atomic_load(ml + 2 * p + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+    __syncthreads();
+    if (threadIdx.x < G) {
+        const int g = threadIdx.x;
+        float M = -INFINITY;
+        for (int s2 = 0; s2 < splits; ++s2) M = fmaxf(M, s_m[s2][g]);
+        float den = 0.f;
+        for (int s2 = 0; s2 < splits; ++s2) {
+            const float wg = s_l[s2][g] > 0.f ? __expf(s_m[s2][g] - M) : 0.f;
+            s_w[s2][g] = wg;
+            den = fmaf(wg, s_l[s2][g], den);
+        }
+        s_inv[g] = 1.0f / den;
+    }
+    __syncthreads();
+    constexpr int kRound = (32 / kTiles) < kMaxSplits ? (32 / kTiles) : kMaxSplits;  // splits loaded together
+    for (int s0 = 0; s0 < splits; s0 += kRound) {
+        f32x4 v[kRound][kTiles];
+#pragma unroll
+        for (int s2 = 0; s2 < kRound; ++s2)
+#pragma unroll
+            for (int jj = 0; jj < kTiles; ++jj) {
+                v[s2][jj] = (f32x4){0.f, 0.f, 0.f, 0.f};
+                if (s0 + s2 < splits && 4 * c < G)
+                    v[s2][jj] = __builtin_bit_cast(f32x4, __builtin_amdgcn_raw_buffer_load_b128(
+                        prs, ((s0 + s2) * kMaxGroup * D + ((wave + NW * jj) * 64 + lane) * 4) * 4, 0, kSysScope));
+            }
+#pragma unroll
+        for (int s2 = 0; s2 < kRound; ++s2) {
+            if (s0 + s2 < splits) {
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    const float wg = s_w[s0 + s2][(4 * c + i) & (kMaxGroup - 1)];
+#pragma unroll
+                    for (int jj = 0; jj < kTiles; ++jj) num[jj][i] = fmaf(wg, v[s2][jj][i], num[jj][i]);
+                }
+            }
+        }
+    }
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
         const int g = 4 * c + i;
         if (g < G) {
+            const float inv = s_inv[g];
 #pragma unroll
-            for (int j = 0; j < 8; ++j) po[g * D + 16 * j + n] = acc[j][i];
+            for (int jj = 0; jj < kTiles; ++jj)
+                o_unit[g * D + 16 * (wave + NW * jj) + n] = float_to_bf16_bits(num[jj][i] * inv);
         }
     }
-    if (c == 0 && n < G) t.dec_ml[part * G + n] = make_float2(m_run, l_run);
 }
 
 // ---------------------------------------------------------------------------------------
@@ -343,7 +531,7 @@ static hipError_t append_launch(hipStream_t s, const Dims &dm, const DevTables &
     return hipGetLastError();
 }
 
-hipError_t launch_append(hipStream_t s, const Dims &dm, const DevTables &t, int dtype, int l0, int nl, int lbase,
+static hipError_t launch_append(hipStream_t s, const Dims &dm, const DevTables &t, int dtype, int l0, int nl, int lbase,
                          const LaunchLayers &ll, const void *k_new, const void *v_new) {
     if (dtype == AIR_BF16)
         return dm.D == 128 ? append_launch<bf16_t, 128, true>(s, dm, t, l0, nl, lbase, ll, k_new, v_new)
@@ -354,27 +542,41 @@ hipError_t launch_append(hipStream_t s, const Dims &dm, const DevTables &t, int 
 
 template <typename T, int D>
 static hipError_t decode_launch(hipStream_t s, const Dims &dm, const DevTables &t, int l0, int nl, int lbase,
-                                const LaunchLayers &ll, const void *q_new, void *out, int splits, bool mfma) {
+                                const LaunchLayers &ll, const void *q_new, void *out, int splits) {
     const int units = nl * dm.B * dm.Hkv;
-    if (mfma)
-        hipLaunchKernelGGL(decode_mfma_kernel, dim3(splits, units), dim3(64), 0, s, dm, t, l0, lbase, ll,
-                           (const bf16_t *)q_new, splits);
-    else
-        hipLaunchKernelGGL((decode_kernel<T, D>), dim3(splits, units), dim3(256), 0, s, dm, t, l0, lbase, ll,
-                           (const T *)q_new, splits);
+    hipLaunchKernelGGL((decode_kernel<T, D>), dim3(splits, units), dim3(256), 0, s, dm, t, l0, lbase, ll,
+                       (const T *)q_new, splits);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     hipLaunchKernelGGL((combine_kernel<T, D>), dim3(units), dim3(256), 0, s, dm, t, l0, lbase, (T *)out, splits);
     return hipGetLastError();
 }
 
+// Generic path: append, split-K attention, combine (three launches).
 hipError_t launch_decode(hipStream_t s, const Dims &dm, const DevTables &t, int dtype, int l0, int nl, int lbase,
-                         const LaunchLayers &ll, const void *q_new, void *out, int splits) {
-    if (dtype == AIR_BF16)
-        return dm.D == 128 ? decode_launch<bf16_t, 128>(s, dm, t, l0, nl, lbase, ll, q_new, out, splits, true)
-                           : decode_launch<bf16_t, 64>(s, dm, t, l0, nl, lbase, ll, q_new, out, splits, false);
-    return dm.D == 128 ? decode_launch<float, 128>(s, dm, t, l0, nl, lbase, ll, q_new, out, splits, false)
-                       : decode_launch<float, 64>(s, dm, t, l0, nl, lbase, ll, q_new, out, splits, false);
+                         const LaunchLayers &ll, const void *q_new, const void *k_new, const void *v_new, void *out,
+                         int splits, int waves) {
+    if (v_transposed(dtype, dm.D)) {  // one launch: append, attention and merge of the partials
+        const dim3 grid(splits, nl * dm.B * dm.Hkv);
+        if (waves == 8)
+            hipLaunchKernelGGL(decode_mfma_kernel<8>, grid, dim3(512), 0, s, dm, t, l0, lbase, ll, (const bf16_t *)q_new,
+                               (const bf16_t *)k_new, (const bf16_t *)v_new, (bf16_t *)out, splits);
+        else if (waves == 4)
+            hipLaunchKernelGGL(decode_mfma_kernel<4>, grid, dim3(256), 0, s, dm, t, l0, lbase, ll, (const bf16_t *)q_new,
+                               (const bf16_t *)k_new, (const bf16_t *)v_new, (bf16_t *)out, splits);
+        else if (waves == 2)
+            hipLaunchKernelGGL(decode_mfma_kernel<2>, grid, dim3(128), 0, s, dm, t, l0, lbase, ll, (const bf16_t *)q_new,
+                               (const bf16_t *)k_new, (const bf16_t *)v_new, (bf16_t *)out, splits);
+        else
+            hipLaunchKernelGGL(decode_mfma_kernel<1>, grid, dim3(64), 0, s, dm, t, l0, lbase, ll, (const bf16_t *)q_new,
+                               (const bf16_t *)k_new, (const bf16_t *)v_new, (bf16_t *)out, splits);
+        return hipGetLastError();
+    }
+    hipError_t e = launch_append(s, dm, t, dtype, l0, nl, lbase, ll, k_new, v_new);
+    if (e != hipSuccess) return e;
+    if (dtype == AIR_BF16) return decode_launch<bf16_t, 64>(s, dm, t, l0, nl, lbase, ll, q_new, out, splits);
+    return dm.D == 128 ? decode_launch<float, 128>(s, dm, t, l0, nl, lbase, ll, q_new, out, splits)
+                       : decode_launch<float, 64>(s, dm, t, l0, nl, lbase, ll, q_new, out, splits);
 }
 
 }  // namespace air

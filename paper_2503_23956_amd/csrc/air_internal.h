@@ -33,7 +33,7 @@ struct SeqArgs {
 // Byte offsets of every table inside the workspace.
 struct WsLayout {
     size_t seq_tab, elite_cnt, elite_idx, row_mtext, row_ztext, row_M, row_w, part, scores;
-    size_t unit_st, unit_sk, s_t, s_k, budgets, base_len, layer_off, indices;
+    size_t unit_st, unit_sk, s_t, s_k, budgets, base_len, layer_off, dec_cnt, indices;
     size_t kcache, vcache, dec_o, dec_ml;
     size_t total;
     int32_t n_chunks;     // ceil(max_vis_len / kChunkKeys)
@@ -54,7 +54,7 @@ struct DevTables {
     float2 *part;
     float *scores;
     double *unit_st, *unit_sk, *s_t, *s_k;
-    int32_t *budgets, *base_len, *layer_off, *indices;
+    int32_t *budgets, *base_len, *layer_off, *dec_cnt, *indices;
     void *kcache, *vcache;
     float *dec_o;
     float2 *dec_ml;
@@ -76,10 +76,9 @@ hipError_t launch_budget(hipStream_t s, const Dims &dm, const DevTables &t, doub
 hipError_t launch_select(hipStream_t s, const Dims &dm, const DevTables &t, int l0, int nl);
 hipError_t launch_gather(hipStream_t s, const Dims &dm, const DevTables &t, int dtype, int l0, int nl,
                          const LaunchLayers &ll, const air_strides &st);
-hipError_t launch_append(hipStream_t s, const Dims &dm, const DevTables &t, int dtype, int l0, int nl, int lbase,
-                         const LaunchLayers &ll, const void *k_new, const void *v_new);
 hipError_t launch_decode(hipStream_t s, const Dims &dm, const DevTables &t, int dtype, int l0, int nl, int lbase,
-                         const LaunchLayers &ll, const void *q_new, void *out, int splits);
+                         const LaunchLayers &ll, const void *q_new, const void *k_new, const void *v_new, void *out,
+                         int splits, int waves);
 
 // The bf16 / head_dim 128 cache keeps V' transposed in blocks of 32 tokens so that the decode
 // kernel can feed it to MFMA straight from global memory: block [128 columns][32 slots], and
