@@ -15,6 +15,7 @@ LIB = os.path.join(HERE, "libaircache.so")
 SOURCES = {
     "air_api.hip": [],
     "air_score.hip": [],
+    "air_score_mfma.hip": [],
     "air_budget.hip": ["-ffp-contract=off"],
     "air_select.hip": [],
     "air_decode.hip": [],

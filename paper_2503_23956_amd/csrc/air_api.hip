@@ -71,6 +71,7 @@ WsLayout make_layout(const air_config &c) {
     w.base_len = take(B * L * 4);
     w.layer_off = take(B * L * 4);
     w.dec_cnt = take(L * B * Hkv * 4);
+    w.moments = take(L * B * Hkv * (size_t)w.n_chunks * 3 * 8);
     w.indices = take(L * B * Hkv * NV * 4);
     w.kcache = take(B * Hkv * (size_t)w.pool_rows * D * esz);
     w.vcache = take(B * Hkv * (size_t)w.pool_rows * D * esz);
@@ -96,6 +97,7 @@ struct air_ctx {
     std::vector<char> scored, compacted;
     std::vector<int32_t> appended;
     int force_splits, force_waves;  // AIR_DECODE_SPLITS / AIR_DECODE_WAVES, 0 = automatic
+    int score_block_mb;             // bytes of K_v scored per pair of passes (AIR_SCORE_BLOCK_MB)
     std::string err;
 };
 
@@ -157,6 +159,7 @@ air_status air_create(const air_config *cfg, void *workspace, size_t workspace_b
     t.base_len = (int32_t *)(w + lay.base_len);
     t.layer_off = (int32_t *)(w + lay.layer_off);
     t.dec_cnt = (int32_t *)(w + lay.dec_cnt);
+    t.moments = (double *)(w + lay.moments);
     t.indices = (int32_t *)(w + lay.indices);
     t.kcache = (void *)(w + lay.kcache);
     t.vcache = (void *)(w + lay.vcache);
@@ -168,6 +171,11 @@ air_status air_create(const air_config *cfg, void *workspace, size_t workspace_b
     if (const char *e = getenv("AIR_DECODE_SPLITS")) {
         const int v = atoi(e);
         if (v == 1 || v == 2 || v == 4 || v == 8 || v == 16) c->force_splits = v;
+    }
+    c->score_block_mb = 160;
+    if (const char *e = getenv("AIR_SCORE_BLOCK_MB")) {
+        const int v = atoi(e);
+        if (v >= 1 && v <= 65536) c->score_block_mb = v;
     }
     if (const char *e = getenv("AIR_DECODE_WAVES")) {
         const int v = atoi(e);
@@ -259,6 +267,17 @@ air_status air_score(air_ctx *ctx, void *stream, int32_t l0, int32_t l1, const a
     memset(&sa, 0, sizeof(sa));
     memcpy(sa.s, seqs, sizeof(air_seq) * ctx->cfg.batch);
     const int dt = ctx->cfg.dtype;
+    const bool mfma = v_transposed(dt, ctx->cfg.head_dim);  // bf16, head_dim 128
+    int group = kMaxLayersPerLaunch;
+    if (mfma) {
+        double layer_bytes = 0.0;
+        for (int b = 0; b < ctx->cfg.batch; ++b) layer_bytes += (double)seqs[b].vis_len * ctx->cfg.n_kv_heads * 128 * 2;
+        const double block = (double)ctx->score_block_mb * 1048576.0;
+        const int n_groups = (int)ceil(layer_bytes * (l1 - l0) / block);
+        group = (l1 - l0 + (n_groups > 0 ? n_groups : 1) - 1) / (n_groups > 0 ? n_groups : 1);
+        if (group < 1) group = 1;
+        if (group > kMaxLayersPerLaunch) group = kMaxLayersPerLaunch;
+    }
     for (int c0 = l0; c0 < l1; c0 += kMaxLayersPerLaunch) {
         const int nl = (l1 - c0 < kMaxLayersPerLaunch) ? l1 - c0 : kMaxLayersPerLaunch;
         LaunchLayers ll;
@@ -269,10 +288,22 @@ air_status air_score(air_ctx *ctx, void *stream, int32_t l0, int32_t l1, const a
             ll.p[i].v = layers[c0 - l0 + i].v;
         }
         hipError_t e = launch_elite(s, ctx->dm, ctx->tab, dt, c0, nl, ll, *strides, sa, ctx->cfg.alpha);
-        if (e == hipSuccess) e = launch_score_pass1(s, ctx->dm, ctx->tab, dt, c0, nl, ll, *strides);
-        if (e == hipSuccess) e = launch_score_rows(s, ctx->dm, ctx->tab, c0, nl);
-        if (e == hipSuccess) e = launch_score_pass2(s, ctx->dm, ctx->tab, dt, c0, nl, ll, *strides);
-        if (e == hipSuccess) e = launch_stats(s, ctx->dm, ctx->tab, c0, nl);
+        if (e == hipSuccess && !mfma) {
+            e = launch_score_pass1(s, ctx->dm, ctx->tab, dt, c0, nl, ll, *strides);
+            if (e == hipSuccess) e = launch_score_rows(s, ctx->dm, ctx->tab, c0, nl);
+            if (e == hipSuccess) e = launch_score_pass2(s, ctx->dm, ctx->tab, dt, c0, nl, ll, *strides);
+            if (e == hipSuccess) e = launch_stats(s, ctx->dm, ctx->tab, c0, nl);
+        }
+        // MFMA path: the two passes over K_v run back to back on groups of layers whose keys fit
+        // the memory-side cache, so that the second pass rarely goes to HBM
+        for (int g0 = 0; mfma && e == hipSuccess && g0 < nl; g0 += group) {
+            const int gn = (nl - g0 < group) ? nl - g0 : group;
+            LaunchLayers lg;
+            memset(&lg, 0, sizeof(lg));
+            for (int i = 0; i < gn; ++i) lg.p[i] = ll.p[g0 + i];
+            e = launch_score_mfma(s, ctx->dm, ctx->tab, 1, c0 + g0, gn, lg, *strides);
+            if (e == hipSuccess) e = launch_score_mfma(s, ctx->dm, ctx->tab, 2, c0 + g0, gn, lg, *strides);
+        }
         if (e != hipSuccess) return hip_fail(ctx, e, "air_score launch");
     }
     if (!ctx->have_seqs) {
@@ -291,7 +322,7 @@ air_status air_budget(air_ctx *ctx, void *stream) {
     for (int l = 0; l < ctx->cfg.n_layers; ++l)
         if (ctx->compacted[l]) return fail(ctx, AIR_ERR_STATE, "air_budget: layers already compacted");
     hipError_t e = launch_budget((hipStream_t)stream, ctx->dm, ctx->tab, ctx->cfg.retention, ctx->cfg.budget_mode,
-                                 ctx->cfg.min_keep, 0);
+                                 ctx->cfg.min_keep, 0, v_transposed(ctx->cfg.dtype, ctx->cfg.head_dim) ? 1 : 0);
     if (e != hipSuccess) return hip_fail(ctx, e, "air_budget launch");
     ctx->budgets_ready = true;
     return AIR_OK;
@@ -448,7 +479,7 @@ air_status air_set_budgets(air_ctx *ctx, const int32_t *host) {
     hipError_t e = hipDeviceSynchronize();
     if (e == hipSuccess) e = hipMemcpy(ctx->tab.budgets, host, (size_t)ctx->dm.B * L * 4, hipMemcpyHostToDevice);
     if (e == hipSuccess) e = launch_budget(nullptr, ctx->dm, ctx->tab, ctx->cfg.retention, ctx->cfg.budget_mode,
-                                           ctx->cfg.min_keep, 1);
+                                           ctx->cfg.min_keep, 1, 0);
     if (e == hipSuccess) e = hipDeviceSynchronize();
     if (e != hipSuccess) return hip_fail(ctx, e, "air_set_budgets");
     ctx->budgets_ready = true;

@@ -1,136 +1,212 @@
-// air_budget: Eq.11 and the cache-layout tables that follow from the budgets.
+// air_budget: Eq.9-11 across layers and the cache-layout tables that follow from the budgets.
 //
-// One workgroup per sequence; thread 0 runs the allocation serially in fp64 (L is at most a
-// few hundred).  This file is compiled with floating-point contraction off so that every
-// operation rounds once, in the order written: layer shares by left-to-right sums,
-// proportional allocation clamped to [min_keep, N_v] by repeatedly pinning the side with
-// the larger total violation, floor + largest remainder (ties to the lower layer).
+// One workgroup per sequence.  Everything that decides an integer runs in fp64 with every
+// operation rounded once, in a fixed order (this file is compiled with floating-point
+// contraction off): per-layer strength / skewness as the left-to-right mean over KV heads,
+// layer shares by left-to-right sums, proportional allocation clamped to [min_keep, N_v] by
+// repeatedly pinning the side with the larger total violation, floor + largest remainder
+// (ties to the lower layer).  Independent per-layer work is spread over the threads; the
+// order-dependent sums stay serial in thread 0.
 #include "air_device.h"
 #include "air_internal.h"
 
 namespace air {
 
-__global__ __launch_bounds__(64) void budget_kernel(Dims dm, DevTables t, double retention, int mode, int min_keep,
-                                                    int skip_allocation) {
-    if (threadIdx.x != 0) return;
+constexpr int kBT = 256;  // threads; also the largest layer count (AIR_MAX_LAYERS)
+
+__global__ __launch_bounds__(kBT) void budget_kernel(Dims dm, DevTables t, double retention, int mode, int min_keep,
+                                                     int skip_allocation, int use_moments) {
+    const int tid = threadIdx.x;
     const int b = blockIdx.x;
     const int L = dm.L;
     const air_seq sq = t.seq_tab[b];
     const int n_vis = sq.vis_len;
-    __shared__ double w[AIR_MAX_LAYERS], x[AIR_MAX_LAYERS], frac[AIR_MAX_LAYERS];
-    __shared__ int kk[AIR_MAX_LAYERS];
-    __shared__ unsigned char is_free[AIR_MAX_LAYERS];
+    __shared__ double w[kBT], x[kBT], frac[kBT], sh_t[kBT], sh_k[kBT];
+    __shared__ int kk[kBT];
+    __shared__ unsigned char is_free[kBT];
+    __shared__ double s_sum_t, s_sum_k;
+    __shared__ long long s_ktot, s_left;
+    __shared__ int s_tot, s_elig;
+    __shared__ double u_st[AIR_MAX_LAYERS * 16], u_sk[AIR_MAX_LAYERS * 16];  // per (layer, KV head), H_kv <= 16 staged
 
     double *s_t = t.s_t + (int64_t)b * L;
     double *s_k = t.s_k + (int64_t)b * L;
     int32_t *budgets = t.budgets + (int64_t)b * L;
 
+    const bool stage = L * dm.Hkv <= AIR_MAX_LAYERS * 16;  // unit statistics fit the LDS staging arrays
     if (!skip_allocation) {
-        // per-layer strength / skewness: mean over the KV heads, left to right
-        for (int l = 0; l < L; ++l) {
+        if (use_moments) {
+            // Eq.9-10 of every (layer, KV head) from the per-chunk power sums of the importance row
+            const int nch = (n_vis + kChunkKeys - 1) / kChunkKeys;
+            for (int p = tid; p < L * dm.Hkv; p += kBT) {
+                const int l = p / dm.Hkv, h = p % dm.Hkv;
+                const int64_t unit = ((int64_t)l * dm.B + b) * dm.Hkv + h;
+                const double *mo = t.moments + unit * dm.n_chunks * 3;
+                double S1 = 0.0, S2 = 0.0, S3 = 0.0;
+                for (int c = 0; c < nch; ++c) {
+                    S1 += mo[3 * c + 0];
+                    S2 += mo[3 * c + 1];
+                    S3 += mo[3 * c + 2];
+                }
+                double sk = 0.0;
+                if (n_vis >= 3) {
+                    const double n = (double)n_vis;
+                    const double mu = S1 / n;
+                    const double c2 = S2 - S1 * mu;                           // sum (x - mu)^2
+                    const double c3 = S3 - 3.0 * mu * S2 + 2.0 * mu * mu * S1;  // sum (x - mu)^3
+                    const double var = c2 / (n - 1.0);
+                    if (var > 0.0) {
+                        const double sigma = sqrt(var);
+                        sk = n / ((n - 1.0) * (n - 2.0)) * (c3 / (sigma * sigma * sigma));
+                    }
+                }
+                t.unit_st[unit] = S1;
+                t.unit_sk[unit] = sk;
+                if (stage) {
+                    u_st[p] = S1;
+                    u_sk[p] = sk;
+                }
+            }
+            __syncthreads();
+        }
+        if (tid < L) {  // mean over the KV heads, left to right
             double a = 0.0, c = 0.0;
             for (int h = 0; h < dm.Hkv; ++h) {
-                const int64_t unit = ((int64_t)l * dm.B + b) * dm.Hkv + h;
-                a += t.unit_st[unit];
-                c += t.unit_sk[unit];
+                const int64_t unit = ((int64_t)tid * dm.B + b) * dm.Hkv + h;
+                const bool lds = use_moments && stage;
+                a += lds ? u_st[tid * dm.Hkv + h] : t.unit_st[unit];
+                c += lds ? u_sk[tid * dm.Hkv + h] : t.unit_sk[unit];
             }
-            s_t[l] = a / (double)dm.Hkv;
-            s_k[l] = c / (double)dm.Hkv;
+            sh_t[tid] = a / (double)dm.Hkv;
+            sh_k[tid] = c / (double)dm.Hkv;
+            s_t[tid] = sh_t[tid];
+            s_k[tid] = sh_k[tid];
         }
-        double sum_t = 0.0, sum_k = 0.0;
-        for (int l = 0; l < L; ++l) {
-            sum_t += s_t[l];
-            sum_k += fmax(s_k[l], 0.0);
+        __syncthreads();
+        const int lo_i = min(min_keep, n_vis);
+        const double lo = (double)lo_i, hi = (double)n_vis;
+        if (tid == 0) {
+            double sum_t = 0.0, sum_k = 0.0;
+            for (int l = 0; l < L; ++l) {
+                sum_t += sh_t[l];
+                sum_k += fmax(sh_k[l], 0.0);
+            }
+            s_sum_t = sum_t;
+            s_sum_k = sum_k;
+            long long k_tot = (long long)floor(retention * (double)n_vis * (double)L + 0.5);
+            const long long k_lo = (long long)L * lo_i, k_hi = (long long)L * n_vis;
+            s_ktot = k_tot < k_lo ? k_lo : (k_tot > k_hi ? k_hi : k_tot);
+            s_tot = 0;
+            s_elig = 0;
         }
-        for (int l = 0; l < L; ++l) {
-            const double a = sum_t > 0.0 ? s_t[l] / sum_t : 1.0 / (double)L;
-            const double c = sum_k > 0.0 ? fmax(s_k[l], 0.0) / sum_k : 1.0 / (double)L;
+        __syncthreads();
+        if (tid < L) {
+            const double a = s_sum_t > 0.0 ? sh_t[tid] / s_sum_t : 1.0 / (double)L;
+            const double c = s_sum_k > 0.0 ? fmax(sh_k[tid], 0.0) / s_sum_k : 1.0 / (double)L;
             double wl;
             if (mode == AIR_BUDGET_UNIFORM) wl = 1.0 / (double)L;
             else if (mode == AIR_BUDGET_STRENGTH) wl = a;
             else if (mode == AIR_BUDGET_SKEW) wl = c;
             else wl = 0.5 * (a + c);
-            w[l] = wl;
+            w[tid] = wl;
+            x[tid] = 0.0;
+            is_free[tid] = 1;
         }
-        const int lo_i = min(min_keep, n_vis);
-        const double lo = (double)lo_i, hi = (double)n_vis;
-        long long k_tot = (long long)floor(retention * (double)n_vis * (double)L + 0.5);
-        const long long k_lo = (long long)L * lo_i, k_hi = (long long)L * n_vis;
-        k_tot = k_tot < k_lo ? k_lo : (k_tot > k_hi ? k_hi : k_tot);
-
-        for (int l = 0; l < L; ++l) {
-            x[l] = 0.0;
-            is_free[l] = 1;
-        }
-        double k_free = (double)k_tot;
-        for (int it = 0; it < L + 1; ++it) {
-            double w_free = 0.0;
-            int n_free = 0;
-            for (int l = 0; l < L; ++l)
-                if (is_free[l]) {
-                    w_free += w[l];
-                    ++n_free;
-                }
-            if (n_free == 0) break;
-            double over = 0.0, under = 0.0;
-            for (int l = 0; l < L; ++l)
-                if (is_free[l]) {
-                    x[l] = w_free > 0.0 ? (w[l] / w_free) * k_free : k_free / (double)n_free;
-                    if (x[l] > hi) over += x[l] - hi;
-                    else if (x[l] < lo) under += lo - x[l];
-                }
-            if (over == 0.0 && under == 0.0) break;
-            const bool pin_hi = over >= under;
-            for (int l = 0; l < L; ++l)
-                if (is_free[l]) {
-                    if (pin_hi && x[l] > hi) {
-                        x[l] = hi;
-                        is_free[l] = 0;
-                        k_free -= hi;
-                    } else if (!pin_hi && x[l] < lo) {
-                        x[l] = lo;
-                        is_free[l] = 0;
-                        k_free -= lo;
+        __syncthreads();
+        if (tid == 0) {
+            double k_free = (double)s_ktot;
+            for (int it = 0; it < L + 1; ++it) {
+                double w_free = 0.0;
+                int n_free = 0;
+                for (int l = 0; l < L; ++l)
+                    if (is_free[l]) {
+                        w_free += w[l];
+                        ++n_free;
                     }
-                }
+                if (n_free == 0) break;
+                double over = 0.0, under = 0.0;
+                for (int l = 0; l < L; ++l)
+                    if (is_free[l]) {
+                        x[l] = w_free > 0.0 ? (w[l] / w_free) * k_free : k_free / (double)n_free;
+                        if (x[l] > hi) over += x[l] - hi;
+                        else if (x[l] < lo) under += lo - x[l];
+                    }
+                if (over == 0.0 && under == 0.0) break;
+                const bool pin_hi = over >= under;
+                for (int l = 0; l < L; ++l)
+                    if (is_free[l]) {
+                        if (pin_hi && x[l] > hi) {
+                            x[l] = hi;
+                            is_free[l] = 0;
+                            k_free -= hi;
+                        } else if (!pin_hi && x[l] < lo) {
+                            x[l] = lo;
+                            is_free[l] = 0;
+                            k_free -= lo;
+                        }
+                    }
+            }
         }
-        long long tot = 0;
-        for (int l = 0; l < L; ++l) {
-            int fl = (int)floor(x[l]);
+        __syncthreads();
+        if (tid < L) {
+            int fl = (int)floor(x[tid]);
             fl = max(lo_i, min(fl, n_vis));
-            kk[l] = fl;
-            frac[l] = x[l] - (double)fl;
-            tot += fl;
+            kk[tid] = fl;
+            frac[tid] = x[tid] - (double)fl;
+            atomicAdd(&s_tot, fl);
+            if (fl < n_vis) atomicAdd(&s_elig, 1);
         }
-        long long left = k_tot - tot;
-        while (left > 0) {
-            int best = -1;
-            for (int l = 0; l < L; ++l)
-                if (kk[l] < n_vis && (best < 0 || frac[l] > frac[best])) best = l;
-            if (best < 0) break;
-            kk[best] += 1;
-            frac[best] = -1.0;
-            --left;
+        __syncthreads();
+        const long long left = s_ktot - (long long)s_tot;
+        if (left > 0 && left <= (long long)s_elig) {
+            // largest remainder: the `left` eligible layers that come first by (fraction descending, layer ascending)
+            int add = 0;
+            if (tid < L && kk[tid] < n_vis) {
+                int rank = 0;
+                for (int j = 0; j < L; ++j)
+                    if (kk[j] < n_vis && (frac[j] > frac[tid] || (frac[j] == frac[tid] && j < tid))) ++rank;
+                add = rank < (int)left ? 1 : 0;
+            }
+            __syncthreads();
+            if (tid < L) kk[tid] += add;
+        } else if (left > 0) {
+            if (tid == 0) {  // more leftovers than eligible layers: hand them out one by one
+                long long rem = left;
+                while (rem > 0) {
+                    int best = -1;
+                    for (int l = 0; l < L; ++l)
+                        if (kk[l] < n_vis && (best < 0 || frac[l] > frac[best])) best = l;
+                    if (best < 0) break;
+                    kk[best] += 1;
+                    frac[best] = -1.0;
+                    --rem;
+                }
+            }
         }
-        for (int l = 0; l < L; ++l) budgets[l] = kk[l];
+        __syncthreads();
+        if (tid < L) budgets[tid] = kk[tid];
+        __syncthreads();
     }
 
     // cache layout: each layer's region holds system + kept + text rows and room for the
     // decode appends, and starts on a multiple of kCacheRowAlign rows
-    const int nonvis = sq.seq_len - sq.vis_len;
-    int off = 0;
-    for (int l = 0; l < L; ++l) {
-        const int len = nonvis + budgets[l];
-        t.base_len[(int64_t)b * L + l] = len;
-        t.layer_off[(int64_t)b * L + l] = off;
-        const int cap = len + dm.max_steps;
-        off += (cap + kCacheRowAlign - 1) / kCacheRowAlign * kCacheRowAlign;
+    if (tid == 0) {
+        const int nonvis = sq.seq_len - sq.vis_len;
+        int off = 0;
+        for (int l = 0; l < L; ++l) {
+            const int len = nonvis + budgets[l];
+            t.base_len[(int64_t)b * L + l] = len;
+            t.layer_off[(int64_t)b * L + l] = off;
+            const int cap = len + dm.max_steps;
+            off += (cap + kCacheRowAlign - 1) / kCacheRowAlign * kCacheRowAlign;
+        }
     }
 }
 
 hipError_t launch_budget(hipStream_t s, const Dims &dm, const DevTables &t, double retention, int mode,
-                         int min_keep, int skip_allocation) {
-    hipLaunchKernelGGL(budget_kernel, dim3(dm.B), dim3(64), 0, s, dm, t, retention, mode, min_keep, skip_allocation);
+                         int min_keep, int skip_allocation, int use_moments) {
+    hipLaunchKernelGGL(budget_kernel, dim3(dm.B), dim3(kBT), 0, s, dm, t, retention, mode, min_keep, skip_allocation,
+                       use_moments);
     return hipGetLastError();
 }
 

@@ -88,4 +88,28 @@ __device__ __forceinline__ double block_sum(double v, double *scratch) {
     return r;
 }
 
+// Exclusive prefix sum of one int per thread over a workgroup of NW waves (thread order).
+// `scratch` holds NW + 1 ints; *total receives the sum.  Contains two barriers.
+template <int NW>
+__device__ __forceinline__ int block_excl_scan(int v, int *scratch, int *total) {
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    int incl = v;
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+        const int y = __shfl_up(incl, o, 64);
+        if (lane >= o) incl += y;
+    }
+    __syncthreads();
+    if (lane == 63) scratch[wave] = incl;
+    __syncthreads();
+    int base = 0, tot = 0;
+#pragma unroll
+    for (int w = 0; w < NW; ++w) {
+        if (w < wave) base += scratch[w];
+        tot += scratch[w];
+    }
+    *total = tot;
+    return base + incl - v;
+}
+
 }  // namespace air

@@ -33,7 +33,7 @@ struct SeqArgs {
 // Byte offsets of every table inside the workspace.
 struct WsLayout {
     size_t seq_tab, elite_cnt, elite_idx, row_mtext, row_ztext, row_M, row_w, part, scores;
-    size_t unit_st, unit_sk, s_t, s_k, budgets, base_len, layer_off, dec_cnt, indices;
+    size_t unit_st, unit_sk, s_t, s_k, budgets, base_len, layer_off, dec_cnt, moments, indices;
     size_t kcache, vcache, dec_o, dec_ml;
     size_t total;
     int32_t n_chunks;     // ceil(max_vis_len / kChunkKeys)
@@ -53,7 +53,7 @@ struct DevTables {
     float *row_mtext, *row_ztext, *row_M, *row_w;
     float2 *part;
     float *scores;
-    double *unit_st, *unit_sk, *s_t, *s_k;
+    double *unit_st, *unit_sk, *s_t, *s_k, *moments;
     int32_t *budgets, *base_len, *layer_off, *dec_cnt, *indices;
     void *kcache, *vcache;
     float *dec_o;
@@ -71,8 +71,10 @@ hipError_t launch_score_rows(hipStream_t s, const Dims &dm, const DevTables &t, 
 hipError_t launch_score_pass2(hipStream_t s, const Dims &dm, const DevTables &t, int dtype, int l0, int nl,
                               const LaunchLayers &ll, const air_strides &st);
 hipError_t launch_stats(hipStream_t s, const Dims &dm, const DevTables &t, int l0, int nl);
+hipError_t launch_score_mfma(hipStream_t s, const Dims &dm, const DevTables &t, int pass, int l0, int nl,
+                             const LaunchLayers &ll, const air_strides &st);
 hipError_t launch_budget(hipStream_t s, const Dims &dm, const DevTables &t, double retention, int mode,
-                         int min_keep, int skip_allocation);
+                         int min_keep, int skip_allocation, int use_moments);
 hipError_t launch_select(hipStream_t s, const Dims &dm, const DevTables &t, int l0, int nl);
 hipError_t launch_gather(hipStream_t s, const Dims &dm, const DevTables &t, int dtype, int l0, int nl,
                          const LaunchLayers &ll, const air_strides &st);

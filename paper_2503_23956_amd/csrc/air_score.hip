@@ -41,7 +41,7 @@ __global__ __launch_bounds__(256) void elite_kernel(Dims dm, DevTables t, int l0
     __shared__ int s_elite[AIR_MAX_TEXT];
     __shared__ double s_q[D];
     __shared__ double s_red[4];
-    __shared__ int s_cnt[257];
+    __shared__ int s_cnt[5];
 
     const int ref = sq.win_start + wl - 1;
     for (int c = tid; c < D; c += 256) s_q[c] = (double)ldf(q + (int64_t)(ref - t0) * st.q_t + c);
@@ -49,9 +49,11 @@ __global__ __launch_bounds__(256) void elite_kernel(Dims dm, DevTables t, int l0
     const double sqrt_d = sqrt((double)D);
     double lmax = -INFINITY;
     for (int j = tid; j < wl; j += 256) {
-        const T *kj = k + (int64_t)(sq.win_start + j) * st.kv_t;
+        float kreg[D];
+        load_row<D>(k + (int64_t)(sq.win_start + j) * st.kv_t, kreg);
         double acc = 0.0;
-        for (int c = 0; c < D; ++c) acc += s_q[c] * (double)ldf(kj + c);
+#pragma unroll
+        for (int c = 0; c < D; ++c) acc += s_q[c] * (double)kreg[c];
         acc = acc / sqrt_d;
         s_logit[j] = acc;
         lmax = fmax(lmax, acc);
@@ -66,19 +68,8 @@ __global__ __launch_bounds__(256) void elite_kernel(Dims dm, DevTables t, int l0
     const int j0 = min(wl, tid * per), j1 = min(wl, j0 + per);
     int cnt = 0;
     for (int j = j0; j < j1; ++j) cnt += (exp(s_logit[j] - smax) >= alpha) ? 1 : 0;
-    s_cnt[tid] = cnt;
-    __syncthreads();
-    if (tid == 0) {
-        int run = 0;
-        for (int i = 0; i < 256; ++i) {
-            int c = s_cnt[i];
-            s_cnt[i] = run;
-            run += c;
-        }
-        s_cnt[256] = run;
-    }
-    __syncthreads();
-    int pos = s_cnt[tid];
+    int R;
+    int pos = block_excl_scan<4>(cnt, s_cnt, &R);
     for (int j = j0; j < j1; ++j) {
         if (exp(s_logit[j] - smax) >= alpha) {
             s_elite[pos] = sq.win_start + j;
@@ -86,31 +77,36 @@ __global__ __launch_bounds__(256) void elite_kernel(Dims dm, DevTables t, int l0
             ++pos;
         }
     }
-    const int R = s_cnt[256];
     if (tid == 0) t.elite_cnt[hrow] = R;
     __syncthreads();
 
-    // elite-text columns of Eq.7: (max, sum-exp) of every elite row over the elite text keys
+    // elite-text columns of Eq.7: (max, sum-exp) of every elite row over the elite text keys.
+    // One wave per row; each (row, key) logit is a 64-lane dot product, computed once for the
+    // maximum and once more for the sum.
     const float scale = 1.0f / sqrtf((float)D);
     const int wave = tid >> 6, lane = tid & 63;
+    constexpr int kPer = D / 64;  // elements per lane
     for (int r = wave; r < R; r += 4) {
         const T *qr = q + (int64_t)(s_elite[r] - t0) * st.q_t;
+        float qv[kPer];
+#pragma unroll
+        for (int e = 0; e < kPer; ++e) qv[e] = ldf(qr + lane * kPer + e);
         float m = -INFINITY;
-        for (int j = lane; j < R; j += 64) {
+        for (int j = 0; j < R; ++j) {
             const T *kj = k + (int64_t)s_elite[j] * st.kv_t;
-            float acc = 0.f;
-            for (int c = 0; c < D; ++c) acc = fmaf(ldf(qr + c), ldf(kj + c), acc);
-            m = fmaxf(m, acc * scale);
+            float a = 0.f;
+#pragma unroll
+            for (int e = 0; e < kPer; ++e) a = fmaf(qv[e], ldf(kj + lane * kPer + e), a);
+            m = fmaxf(m, wave_sum(a) * scale);
         }
-        m = wave_max(m);
         float z = 0.f;
-        for (int j = lane; j < R; j += 64) {
+        for (int j = 0; j < R; ++j) {
             const T *kj = k + (int64_t)s_elite[j] * st.kv_t;
-            float acc = 0.f;
-            for (int c = 0; c < D; ++c) acc = fmaf(ldf(qr + c), ldf(kj + c), acc);
-            z += expf(acc * scale - m);
+            float a = 0.f;
+#pragma unroll
+            for (int e = 0; e < kPer; ++e) a = fmaf(qv[e], ldf(kj + lane * kPer + e), a);
+            z += expf(wave_sum(a) * scale - m);
         }
-        z = wave_sum(z);
         if (lane == 0) {
             t.row_mtext[hrow * W + r] = m;
             t.row_ztext[hrow * W + r] = z;

@@ -11,6 +11,8 @@
 namespace air {
 
 constexpr int kSelThreads = 512;
+constexpr int kSelRegs = 32;                         // scores per thread kept in registers
+constexpr int kSelSpan = kSelThreads * kSelRegs;     // 16384 scores per sweep
 
 __global__ __launch_bounds__(kSelThreads) void select_kernel(Dims dm, DevTables t, int l0) {
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -29,26 +31,43 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(Dims dm, DevTables 
 
     __shared__ uint32_t hist[256];
     __shared__ uint32_t s_prefix, s_kk;
+    __shared__ int s_scan[kSelThreads / 64 + 1];
     __shared__ int s_wgt[kSelThreads / 64], s_weq[kSelThreads / 64];
+
+    // a row of up to kSelSpan scores stays in registers for all passes (element j of thread t is
+    // score t + j * kSelThreads of the sweep); longer rows are re-read sweep by sweep
+    const bool cached = n <= kSelSpan;
+    uint32_t v[kSelRegs];
+    auto load_sweep = [&](int base) {
+#pragma unroll
+        for (int j = 0; j < kSelRegs; ++j) {
+            const int i = base + tid + j * kSelThreads;
+            v[j] = i < n ? key[i] : 0u;
+        }
+    };
+    if (cached) load_sweep(0);
+
     uint32_t prefix = 0, mask = 0, kk = (uint32_t)k;
     for (int pass = 0; pass < 4; ++pass) {
         const int shift = 24 - 8 * pass;
         if (tid < 256) hist[tid] = 0;
         __syncthreads();
-        for (int i = tid; i < n; i += kSelThreads) {
-            const uint32_t v = key[i];
-            if ((v & mask) == prefix) atomicAdd(&hist[(v >> shift) & 255u], 1u);
+        for (int base = 0; base < n; base += kSelSpan) {
+            if (!cached) load_sweep(base);
+#pragma unroll
+            for (int j = 0; j < kSelRegs; ++j) {
+                const int i = base + tid + j * kSelThreads;
+                if (i < n && (v[j] & mask) == prefix) atomicAdd(&hist[(v[j] >> shift) & 255u], 1u);
+            }
         }
         __syncthreads();
-        if (tid == 0) {
-            uint32_t cum = 0;
-            int bin = 255;
-            for (; bin > 0; --bin) {
-                if (cum + hist[bin] >= kk) break;
-                cum += hist[bin];
-            }
-            s_prefix = prefix | ((uint32_t)bin << shift);
-            s_kk = kk - cum;
+        // position p = 255 - bin; the k-th largest lies in the bin whose prefix count first reaches kk
+        const int h = tid < 256 ? (int)hist[255 - tid] : 0;
+        int total;
+        const int excl = block_excl_scan<kSelThreads / 64>(h, s_scan, &total);
+        if (tid < 256 && h > 0 && (uint32_t)excl < kk && kk <= (uint32_t)(excl + h)) {
+            s_prefix = prefix | ((uint32_t)(255 - tid) << shift);
+            s_kk = kk - (uint32_t)excl;
         }
         __syncthreads();
         prefix = s_prefix;
@@ -58,33 +77,38 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(Dims dm, DevTables 
     const uint32_t tau = prefix;  // bit pattern of the k-th largest score; kk of the entries equal to it are kept
 
     int base_gt = 0, base_eq = 0;
-    for (int i0 = 0; i0 < n; i0 += kSelThreads) {
-        const int i = i0 + tid;
-        const uint32_t v = i < n ? key[i] : 0u;
-        const bool gt = i < n && v > tau;
-        const bool eq = i < n && v == tau;
-        const uint64_t bg = __ballot(gt), be = __ballot(eq);
-        const uint64_t below = (1ull << lane) - 1ull;
-        if (lane == 0) {
-            s_wgt[wave] = __popcll(bg);
-            s_weq[wave] = __popcll(be);
-        }
-        __syncthreads();
-        int gt_before = base_gt + __popcll(bg & below), eq_before = base_eq + __popcll(be & below);
-        int tot_gt = 0, tot_eq = 0;
+    for (int base = 0; base < n; base += kSelSpan) {
+        if (!cached) load_sweep(base);
 #pragma unroll
-        for (int w = 0; w < kSelThreads / 64; ++w) {
-            if (w < wave) {
-                gt_before += s_wgt[w];
-                eq_before += s_weq[w];
+        for (int j = 0; j < kSelRegs; ++j) {
+            const int i0 = base + j * kSelThreads;
+            if (i0 >= n) break;  // uniform
+            const int i = i0 + tid;
+            const bool gt = i < n && v[j] > tau;
+            const bool eq = i < n && v[j] == tau;
+            const uint64_t bg = __ballot(gt), be = __ballot(eq);
+            const uint64_t below = (1ull << lane) - 1ull;
+            if (lane == 0) {
+                s_wgt[wave] = __popcll(bg);
+                s_weq[wave] = __popcll(be);
             }
-            tot_gt += s_wgt[w];
-            tot_eq += s_weq[w];
+            __syncthreads();
+            int gt_before = base_gt + __popcll(bg & below), eq_before = base_eq + __popcll(be & below);
+            int tot_gt = 0, tot_eq = 0;
+#pragma unroll
+            for (int w = 0; w < kSelThreads / 64; ++w) {
+                if (w < wave) {
+                    gt_before += s_wgt[w];
+                    eq_before += s_weq[w];
+                }
+                tot_gt += s_wgt[w];
+                tot_eq += s_weq[w];
+            }
+            if (gt || (eq && eq_before < (int)kk)) out[gt_before + min(eq_before, (int)kk)] = i;
+            base_gt += tot_gt;
+            base_eq += tot_eq;
+            __syncthreads();
         }
-        if (gt || (eq && eq_before < (int)kk)) out[gt_before + min(eq_before, (int)kk)] = i;
-        base_gt += tot_gt;
-        base_eq += tot_eq;
-        __syncthreads();
     }
 }
 
