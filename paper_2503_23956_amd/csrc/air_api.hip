@@ -77,6 +77,7 @@ WsLayout make_layout(const air_config &c) {
     w.vcache = take(B * Hkv * (size_t)w.pool_rows * D * esz);
     w.dec_o = take(L * B * Hkv * kMaxSplits * 16 * D * 4);  // per (unit, split): 16 head rows x D
     w.dec_ml = take(L * B * Hq * kMaxSplits * 8);
+    w.stash = v_transposed(c.dtype, c.head_dim) ? take(L * B * Hkv * (size_t)w.n_chunks * kStashRows * kChunkKeys * 4) : off;
     w.total = off;
     return w;
 }
@@ -165,6 +166,7 @@ air_status air_create(const air_config *cfg, void *workspace, size_t workspace_b
     t.vcache = (void *)(w + lay.vcache);
     t.dec_o = (float *)(w + lay.dec_o);
     t.dec_ml = (float2 *)(w + lay.dec_ml);
+    t.stash = (float *)(w + lay.stash);
     c->have_seqs = false;
     c->budgets_ready = false;
     c->force_splits = c->force_waves = 0;
@@ -269,7 +271,9 @@ air_status air_score(air_ctx *ctx, void *stream, int32_t l0, int32_t l1, const a
     const int dt = ctx->cfg.dtype;
     const bool mfma = v_transposed(dt, ctx->cfg.head_dim);  // bf16, head_dim 128
     int group = kMaxLayersPerLaunch;
-    if (mfma) {
+    // Windows that are known to exceed the stash (alpha = 0 turns the whole candidate span into rows)
+    // read K_v twice: run the two kernels over groups of layers whose keys fit the memory-side cache.
+    if (mfma && ctx->cfg.alpha == 0.0 && (int64_t)ctx->dm.G * ctx->cfg.max_window > kStashRows) {
         double layer_bytes = 0.0;
         for (int b = 0; b < ctx->cfg.batch; ++b) layer_bytes += (double)seqs[b].vis_len * ctx->cfg.n_kv_heads * 128 * 2;
         const double block = (double)ctx->score_block_mb * 1048576.0;
@@ -294,8 +298,8 @@ air_status air_score(air_ctx *ctx, void *stream, int32_t l0, int32_t l1, const a
             if (e == hipSuccess) e = launch_score_pass2(s, ctx->dm, ctx->tab, dt, c0, nl, ll, *strides);
             if (e == hipSuccess) e = launch_stats(s, ctx->dm, ctx->tab, c0, nl);
         }
-        // MFMA path: the two passes over K_v run back to back on groups of layers whose keys fit
-        // the memory-side cache, so that the second pass rarely goes to HBM
+        // MFMA path: stream kernel, then finish kernel, per group of layers (one group unless the
+        // window is known to need the second read of K_v)
         for (int g0 = 0; mfma && e == hipSuccess && g0 < nl; g0 += group) {
             const int gn = (nl - g0 < group) ? nl - g0 : group;
             LaunchLayers lg;

@@ -14,6 +14,7 @@ constexpr int kMaxLayersPerLaunch = 32;
 constexpr int kMaxSplits = 16;        // largest split-K factor of the decode attention
 constexpr int kCacheRowAlign = 32;    // layer regions of the compacted cache start on multiples of this
 constexpr int kGatherRows = 32;       // rows copied per workgroup in the compaction gather
+constexpr int kStashRows = 32;        // window rows per unit up to which air_score stashes exponentials (one pass over K_v)
 
 struct LayerPtrs {
     const void *q, *k, *v;
@@ -34,7 +35,7 @@ struct SeqArgs {
 struct WsLayout {
     size_t seq_tab, elite_cnt, elite_idx, row_mtext, row_ztext, row_M, row_w, part, scores;
     size_t unit_st, unit_sk, s_t, s_k, budgets, base_len, layer_off, dec_cnt, moments, indices;
-    size_t kcache, vcache, dec_o, dec_ml;
+    size_t kcache, vcache, dec_o, dec_ml, stash;
     size_t total;
     int32_t n_chunks;     // ceil(max_vis_len / kChunkKeys)
     int64_t pool_rows;    // rows of one (sequence, KV head) cache pool
@@ -56,7 +57,7 @@ struct DevTables {
     double *unit_st, *unit_sk, *s_t, *s_k, *moments;
     int32_t *budgets, *base_len, *layer_off, *dec_cnt, *indices;
     void *kcache, *vcache;
-    float *dec_o;
+    float *dec_o, *stash;
     float2 *dec_ml;
 };
 
