@@ -97,7 +97,7 @@ struct air_ctx {
     std::vector<air_seq> seqs;
     std::vector<char> scored, compacted;
     std::vector<int32_t> appended;
-    int force_splits, force_waves;  // AIR_DECODE_SPLITS / AIR_DECODE_WAVES, 0 = automatic
+    int force_splits, force_waves, force_tiles;  // AIR_DECODE_SPLITS / _WAVES / _TILES, 0 = automatic
     int score_block_mb;             // bytes of K_v scored per pair of passes (AIR_SCORE_BLOCK_MB)
     std::string err;
 };
@@ -169,7 +169,11 @@ air_status air_create(const air_config *cfg, void *workspace, size_t workspace_b
     t.stash = (float *)(w + lay.stash);
     c->have_seqs = false;
     c->budgets_ready = false;
-    c->force_splits = c->force_waves = 0;
+    c->force_splits = c->force_waves = c->force_tiles = 0;
+    if (const char *e = getenv("AIR_DECODE_TILES")) {
+        const int v = atoi(e);
+        if (v == 4 || v == 8) c->force_tiles = v;
+    }
     if (const char *e = getenv("AIR_DECODE_SPLITS")) {
         const int v = atoi(e);
         if (v == 1 || v == 2 || v == 4 || v == 8 || v == 16) c->force_splits = v;
@@ -360,12 +364,13 @@ air_status air_select_compact(air_ctx *ctx, void *stream, int32_t l0, int32_t l1
 }
 
 // Shape of one decode launch: `splits` workgroups of `waves` wavefronts per (layer, sequence, KV
-// head).  A wave works in 128-key iterations, so at the average cache length a unit has
-// ceil(len / 128) wave-iterations.  Up to 8 of them go to the waves of one workgroup (merged
-// through LDS, no exchange through memory); more splits are used only when the units alone
-// cannot fill the chip or a workgroup would loop many times.  AIR_DECODE_SPLITS / AIR_DECODE_WAVES
-// override the choice (tuning aid).
-static void decode_shape(const air_ctx *ctx, int n_layers_in_launch, int appended, int *splits, int *waves) {
+// head); a wave works in iterations of 16 * tiles keys.  Eight waves of 64-key iterations keep
+// every load of an iteration in flight within the 256 registers a lane has at that occupancy.
+// The waves of a workgroup merge through LDS; more than one split per unit (partials exchanged
+// through memory) is used only when the units alone cannot fill the chip or a wave would loop
+// many times.  AIR_DECODE_SPLITS / AIR_DECODE_WAVES / AIR_DECODE_TILES override the choice
+// (tuning aid).
+static void decode_shape(const air_ctx *ctx, int n_layers_in_launch, int appended, int *splits, int *waves, int *tiles) {
     const air_config &c = ctx->cfg;
     const int64_t units = (int64_t)n_layers_in_launch * c.batch * c.n_kv_heads;
     double avg_len = 0.0;
@@ -374,16 +379,18 @@ static void decode_shape(const air_ctx *ctx, int n_layers_in_launch, int appende
         avg_len += (double)(s.seq_len - s.vis_len) + c.retention * (double)s.vis_len + appended + 1;
     }
     avg_len /= c.batch;
-    const int64_t iters = (int64_t)((avg_len + 127.0) / 128.0);
-    int w = 1;
-    while (w < 8 && w < iters) w *= 2;
-    int64_t s = 1;
-    while (s < kMaxSplits && units * s < 256 && iters > (int64_t)w * s) s *= 2;   // fill the chip
-    while (s < kMaxSplits && iters > (int64_t)w * s * 4 && units * s < 2048) s *= 2;  // bound the loop length
-    if (ctx->force_splits > 0) s = ctx->force_splits;
+    int kt = 4, w = 8;
+    if (ctx->force_tiles > 0) kt = ctx->force_tiles;
     if (ctx->force_waves > 0) w = ctx->force_waves;
+    if (kt == 8 && w == 8) w = 4;
+    const int64_t iters = (int64_t)((avg_len + 16.0 * kt - 1.0) / (16.0 * kt));
+    int64_t s = 1;
+    while (s < kMaxSplits && units * s < 256 && iters > (int64_t)w * s) s *= 2;           // fill the chip
+    while (s < kMaxSplits && iters > (int64_t)w * s * 8 && units * s < 2048) s *= 2;  // bound the loop length
+    if (ctx->force_splits > 0) s = ctx->force_splits;
     *splits = (int)s;
     *waves = w;
+    *tiles = kt;
 }
 
 air_status air_decode_attn(air_ctx *ctx, void *stream, int32_t l0, int32_t l1, const void *q_new, const void *k_new,
@@ -404,10 +411,10 @@ air_status air_decode_attn(air_ctx *ctx, void *stream, int32_t l0, int32_t l1, c
         LaunchLayers ll;
         memset(&ll, 0, sizeof(ll));
         for (int i = 0; i < nl; ++i) ll.appended[i] = ctx->appended[c0 + i];
-        int splits = 1, waves = 1;
-        decode_shape(ctx, nl, ctx->appended[c0], &splits, &waves);
+        int splits = 1, waves = 1, tiles = 4;
+        decode_shape(ctx, nl, ctx->appended[c0], &splits, &waves, &tiles);
         hipError_t e = launch_decode(s, ctx->dm, ctx->tab, ctx->cfg.dtype, c0, nl, c0 - l0, ll, q_new, k_new, v_new,
-                                     out, splits, waves);
+                                     out, splits, waves, tiles);
         if (e != hipSuccess) return hip_fail(ctx, e, "air_decode_attn launch");
     }
     for (int l = l0; l < l1; ++l) ctx->appended[l] += 1;

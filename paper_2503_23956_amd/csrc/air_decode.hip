@@ -70,8 +70,8 @@ __global__ __launch_bounds__(128) void append_kernel(Dims dm, DevTables t, int l
 }
 
 // ---------------------------------------------------------------------------------------
-// MFMA decode attention.  Workgroup (split, unit) of NW waves; wave w takes the 128-key chunks
-// w, w+NW, ... of the split's key range.  Lane (n = lane % 16, c = lane / 16).
+// MFMA decode attention.  Workgroup (split, unit) of NW waves; wave w takes the chunks w, w+NW, ...
+// (16*KT keys each) of the split's key range.  Lane (n = lane % 16, c = lane / 16).
 //   scores^T tile (16 keys x 16 heads) = K'(16 keys x 128) * q^T: A = key n, elements 8c..8c+7 of
 //   each 32-element slice; B = head n, same elements; the result leaves lane (n = head, c) with
 //   keys 4c..4c+3 of the tile.  Two tiles cover a 32-token block, so that lane holds 8
@@ -81,13 +81,14 @@ __global__ __launch_bounds__(128) void append_kernel(Dims dm, DevTables t, int l
 // The waves of a workgroup merge through LDS.  With more than one split per unit the
 // workgroups exchange partials through memory and the one that finishes last merges them.
 // ---------------------------------------------------------------------------------------
-template <int NW>
+template <int NW, int KT>
 __global__ __launch_bounds__(64 * NW) void decode_mfma_kernel(Dims dm, DevTables t, int l0, int lbase,
                                                               LaunchLayers ll, const bf16_t *q_new,
                                                               const bf16_t *k_new, const bf16_t *v_new, bf16_t *out,
                                                               int splits) {
     constexpr int D = 128;
-    constexpr int kIter = 128;  // keys per loop iteration of one wave
+    constexpr int kIter = 16 * KT;  // keys per loop iteration of one wave (KT score tiles, KT/2 token blocks)
+    constexpr int TB = KT / 2;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, n = lane & 15, c = lane >> 4;
     const int split = blockIdx.x;
     const int u = blockIdx.y;
@@ -124,32 +125,22 @@ __global__ __launch_bounds__(64 * NW) void decode_mfma_kernel(Dims dm, DevTables
     for (int j = 0; j < 8; ++j) acc[j] = (f32x4){0.f, 0.f, 0.f, 0.f};
 
     for (int kb = k0 + wave * kIter; kb < k1; kb += NW * kIter) {
-        // ---- scores^T for 8 tiles of 16 keys
-        f32x4 s[8];
+        // ---- all loads of the iteration go out first: K' rows of the KT score tiles ...
+        uint4 a[KT][4];
 #pragma unroll
-        for (int tile = 0; tile < 8; ++tile) {
+        for (int tile = 0; tile < KT; ++tile) {
             const int key = kb + 16 * tile + n;
-            s[tile] = (f32x4){0.f, 0.f, 0.f, 0.f};
-            const bool is_new = key == newrow && key < k1;  // only the split that owns the row
-            const bf16_t *src = is_new ? k_new + new_src : kc + (int64_t)key * D;
-            uint4 a[4];
+            const bf16_t *src = (key == newrow) ? k_new + new_src : kc + (int64_t)key * D;
 #pragma unroll
             for (int sl = 0; sl < 4; ++sl) {
-                a[sl] = make_uint4(0, 0, 0, 0);
-                if (key < k1) a[sl] = *reinterpret_cast<const uint4 *>(src + 32 * sl + 8 * c);
+                a[tile][sl] = make_uint4(0, 0, 0, 0);
+                if (key < k1) a[tile][sl] = *reinterpret_cast<const uint4 *>(src + 32 * sl + 8 * c);
             }
-            if (is_new) {
-#pragma unroll
-                for (int sl = 0; sl < 4; ++sl) *reinterpret_cast<uint4 *>(kc + (int64_t)key * D + 32 * sl + 8 * c) = a[sl];
-            }
-#pragma unroll
-            for (int sl = 0; sl < 4; ++sl)
-                s[tile] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a[sl]), qb[sl], s[tile], 0, 0, 0);
         }
-        // ---- V' operands of the 4 token blocks (issued before the softmax arithmetic)
-        uint4 vb[4][8];
+        // ... and the V' operands of the TB token blocks
+        uint4 vb[TB][8];
 #pragma unroll
-        for (int tb = 0; tb < 4; ++tb) {
+        for (int tb = 0; tb < TB; ++tb) {
             const int blk0 = kb + 32 * tb;
 #pragma unroll
             for (int j = 0; j < 8; ++j) {
@@ -157,11 +148,26 @@ __global__ __launch_bounds__(64 * NW) void decode_mfma_kernel(Dims dm, DevTables
                 if (blk0 < k1)
                     vb[tb][j] = *reinterpret_cast<const uint4 *>(vc + (int64_t)blk0 * D + (16 * j + n) * 32 + 8 * c);
             }
-            if (blk0 < k1 && blk0 <= newrow && newrow < blk0 + 32) {
-                // the block that receives the new token: put v_new into its slot; a token that opens a
-                // block also clears the block's other slots.  The patched operands go back to the cache.
-                const int tok = newrow - blk0, slot = v_slot(tok);
-                const bool fresh = tok == 0, mine = c == (slot >> 3);
+        }
+        // ---- scores^T
+        f32x4 s[KT];
+#pragma unroll
+        for (int tile = 0; tile < KT; ++tile) {
+            s[tile] = (f32x4){0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int sl = 0; sl < 4; ++sl)
+                s[tile] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a[tile][sl]), qb[sl], s[tile], 0, 0, 0);
+        }
+        // ---- the block that receives the new token (only in the split that owns the row): put v_new
+        // into its slot; a token that opens a block also clears the block's other slots.  The patched
+        // operands go back to the cache, and so does the new K' row.
+        if (kb <= newrow && newrow < kb + kIter && newrow < k1) {
+            const int tbn = (newrow - kb) >> 5;
+            const int tok = (newrow - kb) & 31, slot = v_slot(tok);
+            const bool fresh = tok == 0, mine = c == (slot >> 3);
+#pragma unroll
+            for (int tb = 0; tb < TB; ++tb) {
+                if (tb != tbn) continue;
 #pragma unroll
                 for (int j = 0; j < 8; ++j) {
                     uint4 x = fresh ? make_uint4(0, 0, 0, 0) : vb[tb][j];
@@ -175,14 +181,18 @@ __global__ __launch_bounds__(64 * NW) void decode_mfma_kernel(Dims dm, DevTables
                         x = make_uint4(w[0], w[1], w[2], w[3]);
                     }
                     vb[tb][j] = x;
-                    if (fresh || mine) *reinterpret_cast<uint4 *>(vc + (int64_t)blk0 * D + (16 * j + n) * 32 + 8 * c) = x;
+                    if (fresh || mine)
+                        *reinterpret_cast<uint4 *>(vc + (int64_t)(kb + 32 * tb) * D + (16 * j + n) * 32 + 8 * c) = x;
                 }
             }
+            if (lane < 16)  // the new K' row: 16 lanes x 16 bytes
+                *reinterpret_cast<uint4 *>(kc + (int64_t)newrow * D + 8 * lane) =
+                    *reinterpret_cast<const uint4 *>(k_new + new_src + 8 * lane);
         }
         // ---- online softmax for head n over the keys this lane holds (4c+i of each tile)
         float mb = -INFINITY;
 #pragma unroll
-        for (int tile = 0; tile < 8; ++tile)
+        for (int tile = 0; tile < KT; ++tile)
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
                 const int key = kb + 16 * tile + 4 * c + i;
@@ -196,7 +206,7 @@ __global__ __launch_bounds__(64 * NW) void decode_mfma_kernel(Dims dm, DevTables
         const float corr = __expf(m_run - m_new);
         float lb = 0.f;
 #pragma unroll
-        for (int tile = 0; tile < 8; ++tile)
+        for (int tile = 0; tile < KT; ++tile)
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
                 const float p = __expf(s[tile][i] - m_new);
@@ -216,7 +226,7 @@ __global__ __launch_bounds__(64 * NW) void decode_mfma_kernel(Dims dm, DevTables
         }
         // ---- P * V
 #pragma unroll
-        for (int tb = 0; tb < 4; ++tb) {
+        for (int tb = 0; tb < TB; ++tb) {
             bf16x8 pa;
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
@@ -555,21 +565,20 @@ static hipError_t decode_launch(hipStream_t s, const Dims &dm, const DevTables &
 // Generic path: append, split-K attention, combine (three launches).
 hipError_t launch_decode(hipStream_t s, const Dims &dm, const DevTables &t, int dtype, int l0, int nl, int lbase,
                          const LaunchLayers &ll, const void *q_new, const void *k_new, const void *v_new, void *out,
-                         int splits, int waves) {
+                         int splits, int waves, int tiles) {
     if (v_transposed(dtype, dm.D)) {  // one launch: append, attention and merge of the partials
         const dim3 grid(splits, nl * dm.B * dm.Hkv);
-        if (waves == 8)
-            hipLaunchKernelGGL(decode_mfma_kernel<8>, grid, dim3(512), 0, s, dm, t, l0, lbase, ll, (const bf16_t *)q_new,
-                               (const bf16_t *)k_new, (const bf16_t *)v_new, (bf16_t *)out, splits);
-        else if (waves == 4)
-            hipLaunchKernelGGL(decode_mfma_kernel<4>, grid, dim3(256), 0, s, dm, t, l0, lbase, ll, (const bf16_t *)q_new,
-                               (const bf16_t *)k_new, (const bf16_t *)v_new, (bf16_t *)out, splits);
-        else if (waves == 2)
-            hipLaunchKernelGGL(decode_mfma_kernel<2>, grid, dim3(128), 0, s, dm, t, l0, lbase, ll, (const bf16_t *)q_new,
-                               (const bf16_t *)k_new, (const bf16_t *)v_new, (bf16_t *)out, splits);
-        else
-            hipLaunchKernelGGL(decode_mfma_kernel<1>, grid, dim3(64), 0, s, dm, t, l0, lbase, ll, (const bf16_t *)q_new,
-                               (const bf16_t *)k_new, (const bf16_t *)v_new, (bf16_t *)out, splits);
+#define AIR_LAUNCH_DECODE(NW, KT)                                                                                  \
+    hipLaunchKernelGGL((decode_mfma_kernel<NW, KT>), grid, dim3(64 * NW), 0, s, dm, t, l0, lbase, ll,              \
+                       (const bf16_t *)q_new, (const bf16_t *)k_new, (const bf16_t *)v_new, (bf16_t *)out, splits)
+        if (waves == 8 && tiles == 4) AIR_LAUNCH_DECODE(8, 4);
+        else if (waves == 4 && tiles == 4) AIR_LAUNCH_DECODE(4, 4);
+        else if (waves == 2 && tiles == 4) AIR_LAUNCH_DECODE(2, 4);
+        else if (waves == 1 && tiles == 4) AIR_LAUNCH_DECODE(1, 4);
+        else if (waves == 4) AIR_LAUNCH_DECODE(4, 8);
+        else if (waves == 2) AIR_LAUNCH_DECODE(2, 8);
+        else AIR_LAUNCH_DECODE(1, 8);
+#undef AIR_LAUNCH_DECODE
         return hipGetLastError();
     }
     hipError_t e = launch_append(s, dm, t, dtype, l0, nl, lbase, ll, k_new, v_new);
