@@ -111,6 +111,13 @@ def _ptr(t) -> int:
     return 0 if t is None else int(t.data_ptr())
 
 
+class Prepared:
+    """Marshalled arguments of a range of layers: air_layer[] / air_strides / air_seq[] plus the tensors they point to."""
+
+    def __init__(self, layers, strides, seqs, n, keepalive):
+        self.layers, self.strides, self.seqs, self.n, self._keepalive = layers, strides, seqs, n, keepalive
+
+
 class AirCache:
     """One context: thin wrapper that keeps the workspace tensor alive and marshals arguments.
 
@@ -181,26 +188,35 @@ class AirCache:
         return arr
 
     # -- the four stages -------------------------------------------------------------
-    def air_score(self, l0: int, l1: int, q_text: Sequence, k: Sequence, v: Sequence, seqs, strides=None):
-        st = strides or self.strides_of(q_text[0], k[0])
-        arr = self._layers(q_text, k, v)
-        sq = self.seq_array(seqs)
-        self._check(self.lib.air_score(self.handle, self._stream(), l0, l1, arr, C.byref(st), sq))
+    def prepare(self, q_text: Optional[Sequence], k: Sequence, v: Sequence, seqs=None) -> "Prepared":
+        """Marshal a set of layers once (descriptor arrays, strides, segments) for repeated stage calls."""
+        return Prepared(self._layers(q_text, k, v), self.strides_of(q_text[0] if q_text is not None else None, k[0]),
+                        self.seq_array(seqs) if seqs is not None else None, len(k), (q_text, k, v))
 
-    def air_reset(self):
-        self._check(self.lib.air_reset(self.handle))
+    def air_score(self, l0: int, l1: int, q_text=None, k=None, v=None, seqs=None, strides=None, prepared=None):
+        """prepared: result of prepare() for exactly the layers [l0, l1) (skips the per-call marshalling)."""
+        p = prepared or self.prepare(q_text, k, v, seqs)
+        st = strides or p.strides
+        assert p.n == l1 - l0 and p.seqs is not None
+        self._check(self.lib.air_score(self.handle, self._stream(), l0, l1, p.layers, C.byref(st), p.seqs))
 
     def air_budget(self):
         self._check(self.lib.air_budget(self.handle, self._stream()))
 
-    def air_select_compact(self, l0: int, l1: int, k: Sequence, v: Sequence, strides=None):
-        st = strides or self.strides_of(None, k[0])
-        arr = self._layers(None, k, v)
-        self._check(self.lib.air_select_compact(self.handle, self._stream(), l0, l1, arr, C.byref(st)))
+    def air_reset(self):
+        self._check(self.lib.air_reset(self.handle))
+
+    def air_select_compact(self, l0: int, l1: int, k=None, v=None, strides=None, prepared=None):
+        p = prepared or self.prepare(None, k, v)
+        st = strides or p.strides
+        assert p.n == l1 - l0
+        self._check(self.lib.air_select_compact(self.handle, self._stream(), l0, l1, p.layers, C.byref(st)))
 
     def air_decode_attn(self, l0: int, l1: int, q_new, k_new, v_new, out):
-        self._check(self.lib.air_decode_attn(self.handle, self._stream(), l0, l1, _ptr(q_new), _ptr(k_new),
-                                             _ptr(v_new), _ptr(out)))
+        """Tensors, or raw device addresses (ints) when the caller has taken them beforehand."""
+        ptr = lambda x: x if isinstance(x, int) else _ptr(x)  # noqa: E731
+        self._check(self.lib.air_decode_attn(self.handle, self._stream(), l0, l1, ptr(q_new), ptr(k_new),
+                                             ptr(v_new), ptr(out)))
 
     # -- inspection ------------------------------------------------------------------
     def air_get_scores(self, l: int) -> np.ndarray:

@@ -43,7 +43,8 @@ __global__ __launch_bounds__(kBT) void budget_kernel(Dims dm, DevTables t, doubl
                 const int64_t unit = ((int64_t)l * dm.B + b) * dm.Hkv + h;
                 const double *mo = t.moments + unit * dm.n_chunks * 3;
                 double S1 = 0.0, S2 = 0.0, S3 = 0.0;
-                for (int c = 0; c < nch; ++c) {
+#pragma unroll 8
+                for (int c = 0; c < nch; ++c) {  // ordered sums; unrolled so that the loads of 8 chunks are in flight together
                     S1 += mo[3 * c + 0];
                     S2 += mo[3 * c + 1];
                     S3 += mo[3 * c + 2];
@@ -190,16 +191,17 @@ __global__ __launch_bounds__(kBT) void budget_kernel(Dims dm, DevTables t, doubl
 
     // cache layout: each layer's region holds system + kept + text rows and room for the
     // decode appends, and starts on a multiple of kCacheRowAlign rows
-    if (tid == 0) {
-        const int nonvis = sq.seq_len - sq.vis_len;
+    if (tid < L) kk[tid] = budgets[tid];
+    __syncthreads();
+    const int nonvis = sq.seq_len - sq.vis_len;
+    if (tid < L) {
         int off = 0;
-        for (int l = 0; l < L; ++l) {
-            const int len = nonvis + budgets[l];
-            t.base_len[(int64_t)b * L + l] = len;
-            t.layer_off[(int64_t)b * L + l] = off;
-            const int cap = len + dm.max_steps;
+        for (int l = 0; l < tid; ++l) {
+            const int cap = nonvis + kk[l] + dm.max_steps;
             off += (cap + kCacheRowAlign - 1) / kCacheRowAlign * kCacheRowAlign;
         }
+        t.base_len[(int64_t)b * L + tid] = nonvis + kk[tid];
+        t.layer_off[(int64_t)b * L + tid] = off;
     }
 }
 

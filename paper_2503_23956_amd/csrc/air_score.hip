@@ -37,41 +37,66 @@ __global__ __launch_bounds__(256) void elite_kernel(Dims dm, DevTables t, int l0
     const int W = dm.max_window;
     const int wl = sq.win_len;
 
-    __shared__ double s_logit[AIR_MAX_TEXT];
-    __shared__ int s_elite[AIR_MAX_TEXT];
-    __shared__ double s_q[D];
+    extern __shared__ double s_dyn[];  // max_window doubles (last-row logits), then max_window ints (elite list)
+    double *s_logit = s_dyn;
+    int *s_elite = reinterpret_cast<int *>(s_dyn + W);
     __shared__ double s_red[4];
     __shared__ int s_cnt[5];
 
     const int ref = sq.win_start + wl - 1;
-    for (int c = tid; c < D; c += 256) s_q[c] = (double)ldf(q + (int64_t)(ref - t0) * st.q_t + c);
-    __syncthreads();
-    const double sqrt_d = sqrt((double)D);
-    double lmax = -INFINITY;
-    for (int j = tid; j < wl; j += 256) {
-        float kreg[D];
-        load_row<D>(k + (int64_t)(sq.win_start + j) * st.kv_t, kreg);
-        double acc = 0.0;
+    // last-row logits in fp64: 16 lanes per candidate key (coalesced row reads), D/16 elements per
+    // lane, 16 candidates per round of the workgroup, 8 rounds of loads in flight
+    constexpr int E = D / 16, UN = 8;
+    const int sub = tid & 15, grp = tid >> 4;
+    double qd[E];
+    {
+        T tmp[E];
+        __builtin_memcpy(tmp, __builtin_assume_aligned(q + (int64_t)(ref - t0) * st.q_t + sub * E, sizeof(T) * E), sizeof(tmp));
 #pragma unroll
-        for (int c = 0; c < D; ++c) acc += s_q[c] * (double)kreg[c];
-        acc = acc / sqrt_d;
-        s_logit[j] = acc;
-        lmax = fmax(lmax, acc);
+        for (int e = 0; e < E; ++e) qd[e] = (double)ldf(&tmp[e]);
     }
+    const double sqrt_d = sqrt((double)D);
+    for (int j0 = 0; j0 < wl; j0 += 16 * UN) {
+        T kv[UN][E];
+#pragma unroll
+        for (int un = 0; un < UN; ++un) {
+            const int j = j0 + un * 16 + grp;
+            if (j < wl)
+                __builtin_memcpy(kv[un], __builtin_assume_aligned(k + (int64_t)(sq.win_start + j) * st.kv_t + sub * E, sizeof(T) * E),
+                                 sizeof(kv[un]));
+        }
+#pragma unroll
+        for (int un = 0; un < UN; ++un) {
+            const int j = j0 + un * 16 + grp;
+            double acc = 0.0;
+            if (j < wl) {
+#pragma unroll
+                for (int e = 0; e < E; ++e) acc += qd[e] * (double)ldf(&kv[un][e]);
+            }
+#pragma unroll
+            for (int o = 1; o < 16; o <<= 1) acc += __shfl_xor(acc, o, 64);
+            if (sub == 0 && j < wl) s_logit[j] = acc / sqrt_d;
+        }
+    }
+    __syncthreads();
+    double lmax = -INFINITY;
+    for (int j = tid; j < wl; j += 256) lmax = fmax(lmax, s_logit[j]);
     lmax = wave_max(lmax);
     if ((tid & 63) == 0) s_red[tid >> 6] = lmax;
     __syncthreads();
     const double smax = fmax(fmax(s_red[0], s_red[1]), fmax(s_red[2], s_red[3]));
 
-    // ordered compaction of the flagged candidates: thread t owns a contiguous slice
+    // ordered compaction of the flagged candidates: thread t owns a contiguous slice (at most 16
+    // candidates, AIR_MAX_TEXT / 256), whose flags it keeps as a bit mask
     const int per = (wl + 255) / 256;
     const int j0 = min(wl, tid * per), j1 = min(wl, j0 + per);
-    int cnt = 0;
-    for (int j = j0; j < j1; ++j) cnt += (exp(s_logit[j] - smax) >= alpha) ? 1 : 0;
+    unsigned flags = 0;
+    for (int j = j0; j < j1; ++j)
+        if (exp(s_logit[j] - smax) >= alpha) flags |= 1u << (j - j0);
     int R;
-    int pos = block_excl_scan<4>(cnt, s_cnt, &R);
+    int pos = block_excl_scan<4>(__popc(flags), s_cnt, &R);
     for (int j = j0; j < j1; ++j) {
-        if (exp(s_logit[j] - smax) >= alpha) {
+        if (flags & (1u << (j - j0))) {
             s_elite[pos] = sq.win_start + j;
             t.elite_idx[hrow * W + pos] = sq.win_start + j;
             ++pos;
@@ -81,8 +106,8 @@ __global__ __launch_bounds__(256) void elite_kernel(Dims dm, DevTables t, int l0
     __syncthreads();
 
     // elite-text columns of Eq.7: (max, sum-exp) of every elite row over the elite text keys.
-    // One wave per row; each (row, key) logit is a 64-lane dot product, computed once for the
-    // maximum and once more for the sum.
+    // One wave per row; each (row, key) logit is a 64-lane dot product.  Up to 8 keys are
+    // scored in one batch of loads; longer rows are scored twice (maximum, then sum).
     const float scale = 1.0f / sqrtf((float)D);
     const int wave = tid >> 6, lane = tid & 63;
     constexpr int kPer = D / 64;  // elements per lane
@@ -91,21 +116,42 @@ __global__ __launch_bounds__(256) void elite_kernel(Dims dm, DevTables t, int l0
         float qv[kPer];
 #pragma unroll
         for (int e = 0; e < kPer; ++e) qv[e] = ldf(qr + lane * kPer + e);
-        float m = -INFINITY;
-        for (int j = 0; j < R; ++j) {
-            const T *kj = k + (int64_t)s_elite[j] * st.kv_t;
-            float a = 0.f;
+        float m = -INFINITY, z = 0.f;
+        if (R <= 8) {
+            float a[8];
 #pragma unroll
-            for (int e = 0; e < kPer; ++e) a = fmaf(qv[e], ldf(kj + lane * kPer + e), a);
-            m = fmaxf(m, wave_sum(a) * scale);
-        }
-        float z = 0.f;
-        for (int j = 0; j < R; ++j) {
-            const T *kj = k + (int64_t)s_elite[j] * st.kv_t;
-            float a = 0.f;
+            for (int j = 0; j < 8; ++j) {
+                a[j] = 0.f;
+                if (j < R) {
+                    const T *kj = k + (int64_t)s_elite[j] * st.kv_t;
 #pragma unroll
-            for (int e = 0; e < kPer; ++e) a = fmaf(qv[e], ldf(kj + lane * kPer + e), a);
-            z += expf(wave_sum(a) * scale - m);
+                    for (int e = 0; e < kPer; ++e) a[j] = fmaf(qv[e], ldf(kj + lane * kPer + e), a[j]);
+                }
+            }
+#pragma unroll
+            for (int j = 0; j < 8; ++j)
+                if (j < R) {
+                    a[j] = wave_sum(a[j]) * scale;
+                    m = fmaxf(m, a[j]);
+                }
+#pragma unroll
+            for (int j = 0; j < 8; ++j)
+                if (j < R) z += expf(a[j] - m);
+        } else {
+            for (int j = 0; j < R; ++j) {
+                const T *kj = k + (int64_t)s_elite[j] * st.kv_t;
+                float a = 0.f;
+#pragma unroll
+                for (int e = 0; e < kPer; ++e) a = fmaf(qv[e], ldf(kj + lane * kPer + e), a);
+                m = fmaxf(m, wave_sum(a) * scale);
+            }
+            for (int j = 0; j < R; ++j) {
+                const T *kj = k + (int64_t)s_elite[j] * st.kv_t;
+                float a = 0.f;
+#pragma unroll
+                for (int e = 0; e < kPer; ++e) a = fmaf(qv[e], ldf(kj + lane * kPer + e), a);
+                z += expf(wave_sum(a) * scale - m);
+            }
         }
         if (lane == 0) {
             t.row_mtext[hrow * W + r] = m;
@@ -275,7 +321,8 @@ __global__ __launch_bounds__(256) void stats_kernel(Dims dm, DevTables t, int l0
 template <typename T, int D>
 static hipError_t elite_launch(hipStream_t s, const Dims &dm, const DevTables &t, int l0, int nl,
                                const LaunchLayers &ll, const air_strides &st, const SeqArgs &seqs, double alpha) {
-    hipLaunchKernelGGL((elite_kernel<T, D>), dim3(dm.Hq, dm.B, nl), dim3(256), 0, s, dm, t, l0, ll, st, seqs, alpha);
+    const size_t lds = (size_t)dm.max_window * (sizeof(double) + sizeof(int));
+    hipLaunchKernelGGL((elite_kernel<T, D>), dim3(dm.Hq, dm.B, nl), dim3(256), lds, s, dm, t, l0, ll, st, seqs, alpha);
     return hipGetLastError();
 }
 

@@ -201,22 +201,45 @@ __global__ __launch_bounds__(256) void score_stream_kernel(Dims dm, DevTables t,
 }
 
 // ---------------------------------------------------------------------------------------
+// One workgroup finishes kFinishChunks consecutive chunks of a unit, so that the row maxima and
+// weights (which need every chunk's partial) are formed once per workgroup, not once per chunk.
+constexpr int kFinishChunks = 4;
+
 __global__ __launch_bounds__(256) void score_finish_kernel(Dims dm, DevTables t, int l0, LaunchLayers ll,
                                                            air_strides st) {
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, n = lane & 15, c = lane >> 4;
     UnitCtx u;
-    if (!unit_setup(dm, t, l0, ll, st, u)) return;
+    {
+        const int first = blockIdx.x * kFinishChunks;
+        const int uu = blockIdx.y;
+        u.kvh = uu % dm.Hkv;
+        u.b = (uu / dm.Hkv) % dm.B;
+        u.li = uu / (dm.Hkv * dm.B);
+        u.l = l0 + u.li;
+        u.sq = t.seq_tab[u.b];
+        if (first * kChunkKeys >= u.sq.vis_len) return;
+        u.chunk = first;
+        u.t0 = u.sq.vis_start + u.sq.vis_len;
+        u.G = dm.G;
+        u.W = dm.max_window;
+        u.q = (const bf16_t *)ll.p[u.li].q + (int64_t)u.b * st.q_b;
+        u.k = (const bf16_t *)ll.p[u.li].k + (int64_t)u.b * st.kv_b + (int64_t)u.kvh * st.kv_h;
+        u.hrow0 = ((int64_t)u.l * dm.B + u.b) * dm.Hq + (int64_t)u.kvh * u.G;
+        u.unit = ((int64_t)u.l * dm.B + u.b) * dm.Hkv + u.kvh;
+    }
     __shared__ int s_pref[17];
     __shared__ float s_M[kRowsLds], s_w[kRowsLds];
+    __shared__ float s_f[kFinishChunks][kStashRows];
     __shared__ double s_mom[4][3];
 
     head_prefix(t, u.hrow0, u.G, s_pref);
     u.R_total = s_pref[u.G];
     const bool stash = u.R_total <= kStashRows;
     const int nch = (u.sq.vis_len + kChunkKeys - 1) / kChunkKeys;
+    const int first = u.chunk, last = min(nch, first + kFinishChunks);
 
     // (M, w) of rows [rs, rs + rows): one wave per row, lanes over the chunk partials.  On the
-    // stash path the weight is folded with the chunk reference: f = w * exp(m_chunk - M).
+    // stash path the weight is also folded with each chunk's reference: f = w * exp(m_chunk - M).
     auto row_params = [&](int rs, int rows) {
         __syncthreads();
         for (int rr = wave; rr < rows; rr += 4) {
@@ -235,43 +258,74 @@ __global__ __launch_bounds__(256) void score_finish_kernel(Dims dm, DevTables t,
             }
             Z = wave_sum(Z);
             Z += (double)(t.row_ztext[slot] * expf(mt - M));
+            const float w = (float)(1.0 / ((double)(s_pref[g + 1] - s_pref[g]) * (double)u.G * Z));
             if (lane == 0) {
-                const float w = (float)(1.0 / ((double)(s_pref[g + 1] - s_pref[g]) * (double)u.G * Z));
                 s_M[rr] = M;
-                s_w[rr] = stash ? w * expf(p[u.chunk].x - M) : w;
+                s_w[rr] = w;
             }
+            if (stash && lane < last - first) s_f[lane][rr] = w * expf(p[first + lane].x - M);
         }
         __syncthreads();
     };
 
-    double m1 = 0.0, m2 = 0.0, m3 = 0.0;
-    if (stash) {
-        row_params(0, u.R_total);
-        const int key = u.chunk * kChunkKeys + tid;
-        const float *sb = t.stash + ((u.unit * dm.n_chunks + u.chunk) * (int64_t)kStashRows) * kChunkKeys + tid;
-        float e[kStashRows];
-#pragma unroll
-        for (int r = 0; r < kStashRows; ++r) e[r] = r < u.R_total ? sb[(int64_t)r * kChunkKeys] : 0.f;
-        float imp = 0.f;
-#pragma unroll
-        for (int r = 0; r < kStashRows; ++r)
-            if (r < u.R_total) imp = fmaf(s_w[r], e[r], imp);
-        if (key < u.sq.vis_len) {
-            t.scores[u.unit * dm.max_vis + key] = imp;
-            const double x = (double)imp;
-            m1 = x;
-            m2 = x * x;
-            m3 = x * x * x;
+    auto put_moments = [&](int chunk, double m1, double m2, double m3) {
+        m1 = wave_sum(m1);
+        m2 = wave_sum(m2);
+        m3 = wave_sum(m3);
+        __syncthreads();
+        if (lane == 0) {
+            s_mom[wave][0] = m1;
+            s_mom[wave][1] = m2;
+            s_mom[wave][2] = m3;
         }
-    } else {
-        const int key0 = u.chunk * kChunkKeys + wave * 64;
+        __syncthreads();
+        if (tid < 3) {
+            double *mo = t.moments + (u.unit * dm.n_chunks + chunk) * 3;
+            mo[tid] = ((s_mom[0][tid] + s_mom[1][tid]) + s_mom[2][tid]) + s_mom[3][tid];
+        }
+    };
+
+    if (stash) {
+        // every stash load of the workgroup's chunks goes out before the row parameters are formed
+        float e[kFinishChunks][kStashRows];
+#pragma unroll
+        for (int ci = 0; ci < kFinishChunks; ++ci) {
+            const float *sb = t.stash + ((u.unit * dm.n_chunks + first + ci) * (int64_t)kStashRows) * kChunkKeys + tid;
+#pragma unroll
+            for (int r = 0; r < kStashRows; ++r)
+                e[ci][r] = (first + ci < last && r < u.R_total) ? sb[(int64_t)r * kChunkKeys] : 0.f;
+        }
+        row_params(0, u.R_total);
+#pragma unroll
+        for (int ci = 0; ci < kFinishChunks; ++ci) {
+            if (first + ci >= last) break;
+            const int key = (first + ci) * kChunkKeys + tid;
+            float imp = 0.f;
+#pragma unroll
+            for (int r = 0; r < kStashRows; ++r)
+                if (r < u.R_total) imp = fmaf(s_f[ci][r], e[ci][r], imp);
+            double m1 = 0.0, m2 = 0.0, m3 = 0.0;
+            if (key < u.sq.vis_len) {
+                t.scores[u.unit * dm.max_vis + key] = imp;
+                const double x = (double)imp;
+                m1 = x;
+                m2 = x * x;
+                m3 = x * x * x;
+            }
+            put_moments(first + ci, m1, m2, m3);
+        }
+        return;
+    }
+    for (int chunk = first; chunk < last; ++chunk) {
+        u.chunk = chunk;
+        const int key0 = chunk * kChunkKeys + wave * 64;
         uint4 kreg[4][4];
         bool valid[4];
         load_keys(u, st, key0, n, c, kreg, valid);
         float acc[4] = {0.f, 0.f, 0.f, 0.f};
         for (int rs = 0; rs < u.R_total; rs += kRowsLds) {
             const int rows_here = min(kRowsLds, u.R_total - rs);
-            row_params(rs, rows_here);
+            if (chunk == first || u.R_total > kRowsLds) row_params(rs, rows_here);
             for (int rb = 0; rb < rows_here; rb += 16) {
                 f32x4 s[4];
                 block_logits(t, u, st, s_pref, rs + rb, n, c, kreg, s);
@@ -288,6 +342,7 @@ __global__ __launch_bounds__(256) void score_finish_kernel(Dims dm, DevTables t,
                 }
             }
         }
+        double m1 = 0.0, m2 = 0.0, m3 = 0.0;
 #pragma unroll
         for (int tile = 0; tile < 4; ++tile) {
             float v = acc[tile];
@@ -301,29 +356,17 @@ __global__ __launch_bounds__(256) void score_finish_kernel(Dims dm, DevTables t,
                 m3 += x * x * x;
             }
         }
-    }
-    m1 = wave_sum(m1);
-    m2 = wave_sum(m2);
-    m3 = wave_sum(m3);
-    if (lane == 0) {
-        s_mom[wave][0] = m1;
-        s_mom[wave][1] = m2;
-        s_mom[wave][2] = m3;
-    }
-    __syncthreads();
-    if (tid < 3) {
-        double *mo = t.moments + (u.unit * dm.n_chunks + u.chunk) * 3;
-        mo[tid] = ((s_mom[0][tid] + s_mom[1][tid]) + s_mom[2][tid]) + s_mom[3][tid];
+        put_moments(chunk, m1, m2, m3);
     }
 }
 
 hipError_t launch_score_mfma(hipStream_t s, const Dims &dm, const DevTables &t, int pass, int l0, int nl,
                              const LaunchLayers &ll, const air_strides &st) {
-    const dim3 grid(dm.n_chunks, nl * dm.B * dm.Hkv);
     if (pass == 1)
-        hipLaunchKernelGGL(score_stream_kernel, grid, dim3(256), 0, s, dm, t, l0, ll, st);
+        hipLaunchKernelGGL(score_stream_kernel, dim3(dm.n_chunks, nl * dm.B * dm.Hkv), dim3(256), 0, s, dm, t, l0, ll, st);
     else
-        hipLaunchKernelGGL(score_finish_kernel, grid, dim3(256), 0, s, dm, t, l0, ll, st);
+        hipLaunchKernelGGL(score_finish_kernel, dim3((dm.n_chunks + kFinishChunks - 1) / kFinishChunks, nl * dm.B * dm.Hkv),
+                           dim3(256), 0, s, dm, t, l0, ll, st);
     return hipGetLastError();
 }
 
