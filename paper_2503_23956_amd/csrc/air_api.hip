@@ -78,6 +78,7 @@ WsLayout make_layout(const air_config &c) {
     w.dec_o = take(L * B * Hkv * kMaxSplits * 16 * D * 4);  // per (unit, split): 16 head rows x D
     w.dec_ml = take(L * B * Hq * kMaxSplits * 8);
     w.stash = v_transposed(c.dtype, c.head_dim) ? take(L * B * Hkv * (size_t)w.n_chunks * kStashRows * kChunkKeys * 4) : off;
+    w.row_f = v_transposed(c.dtype, c.head_dim) ? take(L * B * Hkv * (size_t)kStashRows * w.n_chunks * 4) : off;
     w.total = off;
     return w;
 }
@@ -167,6 +168,7 @@ air_status air_create(const air_config *cfg, void *workspace, size_t workspace_b
     t.dec_o = (float *)(w + lay.dec_o);
     t.dec_ml = (float2 *)(w + lay.dec_ml);
     t.stash = (float *)(w + lay.stash);
+    t.row_f = (float *)(w + lay.row_f);
     c->have_seqs = false;
     c->budgets_ready = false;
     c->force_splits = c->force_waves = c->force_tiles = 0;

@@ -35,7 +35,7 @@ struct SeqArgs {
 struct WsLayout {
     size_t seq_tab, elite_cnt, elite_idx, row_mtext, row_ztext, row_M, row_w, part, scores;
     size_t unit_st, unit_sk, s_t, s_k, budgets, base_len, layer_off, dec_cnt, moments, indices;
-    size_t kcache, vcache, dec_o, dec_ml, stash;
+    size_t kcache, vcache, dec_o, dec_ml, stash, row_f;
     size_t total;
     int32_t n_chunks;     // ceil(max_vis_len / kChunkKeys)
     int64_t pool_rows;    // rows of one (sequence, KV head) cache pool
@@ -57,7 +57,7 @@ struct DevTables {
     double *unit_st, *unit_sk, *s_t, *s_k, *moments;
     int32_t *budgets, *base_len, *layer_off, *dec_cnt, *indices;
     void *kcache, *vcache;
-    float *dec_o, *stash;
+    float *dec_o, *stash, *row_f;
     float2 *dec_ml;
 };
 

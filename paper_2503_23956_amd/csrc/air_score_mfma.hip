@@ -9,14 +9,15 @@
 // steps.
 //
 // Eq.8 needs every row's softmax normaliser before any column can be finished, and the
-// normaliser needs all keys.  Two kernels:
+// normaliser needs all keys.  Three kernels:
 //
 //   score_stream_kernel  reads K_v ONCE.  Per (row, chunk) it leaves the chunk maximum m and
 //       sum-exp z; when the unit has at most kStashRows window rows (the elite window: a few
 //       rows per head) it also stashes e = exp(s - m) per (row, key) in fp32, 4 bytes per row
 //       and key against the 256 bytes of the key itself.
-//   score_finish_kernel  per row: M = max over chunks (and over the elite-text columns),
-//       Z = sum z exp(m - M), weight w = 1 / (R_h G Z).  Units with a stash never touch K again:
+//   score_rows_mfma_kernel  per row: M = max over chunks (and over the elite-text columns),
+//       Z = sum z exp(m - M), weight w = 1 / (R_h G Z).
+//   score_finish_kernel  units with a stash never touch K again:
 //       I[key] = sum_rows e[row][key] * (w exp(m_chunk - M)).  Units with more rows (continuous
 //       or all-text windows) recompute their logits from K_v: I[key] = sum_rows w exp(s - M).
 //       Epilogue: fp64 power sums of I over the chunk, from which the budget kernel forms Eq.9-10.
@@ -201,8 +202,53 @@ __global__ __launch_bounds__(256) void score_stream_kernel(Dims dm, DevTables t,
 }
 
 // ---------------------------------------------------------------------------------------
-// One workgroup finishes kFinishChunks consecutive chunks of a unit, so that the row maxima and
-// weights (which need every chunk's partial) are formed once per workgroup, not once per chunk.
+// Row parameters, once per unit: one wave per window row, lanes over the chunk partials.
+// M = max over chunks and the elite-text columns, Z = sum z exp(m - M) in fp64,
+// w = 1 / (R_h G Z).  Units with a stash also get f[row][chunk] = w exp(m_chunk - M), the factor
+// that turns a stashed exponential into its share of Eq.8.
+__global__ __launch_bounds__(256) void score_rows_mfma_kernel(Dims dm, DevTables t, int l0) {
+    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+    const int uu = blockIdx.x;
+    const int kvh = uu % dm.Hkv;
+    const int b = (uu / dm.Hkv) % dm.B;
+    const int l = l0 + uu / (dm.Hkv * dm.B);
+    const int G = dm.G, W = dm.max_window;
+    const int64_t hrow0 = ((int64_t)l * dm.B + b) * dm.Hq + (int64_t)kvh * G;
+    const int64_t unit = ((int64_t)l * dm.B + b) * dm.Hkv + kvh;
+    const int nch = (t.seq_tab[b].vis_len + kChunkKeys - 1) / kChunkKeys;
+    __shared__ int s_pref[17];
+    head_prefix(t, hrow0, G, s_pref);
+    const int R_total = s_pref[G];
+    const bool stash = R_total <= kStashRows;
+    for (int rho = wave; rho < R_total; rho += 4) {
+        const int g = head_of_row(s_pref, G, rho);
+        const int64_t slot = (hrow0 + g) * W + (rho - s_pref[g]);
+        const float2 *p = t.part + slot * dm.n_chunks;
+        const float mt = t.row_mtext[slot];
+        float M = mt;
+        for (int cc = lane; cc < nch; cc += 64) M = fmaxf(M, p[cc].x);
+        M = wave_max(M);
+        double Z = 0.0;
+        for (int cc = lane; cc < nch; cc += 64) {
+            const float2 x = p[cc];
+            Z += (double)(x.y * expf(x.x - M));
+        }
+        Z = wave_sum(Z);
+        Z += (double)(t.row_ztext[slot] * expf(mt - M));
+        const float w = (float)(1.0 / ((double)(s_pref[g + 1] - s_pref[g]) * (double)G * Z));
+        if (lane == 0) {
+            t.row_M[slot] = M;
+            t.row_w[slot] = w;
+        }
+        if (stash) {
+            float *f = t.row_f + (unit * kStashRows + rho) * dm.n_chunks;
+            for (int cc = lane; cc < nch; cc += 64) f[cc] = w * expf(p[cc].x - M);
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------------------
+// One workgroup finishes kFinishChunks consecutive chunks of a unit.
 constexpr int kFinishChunks = 4;
 
 __global__ __launch_bounds__(256) void score_finish_kernel(Dims dm, DevTables t, int l0, LaunchLayers ll,
@@ -232,41 +278,15 @@ __global__ __launch_bounds__(256) void score_finish_kernel(Dims dm, DevTables t,
     __shared__ float s_f[kFinishChunks][kStashRows];
     __shared__ double s_mom[4][3];
 
+    const int nch = (u.sq.vis_len + kChunkKeys - 1) / kChunkKeys;
+    const int first = u.chunk, last = min(nch, first + kFinishChunks);
+    // factor table of the stash path goes out before anything else; rows past R_total are never used
+    float f_mine = 0.f;
+    if (tid < kFinishChunks * kStashRows && first + tid / kStashRows < last)
+        f_mine = t.row_f[(u.unit * kStashRows + (tid % kStashRows)) * dm.n_chunks + first + tid / kStashRows];
     head_prefix(t, u.hrow0, u.G, s_pref);
     u.R_total = s_pref[u.G];
     const bool stash = u.R_total <= kStashRows;
-    const int nch = (u.sq.vis_len + kChunkKeys - 1) / kChunkKeys;
-    const int first = u.chunk, last = min(nch, first + kFinishChunks);
-
-    // (M, w) of rows [rs, rs + rows): one wave per row, lanes over the chunk partials.  On the
-    // stash path the weight is also folded with each chunk's reference: f = w * exp(m_chunk - M).
-    auto row_params = [&](int rs, int rows) {
-        __syncthreads();
-        for (int rr = wave; rr < rows; rr += 4) {
-            const int rho = rs + rr;
-            const int g = head_of_row(s_pref, u.G, rho);
-            const int64_t slot = (u.hrow0 + g) * u.W + (rho - s_pref[g]);
-            const float2 *p = t.part + slot * dm.n_chunks;
-            const float mt = t.row_mtext[slot];
-            float M = mt;
-            for (int cc = lane; cc < nch; cc += 64) M = fmaxf(M, p[cc].x);
-            M = wave_max(M);
-            double Z = 0.0;
-            for (int cc = lane; cc < nch; cc += 64) {
-                const float2 x = p[cc];
-                Z += (double)(x.y * expf(x.x - M));
-            }
-            Z = wave_sum(Z);
-            Z += (double)(t.row_ztext[slot] * expf(mt - M));
-            const float w = (float)(1.0 / ((double)(s_pref[g + 1] - s_pref[g]) * (double)u.G * Z));
-            if (lane == 0) {
-                s_M[rr] = M;
-                s_w[rr] = w;
-            }
-            if (stash && lane < last - first) s_f[lane][rr] = w * expf(p[first + lane].x - M);
-        }
-        __syncthreads();
-    };
 
     auto put_moments = [&](int chunk, double m1, double m2, double m3) {
         m1 = wave_sum(m1);
@@ -286,7 +306,6 @@ __global__ __launch_bounds__(256) void score_finish_kernel(Dims dm, DevTables t,
     };
 
     if (stash) {
-        // every stash load of the workgroup's chunks goes out before the row parameters are formed
         float e[kFinishChunks][kStashRows];
 #pragma unroll
         for (int ci = 0; ci < kFinishChunks; ++ci) {
@@ -295,7 +314,8 @@ __global__ __launch_bounds__(256) void score_finish_kernel(Dims dm, DevTables t,
             for (int r = 0; r < kStashRows; ++r)
                 e[ci][r] = (first + ci < last && r < u.R_total) ? sb[(int64_t)r * kChunkKeys] : 0.f;
         }
-        row_params(0, u.R_total);
+        if (tid < kFinishChunks * kStashRows) s_f[tid / kStashRows][tid % kStashRows] = (tid % kStashRows) < u.R_total ? f_mine : 0.f;
+        __syncthreads();
 #pragma unroll
         for (int ci = 0; ci < kFinishChunks; ++ci) {
             if (first + ci >= last) break;
@@ -316,6 +336,18 @@ __global__ __launch_bounds__(256) void score_finish_kernel(Dims dm, DevTables t,
         }
         return;
     }
+    // recompute path: (M, w) of a block of rows staged from the row tables
+    auto stage_rows = [&](int rs, int rows) {
+        __syncthreads();
+        for (int rr = tid; rr < rows; rr += 256) {
+            const int rho = rs + rr;
+            const int g = head_of_row(s_pref, u.G, rho);
+            const int64_t slot = (u.hrow0 + g) * u.W + (rho - s_pref[g]);
+            s_M[rr] = t.row_M[slot];
+            s_w[rr] = t.row_w[slot];
+        }
+        __syncthreads();
+    };
     for (int chunk = first; chunk < last; ++chunk) {
         u.chunk = chunk;
         const int key0 = chunk * kChunkKeys + wave * 64;
@@ -325,7 +357,7 @@ __global__ __launch_bounds__(256) void score_finish_kernel(Dims dm, DevTables t,
         float acc[4] = {0.f, 0.f, 0.f, 0.f};
         for (int rs = 0; rs < u.R_total; rs += kRowsLds) {
             const int rows_here = min(kRowsLds, u.R_total - rs);
-            if (chunk == first || u.R_total > kRowsLds) row_params(rs, rows_here);
+            if (chunk == first || u.R_total > kRowsLds) stage_rows(rs, rows_here);
             for (int rb = 0; rb < rows_here; rb += 16) {
                 f32x4 s[4];
                 block_logits(t, u, st, s_pref, rs + rb, n, c, kreg, s);
@@ -364,9 +396,13 @@ hipError_t launch_score_mfma(hipStream_t s, const Dims &dm, const DevTables &t, 
                              const LaunchLayers &ll, const air_strides &st) {
     if (pass == 1)
         hipLaunchKernelGGL(score_stream_kernel, dim3(dm.n_chunks, nl * dm.B * dm.Hkv), dim3(256), 0, s, dm, t, l0, ll, st);
-    else
+    else {
+        hipLaunchKernelGGL(score_rows_mfma_kernel, dim3(nl * dm.B * dm.Hkv), dim3(256), 0, s, dm, t, l0);
+        hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return e;
         hipLaunchKernelGGL(score_finish_kernel, dim3((dm.n_chunks + kFinishChunks - 1) / kFinishChunks, nl * dm.B * dm.Hkv),
                            dim3(256), 0, s, dm, t, l0, ll, st);
+    }
     return hipGetLastError();
 }
 

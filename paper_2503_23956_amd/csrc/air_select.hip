@@ -29,40 +29,53 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(Dims dm, DevTables 
         return;
     }
 
-    __shared__ uint32_t hist[256];
+    __shared__ uint32_t hist[kSelThreads / 64][256];  // one histogram per wave: scores share leading bits, so few bins are hot
     __shared__ uint32_t s_prefix, s_kk;
     __shared__ int s_scan[kSelThreads / 64 + 1];
-    __shared__ int s_wgt[kSelThreads / 64], s_weq[kSelThreads / 64];
 
-    // a row of up to kSelSpan scores stays in registers for all passes (element j of thread t is
-    // score t + j * kSelThreads of the sweep); longer rows are re-read sweep by sweep
+    // A sweep of up to kSelSpan scores stays in registers for all passes: thread t owns the `per`
+    // consecutive scores from base + t * per on.  Rows longer than kSelSpan are re-read sweep by sweep.
     const bool cached = n <= kSelSpan;
+    const int per = cached ? (n + kSelThreads - 1) / kSelThreads : kSelRegs;
     uint32_t v[kSelRegs];
     auto load_sweep = [&](int base) {
 #pragma unroll
         for (int j = 0; j < kSelRegs; ++j) {
-            const int i = base + tid + j * kSelThreads;
-            v[j] = i < n ? key[i] : 0u;
+            const int i = base + tid * per + j;
+            v[j] = (j < per && i < n) ? key[i] : 0u;
         }
     };
+    auto live = [&](int base, int j) { return j < per && base + tid * per + j < n; };
     if (cached) load_sweep(0);
 
     uint32_t prefix = 0, mask = 0, kk = (uint32_t)k;
     for (int pass = 0; pass < 4; ++pass) {
         const int shift = 24 - 8 * pass;
-        if (tid < 256) hist[tid] = 0;
+        for (int i = tid; i < (kSelThreads / 64) * 256; i += kSelThreads) (&hist[0][0])[i] = 0;
         __syncthreads();
         for (int base = 0; base < n; base += kSelSpan) {
             if (!cached) load_sweep(base);
+            // Scores share their leading bits, so in the first passes most of a thread's scores fall
+            // into one bin and whole waves collide on it: each thread counts the scores that share
+            // the digit of its first candidate itself and adds them once; the others add one by one.
+            int d0 = -1, c0 = 0;
 #pragma unroll
-            for (int j = 0; j < kSelRegs; ++j) {
-                const int i = base + tid + j * kSelThreads;
-                if (i < n && (v[j] & mask) == prefix) atomicAdd(&hist[(v[j] >> shift) & 255u], 1u);
-            }
+            for (int j = 0; j < kSelRegs; ++j)
+                if (live(base, j) && (v[j] & mask) == prefix) {
+                    const int dgt = (int)((v[j] >> shift) & 255u);
+                    if (d0 < 0) d0 = dgt;
+                    if (dgt == d0) ++c0;
+                    else atomicAdd(&hist[wave][dgt], 1u);
+                }
+            if (c0 > 0) atomicAdd(&hist[wave][d0], (uint32_t)c0);
         }
         __syncthreads();
         // position p = 255 - bin; the k-th largest lies in the bin whose prefix count first reaches kk
-        const int h = tid < 256 ? (int)hist[255 - tid] : 0;
+        int h = 0;
+        if (tid < 256) {
+#pragma unroll
+            for (int w = 0; w < kSelThreads / 64; ++w) h += (int)hist[w][255 - tid];
+        }
         int total;
         const int excl = block_excl_scan<kSelThreads / 64>(h, s_scan, &total);
         if (tid < 256 && h > 0 && (uint32_t)excl < kk && kk <= (uint32_t)(excl + h)) {
@@ -76,39 +89,30 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(Dims dm, DevTables 
     }
     const uint32_t tau = prefix;  // bit pattern of the k-th largest score; kk of the entries equal to it are kept
 
+    // ordered compaction: count per thread, one scan per sweep, then each thread writes its slice in order
     int base_gt = 0, base_eq = 0;
     for (int base = 0; base < n; base += kSelSpan) {
         if (!cached) load_sweep(base);
+        int c_gt = 0, c_eq = 0;
 #pragma unroll
-        for (int j = 0; j < kSelRegs; ++j) {
-            const int i0 = base + j * kSelThreads;
-            if (i0 >= n) break;  // uniform
-            const int i = i0 + tid;
-            const bool gt = i < n && v[j] > tau;
-            const bool eq = i < n && v[j] == tau;
-            const uint64_t bg = __ballot(gt), be = __ballot(eq);
-            const uint64_t below = (1ull << lane) - 1ull;
-            if (lane == 0) {
-                s_wgt[wave] = __popcll(bg);
-                s_weq[wave] = __popcll(be);
+        for (int j = 0; j < kSelRegs; ++j)
+            if (live(base, j)) {
+                c_gt += v[j] > tau ? 1 : 0;
+                c_eq += v[j] == tau ? 1 : 0;
             }
-            __syncthreads();
-            int gt_before = base_gt + __popcll(bg & below), eq_before = base_eq + __popcll(be & below);
-            int tot_gt = 0, tot_eq = 0;
+        int tot_gt, tot_eq;
+        int gt_before = base_gt + block_excl_scan<kSelThreads / 64>(c_gt, s_scan, &tot_gt);
+        int eq_before = base_eq + block_excl_scan<kSelThreads / 64>(c_eq, s_scan, &tot_eq);
 #pragma unroll
-            for (int w = 0; w < kSelThreads / 64; ++w) {
-                if (w < wave) {
-                    gt_before += s_wgt[w];
-                    eq_before += s_weq[w];
-                }
-                tot_gt += s_wgt[w];
-                tot_eq += s_weq[w];
+        for (int j = 0; j < kSelRegs; ++j)
+            if (live(base, j)) {
+                const bool gt = v[j] > tau, eq = v[j] == tau;
+                if (gt || (eq && eq_before < (int)kk)) out[gt_before + min(eq_before, (int)kk)] = base + tid * per + j;
+                gt_before += gt ? 1 : 0;
+                eq_before += eq ? 1 : 0;
             }
-            if (gt || (eq && eq_before < (int)kk)) out[gt_before + min(eq_before, (int)kk)] = i;
-            base_gt += tot_gt;
-            base_eq += tot_eq;
-            __syncthreads();
-        }
+        base_gt += tot_gt;
+        base_eq += tot_eq;
     }
 }
 
