@@ -209,3 +209,35 @@ def test_decode_long_cache_multiple_iterations_per_split():
 
 def test_config2_full_size():
     _run_case(synth.get_workload(2), 0.10, steps=2)
+
+
+def _sample_units(w, n, seed):
+    rng = np.random.default_rng(seed)
+    units = set()
+    while len(units) < n:
+        units.add((int(rng.integers(w.n_layers)), int(rng.integers(w.batch)), int(rng.integers(w.n_kv_heads))))
+    return sorted(units)
+
+
+@pytest.mark.parametrize("retention", [0.05, 0.25])
+def test_config3_batched_ragged_full_size(retention):
+    # 16 ragged sequences; scores, budgets and index sets of every unit, compaction and decode on a sample
+    w = synth.get_workload(3)
+    _run_case(w, retention, steps=2, check_decode_units=_sample_units(w, 64, 3))
+
+
+def test_config4_video_full_size():
+    w = synth.get_workload(4)
+    _run_case(w, 0.10, steps=2, check_decode_units=_sample_units(w, 48, 4))
+
+
+def test_config5_72b_stress_full_size():
+    # 80 layers (three launches per stage), G = 8, 16384 visual tokens (one full select sweep)
+    w = synth.get_workload(5)
+    _run_case(w, 0.10, steps=2, check_decode_units=_sample_units(w, 48, 5))
+
+
+@pytest.mark.parametrize("retention", [0.01, 0.50])
+def test_config5_shape_retention_extremes(retention):
+    w = synth.get_workload(5).scaled(n_layers=6)
+    _run_case(w, retention, steps=2, check_decode_units=_sample_units(w, 24, 6))
