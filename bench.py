@@ -252,6 +252,15 @@ def main():
                               "score_frac": ab["score"] / (score_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
                               "bytes": ab["compress"]},
     }
+    # measured HBM traffic of the dominant kernel (rocprofv3 byte counters, committed summary), when one
+    # exists for this workload and launch shape
+    try:
+        with open(os.path.join(ROOT, "profiles", "hbm_traffic.json")) as f:
+            tr = json.load(f).get(result["config"]["workload"], {}).get("air_decode_attn")
+        if tr and not args.per_layer:
+            result["roofline"]["traffic"] = tr["fetch_bytes"] + tr["write_bytes"]
+    except (OSError, ValueError):
+        pass
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(w, seqs, retention, host_layers, dec_inputs, n_dec)
     print(json.dumps(result))
