@@ -26,7 +26,8 @@ __global__ __launch_bounds__(kBT) void budget_kernel(Dims dm, DevTables t, doubl
     __shared__ unsigned char is_free[kBT];
     __shared__ double s_sum_t, s_sum_k;
     __shared__ long long s_ktot, s_left;
-    __shared__ int s_tot, s_elig;
+    __shared__ int s_tot, s_elig, s_nfree, s_pin, s_npin;
+    __shared__ double s_wfree, s_kfree, v_over[kBT], v_under[kBT];
     __shared__ double u_st[AIR_MAX_LAYERS * 16], u_sk[AIR_MAX_LAYERS * 16];  // per (layer, KV head), H_kv <= 16 staged
 
     double *s_t = t.s_t + (int64_t)b * L;
@@ -99,6 +100,7 @@ __global__ __launch_bounds__(kBT) void budget_kernel(Dims dm, DevTables t, doubl
             s_ktot = k_tot < k_lo ? k_lo : (k_tot > k_hi ? k_hi : k_tot);
             s_tot = 0;
             s_elig = 0;
+            s_npin = 0;
         }
         __syncthreads();
         if (tid < L) {
@@ -114,38 +116,70 @@ __global__ __launch_bounds__(kBT) void budget_kernel(Dims dm, DevTables t, doubl
             is_free[tid] = 1;
         }
         __syncthreads();
-        if (tid == 0) {
-            double k_free = (double)s_ktot;
-            for (int it = 0; it < L + 1; ++it) {
+        // proportional allocation with clamping.  Per round: thread 0 sums the free weights in layer
+        // order, every layer forms its own x_l (the divisions run in parallel), thread 0 sums the
+        // violations in layer order and picks the side to pin.
+        if (tid == 0) s_kfree = (double)s_ktot;
+        for (int it = 0; it < L + 1; ++it) {
+            __syncthreads();
+            if (tid == 0) {
                 double w_free = 0.0;
                 int n_free = 0;
+#pragma unroll 4
                 for (int l = 0; l < L; ++l)
                     if (is_free[l]) {
                         w_free += w[l];
                         ++n_free;
                     }
-                if (n_free == 0) break;
+                s_wfree = w_free;
+                s_nfree = n_free;
+            }
+            __syncthreads();
+            if (s_nfree == 0) break;
+            if (tid < L) {
+                double vo = 0.0, vu = 0.0;
+                if (is_free[tid]) {
+                    const double xl = s_wfree > 0.0 ? (w[tid] / s_wfree) * s_kfree : s_kfree / (double)s_nfree;
+                    x[tid] = xl;
+                    if (xl > hi) vo = xl - hi;
+                    else if (xl < lo) vu = lo - xl;
+                }
+                v_over[tid] = vo;
+                v_under[tid] = vu;
+            }
+            __syncthreads();
+            if (tid == 0) {
                 double over = 0.0, under = 0.0;
-                for (int l = 0; l < L; ++l)
-                    if (is_free[l]) {
-                        x[l] = w_free > 0.0 ? (w[l] / w_free) * k_free : k_free / (double)n_free;
-                        if (x[l] > hi) over += x[l] - hi;
-                        else if (x[l] < lo) under += lo - x[l];
-                    }
-                if (over == 0.0 && under == 0.0) break;
-                const bool pin_hi = over >= under;
-                for (int l = 0; l < L; ++l)
-                    if (is_free[l]) {
-                        if (pin_hi && x[l] > hi) {
-                            x[l] = hi;
-                            is_free[l] = 0;
-                            k_free -= hi;
-                        } else if (!pin_hi && x[l] < lo) {
-                            x[l] = lo;
-                            is_free[l] = 0;
-                            k_free -= lo;
-                        }
-                    }
+#pragma unroll 4
+                for (int l = 0; l < L; ++l) {  // pinned layers contribute exact zeros
+                    over += v_over[l];
+                    under += v_under[l];
+                }
+                s_pin = (over == 0.0 && under == 0.0) ? 0 : (over >= under ? 1 : 2);
+            }
+            __syncthreads();
+            const int pin = s_pin;
+            if (pin == 0) break;
+            int pinned = 0;
+            if (tid < L && is_free[tid]) {
+                if (pin == 1 && x[tid] > hi) {
+                    x[tid] = hi;
+                    is_free[tid] = 0;
+                    pinned = 1;
+                } else if (pin == 2 && x[tid] < lo) {
+                    x[tid] = lo;
+                    is_free[tid] = 0;
+                    pinned = 1;
+                }
+            }
+            // k_free stays an integer-valued double: subtracting the bound once per pinned layer is exact in any order
+            const unsigned long long any = __ballot(pinned);
+            if (any && (tid & 63) == 0) atomicAdd(&s_npin, __popcll(any));
+            __syncthreads();
+            if (tid == 0) {
+                const double bound = pin == 1 ? hi : lo;
+                for (int q = 0; q < s_npin; ++q) s_kfree -= bound;
+                s_npin = 0;
             }
         }
         __syncthreads();
@@ -164,6 +198,7 @@ __global__ __launch_bounds__(kBT) void budget_kernel(Dims dm, DevTables t, doubl
             int add = 0;
             if (tid < L && kk[tid] < n_vis) {
                 int rank = 0;
+#pragma unroll 4
                 for (int j = 0; j < L; ++j)
                     if (kk[j] < n_vis && (frac[j] > frac[tid] || (frac[j] == frac[tid] && j < tid))) ++rank;
                 add = rank < (int)left ? 1 : 0;
