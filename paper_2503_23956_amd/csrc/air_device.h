@@ -88,6 +88,45 @@ __device__ __forceinline__ double block_sum(double v, double *scratch) {
     return r;
 }
 
+// All-reduce over each group of 16 consecutive lanes with DPP modifiers (no LDS traffic):
+// quad_perm [1,0,3,2], quad_perm [2,3,0,1], row_half_mirror, row_mirror.
+#define AIR_DPP_STEP(OP, v, ctrl) OP((v), __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, (v)), (ctrl), 0xf, 0xf, false)))
+__device__ __forceinline__ float max16(float v) {
+    v = AIR_DPP_STEP(fmaxf, v, 0xB1);
+    v = AIR_DPP_STEP(fmaxf, v, 0x4E);
+    v = AIR_DPP_STEP(fmaxf, v, 0x141);
+    v = AIR_DPP_STEP(fmaxf, v, 0x140);
+    return v;
+}
+__device__ __forceinline__ float add_f(float a, float b) { return a + b; }
+__device__ __forceinline__ float sum16(float v) {
+    v = AIR_DPP_STEP(add_f, v, 0xB1);
+    v = AIR_DPP_STEP(add_f, v, 0x4E);
+    v = AIR_DPP_STEP(add_f, v, 0x141);
+    v = AIR_DPP_STEP(add_f, v, 0x140);
+    return v;
+}
+
+// exp(d * c / log2(e)) = 2^(d * c) for d <= 0 and a constant c given as a hi/lo pair (c_hi + c_lo = c to
+// ~48 bits): the product is split exactly, its integer part goes through ldexp and only the
+// fraction through the hardware exp2, so that the result is good to about 2 ulp for any d.
+__device__ __forceinline__ float exp2_scaled(float d, float c_hi, float c_lo) {
+    const float t = d * c_hi;
+    const float lo = fmaf(d, c_hi, -t) + d * c_lo;
+    const float nf = rintf(t);
+    const float f = (t - nf) + lo;
+    return ldexpf(__builtin_amdgcn_exp2f(f), (int)nf);
+}
+
+// Workgroup barrier that orders LDS traffic only.  __syncthreads() also waits for every
+// outstanding global load and store of the wave (its fence covers global memory), which drains
+// prefetches; use this one where only LDS data crosses the barrier.
+__device__ __forceinline__ void lds_barrier() {
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
+    __builtin_amdgcn_s_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
+}
+
 // Exclusive prefix sum of one int per thread over a workgroup of NW waves (thread order).
 // `scratch` holds NW + 1 ints; *total receives the sum.  Contains two barriers.
 template <int NW>

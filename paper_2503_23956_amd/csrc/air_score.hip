@@ -108,6 +108,8 @@ __global__ __launch_bounds__(256) void elite_kernel(Dims dm, DevTables t, int l0
     // elite-text columns of Eq.7: (max, sum-exp) of every elite row over the elite text keys.
     // One wave per row; each (row, key) logit is a 64-lane dot product.  Up to 8 keys are
     // scored in one batch of loads; longer rows are scored twice (maximum, then sum).
+    // The maximum is kept as the RAW dot product (before the 1/sqrt(d) scale), the sum is of
+    // exp((a - max) / sqrt(d)).
     const float scale = 1.0f / sqrtf((float)D);
     const int wave = tid >> 6, lane = tid & 63;
     constexpr int kPer = D / 64;  // elements per lane
@@ -131,26 +133,26 @@ __global__ __launch_bounds__(256) void elite_kernel(Dims dm, DevTables t, int l0
 #pragma unroll
             for (int j = 0; j < 8; ++j)
                 if (j < R) {
-                    a[j] = wave_sum(a[j]) * scale;
+                    a[j] = wave_sum(a[j]);
                     m = fmaxf(m, a[j]);
                 }
 #pragma unroll
             for (int j = 0; j < 8; ++j)
-                if (j < R) z += expf(a[j] - m);
+                if (j < R) z += expf((a[j] - m) * scale);
         } else {
             for (int j = 0; j < R; ++j) {
                 const T *kj = k + (int64_t)s_elite[j] * st.kv_t;
                 float a = 0.f;
 #pragma unroll
                 for (int e = 0; e < kPer; ++e) a = fmaf(qv[e], ldf(kj + lane * kPer + e), a);
-                m = fmaxf(m, wave_sum(a) * scale);
+                m = fmaxf(m, wave_sum(a));
             }
             for (int j = 0; j < R; ++j) {
                 const T *kj = k + (int64_t)s_elite[j] * st.kv_t;
                 float a = 0.f;
 #pragma unroll
                 for (int e = 0; e < kPer; ++e) a = fmaf(qv[e], ldf(kj + lane * kPer + e), a);
-                z += expf(wave_sum(a) * scale - m);
+                z += expf((wave_sum(a) - m) * scale);
             }
         }
         if (lane == 0) {
@@ -275,9 +277,10 @@ __global__ __launch_bounds__(64) void score_rows_kernel(Dims dm, DevTables t, in
     for (int r = threadIdx.x; r < R; r += 64) {
         const int64_t slot = hrow * W + r;
         const float2 *p = t.part + slot * dm.n_chunks;
-        float M = t.row_mtext[slot];
+        const float mt = t.row_mtext[slot] * (1.0f / sqrtf((float)dm.D));  // stored unscaled
+        float M = mt;
         for (int c = 0; c < nch; ++c) M = fmaxf(M, p[c].x);
-        double Z = (double)t.row_ztext[slot] * exp((double)t.row_mtext[slot] - (double)M);
+        double Z = (double)t.row_ztext[slot] * exp((double)mt - (double)M);
         for (int c = 0; c < nch; ++c) Z += (double)p[c].y * exp((double)p[c].x - (double)M);
         t.row_M[slot] = M;
         t.row_w[slot] = (float)(1.0 / ((double)R * (double)dm.G * Z));

@@ -48,7 +48,7 @@ __device__ __forceinline__ void head_prefix(const DevTables &t, int64_t hrow0, i
         }
         s_pref[G] = run;
     }
-    __syncthreads();
+    lds_barrier();
 }
 
 __device__ __forceinline__ int head_of_row(const int *s_pref, int G, int rho) {
@@ -73,26 +73,32 @@ __device__ __forceinline__ void load_keys(const UnitCtx &u, const air_strides &s
     }
 }
 
-// Scaled logits of one block of 16 rows against the wave's 64 keys.  MFMA row m = 4c'+i' carries
-// list row rbase + 4i' + c' (c' = m / 4, i' = m % 4), so that output lane group c holds rows
-// rbase + c, rbase + 4 + c, ...: with fewer than 16 rows in the block every lane group has the
-// same number of live rows and loops over i stop early.
-__device__ __forceinline__ void block_logits(const DevTables &t, const UnitCtx &u, const air_strides &st,
-                                             const int *s_pref, int rbase, int n, int c, const uint4 (&kreg)[4][4],
-                                             f32x4 (&s)[4]) {
+// A operand of one block of 16 window rows.  MFMA row m = 4c'+i' carries list row rbase + 4i' + c'
+// (c' = m / 4, i' = m % 4), so that output lane group c holds rows rbase + c, rbase + 4 + c, ...:
+// with fewer than 16 rows in the block every lane group has the same number of live rows and
+// loops over i stop early.
+__device__ __forceinline__ void load_rows(const DevTables &t, const UnitCtx &u, const air_strides &st,
+                                          const int *s_pref, int rbase, int n, int c, uint4 (&qa)[4]) {
     const int rho = rbase + 4 * (n & 3) + (n >> 2);
     const int g = head_of_row(s_pref, u.G, rho);
     const bool have = rho < u.R_total;
     int tok = u.t0;
     if (have) tok = t.elite_idx[(u.hrow0 + g) * u.W + (rho - s_pref[g])];
     const bf16_t *qr = u.q + (int64_t)(u.kvh * u.G + g) * st.q_h + (int64_t)(tok - u.t0) * st.q_t;
-    uint4 qa[4];
 #pragma unroll
     for (int sl = 0; sl < 4; ++sl) {
         qa[sl] = make_uint4(0, 0, 0, 0);
         if (have) qa[sl] = *reinterpret_cast<const uint4 *>(qr + 32 * sl + 8 * c);
     }
-    const float scale = 0.08838834764831845f;  // 1/sqrt(128)
+}
+
+// RAW logits (dot products, before the 1/sqrt(d) scale) of a block of 16 rows against the wave's 64
+// keys: lane (key n, c) gets rows rbase + 4i + c.  Maxima are taken and exchanged in raw units and
+// the scale is folded into the exponential, exp((s - M) / sqrt(d)) = 2^((s - M) * kC).
+constexpr float kCHi = 0.127517431974411f, kCLo = -1.1498123564379625e-09f;  // log2(e) / sqrt(128), split
+__device__ __forceinline__ float exp_raw(float d) { return exp2_scaled(d, kCHi, kCLo); }
+
+__device__ __forceinline__ void logits_of(const uint4 (&qa)[4], const uint4 (&kreg)[4][4], f32x4 (&s)[4]) {
 #pragma unroll
     for (int tile = 0; tile < 4; ++tile) {
         s[tile] = (f32x4){0.f, 0.f, 0.f, 0.f};
@@ -100,14 +106,20 @@ __device__ __forceinline__ void block_logits(const DevTables &t, const UnitCtx &
         for (int sl = 0; sl < 4; ++sl)
             s[tile] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, qa[sl]),
                                                               __builtin_bit_cast(bf16x8, kreg[tile][sl]), s[tile], 0, 0, 0);
-#pragma unroll
-        for (int i = 0; i < 4; ++i) s[tile][i] *= scale;
     }
 }
 
+__device__ __forceinline__ void block_logits(const DevTables &t, const UnitCtx &u, const air_strides &st,
+                                             const int *s_pref, int rbase, int n, int c, const uint4 (&kreg)[4][4],
+                                             f32x4 (&s)[4]) {
+    uint4 qa[4];
+    load_rows(t, u, st, s_pref, rbase, n, c, qa);
+    logits_of(qa, kreg, s);
+}
+
 __device__ __forceinline__ bool unit_setup(const Dims &dm, const DevTables &t, int l0, const LaunchLayers &ll,
-                                           const air_strides &st, UnitCtx &u) {
-    u.chunk = blockIdx.x;
+                                           const air_strides &st, UnitCtx &u, int chunks_per_wg) {
+    u.chunk = blockIdx.x * chunks_per_wg;  // first chunk of this workgroup
     const int uu = blockIdx.y;
     u.kvh = uu % dm.Hkv;
     u.b = (uu / dm.Hkv) % dm.B;
@@ -126,77 +138,100 @@ __device__ __forceinline__ bool unit_setup(const Dims &dm, const DevTables &t, i
 }
 
 // ---------------------------------------------------------------------------------------
-__global__ __launch_bounds__(256) void score_stream_kernel(Dims dm, DevTables t, int l0, LaunchLayers ll,
-                                                           air_strides st) {
+// One workgroup streams kStreamChunks consecutive chunks of a unit; the keys of the next chunk are
+// requested before the current one is scored, so that the memory pipe never drains while the
+// workgroup computes.  The window rows (A operands) of the first two row blocks are loaded once.
+// Stash layout of one (unit, chunk, row): 256 floats, key 64w + 16 tile + n at position 64w + 4n + tile,
+// i.e. the four tiles of a lane are one 16-byte store.
+constexpr int kStreamChunks = 1;
+
+__device__ __forceinline__ int stash_pos(int key_in_chunk) {
+    return (key_in_chunk & ~63) | ((key_in_chunk & 15) << 2) | ((key_in_chunk >> 4) & 3);
+}
+
+__global__ __launch_bounds__(256, 3) void score_stream_kernel(Dims dm, DevTables t, int l0, LaunchLayers ll,
+                                                              air_strides st) {
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, n = lane & 15, c = lane >> 4;
     UnitCtx u;
-    if (!unit_setup(dm, t, l0, ll, st, u)) return;
+    if (!unit_setup(dm, t, l0, ll, st, u, kStreamChunks)) return;
     __shared__ int s_pref[17];
     __shared__ float s_pm[4][16], s_pz[4][16], s_mw[16];
 
-    const int key0 = u.chunk * kChunkKeys + wave * 64;
-    uint4 kreg[4][4];
-    bool valid[4];
-    load_keys(u, st, key0, n, c, kreg, valid);
+    const int nch = (u.sq.vis_len + kChunkKeys - 1) / kChunkKeys;
+    const int first = u.chunk, last = min(nch, first + kStreamChunks);
+    uint4 kreg[4][4], knext[4][4];
+    bool valid[4], vnext[4];
+    load_keys(u, st, first * kChunkKeys + wave * 64, n, c, kreg, valid);
     head_prefix(t, u.hrow0, u.G, s_pref);
     u.R_total = s_pref[u.G];
     const bool stash = u.R_total <= kStashRows;
-    float *stash_base = t.stash + ((u.unit * dm.n_chunks + u.chunk) * (int64_t)kStashRows) * kChunkKeys;
+    uint4 qa0[4], qa1[4];
+    load_rows(t, u, st, s_pref, 0, n, c, qa0);
+    load_rows(t, u, st, s_pref, 16, n, c, qa1);
 
-    for (int rb = 0; rb < u.R_total; rb += 16) {
-        f32x4 s[4];
-        block_logits(t, u, st, s_pref, rb, n, c, kreg, s);
-        const int n_i = min(4, (u.R_total - rb + 3) >> 2);  // live values of i (uniform over the workgroup)
-        float m[4];
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            m[i] = -INFINITY;
-            if (i >= n_i) continue;
-            float mx = -INFINITY;
+    for (int ci = 0; ci < kStreamChunks; ++ci) {
+        const int chunk = first + ci;
+        if (chunk >= last) break;
+        if (chunk + 1 < last) load_keys(u, st, (chunk + 1) * kChunkKeys + wave * 64, n, c, knext, vnext);
+        float *stash_base = t.stash + ((u.unit * dm.n_chunks + chunk) * (int64_t)kStashRows) * kChunkKeys;
+        for (int rb = 0; rb < u.R_total; rb += 16) {
+            f32x4 s[4];
+            if (rb == 0) logits_of(qa0, kreg, s);
+            else if (rb == 16) logits_of(qa1, kreg, s);
+            else block_logits(t, u, st, s_pref, rb, n, c, kreg, s);
+            const int n_i = min(4, (u.R_total - rb + 3) >> 2);  // live values of i (uniform over the workgroup)
+            float m[4];
 #pragma unroll
-            for (int tile = 0; tile < 4; ++tile) mx = fmaxf(mx, valid[tile] ? s[tile][i] : -INFINITY);
+            for (int i = 0; i < 4; ++i) {
+                m[i] = -INFINITY;
+                if (i >= n_i) continue;
+                float mx = -INFINITY;
 #pragma unroll
-            for (int o = 1; o < 16; o <<= 1) mx = fmaxf(mx, __shfl_xor(mx, o, 64));
-            m[i] = mx;
-        }
-        __syncthreads();
-        if (n == 0) {
-#pragma unroll
-            for (int i = 0; i < 4; ++i) s_pm[wave][4 * i + c] = m[i];  // indexed by list row within the block
-        }
-        __syncthreads();
-        // chunk maximum of every row: the reference of the stashed exponentials
-        float z[4];
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            z[i] = 0.f;
-            if (i >= n_i) continue;
-            const int r = 4 * i + c;
-            const float M = fmaxf(fmaxf(s_pm[0][r], s_pm[1][r]), fmaxf(s_pm[2][r], s_pm[3][r]));
-            float zz = 0.f;
-#pragma unroll
-            for (int tile = 0; tile < 4; ++tile) {
-                const float e = valid[tile] ? expf(s[tile][i] - M) : 0.f;
-                zz += e;
-                if (stash && rb + r < u.R_total)
-                    stash_base[(int64_t)(rb + r) * kChunkKeys + wave * 64 + 16 * tile + n] = e;
+                for (int tile = 0; tile < 4; ++tile) mx = fmaxf(mx, valid[tile] ? s[tile][i] : -INFINITY);
+                m[i] = max16(mx);
             }
+            lds_barrier();
+            if (n == 0) {
 #pragma unroll
-            for (int o = 1; o < 16; o <<= 1) zz += __shfl_xor(zz, o, 64);
-            z[i] = zz;
-            if (wave == 0 && n == 0) s_mw[r] = M;
-        }
-        if (n == 0) {
+                for (int i = 0; i < 4; ++i) s_pm[wave][4 * i + c] = m[i];  // indexed by list row within the block
+            }
+            lds_barrier();
+            // chunk maximum of every row: the reference of the stashed exponentials
+            float z[4];
 #pragma unroll
-            for (int i = 0; i < 4; ++i) s_pz[wave][4 * i + c] = z[i];
+            for (int i = 0; i < 4; ++i) {
+                z[i] = 0.f;
+                if (i >= n_i) continue;
+                const int r = 4 * i + c;
+                const float M = fmaxf(fmaxf(s_pm[0][r], s_pm[1][r]), fmaxf(s_pm[2][r], s_pm[3][r]));
+                f32x4 e;
+#pragma unroll
+                for (int tile = 0; tile < 4; ++tile) e[tile] = valid[tile] ? exp_raw(s[tile][i] - M) : 0.f;
+                float zz = (e[0] + e[1]) + (e[2] + e[3]);
+                if (stash && rb + r < u.R_total)
+                    *reinterpret_cast<f32x4 *>(stash_base + (int64_t)(rb + r) * kChunkKeys + wave * 64 + 4 * n) = e;
+                z[i] = sum16(zz);
+                if (wave == 0 && n == 0) s_mw[r] = M;
+            }
+            if (n == 0) {
+#pragma unroll
+                for (int i = 0; i < 4; ++i) s_pz[wave][4 * i + c] = z[i];
+            }
+            lds_barrier();
+            if (tid < 16 && rb + tid < u.R_total) {
+                const int rho = rb + tid;
+                const float Z = (s_pz[0][tid] + s_pz[1][tid]) + (s_pz[2][tid] + s_pz[3][tid]);
+                const int g = head_of_row(s_pref, u.G, rho);
+                const int64_t slot = (u.hrow0 + g) * u.W + (rho - s_pref[g]);
+                t.part[slot * dm.n_chunks + chunk] = make_float2(s_mw[tid], Z);
+            }
         }
-        __syncthreads();
-        if (tid < 16 && rb + tid < u.R_total) {
-            const int rho = rb + tid;
-            const float Z = (s_pz[0][tid] + s_pz[1][tid]) + (s_pz[2][tid] + s_pz[3][tid]);
-            const int g = head_of_row(s_pref, u.G, rho);
-            const int64_t slot = (u.hrow0 + g) * u.W + (rho - s_pref[g]);
-            t.part[slot * dm.n_chunks + u.chunk] = make_float2(s_mw[tid], Z);
+#pragma unroll
+        for (int tile = 0; tile < 4; ++tile) {
+            valid[tile] = vnext[tile];
+#pragma unroll
+            for (int sl = 0; sl < 4; ++sl) kreg[tile][sl] = knext[tile][sl];
         }
     }
 }
@@ -231,18 +266,18 @@ __global__ __launch_bounds__(256) void score_rows_mfma_kernel(Dims dm, DevTables
         double Z = 0.0;
         for (int cc = lane; cc < nch; cc += 64) {
             const float2 x = p[cc];
-            Z += (double)(x.y * expf(x.x - M));
+            Z += (double)(x.y * exp_raw(x.x - M));
         }
         Z = wave_sum(Z);
-        Z += (double)(t.row_ztext[slot] * expf(mt - M));
+        Z += (double)(t.row_ztext[slot] * exp_raw(mt - M));
         const float w = (float)(1.0 / ((double)(s_pref[g + 1] - s_pref[g]) * (double)G * Z));
         if (lane == 0) {
-            t.row_M[slot] = M;
+            t.row_M[slot] = M;  // raw units
             t.row_w[slot] = w;
         }
         if (stash) {
             float *f = t.row_f + (unit * kStashRows + rho) * dm.n_chunks;
-            for (int cc = lane; cc < nch; cc += 64) f[cc] = w * expf(p[cc].x - M);
+            for (int cc = lane; cc < nch; cc += 64) f[cc] = w * exp_raw(p[cc].x - M);
         }
     }
 }
@@ -255,24 +290,7 @@ __global__ __launch_bounds__(256) void score_finish_kernel(Dims dm, DevTables t,
                                                            air_strides st) {
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, n = lane & 15, c = lane >> 4;
     UnitCtx u;
-    {
-        const int first = blockIdx.x * kFinishChunks;
-        const int uu = blockIdx.y;
-        u.kvh = uu % dm.Hkv;
-        u.b = (uu / dm.Hkv) % dm.B;
-        u.li = uu / (dm.Hkv * dm.B);
-        u.l = l0 + u.li;
-        u.sq = t.seq_tab[u.b];
-        if (first * kChunkKeys >= u.sq.vis_len) return;
-        u.chunk = first;
-        u.t0 = u.sq.vis_start + u.sq.vis_len;
-        u.G = dm.G;
-        u.W = dm.max_window;
-        u.q = (const bf16_t *)ll.p[u.li].q + (int64_t)u.b * st.q_b;
-        u.k = (const bf16_t *)ll.p[u.li].k + (int64_t)u.b * st.kv_b + (int64_t)u.kvh * st.kv_h;
-        u.hrow0 = ((int64_t)u.l * dm.B + u.b) * dm.Hq + (int64_t)u.kvh * u.G;
-        u.unit = ((int64_t)u.l * dm.B + u.b) * dm.Hkv + u.kvh;
-    }
+    if (!unit_setup(dm, t, l0, ll, st, u, kFinishChunks)) return;
     __shared__ int s_pref[17];
     __shared__ float s_M[kRowsLds], s_w[kRowsLds];
     __shared__ float s_f[kFinishChunks][kStashRows];
@@ -309,7 +327,7 @@ __global__ __launch_bounds__(256) void score_finish_kernel(Dims dm, DevTables t,
         float e[kFinishChunks][kStashRows];
 #pragma unroll
         for (int ci = 0; ci < kFinishChunks; ++ci) {
-            const float *sb = t.stash + ((u.unit * dm.n_chunks + first + ci) * (int64_t)kStashRows) * kChunkKeys + tid;
+            const float *sb = t.stash + ((u.unit * dm.n_chunks + first + ci) * (int64_t)kStashRows) * kChunkKeys + stash_pos(tid);
 #pragma unroll
             for (int r = 0; r < kStashRows; ++r)
                 e[ci][r] = (first + ci < last && r < u.R_total) ? sb[(int64_t)r * kChunkKeys] : 0.f;
@@ -370,7 +388,7 @@ __global__ __launch_bounds__(256) void score_finish_kernel(Dims dm, DevTables t,
                     const float M = have ? s_M[rr] : 0.f;
                     const float w = have ? s_w[rr] : 0.f;
 #pragma unroll
-                    for (int tile = 0; tile < 4; ++tile) acc[tile] = fmaf(w, expf(s[tile][i] - M), acc[tile]);
+                    for (int tile = 0; tile < 4; ++tile) acc[tile] = fmaf(w, exp_raw(s[tile][i] - M), acc[tile]);
                 }
             }
         }
@@ -395,7 +413,8 @@ __global__ __launch_bounds__(256) void score_finish_kernel(Dims dm, DevTables t,
 hipError_t launch_score_mfma(hipStream_t s, const Dims &dm, const DevTables &t, int pass, int l0, int nl,
                              const LaunchLayers &ll, const air_strides &st) {
     if (pass == 1)
-        hipLaunchKernelGGL(score_stream_kernel, dim3(dm.n_chunks, nl * dm.B * dm.Hkv), dim3(256), 0, s, dm, t, l0, ll, st);
+        hipLaunchKernelGGL(score_stream_kernel, dim3((dm.n_chunks + kStreamChunks - 1) / kStreamChunks, nl * dm.B * dm.Hkv),
+                           dim3(256), 0, s, dm, t, l0, ll, st);
     else {
         hipLaunchKernelGGL(score_rows_mfma_kernel, dim3(nl * dm.B * dm.Hkv), dim3(256), 0, s, dm, t, l0);
         hipError_t e = hipGetLastError();
