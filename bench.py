@@ -241,6 +241,7 @@ def main():
                    "decode_steps": n_dec, "decode_launch": "per-layer" if args.per_layer else "all-layers"},
         "compress_us_per_layer": compress_ms * 1e3 / L,
         "decode_tokens_per_s": w.batch * n_dec / (decode_ms * 1e-3),
+        "budgets_min_mean_max": [int(np.min(budgets)), float(np.mean(budgets)), int(np.max(budgets))],
         "stage_us": {"score": score_ms * 1e3, "budget": budget_ms * 1e3, "select_compact": select_ms * 1e3,
                      "decode_per_step": decode_ms * 1e3 / n_dec},
         "roofline": {"kernel": "air_decode_attn", "bound": "hbm", "achieved": dec_gbs, "peak": HBM_PEAK_GBS,

@@ -174,7 +174,7 @@ air_status air_create(const air_config *cfg, void *workspace, size_t workspace_b
     c->force_splits = c->force_waves = c->force_tiles = 0;
     if (const char *e = getenv("AIR_DECODE_TILES")) {
         const int v = atoi(e);
-        if (v == 4 || v == 8) c->force_tiles = v;
+        if (v == 2 || v == 4 || v == 8) c->force_tiles = v;
     }
     if (const char *e = getenv("AIR_DECODE_SPLITS")) {
         const int v = atoi(e);
@@ -297,7 +297,8 @@ air_status air_score(air_ctx *ctx, void *stream, int32_t l0, int32_t l1, const a
             ll.p[i].k = layers[c0 - l0 + i].k;
             ll.p[i].v = layers[c0 - l0 + i].v;
         }
-        hipError_t e = launch_elite(s, ctx->dm, ctx->tab, dt, c0, nl, ll, *strides, sa, ctx->cfg.alpha);
+        hipError_t e = mfma ? launch_elite_mfma(s, ctx->dm, ctx->tab, c0, nl, ll, *strides, sa, ctx->cfg.alpha)
+                            : launch_elite(s, ctx->dm, ctx->tab, dt, c0, nl, ll, *strides, sa, ctx->cfg.alpha);
         if (e == hipSuccess && !mfma) {
             e = launch_score_pass1(s, ctx->dm, ctx->tab, dt, c0, nl, ll, *strides);
             if (e == hipSuccess) e = launch_score_rows(s, ctx->dm, ctx->tab, c0, nl);
@@ -368,13 +369,14 @@ air_status air_select_compact(air_ctx *ctx, void *stream, int32_t l0, int32_t l1
 // Shape of one decode launch: `splits` workgroups of `waves` wavefronts per (layer, sequence, KV
 // head); a wave works in iterations of 16 * tiles keys.  Eight waves of 64-key iterations keep
 // every load of an iteration in flight within the 256 registers a lane has at that occupancy.
-// The waves of a workgroup merge through LDS; more than one split per unit (partials exchanged
-// through memory) is used only when the units alone cannot fill the chip or a wave would loop
-// many times.  AIR_DECODE_SPLITS / AIR_DECODE_WAVES / AIR_DECODE_TILES override the choice
-// (tuning aid).
+// The waves of a workgroup merge through LDS, which is cheap; further splits exchange partials
+// through memory (merged by the last workgroup to finish), which costs about as much as two
+// more iterations per wave, so they are added only while a wave would otherwise run more than
+// kItersPerWave iterations at the average cache length and the launch is short of workgroups.
+// AIR_DECODE_SPLITS / AIR_DECODE_WAVES / AIR_DECODE_TILES override the choice (tuning aid).
 static void decode_shape(const air_ctx *ctx, int n_layers_in_launch, int appended, int *splits, int *waves, int *tiles) {
+    constexpr int kItersPerWave = 3, kEnoughWorkgroups = 256;
     const air_config &c = ctx->cfg;
-    const int64_t units = (int64_t)n_layers_in_launch * c.batch * c.n_kv_heads;
     double avg_len = 0.0;
     for (int b = 0; b < c.batch; ++b) {
         const air_seq &s = ctx->seqs[b];
@@ -386,9 +388,9 @@ static void decode_shape(const air_ctx *ctx, int n_layers_in_launch, int appende
     if (ctx->force_waves > 0) w = ctx->force_waves;
     if (kt == 8 && w == 8) w = 4;
     const int64_t iters = (int64_t)((avg_len + 16.0 * kt - 1.0) / (16.0 * kt));
+    const int64_t units = (int64_t)n_layers_in_launch * c.batch * c.n_kv_heads;
     int64_t s = 1;
-    while (s < kMaxSplits && units * s < 256 && iters > (int64_t)w * s) s *= 2;           // fill the chip
-    while (s < kMaxSplits && iters > (int64_t)w * s * 8 && units * s < 2048) s *= 2;  // bound the loop length
+    while (s < kMaxSplits && iters > (int64_t)kItersPerWave * w * s && units * s < kEnoughWorkgroups) s *= 2;
     if (ctx->force_splits > 0) s = ctx->force_splits;
     *splits = (int)s;
     *waves = w;
@@ -533,14 +535,20 @@ air_status air_get_cache(air_ctx *ctx, int32_t l, int32_t b, int32_t h, void *k_
     const size_t esz = ctx->cfg.dtype == AIR_BF16 ? 2 : 4;
     const size_t row0 = ((size_t)b * ctx->dm.Hkv + h) * (size_t)ctx->dm.pool_rows + off;
     const size_t rb = (size_t)ctx->dm.D * esz;
-    st = d2h(ctx, k_host, (char *)ctx->tab.kcache + row0 * rb, (size_t)len * rb);
-    if (st != AIR_OK) return st;
-    if (!v_transposed(ctx->cfg.dtype, ctx->dm.D))
+    if (!v_transposed(ctx->cfg.dtype, ctx->dm.D)) {
+        st = d2h(ctx, k_host, (char *)ctx->tab.kcache + row0 * rb, (size_t)len * rb);
+        if (st != AIR_OK) return st;
         return d2h(ctx, v_host, (char *)ctx->tab.vcache + row0 * rb, (size_t)len * rb);
-    // block-transposed V': fetch whole 32-token blocks and put the tokens back in row order
+    }
+    // tiled K' and block-transposed V': fetch whole 32-token blocks and put the tokens back in row order
     const int D = ctx->dm.D;
     const size_t n_blk = ((size_t)len + 31) / 32;
     std::vector<uint16_t> raw(n_blk * 32 * D);
+    st = d2h(ctx, raw.data(), (char *)ctx->tab.kcache + row0 * rb, raw.size() * 2);
+    if (st != AIR_OK) return st;
+    uint16_t *kh = (uint16_t *)k_host;
+    for (int r = 0; r < len; ++r)
+        for (int col = 0; col < D; ++col) kh[(size_t)r * D + col] = raw[k_tiled(r, col)];
     st = d2h(ctx, raw.data(), (char *)ctx->tab.vcache + row0 * rb, raw.size() * 2);
     if (st != AIR_OK) return st;
     uint16_t *vh = (uint16_t *)v_host;

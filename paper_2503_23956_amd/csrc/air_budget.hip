@@ -37,8 +37,9 @@ __global__ __launch_bounds__(kBT) void budget_kernel(Dims dm, DevTables t, doubl
     const bool stage = L * dm.Hkv <= AIR_MAX_LAYERS * 16;  // unit statistics fit the LDS staging arrays
     if (!skip_allocation) {
         if (use_moments) {
-            // Eq.9-10 of every (layer, KV head) from the per-chunk power sums of the importance row
-            const int nch = (n_vis + kChunkKeys - 1) / kChunkKeys;
+            // Eq.9-10 of every (layer, KV head) from the power sums of the importance row (one entry per
+            // kFinishChunks chunks)
+            const int nch = ((n_vis + kChunkKeys - 1) / kChunkKeys + kFinishChunks - 1) / kFinishChunks;  // entries per unit
             for (int p = tid; p < L * dm.Hkv; p += kBT) {
                 const int l = p / dm.Hkv, h = p % dm.Hkv;
                 const int64_t unit = ((int64_t)l * dm.B + b) * dm.Hkv + h;

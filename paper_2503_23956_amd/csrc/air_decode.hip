@@ -1,8 +1,8 @@
 // air_decode_attn: Eq.2 append, then softmax(q K'^T / sqrt(d)) V' over the compacted cache.
 //
 //   decode_mfma_kernel bf16, head_dim 128, ONE launch per call: one wavefront per (split, unit).
-//                      K' rows and the block-transposed V' go from global memory straight into
-//                      MFMA operands; the G query heads of the group are the second MFMA
+//                      The tiled K' and the block-transposed V' go from global memory straight into
+//                      MFMA operands, every load instruction reading 1 KB of consecutive memory; the G query heads of the group are the second MFMA
 //                      dimension.  The wave whose key range holds the new token takes it from
 //                      k_new / v_new and stores it into the cache (Eq.2); the wave of a unit that
 //                      finishes last merges the unit's split-K partials.
@@ -78,6 +78,13 @@ __global__ __launch_bounds__(128) void append_kernel(Dims dm, DevTables t, int l
 //   probabilities of head n: exactly the A operand of P*V for the block when the block's tokens
 //   are stored in v_slot order.  B of P*V = 16 bytes of the transposed V' block per lane, and the
 //   accumulator of output tile j keeps heads 4c..4c+3 of column 16j + n.
+// The kernel is bound by instruction issue as much as by memory when there are few units, so the
+// key loop carries no predication: tiles past the end of the range re-read the last valid tile
+// (their scores are masked, in the one iteration that has a tail), and the token this call appends
+// (Eq.2) is not read through the cache at all: one wave of the split that owns its row scores it
+// from k_new / v_new on the vector ALU and stores it into the cache.
+// Softmax runs in the base-2 domain: logits are scaled by log2(e)/sqrt(d) and exponentiated with
+// exp2; running maxima and the exchanged partial maxima are in that domain.
 // The waves of a workgroup merge through LDS.  With more than one split per unit the
 // workgroups exchange partials through memory and the one that finishes last merges them.
 // ---------------------------------------------------------------------------------------
@@ -98,9 +105,10 @@ __global__ __launch_bounds__(64 * NW) void decode_mfma_kernel(Dims dm, DevTables
     const int l = l0 + li;
     const int G = dm.G;
     const int len = t.base_len[(int64_t)b * dm.L + l] + ll.appended[li] + 1;
-    const int newrow = len - 1;  // the token appended by this call (Eq.2): read from k_new / v_new, stored to the cache
+    const int newrow = len - 1;  // the token appended by this call (Eq.2): scored from k_new / v_new, stored to the cache
     int k0, k1;
     split_range(len, splits, split, k0, k1);
+    const int kend = min(k1, newrow);  // the split's keys that are in the cache: [k0, kend)
     const int64_t row0 = ((int64_t)b * dm.Hkv + kvh) * dm.pool_rows + t.layer_off[(int64_t)b * dm.L + l];
     bf16_t *kc = (bf16_t *)t.kcache + row0 * D;
     bf16_t *vc = (bf16_t *)t.vcache + row0 * D;
@@ -118,36 +126,30 @@ __global__ __launch_bounds__(64 * NW) void decode_mfma_kernel(Dims dm, DevTables
             qb[s] = __builtin_bit_cast(bf16x8, x);
         }
     }
-    const float scale = 0.08838834764831845f;  // 1/sqrt(128)
+    constexpr float kScale2 = 0.08838834764831845f * 1.4426950408889634f;  // log2(e) / sqrt(128)
     float m_run = -INFINITY, l_run = 0.f;
     f32x4 acc[8];
 #pragma unroll
     for (int j = 0; j < 8; ++j) acc[j] = (f32x4){0.f, 0.f, 0.f, 0.f};
 
-    for (int kb = k0 + wave * kIter; kb < k1; kb += NW * kIter) {
-        // ---- all loads of the iteration go out first: K' rows of the KT score tiles ...
+    const int last16 = (kend - 1) & ~15, last32 = (kend - 1) & ~31;  // last tile / block with a cached key
+    const int kb_first = k0 + wave * kIter;
+    for (int kb = kb_first; kb < kend; kb += NW * kIter) {
+        // ---- all loads of the iteration go out first: the KT score tiles of K' ...
         uint4 a[KT][4];
 #pragma unroll
         for (int tile = 0; tile < KT; ++tile) {
-            const int key = kb + 16 * tile + n;
-            const bf16_t *src = (key == newrow) ? k_new + new_src : kc + (int64_t)key * D;
+            const bf16_t *src = kc + (int64_t)min(kb + 16 * tile, last16) * D + 128 * c + 8 * n;
 #pragma unroll
-            for (int sl = 0; sl < 4; ++sl) {
-                a[tile][sl] = make_uint4(0, 0, 0, 0);
-                if (key < k1) a[tile][sl] = *reinterpret_cast<const uint4 *>(src + 32 * sl + 8 * c);
-            }
+            for (int sl = 0; sl < 4; ++sl) a[tile][sl] = *reinterpret_cast<const uint4 *>(src + 512 * sl);
         }
         // ... and the V' operands of the TB token blocks
         uint4 vb[TB][8];
 #pragma unroll
         for (int tb = 0; tb < TB; ++tb) {
-            const int blk0 = kb + 32 * tb;
+            const bf16_t *src = vc + (int64_t)min(kb + 32 * tb, last32) * D + 32 * n + 8 * c;
 #pragma unroll
-            for (int j = 0; j < 8; ++j) {
-                vb[tb][j] = make_uint4(0, 0, 0, 0);
-                if (blk0 < k1)
-                    vb[tb][j] = *reinterpret_cast<const uint4 *>(vc + (int64_t)blk0 * D + (16 * j + n) * 32 + 8 * c);
-            }
+            for (int j = 0; j < 8; ++j) vb[tb][j] = *reinterpret_cast<const uint4 *>(src + 512 * j);
         }
         // ---- scores^T
         f32x4 s[KT];
@@ -158,71 +160,44 @@ __global__ __launch_bounds__(64 * NW) void decode_mfma_kernel(Dims dm, DevTables
             for (int sl = 0; sl < 4; ++sl)
                 s[tile] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a[tile][sl]), qb[sl], s[tile], 0, 0, 0);
         }
-        // ---- the block that receives the new token (only in the split that owns the row): put v_new
-        // into its slot; a token that opens a block also clears the block's other slots.  The patched
-        // operands go back to the cache, and so does the new K' row.
-        if (kb <= newrow && newrow < kb + kIter && newrow < k1) {
-            const int tbn = (newrow - kb) >> 5;
-            const int tok = (newrow - kb) & 31, slot = v_slot(tok);
-            const bool fresh = tok == 0, mine = c == (slot >> 3);
+        if (kb + kIter > kend) {  // the iteration with the tail (uniform over the wave)
 #pragma unroll
-            for (int tb = 0; tb < TB; ++tb) {
-                if (tb != tbn) continue;
+            for (int tile = 0; tile < KT; ++tile)
 #pragma unroll
-                for (int j = 0; j < 8; ++j) {
-                    uint4 x = fresh ? make_uint4(0, 0, 0, 0) : vb[tb][j];
-                    if (mine) {
-                        const uint32_t val = v_new[new_src + 16 * j + n];
-                        uint32_t w[4] = {x.x, x.y, x.z, x.w};
-                        const int e = slot & 7;
-#pragma unroll
-                        for (int q4 = 0; q4 < 4; ++q4)
-                            if ((e >> 1) == q4) w[q4] = (e & 1) ? ((w[q4] & 0x0000ffffu) | (val << 16)) : ((w[q4] & 0xffff0000u) | val);
-                        x = make_uint4(w[0], w[1], w[2], w[3]);
-                    }
-                    vb[tb][j] = x;
-                    if (fresh || mine)
-                        *reinterpret_cast<uint4 *>(vc + (int64_t)(kb + 32 * tb) * D + (16 * j + n) * 32 + 8 * c) = x;
-                }
-            }
-            if (lane < 16)  // the new K' row: 16 lanes x 16 bytes
-                *reinterpret_cast<uint4 *>(kc + (int64_t)newrow * D + 8 * lane) =
-                    *reinterpret_cast<const uint4 *>(k_new + new_src + 8 * lane);
+                for (int i = 0; i < 4; ++i)
+                    if (kb + 16 * tile + 4 * c + i >= kend) s[tile][i] = -INFINITY;
         }
         // ---- online softmax for head n over the keys this lane holds (4c+i of each tile)
-        float mb = -INFINITY;
+        float mb = s[0][0];
 #pragma unroll
         for (int tile = 0; tile < KT; ++tile)
 #pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                const int key = kb + 16 * tile + 4 * c + i;
-                const float v = key < k1 ? s[tile][i] * scale : -INFINITY;
-                s[tile][i] = v;
-                mb = fmaxf(mb, v);
-            }
+            for (int i = 0; i < 4; ++i) mb = fmaxf(mb, s[tile][i]);
         mb = fmaxf(mb, __shfl_xor(mb, 16, 64));
         mb = fmaxf(mb, __shfl_xor(mb, 32, 64));
-        const float m_new = fmaxf(m_run, mb);
-        const float corr = __expf(m_run - m_new);
+        const float m_new = fmaxf(m_run, mb * kScale2);  // finite: key kb is valid
+        const float corr = __builtin_amdgcn_exp2f(m_run - m_new);
         float lb = 0.f;
 #pragma unroll
         for (int tile = 0; tile < KT; ++tile)
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
-                const float p = __expf(s[tile][i] - m_new);
+                const float p = __builtin_amdgcn_exp2f(fmaf(s[tile][i], kScale2, -m_new));
                 s[tile][i] = p;
                 lb += p;
             }
         lb += __shfl_xor(lb, 16, 64);
         lb += __shfl_xor(lb, 32, 64);
-        l_run = l_run * corr + lb;
+        l_run = fmaf(l_run, corr, lb);
         m_run = m_new;
         // accumulator rows are heads 4c..4c+3: fetch their rescale factors from lanes 4c+i
+        if (kb != kb_first && __ballot(corr != 1.0f) != 0ull) {
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            const float f = __shfl(corr, 4 * c + i, 64);
+            for (int i = 0; i < 4; ++i) {
+                const float f = __shfl(corr, 4 * c + i, 64);
 #pragma unroll
-            for (int j = 0; j < 8; ++j) acc[j][i] *= f;
+                for (int j = 0; j < 8; ++j) acc[j][i] *= f;
+            }
         }
         // ---- P * V
 #pragma unroll
@@ -239,48 +214,106 @@ __global__ __launch_bounds__(64 * NW) void decode_mfma_kernel(Dims dm, DevTables
         }
     }
 
-    // ---- merge the NW waves of the workgroup through LDS: wave w ends up with output tiles
-    // w, w+NW, ... (heads 4c..4c+3, column 16j+n) summed over all waves, plus the merged (max, sum)
+    // ---- the appended token (Eq.2): the wave of the owning split that would take the next chunk.
+    // Score of head n on the vector ALU, folded into the running softmax with fp32 probabilities,
+    // then the row goes into the cache: K' into its places of the tile, V' into its slot of the
+    // block (a token that opens a block writes the block's other slots as zeros).  Other waves and
+    // splits never use these places in this launch: their reads of them are masked or carry zero
+    // probability.
+    if (newrow >= k0 && newrow < k1 && wave == ((kend - k0 + kIter - 1) / kIter) % NW) {
+        float sn = 0.f;
+#pragma unroll
+        for (int sl = 0; sl < 4; ++sl) {
+            const uint4 kx = *reinterpret_cast<const uint4 *>(k_new + new_src + 32 * sl + 8 * c);
+            const uint4 qx = __builtin_bit_cast(uint4, qb[sl]);
+            const uint32_t kw[4] = {kx.x, kx.y, kx.z, kx.w}, qw[4] = {qx.x, qx.y, qx.z, qx.w};
+#pragma unroll
+            for (int w4 = 0; w4 < 4; ++w4) {
+                sn = fmaf(__uint_as_float(qw[w4] << 16), __uint_as_float(kw[w4] << 16), sn);
+                sn = fmaf(__uint_as_float(qw[w4] & 0xffff0000u), __uint_as_float(kw[w4] & 0xffff0000u), sn);
+            }
+        }
+        sn += __shfl_xor(sn, 16, 64);
+        sn += __shfl_xor(sn, 32, 64);
+        sn *= kScale2;
+        const float m_new = fmaxf(m_run, sn);
+        const float corr = __builtin_amdgcn_exp2f(m_run - m_new);
+        const float pn = __builtin_amdgcn_exp2f(sn - m_new);
+        l_run = fmaf(l_run, corr, pn);
+        m_run = m_new;
+        float vn[8];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) vn[j] = bf16_bits_to_float(v_new[new_src + 16 * j + n]);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const float f = __shfl(corr, 4 * c + i, 64), pp = __shfl(pn, 4 * c + i, 64);
+#pragma unroll
+            for (int j = 0; j < 8; ++j) acc[j][i] = fmaf(acc[j][i], f, pp * vn[j]);
+        }
+        if (lane < 16)  // the new K' row: 16 lanes x 16 bytes into the row's places of its tile
+            *reinterpret_cast<uint4 *>(kc + k_tiled(newrow, 8 * lane)) =
+                *reinterpret_cast<const uint4 *>(k_new + new_src + 8 * lane);
+        const int tok = newrow & 31, slot = v_slot(tok);
+#pragma unroll
+        for (int h2 = 0; h2 < 2; ++h2) {
+            const int col = lane + 64 * h2;
+            bf16_t *vrow = vc + (int64_t)(newrow & ~31) * D + col * 32;
+            const bf16_t val = v_new[new_src + col];
+            if (tok == 0) {  // slot 0 of a new block
+                const uint4 z = make_uint4(0, 0, 0, 0);
+                reinterpret_cast<uint4 *>(vrow)[0] = make_uint4(val, 0, 0, 0);
+                reinterpret_cast<uint4 *>(vrow)[1] = z;
+                reinterpret_cast<uint4 *>(vrow)[2] = z;
+                reinterpret_cast<uint4 *>(vrow)[3] = z;
+            } else {
+                vrow[slot] = val;
+            }
+        }
+    }
+
+    // ---- merge the NW waves of the workgroup through LDS.  Every wave first rescales its partial
+    // to the workgroup's maximum, so that the merge is a plain sum: wave w ends up with output
+    // tiles w, w+NW, ... (heads 4c..4c+3, column 16j+n), plus the merged (max, sum) of those heads.
     __shared__ f32x4 s_acc[NW][8][64];
-    __shared__ float s_mw[NW][kMaxGroup], s_lw[NW][kMaxGroup];
+    __shared__ float s_mw[kMaxGroup][NW], s_lw[kMaxGroup][NW];
     __shared__ int s_prev;
     float mrg_m[4], mrg_l[4];  // merged max / sum of heads 4c+i
     if (NW > 1) {
-#pragma unroll
-        for (int j = 0; j < 8; ++j) s_acc[wave][j][lane] = acc[j];
-        if (c == 0) {
-            s_mw[wave][n] = m_run;
-            s_lw[wave][n] = l_run;
-        }
+        if (c == 0) s_mw[n][wave] = m_run;
         __syncthreads();
-        float wgt[NW][4];
+        float M = s_mw[n][0];
+#pragma unroll
+        for (int w = 1; w < NW; ++w) M = fmaxf(M, s_mw[n][w]);
+        const float f = m_run == -INFINITY ? 0.f : __builtin_amdgcn_exp2f(m_run - M);
+        if (c == 0) s_lw[n][wave] = l_run * f;
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
-            const int g = 4 * c + i;
-            float M = -INFINITY;
+            const float fi = __shfl(f, 4 * c + i, 64);
+            mrg_m[i] = __shfl(M, 4 * c + i, 64);
 #pragma unroll
-            for (int w = 0; w < NW; ++w) M = fmaxf(M, s_mw[w][g]);
-            float Lsum = 0.f;
-#pragma unroll
-            for (int w = 0; w < NW; ++w) {
-                const float lw = s_lw[w][g];
-                wgt[w][i] = lw > 0.f ? __expf(s_mw[w][g] - M) : 0.f;
-                Lsum = fmaf(wgt[w][i], lw, Lsum);
-            }
-            mrg_m[i] = M;
-            mrg_l[i] = Lsum;
+            for (int j = 0; j < 8; ++j) acc[j][i] *= fi;
         }
+#pragma unroll
+        for (int j = 0; j < 8; ++j) s_acc[wave][j][lane] = acc[j];
+        __syncthreads();
 #pragma unroll
         for (int jj = 0; jj < 8 / NW; ++jj) {
             const int j = wave + NW * jj;
-            f32x4 sum = (f32x4){0.f, 0.f, 0.f, 0.f};
+            f32x4 sum = s_acc[0][j][lane];
 #pragma unroll
-            for (int w = 0; w < NW; ++w) {
+            for (int w = 1; w < NW; ++w) {
                 const f32x4 x = s_acc[w][j][lane];
 #pragma unroll
-                for (int i = 0; i < 4; ++i) sum[i] = fmaf(wgt[w][i], x[i], sum[i]);
+                for (int i = 0; i < 4; ++i) sum[i] += x[i];
             }
             acc[jj] = sum;  // tile wave + NW*jj
+        }
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            float Lsum = s_lw[4 * c + i][0];
+#pragma unroll
+            for (int w = 1; w < NW; ++w) Lsum += s_lw[4 * c + i][w];
+            mrg_l[i] = Lsum;
         }
     } else {
 #pragma unroll
@@ -296,7 +329,7 @@ __global__ __launch_bounds__(64 * NW) void decode_mfma_kernel(Dims dm, DevTables
         for (int i = 0; i < 4; ++i) {
             const int g = 4 * c + i;
             if (g < G) {
-                const float inv = 1.0f / mrg_l[i];
+                const float inv = __builtin_amdgcn_rcpf(mrg_l[i]);
 #pragma unroll
                 for (int jj = 0; jj < kTiles; ++jj)
                     o_unit[g * D + 16 * (wave + NW * jj) + n] = float_to_bf16_bits(acc[jj][i] * inv);
@@ -357,7 +390,7 @@ __global__ __launch_bounds__(64 * NW) void decode_mfma_kernel(Dims dm, DevTables
         for (int s2 = 0; s2 < splits; ++s2) M = fmaxf(M, s_m[s2][g]);
         float den = 0.f;
         for (int s2 = 0; s2 < splits; ++s2) {
-            const float wg = s_l[s2][g] > 0.f ? __expf(s_m[s2][g] - M) : 0.f;
+            const float wg = s_l[s2][g] > 0.f ? __builtin_amdgcn_exp2f(s_m[s2][g] - M) : 0.f;
             s_w[s2][g] = wg;
             den = fmaf(wg, s_l[s2][g], den);
         }
@@ -575,6 +608,10 @@ hipError_t launch_decode(hipStream_t s, const Dims &dm, const DevTables &t, int 
         else if (waves == 4 && tiles == 4) AIR_LAUNCH_DECODE(4, 4);
         else if (waves == 2 && tiles == 4) AIR_LAUNCH_DECODE(2, 4);
         else if (waves == 1 && tiles == 4) AIR_LAUNCH_DECODE(1, 4);
+        else if (waves == 8 && tiles == 2) AIR_LAUNCH_DECODE(8, 2);
+        else if (waves == 4 && tiles == 2) AIR_LAUNCH_DECODE(4, 2);
+        else if (waves == 2 && tiles == 2) AIR_LAUNCH_DECODE(2, 2);
+        else if (waves == 1 && tiles == 2) AIR_LAUNCH_DECODE(1, 2);
         else if (waves == 4) AIR_LAUNCH_DECODE(4, 8);
         else if (waves == 2) AIR_LAUNCH_DECODE(2, 8);
         else AIR_LAUNCH_DECODE(1, 8);

@@ -14,6 +14,7 @@ constexpr int kMaxLayersPerLaunch = 32;
 constexpr int kMaxSplits = 16;        // largest split-K factor of the decode attention
 constexpr int kCacheRowAlign = 32;    // layer regions of the compacted cache start on multiples of this
 constexpr int kGatherRows = 32;       // rows copied per workgroup in the compaction gather
+constexpr int kFinishChunks = 4;      // chunks finished (and summed into one power-sum entry) per workgroup of air_score's last kernel
 constexpr int kStashRows = 32;        // window rows per unit up to which air_score stashes exponentials (one pass over K_v)
 
 struct LayerPtrs {
@@ -72,6 +73,8 @@ hipError_t launch_score_rows(hipStream_t s, const Dims &dm, const DevTables &t, 
 hipError_t launch_score_pass2(hipStream_t s, const Dims &dm, const DevTables &t, int dtype, int l0, int nl,
                               const LaunchLayers &ll, const air_strides &st);
 hipError_t launch_stats(hipStream_t s, const Dims &dm, const DevTables &t, int l0, int nl);
+hipError_t launch_elite_mfma(hipStream_t s, const Dims &dm, const DevTables &t, int l0, int nl, const LaunchLayers &ll,
+                             const air_strides &st, const SeqArgs &seqs, double alpha);
 hipError_t launch_score_mfma(hipStream_t s, const Dims &dm, const DevTables &t, int pass, int l0, int nl,
                              const LaunchLayers &ll, const air_strides &st);
 hipError_t launch_budget(hipStream_t s, const Dims &dm, const DevTables &t, double retention, int mode,
@@ -89,5 +92,12 @@ hipError_t launch_decode(hipStream_t s, const Dims &dm, const DevTables &t, int 
 // after the two 16-key score tiles of a block are exactly the 8 contraction slots it must supply.
 inline bool v_transposed(int dtype, int head_dim) { return dtype == AIR_BF16 && head_dim == 128; }
 __host__ __device__ inline int v_slot(int t) { return ((t & 15) >> 2) * 8 + (t >> 4) * 4 + (t & 3); }
+// The same cache keeps K' in tiles of 16 tokens, [4 slices][4 parts][16 tokens][8 elements]: element
+// e of token r sits at k_tiled(r, e) elements from the unit's base.  Lane (token n, part c) of a
+// wave then finds the 16 bytes it feeds to MFMA for slice sl at byte 1024 sl + 256 c + 16 n of the
+// tile: each of the four loads of a tile covers 1 KB of consecutive memory.
+__host__ __device__ inline int64_t k_tiled(int64_t r, int e) {
+    return (r >> 4) * 2048 + (e >> 5) * 512 + ((e >> 3) & 3) * 128 + (r & 15) * 8 + (e & 7);
+}
 
 }  // namespace air

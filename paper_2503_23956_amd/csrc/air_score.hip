@@ -1,7 +1,7 @@
 // air_score: Alg.1 first loop (Eq.4-10).
 //
 // Kernels, in stream order, for a range of layers:
-//   elite_kernel       Eq.4 (last row) + Eq.5: elite index set of every query head, and the
+//   elite_kernel       Eq.4 (last row) + Eq.5: elite index set of every query head (one workgroup per KV group), and the
 //                      contribution of the elite text keys to each elite row's softmax.
 //   score_pass1_kernel Eq.6-7: per 256-key chunk of K_v, the running (max, sum-exp) of every
 //                      elite row.
@@ -17,148 +17,175 @@ namespace air {
 constexpr int kRowBlock = 8;  // elite rows scored together per pass over the registers holding a key
 
 // ---------------------------------------------------------------------------------------
-// Eq.4-5.  One workgroup per (query head, sequence, layer).  The decision of Eq.5 is taken
-// in fp64: exp(s_j - max_j s) >= alpha, the form in which the softmax normaliser of Eq.4 has
-// cancelled.
+// Eq.4-5.  One workgroup per (KV head, sequence, layer): the candidate text keys are read once
+// for all G query heads of the group.  The decision of Eq.5 is taken in fp64:
+// exp(s_j - max_j s) >= alpha, the form in which the softmax normaliser of Eq.4 has cancelled.
+//   phase 1 (all threads): last-row logits of every head of the batch against every candidate,
+//           16 lanes per candidate key (coalesced row reads), D/16 elements per lane, fp64.
+//   phase 2 (one wave per head): maximum, threshold, ordered compaction of the elite positions,
+//           then the elite-text columns of Eq.7 for that head's elite rows.
+// Heads are processed in batches of `gb` so that gb * max_window logits fit the LDS.
 // ---------------------------------------------------------------------------------------
+__device__ __forceinline__ double sum16_f64(double v) {
+    // all-reduce over 16 consecutive lanes, DPP on the two halves of the double
+#define AIR_DPP_F64(ctrl)                                                                                  \
+    {                                                                                                      \
+        const unsigned long long u = __builtin_bit_cast(unsigned long long, v);                            \
+        const int lo = __builtin_amdgcn_update_dpp(0, (int)(unsigned)u, (ctrl), 0xf, 0xf, false);           \
+        const int hi = __builtin_amdgcn_update_dpp(0, (int)(unsigned)(u >> 32), (ctrl), 0xf, 0xf, false);   \
+        v += __builtin_bit_cast(double, ((unsigned long long)(unsigned)hi << 32) | (unsigned)lo);           \
+    }
+    AIR_DPP_F64(0xB1)
+    AIR_DPP_F64(0x4E)
+    AIR_DPP_F64(0x141)
+    AIR_DPP_F64(0x140)
+#undef AIR_DPP_F64
+    return v;
+}
+
 template <typename T, int D>
 __global__ __launch_bounds__(256) void elite_kernel(Dims dm, DevTables t, int l0, LaunchLayers ll, air_strides st,
-                                                    SeqArgs seqs, double alpha) {
-    const int tid = threadIdx.x;
-    const int h = blockIdx.x, b = blockIdx.y, li = blockIdx.z;
+                                                    SeqArgs seqs, double alpha, int gb) {
+    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+    const int kvh = blockIdx.x, b = blockIdx.y, li = blockIdx.z;
     const int l = l0 + li;
     const air_seq sq = seqs.s[b];
-    if (li == 0 && h == 0 && tid == 0) t.seq_tab[b] = sq;
+    if (li == 0 && kvh == 0 && tid == 0) t.seq_tab[b] = sq;
     const int t0 = sq.vis_start + sq.vis_len;
-    const int kvh = h / dm.G;
-    const T *q = (const T *)ll.p[li].q + (int64_t)b * st.q_b + (int64_t)h * st.q_h;
+    const int G = dm.G, W = dm.max_window, wl = sq.win_len;
+    const T *qb = (const T *)ll.p[li].q + (int64_t)b * st.q_b;
     const T *k = (const T *)ll.p[li].k + (int64_t)b * st.kv_b + (int64_t)kvh * st.kv_h;
-    const int64_t hrow = ((int64_t)l * dm.B + b) * dm.Hq + h;
-    const int W = dm.max_window;
-    const int wl = sq.win_len;
-
-    extern __shared__ double s_dyn[];  // max_window doubles (last-row logits), then max_window ints (elite list)
-    double *s_logit = s_dyn;
-    int *s_elite = reinterpret_cast<int *>(s_dyn + W);
-    __shared__ double s_red[4];
-    __shared__ int s_cnt[5];
-
     const int ref = sq.win_start + wl - 1;
-    // last-row logits in fp64: 16 lanes per candidate key (coalesced row reads), D/16 elements per
-    // lane, 16 candidates per round of the workgroup, 8 rounds of loads in flight
-    constexpr int E = D / 16, UN = 8;
+
+    extern __shared__ double s_dyn[];  // gb * max_window doubles (last-row logits), then as many ints (elite lists)
+    double *s_logit = s_dyn;
+    int *s_elite = reinterpret_cast<int *>(s_dyn + (size_t)gb * W);
+
+    constexpr int E = D / 16, UN = 4, HB = 8;  // elements per lane, candidate rounds in flight, heads per register batch
     const int sub = tid & 15, grp = tid >> 4;
-    double qd[E];
-    {
-        T tmp[E];
-        __builtin_memcpy(tmp, __builtin_assume_aligned(q + (int64_t)(ref - t0) * st.q_t + sub * E, sizeof(T) * E), sizeof(tmp));
-#pragma unroll
-        for (int e = 0; e < E; ++e) qd[e] = (double)ldf(&tmp[e]);
-    }
     const double sqrt_d = sqrt((double)D);
-    for (int j0 = 0; j0 < wl; j0 += 16 * UN) {
-        T kv[UN][E];
-#pragma unroll
-        for (int un = 0; un < UN; ++un) {
-            const int j = j0 + un * 16 + grp;
-            if (j < wl)
-                __builtin_memcpy(kv[un], __builtin_assume_aligned(k + (int64_t)(sq.win_start + j) * st.kv_t + sub * E, sizeof(T) * E),
-                                 sizeof(kv[un]));
-        }
-#pragma unroll
-        for (int un = 0; un < UN; ++un) {
-            const int j = j0 + un * 16 + grp;
-            double acc = 0.0;
-            if (j < wl) {
-#pragma unroll
-                for (int e = 0; e < E; ++e) acc += qd[e] * (double)ldf(&kv[un][e]);
-            }
-#pragma unroll
-            for (int o = 1; o < 16; o <<= 1) acc += __shfl_xor(acc, o, 64);
-            if (sub == 0 && j < wl) s_logit[j] = acc / sqrt_d;
-        }
-    }
-    __syncthreads();
-    double lmax = -INFINITY;
-    for (int j = tid; j < wl; j += 256) lmax = fmax(lmax, s_logit[j]);
-    lmax = wave_max(lmax);
-    if ((tid & 63) == 0) s_red[tid >> 6] = lmax;
-    __syncthreads();
-    const double smax = fmax(fmax(s_red[0], s_red[1]), fmax(s_red[2], s_red[3]));
-
-    // ordered compaction of the flagged candidates: thread t owns a contiguous slice (at most 16
-    // candidates, AIR_MAX_TEXT / 256), whose flags it keeps as a bit mask
-    const int per = (wl + 255) / 256;
-    const int j0 = min(wl, tid * per), j1 = min(wl, j0 + per);
-    unsigned flags = 0;
-    for (int j = j0; j < j1; ++j)
-        if (exp(s_logit[j] - smax) >= alpha) flags |= 1u << (j - j0);
-    int R;
-    int pos = block_excl_scan<4>(__popc(flags), s_cnt, &R);
-    for (int j = j0; j < j1; ++j) {
-        if (flags & (1u << (j - j0))) {
-            s_elite[pos] = sq.win_start + j;
-            t.elite_idx[hrow * W + pos] = sq.win_start + j;
-            ++pos;
-        }
-    }
-    if (tid == 0) t.elite_cnt[hrow] = R;
-    __syncthreads();
-
-    // elite-text columns of Eq.7: (max, sum-exp) of every elite row over the elite text keys.
-    // One wave per row; each (row, key) logit is a 64-lane dot product.  Up to 8 keys are
-    // scored in one batch of loads; longer rows are scored twice (maximum, then sum).
-    // The maximum is kept as the RAW dot product (before the 1/sqrt(d) scale), the sum is of
-    // exp((a - max) / sqrt(d)).
     const float scale = 1.0f / sqrtf((float)D);
-    const int wave = tid >> 6, lane = tid & 63;
-    constexpr int kPer = D / 64;  // elements per lane
-    for (int r = wave; r < R; r += 4) {
-        const T *qr = q + (int64_t)(s_elite[r] - t0) * st.q_t;
-        float qv[kPer];
+
+    for (int g0 = 0; g0 < G; g0 += gb) {
+        const int ng = min(gb, G - g0);
+        // ---- phase 1
+        for (int hb = 0; hb < ng; hb += HB) {
+            const int nh = min(HB, ng - hb);
+            double qd[HB][E];
 #pragma unroll
-        for (int e = 0; e < kPer; ++e) qv[e] = ldf(qr + lane * kPer + e);
-        float m = -INFINITY, z = 0.f;
-        if (R <= 8) {
-            float a[8];
+            for (int hh = 0; hh < HB; ++hh) {
+                T tmp[E];
+                const int h = kvh * G + g0 + hb + (hh < nh ? hh : 0);
+                __builtin_memcpy(tmp, __builtin_assume_aligned(qb + (int64_t)h * st.q_h + (int64_t)(ref - t0) * st.q_t + sub * E,
+                                                               sizeof(T) * E), sizeof(tmp));
 #pragma unroll
-            for (int j = 0; j < 8; ++j) {
-                a[j] = 0.f;
-                if (j < R) {
-                    const T *kj = k + (int64_t)s_elite[j] * st.kv_t;
+                for (int e = 0; e < E; ++e) qd[hh][e] = (double)ldf(&tmp[e]);
+            }
+            for (int j0 = 0; j0 < wl; j0 += 16 * UN) {
+                T kv[UN][E];
 #pragma unroll
-                    for (int e = 0; e < kPer; ++e) a[j] = fmaf(qv[e], ldf(kj + lane * kPer + e), a[j]);
+                for (int un = 0; un < UN; ++un) {
+                    const int j = j0 + un * 16 + grp;
+                    if (j < wl)
+                        __builtin_memcpy(kv[un], __builtin_assume_aligned(k + (int64_t)(sq.win_start + j) * st.kv_t + sub * E,
+                                                                          sizeof(T) * E), sizeof(kv[un]));
+                }
+#pragma unroll
+                for (int un = 0; un < UN; ++un) {
+                    const int j = j0 + un * 16 + grp;
+                    double kd[E];
+#pragma unroll
+                    for (int e = 0; e < E; ++e) kd[e] = j < wl ? (double)ldf(&kv[un][e]) : 0.0;
+#pragma unroll
+                    for (int hh = 0; hh < HB; ++hh) {
+                        if (hh >= nh) break;
+                        double acc = 0.0;
+#pragma unroll
+                        for (int e = 0; e < E; ++e) acc += qd[hh][e] * kd[e];
+                        acc = sum16_f64(acc);
+                        if (sub == 0 && j < wl) s_logit[(size_t)(hb + hh) * W + j] = acc / sqrt_d;
+                    }
                 }
             }
-#pragma unroll
-            for (int j = 0; j < 8; ++j)
-                if (j < R) {
-                    a[j] = wave_sum(a[j]);
-                    m = fmaxf(m, a[j]);
+        }
+        __syncthreads();
+        // ---- phase 2
+        for (int hh = wave; hh < ng; hh += 4) {
+            const int h = kvh * G + g0 + hh;
+            const int64_t hrow = ((int64_t)l * dm.B + b) * dm.Hq + h;
+            const double *logit = s_logit + (size_t)hh * W;
+            int *elite = s_elite + (size_t)hh * W;
+            double lmax = -INFINITY;
+            for (int j = lane; j < wl; j += 64) lmax = fmax(lmax, logit[j]);
+            const double smax = wave_max(lmax);
+            int R = 0;
+            for (int j0 = 0; j0 < wl; j0 += 64) {
+                const int j = j0 + lane;
+                const bool flag = j < wl && exp(logit[j] - smax) >= alpha;
+                const unsigned long long bal = __ballot(flag);
+                if (flag) {
+                    const int pos = R + __popcll(bal & ((1ull << lane) - 1ull));
+                    elite[pos] = sq.win_start + j;
+                    t.elite_idx[hrow * W + pos] = sq.win_start + j;
                 }
-#pragma unroll
-            for (int j = 0; j < 8; ++j)
-                if (j < R) z += expf((a[j] - m) * scale);
-        } else {
-            for (int j = 0; j < R; ++j) {
-                const T *kj = k + (int64_t)s_elite[j] * st.kv_t;
-                float a = 0.f;
-#pragma unroll
-                for (int e = 0; e < kPer; ++e) a = fmaf(qv[e], ldf(kj + lane * kPer + e), a);
-                m = fmaxf(m, wave_sum(a));
+                R += __popcll(bal);
             }
-            for (int j = 0; j < R; ++j) {
-                const T *kj = k + (int64_t)s_elite[j] * st.kv_t;
-                float a = 0.f;
+            if (lane == 0) t.elite_cnt[hrow] = R;
+            // elite-text columns of Eq.7: (max, sum-exp) of every elite row over the elite text keys; each
+            // (row, key) logit is a 64-lane dot product.  Up to 8 keys are scored in one batch of loads,
+            // longer rows are scored twice (maximum, then sum).  The maximum is kept as the RAW dot
+            // product (before the 1/sqrt(d) scale), the sum is of exp((a - max) / sqrt(d)).
+            constexpr int kPer = D / 64;  // elements per lane
+            const T *q = qb + (int64_t)h * st.q_h;
+            for (int r = 0; r < R; ++r) {
+                const T *qr = q + (int64_t)(elite[r] - t0) * st.q_t;
+                float qv[kPer];
 #pragma unroll
-                for (int e = 0; e < kPer; ++e) a = fmaf(qv[e], ldf(kj + lane * kPer + e), a);
-                z += expf((wave_sum(a) - m) * scale);
+                for (int e = 0; e < kPer; ++e) qv[e] = ldf(qr + lane * kPer + e);
+                float m = -INFINITY, z = 0.f;
+                if (R <= 8) {
+                    float a[8];
+#pragma unroll
+                    for (int j = 0; j < 8; ++j) {
+                        a[j] = 0.f;
+                        if (j < R) {
+                            const T *kj = k + (int64_t)elite[j] * st.kv_t;
+#pragma unroll
+                            for (int e = 0; e < kPer; ++e) a[j] = fmaf(qv[e], ldf(kj + lane * kPer + e), a[j]);
+                        }
+                    }
+#pragma unroll
+                    for (int j = 0; j < 8; ++j)
+                        if (j < R) {
+                            a[j] = wave_sum(a[j]);
+                            m = fmaxf(m, a[j]);
+                        }
+#pragma unroll
+                    for (int j = 0; j < 8; ++j)
+                        if (j < R) z += expf((a[j] - m) * scale);
+                } else {
+                    for (int j = 0; j < R; ++j) {
+                        const T *kj = k + (int64_t)elite[j] * st.kv_t;
+                        float a = 0.f;
+#pragma unroll
+                        for (int e = 0; e < kPer; ++e) a = fmaf(qv[e], ldf(kj + lane * kPer + e), a);
+                        m = fmaxf(m, wave_sum(a));
+                    }
+                    for (int j = 0; j < R; ++j) {
+                        const T *kj = k + (int64_t)elite[j] * st.kv_t;
+                        float a = 0.f;
+#pragma unroll
+                        for (int e = 0; e < kPer; ++e) a = fmaf(qv[e], ldf(kj + lane * kPer + e), a);
+                        z += expf((wave_sum(a) - m) * scale);
+                    }
+                }
+                if (lane == 0) {
+                    t.row_mtext[hrow * W + r] = m;
+                    t.row_ztext[hrow * W + r] = z;
+                }
             }
         }
-        if (lane == 0) {
-            t.row_mtext[hrow * W + r] = m;
-            t.row_ztext[hrow * W + r] = z;
-        }
+        __syncthreads();
     }
 }
 
@@ -324,8 +351,11 @@ __global__ __launch_bounds__(256) void stats_kernel(Dims dm, DevTables t, int l0
 template <typename T, int D>
 static hipError_t elite_launch(hipStream_t s, const Dims &dm, const DevTables &t, int l0, int nl,
                                const LaunchLayers &ll, const air_strides &st, const SeqArgs &seqs, double alpha) {
-    const size_t lds = (size_t)dm.max_window * (sizeof(double) + sizeof(int));
-    hipLaunchKernelGGL((elite_kernel<T, D>), dim3(dm.Hq, dm.B, nl), dim3(256), lds, s, dm, t, l0, ll, st, seqs, alpha);
+    const size_t per_head = (size_t)dm.max_window * (sizeof(double) + sizeof(int));
+    int gb = (int)(49152 / per_head);  // heads whose logits share the LDS
+    gb = gb < 1 ? 1 : (gb > dm.G ? dm.G : gb);
+    hipLaunchKernelGGL((elite_kernel<T, D>), dim3(dm.Hkv, dm.B, nl), dim3(256), gb * per_head, s, dm, t, l0, ll, st, seqs,
+                       alpha, gb);
     return hipGetLastError();
 }
 

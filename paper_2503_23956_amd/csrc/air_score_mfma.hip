@@ -283,8 +283,7 @@ __global__ __launch_bounds__(256) void score_rows_mfma_kernel(Dims dm, DevTables
 }
 
 // ---------------------------------------------------------------------------------------
-// One workgroup finishes kFinishChunks consecutive chunks of a unit.
-constexpr int kFinishChunks = 4;
+// One workgroup finishes kFinishChunks consecutive chunks of a unit and leaves one power-sum entry.
 
 __global__ __launch_bounds__(256) void score_finish_kernel(Dims dm, DevTables t, int l0, LaunchLayers ll,
                                                            air_strides st) {
@@ -306,52 +305,46 @@ __global__ __launch_bounds__(256) void score_finish_kernel(Dims dm, DevTables t,
     u.R_total = s_pref[u.G];
     const bool stash = u.R_total <= kStashRows;
 
-    auto put_moments = [&](int chunk, double m1, double m2, double m3) {
+    // fp64 power sums of I over the workgroup's chunks, summed in a fixed order; one entry per workgroup
+    double m1 = 0.0, m2 = 0.0, m3 = 0.0;
+    auto put_moments = [&]() {
         m1 = wave_sum(m1);
         m2 = wave_sum(m2);
         m3 = wave_sum(m3);
-        __syncthreads();
         if (lane == 0) {
             s_mom[wave][0] = m1;
             s_mom[wave][1] = m2;
             s_mom[wave][2] = m3;
         }
-        __syncthreads();
+        lds_barrier();
         if (tid < 3) {
-            double *mo = t.moments + (u.unit * dm.n_chunks + chunk) * 3;
+            double *mo = t.moments + (u.unit * dm.n_chunks + blockIdx.x) * 3;
             mo[tid] = ((s_mom[0][tid] + s_mom[1][tid]) + s_mom[2][tid]) + s_mom[3][tid];
         }
     };
 
     if (stash) {
-        float e[kFinishChunks][kStashRows];
-#pragma unroll
-        for (int ci = 0; ci < kFinishChunks; ++ci) {
-            const float *sb = t.stash + ((u.unit * dm.n_chunks + first + ci) * (int64_t)kStashRows) * kChunkKeys + stash_pos(tid);
-#pragma unroll
-            for (int r = 0; r < kStashRows; ++r)
-                e[ci][r] = (first + ci < last && r < u.R_total) ? sb[(int64_t)r * kChunkKeys] : 0.f;
-        }
         if (tid < kFinishChunks * kStashRows) s_f[tid / kStashRows][tid % kStashRows] = (tid % kStashRows) < u.R_total ? f_mine : 0.f;
-        __syncthreads();
+        lds_barrier();
+        for (int ci = 0; ci < last - first; ++ci) {  // one chunk at a time: few registers, many workgroups per CU
+            const float *sb = t.stash + ((u.unit * dm.n_chunks + first + ci) * (int64_t)kStashRows) * kChunkKeys + stash_pos(tid);
+            float e[kStashRows];
 #pragma unroll
-        for (int ci = 0; ci < kFinishChunks; ++ci) {
-            if (first + ci >= last) break;
-            const int key = (first + ci) * kChunkKeys + tid;
+            for (int r = 0; r < kStashRows; ++r) e[r] = r < u.R_total ? sb[(int64_t)r * kChunkKeys] : 0.f;
             float imp = 0.f;
 #pragma unroll
             for (int r = 0; r < kStashRows; ++r)
-                if (r < u.R_total) imp = fmaf(s_f[ci][r], e[ci][r], imp);
-            double m1 = 0.0, m2 = 0.0, m3 = 0.0;
+                if (r < u.R_total) imp = fmaf(s_f[ci][r], e[r], imp);
+            const int key = (first + ci) * kChunkKeys + tid;
             if (key < u.sq.vis_len) {
                 t.scores[u.unit * dm.max_vis + key] = imp;
                 const double x = (double)imp;
-                m1 = x;
-                m2 = x * x;
-                m3 = x * x * x;
+                m1 += x;
+                m2 += x * x;
+                m3 += x * x * x;
             }
-            put_moments(first + ci, m1, m2, m3);
         }
+        put_moments();
         return;
     }
     // recompute path: (M, w) of a block of rows staged from the row tables
@@ -392,7 +385,6 @@ __global__ __launch_bounds__(256) void score_finish_kernel(Dims dm, DevTables t,
                 }
             }
         }
-        double m1 = 0.0, m2 = 0.0, m3 = 0.0;
 #pragma unroll
         for (int tile = 0; tile < 4; ++tile) {
             float v = acc[tile];
@@ -406,8 +398,180 @@ __global__ __launch_bounds__(256) void score_finish_kernel(Dims dm, DevTables t,
                 m3 += x * x * x;
             }
         }
-        put_moments(chunk, m1, m2, m3);
     }
+    put_moments();
+}
+
+// ---------------------------------------------------------------------------------------
+// Eq.4-5 for bf16 / head_dim 128.  One workgroup per (KV head, sequence, layer).
+//   phase 1: raw last-row logits of the G heads against every candidate text key on MFMA
+//            (fp32 accumulation), into LDS.
+//   phase 2: one wave per head.  Eq.5 is decided as the fp64 test exp((a_j - a_max)/sqrt(d)) >= alpha.
+//            The fp32 logits settle every candidate that is not within kEliteMargin of the
+//            threshold; the maximum and the few candidates inside the margin are recomputed as
+//            exact fp64 dot products (bf16 products are exact, the sum is fp64) before deciding.
+//            Then the ordered compaction of the elite positions and the elite-text columns of Eq.7.
+// ---------------------------------------------------------------------------------------
+constexpr int kEliteWaves = 8;      // phase 2 takes one head per wave
+constexpr float kEliteMargin = 4e-3f;  // raw-logit units; fp32 accumulation of 128 bf16 products of this size errs by < 1e-3
+
+__device__ __forceinline__ double dot64_wave(const bf16_t *a, const bf16_t *b, int lane) {
+    const uint32_t ua = reinterpret_cast<const uint32_t *>(a)[lane], ub = reinterpret_cast<const uint32_t *>(b)[lane];
+    const double p = (double)__uint_as_float(ua << 16) * (double)__uint_as_float(ub << 16) +
+                     (double)__uint_as_float(ua & 0xffff0000u) * (double)__uint_as_float(ub & 0xffff0000u);
+    return wave_sum(p);
+}
+
+__global__ __launch_bounds__(64 * kEliteWaves) void elite_mfma_kernel(Dims dm, DevTables t, int l0, LaunchLayers ll, air_strides st,
+                                                         SeqArgs seqs, double alpha, int gb) {
+    constexpr int D = 128;
+    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, n = lane & 15, c = lane >> 4;
+    const int kvh = blockIdx.x, b = blockIdx.y, li = blockIdx.z;
+    const int l = l0 + li;
+    const air_seq sq = seqs.s[b];
+    if (li == 0 && kvh == 0 && tid == 0) t.seq_tab[b] = sq;
+    const int t0 = sq.vis_start + sq.vis_len;
+    const int G = dm.G, W = dm.max_window, wl = sq.win_len;
+    const bf16_t *qb = (const bf16_t *)ll.p[li].q + (int64_t)b * st.q_b;
+    const bf16_t *k = (const bf16_t *)ll.p[li].k + (int64_t)b * st.kv_b + (int64_t)kvh * st.kv_h;
+    const int ref = sq.win_start + wl - 1;
+    extern __shared__ float s_dynf[];  // gb * max_window raw logits, then as many ints (elite lists)
+    float *s_logit = s_dynf;
+    int *s_elite = reinterpret_cast<int *>(s_dynf + (size_t)gb * W);
+    const double inv_sqrt_d = 1.0 / sqrt((double)D);
+    const double ln_alpha = alpha > 0.0 ? log(alpha) : -INFINITY;
+    const float scale = 0.08838834764831845f;
+
+    for (int g0 = 0; g0 < G; g0 += gb) {
+        const int ng = min(gb, G - g0);
+        // ---- phase 1: A = reference queries of heads g0 .. g0+ng-1 (MFMA row m = head), B = candidate keys
+        uint4 qa[4];
+        {
+            const bf16_t *qr = qb + (int64_t)(kvh * G + g0 + (n < ng ? n : 0)) * st.q_h + (int64_t)(ref - t0) * st.q_t;
+#pragma unroll
+            for (int sl = 0; sl < 4; ++sl) {
+                qa[sl] = make_uint4(0, 0, 0, 0);
+                if (n < ng) qa[sl] = *reinterpret_cast<const uint4 *>(qr + 32 * sl + 8 * c);
+            }
+        }
+        for (int j0 = wave * 16; j0 < wl; j0 += 16 * kEliteWaves) {
+            const int j = j0 + n;
+            uint4 kb[4];
+#pragma unroll
+            for (int sl = 0; sl < 4; ++sl) {
+                kb[sl] = make_uint4(0, 0, 0, 0);
+                if (j < wl) kb[sl] = *reinterpret_cast<const uint4 *>(k + (int64_t)(sq.win_start + j) * st.kv_t + 32 * sl + 8 * c);
+            }
+            f32x4 s4 = (f32x4){0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int sl = 0; sl < 4; ++sl)
+                s4 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, qa[sl]), __builtin_bit_cast(bf16x8, kb[sl]), s4, 0, 0, 0);
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+                if (4 * c + i < ng && j < wl) s_logit[(size_t)(4 * c + i) * W + j] = s4[i];
+        }
+        __syncthreads();
+        // ---- phase 2
+        for (int hh = wave; hh < ng; hh += kEliteWaves) {
+            const int h = kvh * G + g0 + hh;
+            const int64_t hrow = ((int64_t)l * dm.B + b) * dm.Hq + h;
+            const float *logit = s_logit + (size_t)hh * W;
+            int *elite = s_elite + (size_t)hh * W;
+            const bf16_t *q = qb + (int64_t)h * st.q_h;
+            const bf16_t *qref = q + (int64_t)(ref - t0) * st.q_t;
+            float m32 = -INFINITY;
+            for (int j = lane; j < wl; j += 64) m32 = fmaxf(m32, logit[j]);
+            m32 = wave_max(m32);
+            // exact maximum: every candidate within the margin of the fp32 maximum is recomputed
+            double amax = -INFINITY;
+            for (int j0 = 0; j0 < wl; j0 += 64) {
+                const int j = j0 + lane;
+                unsigned long long near = __ballot(j < wl && logit[j] >= m32 - kEliteMargin);
+                while (near) {
+                    const int src = __ffsll(near) - 1;
+                    near &= near - 1;
+                    amax = fmax(amax, dot64_wave(qref, k + (int64_t)(sq.win_start + j0 + src) * st.kv_t, lane));
+                }
+            }
+            int R = 0;
+            for (int j0 = 0; j0 < wl; j0 += 64) {
+                const int j = j0 + lane;
+                // x > 0 <=> exp((a_j - a_max) / sqrt(d)) > alpha
+                const double x = j < wl ? ((double)logit[j] - amax) * inv_sqrt_d - ln_alpha : -1.0;
+                bool flag = j < wl && x > 0.0;
+                unsigned long long unsure = __ballot(j < wl && fabs(x) <= (double)(kEliteMargin * scale));
+                while (unsure) {
+                    const int src = __ffsll(unsure) - 1;
+                    unsure &= unsure - 1;
+                    const double a = dot64_wave(qref, k + (int64_t)(sq.win_start + j0 + src) * st.kv_t, lane);
+                    const bool f = exp((a - amax) * inv_sqrt_d) >= alpha;
+                    if (lane == src) flag = f;
+                }
+                const unsigned long long bal = __ballot(flag);
+                if (flag) {
+                    const int pos = R + __popcll(bal & ((1ull << lane) - 1ull));
+                    elite[pos] = sq.win_start + j;
+                    t.elite_idx[hrow * W + pos] = sq.win_start + j;
+                }
+                R += __popcll(bal);
+            }
+            if (lane == 0) t.elite_cnt[hrow] = R;
+            // elite-text columns of Eq.7: (max, sum-exp) of every elite row over the elite text keys; each
+            // (row, key) logit is a 64-lane dot product.  Up to 8 keys are scored in one batch of loads,
+            // longer rows are scored twice (maximum, then sum).  The maximum is kept as the RAW dot
+            // product (before the 1/sqrt(d) scale), the sum is of exp((a - max) / sqrt(d)).
+            for (int r = 0; r < R; ++r) {
+                const bf16_t *qr = q + (int64_t)(elite[r] - t0) * st.q_t;
+                const uint32_t uq = reinterpret_cast<const uint32_t *>(qr)[lane];
+                const float q0 = __uint_as_float(uq << 16), q1 = __uint_as_float(uq & 0xffff0000u);
+                float m = -INFINITY, z = 0.f;
+                if (R <= 8) {
+                    float a[8];
+#pragma unroll
+                    for (int j = 0; j < 8; ++j) {
+                        a[j] = 0.f;
+                        if (j < R) {
+                            const uint32_t uk = reinterpret_cast<const uint32_t *>(k + (int64_t)elite[j] * st.kv_t)[lane];
+                            a[j] = fmaf(q1, __uint_as_float(uk & 0xffff0000u), q0 * __uint_as_float(uk << 16));
+                        }
+                    }
+#pragma unroll
+                    for (int j = 0; j < 8; ++j)
+                        if (j < R) {
+                            a[j] = wave_sum(a[j]);
+                            m = fmaxf(m, a[j]);
+                        }
+#pragma unroll
+                    for (int j = 0; j < 8; ++j)
+                        if (j < R) z += expf((a[j] - m) * scale);
+                } else {
+                    for (int j = 0; j < R; ++j) {
+                        const uint32_t uk = reinterpret_cast<const uint32_t *>(k + (int64_t)elite[j] * st.kv_t)[lane];
+                        m = fmaxf(m, wave_sum(fmaf(q1, __uint_as_float(uk & 0xffff0000u), q0 * __uint_as_float(uk << 16))));
+                    }
+                    for (int j = 0; j < R; ++j) {
+                        const uint32_t uk = reinterpret_cast<const uint32_t *>(k + (int64_t)elite[j] * st.kv_t)[lane];
+                        z += expf((wave_sum(fmaf(q1, __uint_as_float(uk & 0xffff0000u), q0 * __uint_as_float(uk << 16))) - m) * scale);
+                    }
+                }
+                if (lane == 0) {
+                    t.row_mtext[hrow * W + r] = m;
+                    t.row_ztext[hrow * W + r] = z;
+                }
+            }
+        }
+        __syncthreads();
+    }
+}
+
+hipError_t launch_elite_mfma(hipStream_t s, const Dims &dm, const DevTables &t, int l0, int nl, const LaunchLayers &ll,
+                             const air_strides &st, const SeqArgs &seqs, double alpha) {
+    const size_t per_head = (size_t)dm.max_window * (sizeof(float) + sizeof(int));
+    int gb = (int)(49152 / per_head);  // heads whose logits share the LDS
+    gb = gb < 1 ? 1 : (gb > dm.G ? dm.G : gb);
+    hipLaunchKernelGGL(elite_mfma_kernel, dim3(dm.Hkv, dm.B, nl), dim3(64 * kEliteWaves), gb * per_head, s, dm, t, l0, ll, st, seqs,
+                       alpha, gb);
+    return hipGetLastError();
 }
 
 hipError_t launch_score_mfma(hipStream_t s, const Dims &dm, const DevTables &t, int pass, int l0, int nl,

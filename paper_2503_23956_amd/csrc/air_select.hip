@@ -152,8 +152,9 @@ __global__ __launch_bounds__(256) void gather_kernel(Dims dm, DevTables t, int l
     }
 }
 
-// bf16 / head_dim 128: same K' copy, but V' is written block-transposed (see v_slot): one
-// workgroup stages the 32 gathered V rows of a block in LDS and writes [128 columns][32 slots].
+// bf16 / head_dim 128: the cache is written in the layouts the decode kernel feeds to MFMA.  One
+// workgroup stages the 32 gathered K and V rows of a block in LDS and writes K' as two 16-token
+// tiles (see k_tiled) and V' block-transposed, [128 columns][32 slots] (see v_slot).
 // Slots of the last block that have no token yet are written as zeros.
 __global__ __launch_bounds__(256) void gather_vt_kernel(Dims dm, DevTables t, int l0, LaunchLayers ll, air_strides st) {
     constexpr int D = 128;
@@ -173,24 +174,31 @@ __global__ __launch_bounds__(256) void gather_vt_kernel(Dims dm, DevTables t, in
     const int64_t dst_row0 = ((int64_t)b * dm.Hkv + kvh) * dm.pool_rows + t.layer_off[(int64_t)b * dm.L + l];
     T *kdst = (T *)t.kcache + dst_row0 * D;
     T *vdst = (T *)t.vcache + dst_row0 * D;
-    __shared__ bf16_t tile[32][D + 8];  // indexed [slot][column]; +8 keeps the 16-byte row alignment and spreads banks
+    __shared__ bf16_t tile[32][D + 8];   // V rows, indexed [slot][column]; +8 keeps the 16-byte row alignment and spreads banks
+    __shared__ bf16_t ktile[32][D + 8];  // K rows, indexed [row][column]
     for (int r0 = blockIdx.x * 32; r0 < n_rows; r0 += gridDim.x * 32) {
         for (int v = threadIdx.x; v < 32 * 16; v += 256) {
             const int row = v >> 4, c = (v & 15) * 8;
             const int j = r0 + row;
-            uint4 vx = make_uint4(0, 0, 0, 0);
+            uint4 vx = make_uint4(0, 0, 0, 0), kx = vx;
             if (j < n_rows) {
                 int tok;
                 if (j < sq.vis_start) tok = j;
                 else if (j < sq.vis_start + kl) tok = sq.vis_start + idx[j - sq.vis_start];
                 else tok = sq.vis_start + sq.vis_len + (j - sq.vis_start - kl);
-                const uint4 kx = *reinterpret_cast<const uint4 *>(ksrc + (int64_t)tok * st.kv_t + c);
+                kx = *reinterpret_cast<const uint4 *>(ksrc + (int64_t)tok * st.kv_t + c);
                 vx = *reinterpret_cast<const uint4 *>(vsrc + (int64_t)tok * st.kv_t + c);
-                *reinterpret_cast<uint4 *>(kdst + (int64_t)j * D + c) = kx;
             }
+            *reinterpret_cast<uint4 *>(&ktile[row][c]) = kx;
             *reinterpret_cast<uint4 *>(&tile[v_slot(row)][c]) = vx;
         }
         __syncthreads();
+        // K': the two 16-token tiles of the block in k_tiled order, 16 bytes per thread, consecutive in memory
+        for (int v = threadIdx.x; v < 32 * 16; v += 256) {
+            const int tl = v >> 8, sl = (v >> 6) & 3, c = (v >> 4) & 3, n = v & 15;
+            *reinterpret_cast<uint4 *>(kdst + (int64_t)r0 * D + (int64_t)v * 8) =
+                *reinterpret_cast<const uint4 *>(&ktile[16 * tl + n][32 * sl + 8 * c]);
+        }
         for (int v = threadIdx.x; v < D * 4; v += 256) {
             const int col = v >> 2, c = v & 3;
             uint32_t w[4];
