@@ -383,12 +383,12 @@ static void decode_shape(const air_ctx *ctx, int n_layers_in_launch, int appende
         avg_len += (double)(s.seq_len - s.vis_len) + c.retention * (double)s.vis_len + appended + 1;
     }
     avg_len /= c.batch;
-    int kt = 4, w = 8;
+    const int64_t units = (int64_t)n_layers_in_launch * c.batch * c.n_kv_heads;
+    int kt = 4, w = units >= 1024 ? 4 : 8;  // with many short units, smaller workgroups overlap each other's start and end
     if (ctx->force_tiles > 0) kt = ctx->force_tiles;
     if (ctx->force_waves > 0) w = ctx->force_waves;
     if (kt == 8 && w == 8) w = 4;
     const int64_t iters = (int64_t)((avg_len + 16.0 * kt - 1.0) / (16.0 * kt));
-    const int64_t units = (int64_t)n_layers_in_launch * c.batch * c.n_kv_heads;
     int64_t s = 1;
     while (s < kMaxSplits && iters > (int64_t)kItersPerWave * w * s && units * s < kEnoughWorkgroups) s *= 2;
     if (ctx->force_splits > 0) s = ctx->force_splits;
@@ -554,7 +554,7 @@ air_status air_get_cache(air_ctx *ctx, int32_t l, int32_t b, int32_t h, void *k_
     uint16_t *vh = (uint16_t *)v_host;
     for (int r = 0; r < len; ++r)
         for (int col = 0; col < D; ++col)
-            vh[(size_t)r * D + col] = raw[((size_t)(r / 32) * D + col) * 32 + v_slot(r % 32)];
+            vh[(size_t)r * D + col] = raw[v_tiled(r, col)];
     return AIR_OK;
 }
 

@@ -31,7 +31,7 @@ __device__ __forceinline__ void split_range(int len, int splits, int split, int 
 // ---------------------------------------------------------------------------------------
 // append (Eq.2)
 // ---------------------------------------------------------------------------------------
-template <typename T, int D, bool VT>
+template <typename T, int D>
 __global__ __launch_bounds__(128) void append_kernel(Dims dm, DevTables t, int l0, int lbase, LaunchLayers ll,
                                                      const T *k_new, const T *v_new) {
     const int u = blockIdx.x;
@@ -47,25 +47,7 @@ __global__ __launch_bounds__(128) void append_kernel(Dims dm, DevTables t, int l
     if (tid < kVec) {
         const int c = tid * (16 / (int)sizeof(T));
         *reinterpret_cast<uint4 *>((T *)t.kcache + (row0 + row) * D + c) = *reinterpret_cast<const uint4 *>(k_new + src + c);
-        if (!VT)
-            *reinterpret_cast<uint4 *>((T *)t.vcache + (row0 + row) * D + c) = *reinterpret_cast<const uint4 *>(v_new + src + c);
-    }
-    if (VT && tid < D) {
-        // column tid of the transposed block; a token that opens a new block clears the block's row first
-        bf16_t *vrow = (bf16_t *)t.vcache + (row0 + (row & ~31)) * D + (int64_t)tid * 32;
-        const int tok = row & 31;
-        const bf16_t val = ((const bf16_t *)v_new)[src + tid];
-        if (tok == 0) {
-            uint4 z = make_uint4(0, 0, 0, 0);
-            uint4 first = z;
-            first.x = val;  // slot of token 0 is 0
-            reinterpret_cast<uint4 *>(vrow)[0] = first;
-            reinterpret_cast<uint4 *>(vrow)[1] = z;
-            reinterpret_cast<uint4 *>(vrow)[2] = z;
-            reinterpret_cast<uint4 *>(vrow)[3] = z;
-        } else {
-            vrow[v_slot(tok)] = val;
-        }
+        *reinterpret_cast<uint4 *>((T *)t.vcache + (row0 + row) * D + c) = *reinterpret_cast<const uint4 *>(v_new + src + c);
     }
 }
 
@@ -104,6 +86,19 @@ __global__ __launch_bounds__(64 * NW) void decode_mfma_kernel(Dims dm, DevTables
     const int li = u / (dm.Hkv * dm.B);
     const int l = l0 + li;
     const int G = dm.G;
+    // The token this call appends (Eq.2): every wave fetches its k_new / v_new values first thing (the
+    // addresses depend on the block index only), so they are long there when the wave that owns the
+    // token needs them.
+    const int64_t new_src = (((int64_t)(lbase + li) * dm.B + b) * dm.Hkv + kvh) * D;
+    uint4 knew[4], krow;
+    bf16_t vnew[8], vcol[2];
+#pragma unroll
+    for (int sl = 0; sl < 4; ++sl) knew[sl] = *reinterpret_cast<const uint4 *>(k_new + new_src + 32 * sl + 8 * c);
+    krow = *reinterpret_cast<const uint4 *>(k_new + new_src + 8 * n);
+#pragma unroll
+    for (int j = 0; j < 8; ++j) vnew[j] = v_new[new_src + 16 * j + n];
+    vcol[0] = v_new[new_src + lane];
+    vcol[1] = v_new[new_src + 64 + lane];
     const int len = t.base_len[(int64_t)b * dm.L + l] + ll.appended[li] + 1;
     const int newrow = len - 1;  // the token appended by this call (Eq.2): scored from k_new / v_new, stored to the cache
     int k0, k1;
@@ -113,7 +108,6 @@ __global__ __launch_bounds__(64 * NW) void decode_mfma_kernel(Dims dm, DevTables
     bf16_t *kc = (bf16_t *)t.kcache + row0 * D;
     bf16_t *vc = (bf16_t *)t.vcache + row0 * D;
     const int64_t unit = ((int64_t)l * dm.B + b) * dm.Hkv + kvh;
-    const int64_t new_src = (((int64_t)(lbase + li) * dm.B + b) * dm.Hkv + kvh) * D;
     bf16_t *o_unit = out + (((int64_t)(lbase + li) * dm.B + b) * dm.Hq + (int64_t)kvh * G) * D;
 
     bf16x8 qb[4];
@@ -132,25 +126,75 @@ __global__ __launch_bounds__(64 * NW) void decode_mfma_kernel(Dims dm, DevTables
 #pragma unroll
     for (int j = 0; j < 8; ++j) acc[j] = (f32x4){0.f, 0.f, 0.f, 0.f};
 
+    // ---- the appended token belongs to the wave of the owning split that would take the next
+    // chunk.  The row goes into the cache at once, so that the stores complete behind the cache
+    // loads: K' into its places of the tile, V' into its slot of the block (a token that opens a
+    // block writes the block's other slots as zeros).  Other waves and splits never use these
+    // places in this launch: their reads of them are masked or carry zero probability.  The
+    // token's own score (vector ALU) starts the wave's running softmax: max = score, sum = 1,
+    // accumulator = v_new for every head.
+    const bool owns_new = newrow >= k0 && newrow < k1 && wave == ((kend - k0 + kIter - 1) / kIter) % NW;
+    if (owns_new) {
+        if (lane < 16)  // the new K' row: 16 lanes x 16 bytes
+            *reinterpret_cast<uint4 *>(kc + k_tiled(newrow, 8 * lane)) = krow;
+        const int tok = newrow & 31;
+#pragma unroll
+        for (int h2 = 0; h2 < 2; ++h2) {
+            const int col = lane + 64 * h2;
+            if (tok == 0) {  // a new block: the column's other slots are written as zeros
+                bf16_t *vcolp = vc + (int64_t)newrow * D + (col >> 4) * 512 + (col & 15) * 8;  // slot group 0; +128 per group
+                const uint4 z = make_uint4(0, 0, 0, 0);
+                *reinterpret_cast<uint4 *>(vcolp) = make_uint4(vcol[h2], 0, 0, 0);  // token 0 sits in slot 0
+                *reinterpret_cast<uint4 *>(vcolp + 128) = z;
+                *reinterpret_cast<uint4 *>(vcolp + 256) = z;
+                *reinterpret_cast<uint4 *>(vcolp + 384) = z;
+            } else {
+                vc[v_tiled(newrow, col)] = vcol[h2];
+            }
+        }
+        float sn = 0.f;
+#pragma unroll
+        for (int sl = 0; sl < 4; ++sl) {
+            const uint4 kx = knew[sl];
+            const uint4 qx = __builtin_bit_cast(uint4, qb[sl]);
+            const uint32_t kw[4] = {kx.x, kx.y, kx.z, kx.w}, qw[4] = {qx.x, qx.y, qx.z, qx.w};
+#pragma unroll
+            for (int w4 = 0; w4 < 4; ++w4) {
+                sn = fmaf(__uint_as_float(qw[w4] << 16), __uint_as_float(kw[w4] << 16), sn);
+                sn = fmaf(__uint_as_float(qw[w4] & 0xffff0000u), __uint_as_float(kw[w4] & 0xffff0000u), sn);
+            }
+        }
+        sn += __shfl_xor(sn, 16, 64);
+        sn += __shfl_xor(sn, 32, 64);
+        m_run = sn * kScale2;
+        l_run = 1.f;
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            const float v = bf16_bits_to_float(vnew[j]);
+            acc[j] = (f32x4){v, v, v, v};
+        }
+    }
+
     const int last16 = (kend - 1) & ~15, last32 = (kend - 1) & ~31;  // last tile / block with a cached key
     const int kb_first = k0 + wave * kIter;
-    for (int kb = kb_first; kb < kend; kb += NW * kIter) {
-        // ---- all loads of the iteration go out first: the KT score tiles of K' ...
-        uint4 a[KT][4];
+    constexpr int kStep = NW * kIter;  // distance between two chunks of one wave
+
+    // all loads of a chunk: the KT score tiles of K' and the V' operands of the TB token blocks
+    auto load_chunk = [&](uint4(&a)[KT][4], uint4(&vb)[TB][8], int kb) {
 #pragma unroll
         for (int tile = 0; tile < KT; ++tile) {
-            const bf16_t *src = kc + (int64_t)min(kb + 16 * tile, last16) * D + 128 * c + 8 * n;
+            const bf16_t *src = kc + (int64_t)min(kb + 16 * tile, last16) * D + 32 * n + 8 * c;
 #pragma unroll
             for (int sl = 0; sl < 4; ++sl) a[tile][sl] = *reinterpret_cast<const uint4 *>(src + 512 * sl);
         }
-        // ... and the V' operands of the TB token blocks
-        uint4 vb[TB][8];
 #pragma unroll
         for (int tb = 0; tb < TB; ++tb) {
-            const bf16_t *src = vc + (int64_t)min(kb + 32 * tb, last32) * D + 32 * n + 8 * c;
+            const bf16_t *src = vc + (int64_t)min(kb + 32 * tb, last32) * D + 128 * c + 8 * n;
 #pragma unroll
             for (int j = 0; j < 8; ++j) vb[tb][j] = *reinterpret_cast<const uint4 *>(src + 512 * j);
         }
+    };
+    auto compute_chunk = [&](const uint4(&a)[KT][4], const uint4(&vb)[TB][8], int kb) {
         // ---- scores^T
         f32x4 s[KT];
 #pragma unroll
@@ -160,7 +204,7 @@ __global__ __launch_bounds__(64 * NW) void decode_mfma_kernel(Dims dm, DevTables
             for (int sl = 0; sl < 4; ++sl)
                 s[tile] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a[tile][sl]), qb[sl], s[tile], 0, 0, 0);
         }
-        if (kb + kIter > kend) {  // the iteration with the tail (uniform over the wave)
+        if (kb + kIter > kend) {  // the chunk with the tail (uniform over the wave)
 #pragma unroll
             for (int tile = 0; tile < KT; ++tile)
 #pragma unroll
@@ -191,7 +235,7 @@ __global__ __launch_bounds__(64 * NW) void decode_mfma_kernel(Dims dm, DevTables
         l_run = fmaf(l_run, corr, lb);
         m_run = m_new;
         // accumulator rows are heads 4c..4c+3: fetch their rescale factors from lanes 4c+i
-        if (kb != kb_first && __ballot(corr != 1.0f) != 0ull) {
+        if ((owns_new || kb != kb_first) && __ballot(corr != 1.0f) != 0ull) {
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
                 const float f = __shfl(corr, 4 * c + i, 64);
@@ -212,61 +256,38 @@ __global__ __launch_bounds__(64 * NW) void decode_mfma_kernel(Dims dm, DevTables
             for (int j = 0; j < 8; ++j)
                 acc[j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(pa, __builtin_bit_cast(bf16x8, vb[tb][j]), acc[j], 0, 0, 0);
         }
-    }
-
-    // ---- the appended token (Eq.2): the wave of the owning split that would take the next chunk.
-    // Score of head n on the vector ALU, folded into the running softmax with fp32 probabilities,
-    // then the row goes into the cache: K' into its places of the tile, V' into its slot of the
-    // block (a token that opens a block writes the block's other slots as zeros).  Other waves and
-    // splits never use these places in this launch: their reads of them are masked or carry zero
-    // probability.
-    if (newrow >= k0 && newrow < k1 && wave == ((kend - k0 + kIter - 1) / kIter) % NW) {
-        float sn = 0.f;
-#pragma unroll
-        for (int sl = 0; sl < 4; ++sl) {
-            const uint4 kx = *reinterpret_cast<const uint4 *>(k_new + new_src + 32 * sl + 8 * c);
-            const uint4 qx = __builtin_bit_cast(uint4, qb[sl]);
-            const uint32_t kw[4] = {kx.x, kx.y, kx.z, kx.w}, qw[4] = {qx.x, qx.y, qx.z, qx.w};
-#pragma unroll
-            for (int w4 = 0; w4 < 4; ++w4) {
-                sn = fmaf(__uint_as_float(qw[w4] << 16), __uint_as_float(kw[w4] << 16), sn);
-                sn = fmaf(__uint_as_float(qw[w4] & 0xffff0000u), __uint_as_float(kw[w4] & 0xffff0000u), sn);
-            }
+    };
+    // Two chunk buffers: while one chunk is multiplied the loads of the wave's next chunk are in
+    // flight.  Loads are issued only for chunks that exist, and the loop is laid out so that every
+    // path reaches a compute step with the same loads behind it (the wait counts stay exact).
+    if constexpr (KT > 2) {  // two buffers of this size do not fit the registers: load, then multiply
+        for (int kb = kb_first; kb < kend; kb += kStep) {
+            uint4 a0[KT][4], v0[TB][8];
+            load_chunk(a0, v0, kb);
+            compute_chunk(a0, v0, kb);
         }
-        sn += __shfl_xor(sn, 16, 64);
-        sn += __shfl_xor(sn, 32, 64);
-        sn *= kScale2;
-        const float m_new = fmaxf(m_run, sn);
-        const float corr = __builtin_amdgcn_exp2f(m_run - m_new);
-        const float pn = __builtin_amdgcn_exp2f(sn - m_new);
-        l_run = fmaf(l_run, corr, pn);
-        m_run = m_new;
-        float vn[8];
-#pragma unroll
-        for (int j = 0; j < 8; ++j) vn[j] = bf16_bits_to_float(v_new[new_src + 16 * j + n]);
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            const float f = __shfl(corr, 4 * c + i, 64), pp = __shfl(pn, 4 * c + i, 64);
-#pragma unroll
-            for (int j = 0; j < 8; ++j) acc[j][i] = fmaf(acc[j][i], f, pp * vn[j]);
-        }
-        if (lane < 16)  // the new K' row: 16 lanes x 16 bytes into the row's places of its tile
-            *reinterpret_cast<uint4 *>(kc + k_tiled(newrow, 8 * lane)) =
-                *reinterpret_cast<const uint4 *>(k_new + new_src + 8 * lane);
-        const int tok = newrow & 31, slot = v_slot(tok);
-#pragma unroll
-        for (int h2 = 0; h2 < 2; ++h2) {
-            const int col = lane + 64 * h2;
-            bf16_t *vrow = vc + (int64_t)(newrow & ~31) * D + col * 32;
-            const bf16_t val = v_new[new_src + col];
-            if (tok == 0) {  // slot 0 of a new block
-                const uint4 z = make_uint4(0, 0, 0, 0);
-                reinterpret_cast<uint4 *>(vrow)[0] = make_uint4(val, 0, 0, 0);
-                reinterpret_cast<uint4 *>(vrow)[1] = z;
-                reinterpret_cast<uint4 *>(vrow)[2] = z;
-                reinterpret_cast<uint4 *>(vrow)[3] = z;
-            } else {
-                vrow[slot] = val;
+    } else if (kb_first < kend) {
+        uint4 a0[KT][4], v0[TB][8], a1[KT][4], v1[TB][8];
+        int kb = kb_first;
+        load_chunk(a0, v0, kb);
+        if (kb + kStep >= kend) {
+            compute_chunk(a0, v0, kb);
+        } else {
+            load_chunk(a1, v1, kb + kStep);
+            while (true) {
+                compute_chunk(a0, v0, kb);
+                if (kb + 2 * kStep >= kend) {
+                    compute_chunk(a1, v1, kb + kStep);
+                    break;
+                }
+                load_chunk(a0, v0, kb + 2 * kStep);
+                compute_chunk(a1, v1, kb + kStep);
+                if (kb + 3 * kStep >= kend) {
+                    compute_chunk(a0, v0, kb + 2 * kStep);
+                    break;
+                }
+                load_chunk(a1, v1, kb + 3 * kStep);
+                kb += 2 * kStep;
             }
         }
     }
@@ -566,21 +587,19 @@ __global__ __launch_bounds__(256) void combine_kernel(Dims dm, DevTables t, int 
     }
 }
 
-template <typename T, int D, bool VT>
+template <typename T, int D>
 static hipError_t append_launch(hipStream_t s, const Dims &dm, const DevTables &t, int l0, int nl, int lbase,
                                 const LaunchLayers &ll, const void *k_new, const void *v_new) {
-    hipLaunchKernelGGL((append_kernel<T, D, VT>), dim3(nl * dm.B * dm.Hkv), dim3(128), 0, s, dm, t, l0, lbase, ll,
+    hipLaunchKernelGGL((append_kernel<T, D>), dim3(nl * dm.B * dm.Hkv), dim3(128), 0, s, dm, t, l0, lbase, ll,
                        (const T *)k_new, (const T *)v_new);
     return hipGetLastError();
 }
 
 static hipError_t launch_append(hipStream_t s, const Dims &dm, const DevTables &t, int dtype, int l0, int nl, int lbase,
                          const LaunchLayers &ll, const void *k_new, const void *v_new) {
-    if (dtype == AIR_BF16)
-        return dm.D == 128 ? append_launch<bf16_t, 128, true>(s, dm, t, l0, nl, lbase, ll, k_new, v_new)
-                           : append_launch<bf16_t, 64, false>(s, dm, t, l0, nl, lbase, ll, k_new, v_new);
-    return dm.D == 128 ? append_launch<float, 128, false>(s, dm, t, l0, nl, lbase, ll, k_new, v_new)
-                       : append_launch<float, 64, false>(s, dm, t, l0, nl, lbase, ll, k_new, v_new);
+    if (dtype == AIR_BF16) return append_launch<bf16_t, 64>(s, dm, t, l0, nl, lbase, ll, k_new, v_new);  // head_dim 128 takes the MFMA kernel
+    return dm.D == 128 ? append_launch<float, 128>(s, dm, t, l0, nl, lbase, ll, k_new, v_new)
+                       : append_launch<float, 64>(s, dm, t, l0, nl, lbase, ll, k_new, v_new);
 }
 
 template <typename T, int D>

@@ -86,18 +86,28 @@ hipError_t launch_decode(hipStream_t s, const Dims &dm, const DevTables &t, int 
                          const LaunchLayers &ll, const void *q_new, const void *k_new, const void *v_new, void *out,
                          int splits, int waves, int tiles);
 
-// The bf16 / head_dim 128 cache keeps V' transposed in blocks of 32 tokens so that the decode
-// kernel can feed it to MFMA straight from global memory: block [128 columns][32 slots], and
-// token t of the block sits in slot v_slot(t).  With this order the 8 probabilities a lane holds
-// after the two 16-key score tiles of a block are exactly the 8 contraction slots it must supply.
+// The bf16 / head_dim 128 cache is laid out so that the decode kernel can feed it to MFMA straight
+// from global memory, every load instruction of a wave reading 1 KB of consecutive memory, and so
+// that one token touches few cache lines (appending a token costs by the line it writes).
+//
+// K' in tiles of 16 tokens, [4 slices][16 tokens][32 elements]: lane (token n, part c) of a wave finds
+// the 16 bytes it feeds to MFMA for slice sl at byte 1024 sl + 64 n + 16 c of the tile.  A token's
+// row is four runs of 64 bytes.
+//
+// V' transposed in blocks of 32 tokens, [8 column tiles][4 slot groups][16 columns][8 slots]: token t
+// of the block sits in slot v_slot(t).  With this order the 8 probabilities a lane holds after the
+// two 16-key score tiles of a block are exactly the 8 contraction slots it must supply, and lane
+// (column n of tile j, group c) finds its 16 bytes at byte 1024 j + 256 c + 16 n of the block.
+// A token touches 2 bytes in every 16 of one 256-byte run per column tile.
 inline bool v_transposed(int dtype, int head_dim) { return dtype == AIR_BF16 && head_dim == 128; }
 __host__ __device__ inline int v_slot(int t) { return ((t & 15) >> 2) * 8 + (t >> 4) * 4 + (t & 3); }
-// The same cache keeps K' in tiles of 16 tokens, [4 slices][4 parts][16 tokens][8 elements]: element
-// e of token r sits at k_tiled(r, e) elements from the unit's base.  Lane (token n, part c) of a
-// wave then finds the 16 bytes it feeds to MFMA for slice sl at byte 1024 sl + 256 c + 16 n of the
-// tile: each of the four loads of a tile covers 1 KB of consecutive memory.
+// element offsets from the unit's base of element e of K' row r / column col of V' row r
 __host__ __device__ inline int64_t k_tiled(int64_t r, int e) {
-    return (r >> 4) * 2048 + (e >> 5) * 512 + ((e >> 3) & 3) * 128 + (r & 15) * 8 + (e & 7);
+    return (r >> 4) * 2048 + (e >> 5) * 512 + (r & 15) * 32 + (e & 31);
+}
+__host__ __device__ inline int64_t v_tiled(int64_t r, int col) {
+    const int slot = v_slot((int)(r & 31));
+    return (r >> 5) * 4096 + (col >> 4) * 512 + (slot >> 3) * 128 + (col & 15) * 8 + (slot & 7);
 }
 
 }  // namespace air

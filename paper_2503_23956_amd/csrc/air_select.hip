@@ -154,7 +154,7 @@ __global__ __launch_bounds__(256) void gather_kernel(Dims dm, DevTables t, int l
 
 // bf16 / head_dim 128: the cache is written in the layouts the decode kernel feeds to MFMA.  One
 // workgroup stages the 32 gathered K and V rows of a block in LDS and writes K' as two 16-token
-// tiles (see k_tiled) and V' block-transposed, [128 columns][32 slots] (see v_slot).
+// tiles (see k_tiled) and V' block-transposed (see v_tiled).
 // Slots of the last block that have no token yet are written as zeros.
 __global__ __launch_bounds__(256) void gather_vt_kernel(Dims dm, DevTables t, int l0, LaunchLayers ll, air_strides st) {
     constexpr int D = 128;
@@ -195,17 +195,18 @@ __global__ __launch_bounds__(256) void gather_vt_kernel(Dims dm, DevTables t, in
         __syncthreads();
         // K': the two 16-token tiles of the block in k_tiled order, 16 bytes per thread, consecutive in memory
         for (int v = threadIdx.x; v < 32 * 16; v += 256) {
-            const int tl = v >> 8, sl = (v >> 6) & 3, c = (v >> 4) & 3, n = v & 15;
+            const int tl = v >> 8, sl = (v >> 6) & 3, n = (v >> 2) & 15, c = v & 3;
             *reinterpret_cast<uint4 *>(kdst + (int64_t)r0 * D + (int64_t)v * 8) =
                 *reinterpret_cast<const uint4 *>(&ktile[16 * tl + n][32 * sl + 8 * c]);
         }
+        // V': the block in v_tiled order, 8 slots of one column per thread, consecutive in memory
         for (int v = threadIdx.x; v < D * 4; v += 256) {
-            const int col = v >> 2, c = v & 3;
+            const int j = v >> 6, c = (v >> 4) & 3, col = 16 * j + (v & 15);
             uint32_t w[4];
 #pragma unroll
-            for (int j = 0; j < 4; ++j)
-                w[j] = (uint32_t)tile[8 * c + 2 * j][col] | ((uint32_t)tile[8 * c + 2 * j + 1][col] << 16);
-            *reinterpret_cast<uint4 *>(vdst + (int64_t)r0 * D + col * 32 + 8 * c) = make_uint4(w[0], w[1], w[2], w[3]);
+            for (int i = 0; i < 4; ++i)
+                w[i] = (uint32_t)tile[8 * c + 2 * i][col] | ((uint32_t)tile[8 * c + 2 * i + 1][col] << 16);
+            *reinterpret_cast<uint4 *>(vdst + (int64_t)r0 * D + (int64_t)v * 8) = make_uint4(w[0], w[1], w[2], w[3]);
         }
         __syncthreads();
     }
