@@ -79,6 +79,7 @@ WsLayout make_layout(const air_config &c) {
     w.dec_ml = take(L * B * Hq * kMaxSplits * 8);
     w.stash = v_transposed(c.dtype, c.head_dim) ? take(L * B * Hkv * (size_t)w.n_chunks * kStashRows * kChunkKeys * 4) : off;
     w.row_f = v_transposed(c.dtype, c.head_dim) ? take(L * B * Hkv * (size_t)kStashRows * w.n_chunks * 4) : off;
+    w.unit_R = take(L * B * Hkv * 4);
     w.total = off;
     return w;
 }
@@ -169,6 +170,7 @@ air_status air_create(const air_config *cfg, void *workspace, size_t workspace_b
     t.dec_ml = (float2 *)(w + lay.dec_ml);
     t.stash = (float *)(w + lay.stash);
     t.row_f = (float *)(w + lay.row_f);
+    t.unit_R = (int32_t *)(w + lay.unit_R);
     c->have_seqs = false;
     c->budgets_ready = false;
     c->force_splits = c->force_waves = c->force_tiles = 0;
@@ -312,8 +314,8 @@ air_status air_score(air_ctx *ctx, void *stream, int32_t l0, int32_t l1, const a
             LaunchLayers lg;
             memset(&lg, 0, sizeof(lg));
             for (int i = 0; i < gn; ++i) lg.p[i] = ll.p[g0 + i];
-            e = launch_score_mfma(s, ctx->dm, ctx->tab, 1, c0 + g0, gn, lg, *strides);
-            if (e == hipSuccess) e = launch_score_mfma(s, ctx->dm, ctx->tab, 2, c0 + g0, gn, lg, *strides);
+            e = launch_score_mfma(s, ctx->dm, ctx->tab, 1, c0 + g0, gn, lg, *strides, sa);
+            if (e == hipSuccess) e = launch_score_mfma(s, ctx->dm, ctx->tab, 2, c0 + g0, gn, lg, *strides, sa);
         }
         if (e != hipSuccess) return hip_fail(ctx, e, "air_score launch");
     }

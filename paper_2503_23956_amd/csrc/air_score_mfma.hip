@@ -23,6 +23,7 @@
 //       Epilogue: fp64 power sums of I over the chunk, from which the budget kernel forms Eq.9-10.
 #include "air_device.h"
 #include "air_internal.h"
+#include <type_traits>
 
 namespace air {
 
@@ -57,19 +58,17 @@ __device__ __forceinline__ int head_of_row(const int *s_pref, int G, int rho) {
     return g;
 }
 
-// keys of one wave: 4 tiles of 16, as MFMA B operands
+// keys of one wave: 4 tiles of 16, as MFMA B operands.  Keys past the end of the visual span re-read
+// the last one (no predication in front of the loads); `valid` masks their logits.
 __device__ __forceinline__ void load_keys(const UnitCtx &u, const air_strides &st, int key0, int n, int c,
                                           uint4 (&kreg)[4][4], bool (&valid)[4]) {
 #pragma unroll
     for (int tile = 0; tile < 4; ++tile) {
         const int key = key0 + 16 * tile + n;
         valid[tile] = key < u.sq.vis_len;
+        const bf16_t *src = u.k + (int64_t)(u.sq.vis_start + min(key, u.sq.vis_len - 1)) * st.kv_t + 8 * c;
 #pragma unroll
-        for (int sl = 0; sl < 4; ++sl) {
-            kreg[tile][sl] = make_uint4(0, 0, 0, 0);
-            if (valid[tile])
-                kreg[tile][sl] = *reinterpret_cast<const uint4 *>(u.k + (int64_t)(u.sq.vis_start + key) * st.kv_t + 32 * sl + 8 * c);
-        }
+        for (int sl = 0; sl < 4; ++sl) kreg[tile][sl] = *reinterpret_cast<const uint4 *>(src + 32 * sl);
     }
 }
 
@@ -97,6 +96,9 @@ __device__ __forceinline__ void load_rows(const DevTables &t, const UnitCtx &u, 
 // the scale is folded into the exponential, exp((s - M) / sqrt(d)) = 2^((s - M) * kC).
 constexpr float kCHi = 0.127517431974411f, kCLo = -1.1498123564379625e-09f;  // log2(e) / sqrt(128), split
 __device__ __forceinline__ float exp_raw(float d) { return exp2_scaled(d, kCHi, kCLo); }
+// The per-key exponentials take the one-multiply form: its rounding of d * kCHi costs a relative
+// 0.7 * 2^-24 * |log2 of the result|, below 6e-6 down to the smallest fp32 the result can be.
+__device__ __forceinline__ float exp_key(float d) { return __builtin_amdgcn_exp2f(d * kCHi); }
 
 __device__ __forceinline__ void logits_of(const uint4 (&qa)[4], const uint4 (&kreg)[4][4], f32x4 (&s)[4]) {
 #pragma unroll
@@ -117,7 +119,7 @@ __device__ __forceinline__ void block_logits(const DevTables &t, const UnitCtx &
     logits_of(qa, kreg, s);
 }
 
-__device__ __forceinline__ bool unit_setup(const Dims &dm, const DevTables &t, int l0, const LaunchLayers &ll,
+__device__ __forceinline__ bool unit_setup(const Dims &dm, const SeqArgs &seqs, int l0, const LaunchLayers &ll,
                                            const air_strides &st, UnitCtx &u, int chunks_per_wg) {
     u.chunk = blockIdx.x * chunks_per_wg;  // first chunk of this workgroup
     const int uu = blockIdx.y;
@@ -125,7 +127,7 @@ __device__ __forceinline__ bool unit_setup(const Dims &dm, const DevTables &t, i
     u.b = (uu / dm.Hkv) % dm.B;
     u.li = uu / (dm.Hkv * dm.B);
     u.l = l0 + u.li;
-    u.sq = t.seq_tab[u.b];
+    u.sq = seqs.s[u.b];  // from the kernel arguments: no table read in front of the key loads
     if (u.chunk * kChunkKeys >= u.sq.vis_len) return false;
     u.t0 = u.sq.vis_start + u.sq.vis_len;
     u.G = dm.G;
@@ -140,7 +142,7 @@ __device__ __forceinline__ bool unit_setup(const Dims &dm, const DevTables &t, i
 // ---------------------------------------------------------------------------------------
 // One workgroup streams kStreamChunks consecutive chunks of a unit; the keys of the next chunk are
 // requested before the current one is scored, so that the memory pipe never drains while the
-// workgroup computes.  The window rows (A operands) of the first two row blocks are loaded once.
+// workgroup computes.  The window rows (A operands) of the first row block are loaded once.
 // Stash layout of one (unit, chunk, row): 256 floats, key 64w + 16 tile + n at position 64w + 4n + tile,
 // i.e. the four tiles of a lane are one 16-byte store.
 constexpr int kStreamChunks = 1;
@@ -149,11 +151,11 @@ __device__ __forceinline__ int stash_pos(int key_in_chunk) {
     return (key_in_chunk & ~63) | ((key_in_chunk & 15) << 2) | ((key_in_chunk >> 4) & 3);
 }
 
-__global__ __launch_bounds__(256, 3) void score_stream_kernel(Dims dm, DevTables t, int l0, LaunchLayers ll,
-                                                              air_strides st) {
+__global__ __launch_bounds__(256, 4) void score_stream_kernel(Dims dm, DevTables t, int l0, LaunchLayers ll,
+                                                              air_strides st, SeqArgs seqs) {
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, n = lane & 15, c = lane >> 4;
     UnitCtx u;
-    if (!unit_setup(dm, t, l0, ll, st, u, kStreamChunks)) return;
+    if (!unit_setup(dm, seqs, l0, ll, st, u, kStreamChunks)) return;
     __shared__ int s_pref[17];
     __shared__ float s_pm[4][16], s_pz[4][16], s_mw[16];
 
@@ -165,9 +167,8 @@ __global__ __launch_bounds__(256, 3) void score_stream_kernel(Dims dm, DevTables
     head_prefix(t, u.hrow0, u.G, s_pref);
     u.R_total = s_pref[u.G];
     const bool stash = u.R_total <= kStashRows;
-    uint4 qa0[4], qa1[4];
+    uint4 qa0[4];
     load_rows(t, u, st, s_pref, 0, n, c, qa0);
-    load_rows(t, u, st, s_pref, 16, n, c, qa1);
 
 #pragma unroll
     for (int ci = 0; ci < kStreamChunks; ++ci) {
@@ -178,7 +179,6 @@ __global__ __launch_bounds__(256, 3) void score_stream_kernel(Dims dm, DevTables
         for (int rb = 0; rb < u.R_total; rb += 16) {
             f32x4 s[4];
             if (rb == 0) logits_of(qa0, kreg, s);
-            else if (rb == 16) logits_of(qa1, kreg, s);
             else block_logits(t, u, st, s_pref, rb, n, c, kreg, s);
             const int n_i = min(4, (u.R_total - rb + 3) >> 2);  // live values of i (uniform over the workgroup)
             float m[4];
@@ -207,7 +207,7 @@ __global__ __launch_bounds__(256, 3) void score_stream_kernel(Dims dm, DevTables
                 const float M = fmaxf(fmaxf(s_pm[0][r], s_pm[1][r]), fmaxf(s_pm[2][r], s_pm[3][r]));
                 f32x4 e;
 #pragma unroll
-                for (int tile = 0; tile < 4; ++tile) e[tile] = valid[tile] ? exp_raw(s[tile][i] - M) : 0.f;
+                for (int tile = 0; tile < 4; ++tile) e[tile] = valid[tile] ? exp_key(s[tile][i] - M) : 0.f;
                 float zz = (e[0] + e[1]) + (e[2] + e[3]);
                 if (stash && rb + r < u.R_total)
                     *reinterpret_cast<f32x4 *>(stash_base + (int64_t)(rb + r) * kChunkKeys + wave * 64 + 4 * n) = e;
@@ -255,6 +255,7 @@ __global__ __launch_bounds__(256) void score_rows_mfma_kernel(Dims dm, DevTables
     head_prefix(t, hrow0, G, s_pref);
     const int R_total = s_pref[G];
     const bool stash = R_total <= kStashRows;
+    if (tid == 0) t.unit_R[unit] = R_total;
     for (int rho = wave; rho < R_total; rho += 4) {
         const int g = head_of_row(s_pref, G, rho);
         const int64_t slot = (hrow0 + g) * W + (rho - s_pref[g]);
@@ -286,10 +287,10 @@ __global__ __launch_bounds__(256) void score_rows_mfma_kernel(Dims dm, DevTables
 // One workgroup finishes kFinishChunks consecutive chunks of a unit and leaves one power-sum entry.
 
 __global__ __launch_bounds__(256) void score_finish_kernel(Dims dm, DevTables t, int l0, LaunchLayers ll,
-                                                           air_strides st) {
+                                                           air_strides st, SeqArgs seqs) {
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, n = lane & 15, c = lane >> 4;
     UnitCtx u;
-    if (!unit_setup(dm, t, l0, ll, st, u, kFinishChunks)) return;
+    if (!unit_setup(dm, seqs, l0, ll, st, u, kFinishChunks)) return;
     __shared__ int s_pref[17];
     __shared__ float s_M[kRowsLds], s_w[kRowsLds];
     __shared__ float s_f[kFinishChunks][kStashRows];
@@ -301,9 +302,9 @@ __global__ __launch_bounds__(256) void score_finish_kernel(Dims dm, DevTables t,
     float f_mine = 0.f;
     if (tid < kFinishChunks * kStashRows && first + tid / kStashRows < last)
         f_mine = t.row_f[(u.unit * kStashRows + (tid % kStashRows)) * dm.n_chunks + first + tid / kStashRows];
-    head_prefix(t, u.hrow0, u.G, s_pref);
-    u.R_total = s_pref[u.G];
+    u.R_total = t.unit_R[u.unit];
     const bool stash = u.R_total <= kStashRows;
+    if (!stash) head_prefix(t, u.hrow0, u.G, s_pref);
 
     // fp64 power sums of I over the workgroup's chunks, summed in a fixed order; one entry per workgroup
     double m1 = 0.0, m2 = 0.0, m3 = 0.0;
@@ -326,22 +327,55 @@ __global__ __launch_bounds__(256) void score_finish_kernel(Dims dm, DevTables t,
     if (stash) {
         if (tid < kFinishChunks * kStashRows) s_f[tid / kStashRows][tid % kStashRows] = (tid % kStashRows) < u.R_total ? f_mine : 0.f;
         lds_barrier();
-        for (int ci = 0; ci < last - first; ++ci) {  // one chunk at a time: few registers, many workgroups per CU
-            const float *sb = t.stash + ((u.unit * dm.n_chunks + first + ci) * (int64_t)kStashRows) * kChunkKeys + stash_pos(tid);
-            float e[kStashRows];
+        // All stashed values of the workgroup's chunks are requested at once when the list is short
+        // (rows past the list re-read its last row against a zero factor, chunks past the end re-read
+        // the last chunk and are not stored); longer lists go chunk by chunk.
+        auto finish_all = [&](auto rb_tag) __attribute__((always_inline)) {
+            constexpr int RB = decltype(rb_tag)::value;
+            float e[kFinishChunks][RB];
 #pragma unroll
-            for (int r = 0; r < kStashRows; ++r) e[r] = r < u.R_total ? sb[(int64_t)r * kChunkKeys] : 0.f;
-            float imp = 0.f;
+            for (int ci = 0; ci < kFinishChunks; ++ci) {
+                const float *sb = t.stash + ((u.unit * dm.n_chunks + min(first + ci, last - 1)) * (int64_t)kStashRows) * kChunkKeys + stash_pos(tid);
 #pragma unroll
-            for (int r = 0; r < kStashRows; ++r)
-                if (r < u.R_total) imp = fmaf(s_f[ci][r], e[r], imp);
-            const int key = (first + ci) * kChunkKeys + tid;
-            if (key < u.sq.vis_len) {
-                t.scores[u.unit * dm.max_vis + key] = imp;
-                const double x = (double)imp;
-                m1 += x;
-                m2 += x * x;
-                m3 += x * x * x;
+                for (int r = 0; r < RB; ++r) e[ci][r] = sb[(int64_t)min(r, u.R_total - 1) * kChunkKeys];
+            }
+#pragma unroll
+            for (int ci = 0; ci < kFinishChunks; ++ci) {
+                float imp = 0.f;
+#pragma unroll
+                for (int r = 0; r < RB; ++r) imp = fmaf(s_f[ci][r], e[ci][r], imp);
+                const int key = (first + ci) * kChunkKeys + tid;
+                if (first + ci < last && key < u.sq.vis_len) {
+                    t.scores[u.unit * dm.max_vis + key] = imp;
+                    const double x = (double)imp;
+                    m1 += x;
+                    m2 += x * x;
+                    m3 += x * x * x;
+                }
+            }
+        };
+        if (u.R_total <= 8 && u.R_total > 0) {
+            finish_all(std::integral_constant<int, 8>());
+        } else if (u.R_total <= 16 && u.R_total > 0) {
+            finish_all(std::integral_constant<int, 16>());
+        } else {
+            for (int ci = 0; ci < last - first; ++ci) {
+                const float *sb = t.stash + ((u.unit * dm.n_chunks + first + ci) * (int64_t)kStashRows) * kChunkKeys + stash_pos(tid);
+                float e[kStashRows];
+#pragma unroll
+                for (int r = 0; r < kStashRows; ++r) e[r] = r < u.R_total ? sb[(int64_t)r * kChunkKeys] : 0.f;
+                float imp = 0.f;
+#pragma unroll
+                for (int r = 0; r < kStashRows; ++r)
+                    if (r < u.R_total) imp = fmaf(s_f[ci][r], e[r], imp);
+                const int key = (first + ci) * kChunkKeys + tid;
+                if (key < u.sq.vis_len) {
+                    t.scores[u.unit * dm.max_vis + key] = imp;
+                    const double x = (double)imp;
+                    m1 += x;
+                    m2 += x * x;
+                    m3 += x * x * x;
+                }
             }
         }
         put_moments();
@@ -381,7 +415,7 @@ __global__ __launch_bounds__(256) void score_finish_kernel(Dims dm, DevTables t,
                     const float M = have ? s_M[rr] : 0.f;
                     const float w = have ? s_w[rr] : 0.f;
 #pragma unroll
-                    for (int tile = 0; tile < 4; ++tile) acc[tile] = fmaf(w, exp_raw(s[tile][i] - M), acc[tile]);
+                    for (int tile = 0; tile < 4; ++tile) acc[tile] = fmaf(w, exp_key(s[tile][i] - M), acc[tile]);
                 }
             }
         }
@@ -575,16 +609,16 @@ hipError_t launch_elite_mfma(hipStream_t s, const Dims &dm, const DevTables &t, 
 }
 
 hipError_t launch_score_mfma(hipStream_t s, const Dims &dm, const DevTables &t, int pass, int l0, int nl,
-                             const LaunchLayers &ll, const air_strides &st) {
+                             const LaunchLayers &ll, const air_strides &st, const SeqArgs &seqs) {
     if (pass == 1)
         hipLaunchKernelGGL(score_stream_kernel, dim3((dm.n_chunks + kStreamChunks - 1) / kStreamChunks, nl * dm.B * dm.Hkv),
-                           dim3(256), 0, s, dm, t, l0, ll, st);
+                           dim3(256), 0, s, dm, t, l0, ll, st, seqs);
     else {
         hipLaunchKernelGGL(score_rows_mfma_kernel, dim3(nl * dm.B * dm.Hkv), dim3(256), 0, s, dm, t, l0);
         hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;
         hipLaunchKernelGGL(score_finish_kernel, dim3((dm.n_chunks + kFinishChunks - 1) / kFinishChunks, nl * dm.B * dm.Hkv),
-                           dim3(256), 0, s, dm, t, l0, ll, st);
+                           dim3(256), 0, s, dm, t, l0, ll, st, seqs);
     }
     return hipGetLastError();
 }
