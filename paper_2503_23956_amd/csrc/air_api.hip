@@ -80,6 +80,7 @@ WsLayout make_layout(const air_config &c) {
     w.stash = v_transposed(c.dtype, c.head_dim) ? take(L * B * Hkv * (size_t)w.n_chunks * kStashRows * kChunkKeys * 4) : off;
     w.row_f = v_transposed(c.dtype, c.head_dim) ? take(L * B * Hkv * (size_t)kStashRows * w.n_chunks * 4) : off;
     w.unit_R = take(L * B * Hkv * 4);
+    w.len_off = take(B * L * 8);
     w.total = off;
     return w;
 }
@@ -171,6 +172,7 @@ air_status air_create(const air_config *cfg, void *workspace, size_t workspace_b
     t.stash = (float *)(w + lay.stash);
     t.row_f = (float *)(w + lay.row_f);
     t.unit_R = (int32_t *)(w + lay.unit_R);
+    t.len_off = (int2 *)(w + lay.len_off);
     c->have_seqs = false;
     c->budgets_ready = false;
     c->force_splits = c->force_waves = c->force_tiles = 0;

@@ -238,6 +238,7 @@ __global__ __launch_bounds__(kBT) void budget_kernel(Dims dm, DevTables t, doubl
         }
         t.base_len[(int64_t)b * L + tid] = nonvis + kk[tid];
         t.layer_off[(int64_t)b * L + tid] = off;
+        t.len_off[(int64_t)b * L + tid] = make_int2(nonvis + kk[tid], off);
     }
 }
 

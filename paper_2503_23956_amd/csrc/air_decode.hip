@@ -99,12 +99,13 @@ __global__ __launch_bounds__(64 * NW) void decode_mfma_kernel(Dims dm, DevTables
     for (int j = 0; j < 8; ++j) vnew[j] = v_new[new_src + 16 * j + n];
     vcol[0] = v_new[new_src + lane];
     vcol[1] = v_new[new_src + 64 + lane];
-    const int len = t.base_len[(int64_t)b * dm.L + l] + ll.appended[li] + 1;
+    const int2 len_off = t.len_off[(int64_t)b * dm.L + l];
+    const int len = len_off.x + ll.appended[li] + 1;
     const int newrow = len - 1;  // the token appended by this call (Eq.2): scored from k_new / v_new, stored to the cache
     int k0, k1;
     split_range(len, splits, split, k0, k1);
     const int kend = min(k1, newrow);  // the split's keys that are in the cache: [k0, kend)
-    const int64_t row0 = ((int64_t)b * dm.Hkv + kvh) * dm.pool_rows + t.layer_off[(int64_t)b * dm.L + l];
+    const int64_t row0 = ((int64_t)b * dm.Hkv + kvh) * dm.pool_rows + len_off.y;
     bf16_t *kc = (bf16_t *)t.kcache + row0 * D;
     bf16_t *vc = (bf16_t *)t.vcache + row0 * D;
     const int64_t unit = ((int64_t)l * dm.B + b) * dm.Hkv + kvh;

@@ -36,7 +36,7 @@ struct SeqArgs {
 struct WsLayout {
     size_t seq_tab, elite_cnt, elite_idx, row_mtext, row_ztext, row_M, row_w, part, scores;
     size_t unit_st, unit_sk, s_t, s_k, budgets, base_len, layer_off, dec_cnt, moments, indices;
-    size_t kcache, vcache, dec_o, dec_ml, stash, row_f, unit_R;
+    size_t kcache, vcache, dec_o, dec_ml, stash, row_f, unit_R, len_off;
     size_t total;
     int32_t n_chunks;     // ceil(max_vis_len / kChunkKeys)
     int64_t pool_rows;    // rows of one (sequence, KV head) cache pool
@@ -59,6 +59,7 @@ struct DevTables {
     int32_t *budgets, *base_len, *layer_off, *dec_cnt, *indices;
     void *kcache, *vcache;
     float *dec_o, *stash, *row_f;
+    int2 *len_off;    // (base_len, layer_off) of a (sequence, layer) side by side: one read for the decode kernel
     int32_t *unit_R;  // window rows of a unit (all heads of the group), left by the row-parameter kernel
     float2 *dec_ml;
 };
