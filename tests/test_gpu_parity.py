@@ -207,6 +207,17 @@ def test_decode_long_cache_multiple_iterations_per_split():
     _run_case(w, 1.00, steps=2)
 
 
+@pytest.mark.parametrize("splits,waves,tiles", [(4, 8, 4), (1, 2, 2), (2, 4, 2), (1, 1, 8), (16, 1, 4), (2, 2, 8)])
+def test_decode_forced_launch_shapes(monkeypatch, splits, waves, tiles):
+    # every compiled launch shape of the decode kernel (split-K exchange, 32-key double-buffered chunks,
+    # 128-key chunks) against the oracle, with appends that cross token-block and split boundaries
+    monkeypatch.setenv("AIR_DECODE_SPLITS", str(splits))
+    monkeypatch.setenv("AIR_DECODE_WAVES", str(waves))
+    monkeypatch.setenv("AIR_DECODE_TILES", str(tiles))
+    w = synth.get_workload(2).scaled(n_layers=2, n_vis=900, n_text=37, decode_steps=36)
+    _run_case(w, 0.25, steps=36)
+
+
 def test_config2_full_size():
     _run_case(synth.get_workload(2), 0.10, steps=2)
 
