@@ -241,7 +241,8 @@ __global__ __launch_bounds__(256, 4) void score_stream_kernel(Dims dm, DevTables
 // M = max over chunks and the elite-text columns, Z = sum z exp(m - M) in fp64,
 // w = 1 / (R_h G Z).  Units with a stash also get f[row][chunk] = w exp(m_chunk - M), the factor
 // that turns a stashed exponential into its share of Eq.8.
-__global__ __launch_bounds__(256) void score_rows_mfma_kernel(Dims dm, DevTables t, int l0) {
+constexpr int kRowWaves = 16;  // one wave per row: a unit's usual dozen rows are done in one round of loads
+__global__ __launch_bounds__(64 * kRowWaves) void score_rows_mfma_kernel(Dims dm, DevTables t, int l0, SeqArgs seqs) {
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
     const int uu = blockIdx.x;
     const int kvh = uu % dm.Hkv;
@@ -250,27 +251,28 @@ __global__ __launch_bounds__(256) void score_rows_mfma_kernel(Dims dm, DevTables
     const int G = dm.G, W = dm.max_window;
     const int64_t hrow0 = ((int64_t)l * dm.B + b) * dm.Hq + (int64_t)kvh * G;
     const int64_t unit = ((int64_t)l * dm.B + b) * dm.Hkv + kvh;
-    const int nch = (t.seq_tab[b].vis_len + kChunkKeys - 1) / kChunkKeys;
+    const int nch = (seqs.s[b].vis_len + kChunkKeys - 1) / kChunkKeys;
     __shared__ int s_pref[17];
     head_prefix(t, hrow0, G, s_pref);
     const int R_total = s_pref[G];
     const bool stash = R_total <= kStashRows;
     if (tid == 0) t.unit_R[unit] = R_total;
-    for (int rho = wave; rho < R_total; rho += 4) {
+    for (int rho = wave; rho < R_total; rho += kRowWaves) {
         const int g = head_of_row(s_pref, G, rho);
         const int64_t slot = (hrow0 + g) * W + (rho - s_pref[g]);
         const float2 *p = t.part + slot * dm.n_chunks;
-        const float mt = t.row_mtext[slot];
-        float M = mt;
-        for (int cc = lane; cc < nch; cc += 64) M = fmaxf(M, p[cc].x);
+        const float mt = t.row_mtext[slot], zt = t.row_ztext[slot];
+        const float2 p0 = lane < nch ? p[lane] : make_float2(-INFINITY, 0.f);  // the first 64 chunks stay in registers
+        float M = fmaxf(mt, p0.x);
+        for (int cc = lane + 64; cc < nch; cc += 64) M = fmaxf(M, p[cc].x);
         M = wave_max(M);
-        double Z = 0.0;
-        for (int cc = lane; cc < nch; cc += 64) {
+        double Z = lane < nch ? (double)(p0.y * exp_raw(p0.x - M)) : 0.0;
+        for (int cc = lane + 64; cc < nch; cc += 64) {
             const float2 x = p[cc];
             Z += (double)(x.y * exp_raw(x.x - M));
         }
         Z = wave_sum(Z);
-        Z += (double)(t.row_ztext[slot] * exp_raw(mt - M));
+        Z += (double)(zt * exp_raw(mt - M));
         const float w = (float)(1.0 / ((double)(s_pref[g + 1] - s_pref[g]) * (double)G * Z));
         if (lane == 0) {
             t.row_M[slot] = M;  // raw units
@@ -278,7 +280,8 @@ __global__ __launch_bounds__(256) void score_rows_mfma_kernel(Dims dm, DevTables
         }
         if (stash) {
             float *f = t.row_f + (unit * kStashRows + rho) * dm.n_chunks;
-            for (int cc = lane; cc < nch; cc += 64) f[cc] = w * exp_raw(p[cc].x - M);
+            if (lane < nch) f[lane] = w * exp_raw(p0.x - M);
+            for (int cc = lane + 64; cc < nch; cc += 64) f[cc] = w * exp_raw(p[cc].x - M);
         }
     }
 }
@@ -614,7 +617,7 @@ hipError_t launch_score_mfma(hipStream_t s, const Dims &dm, const DevTables &t, 
         hipLaunchKernelGGL(score_stream_kernel, dim3((dm.n_chunks + kStreamChunks - 1) / kStreamChunks, nl * dm.B * dm.Hkv),
                            dim3(256), 0, s, dm, t, l0, ll, st, seqs);
     else {
-        hipLaunchKernelGGL(score_rows_mfma_kernel, dim3(nl * dm.B * dm.Hkv), dim3(256), 0, s, dm, t, l0);
+        hipLaunchKernelGGL(score_rows_mfma_kernel, dim3(nl * dm.B * dm.Hkv), dim3(64 * kRowWaves), 0, s, dm, t, l0, seqs);
         hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;
         hipLaunchKernelGGL(score_finish_kernel, dim3((dm.n_chunks + kFinishChunks - 1) / kFinishChunks, nl * dm.B * dm.Hkv),
