@@ -70,9 +70,22 @@ __global__ __launch_bounds__(128) void append_kernel(Dims dm, DevTables t, int l
 // The waves of a workgroup merge through LDS.  With more than one split per unit the
 // workgroups exchange partials through memory and the one that finishes last merges them.
 // ---------------------------------------------------------------------------------------
+// What the MFMA decode kernel needs of the tables and of the per-layer launch block: a short
+// argument block (the kernel starts with the loads of its arguments).
+struct DecodeTabs {
+    const int2 *len_off;
+    void *kcache, *vcache;
+    float *dec_o;
+    float2 *dec_ml;
+    int32_t *dec_cnt;
+};
+struct DecodeSteps {
+    int32_t appended[kMaxLayersPerLaunch];
+};
+
 template <int NW, int KT>
-__global__ __launch_bounds__(64 * NW) void decode_mfma_kernel(Dims dm, DevTables t, int l0, int lbase,
-                                                              LaunchLayers ll, const bf16_t *q_new,
+__global__ __launch_bounds__(64 * NW) void decode_mfma_kernel(Dims dm, DecodeTabs t, int l0, int lbase,
+                                                              DecodeSteps ll, const bf16_t *q_new,
                                                               const bf16_t *k_new, const bf16_t *v_new, bf16_t *out,
                                                               int splits) {
     constexpr int D = 128;
@@ -621,8 +634,17 @@ hipError_t launch_decode(hipStream_t s, const Dims &dm, const DevTables &t, int 
                          int splits, int waves, int tiles) {
     if (v_transposed(dtype, dm.D)) {  // one launch: append, attention and merge of the partials
         const dim3 grid(splits, nl * dm.B * dm.Hkv);
+        DecodeTabs dt;
+        dt.len_off = t.len_off;
+        dt.kcache = t.kcache;
+        dt.vcache = t.vcache;
+        dt.dec_o = t.dec_o;
+        dt.dec_ml = t.dec_ml;
+        dt.dec_cnt = t.dec_cnt;
+        DecodeSteps ds;
+        for (int i = 0; i < kMaxLayersPerLaunch; ++i) ds.appended[i] = ll.appended[i];
 #define AIR_LAUNCH_DECODE(NW, KT)                                                                                  \
-    hipLaunchKernelGGL((decode_mfma_kernel<NW, KT>), grid, dim3(64 * NW), 0, s, dm, t, l0, lbase, ll,              \
+    hipLaunchKernelGGL((decode_mfma_kernel<NW, KT>), grid, dim3(64 * NW), 0, s, dm, dt, l0, lbase, ds,             \
                        (const bf16_t *)q_new, (const bf16_t *)k_new, (const bf16_t *)v_new, (bf16_t *)out, splits)
         if (waves == 8 && tiles == 4) AIR_LAUNCH_DECODE(8, 4);
         else if (waves == 4 && tiles == 4) AIR_LAUNCH_DECODE(4, 4);
