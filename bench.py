@@ -118,6 +118,9 @@ def main():
     ap.add_argument("--decode-steps", type=int, default=None)
     ap.add_argument("--per-layer", action="store_true", help="one air_decode_attn call per layer instead of one per step")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--retention-sweep", action="store_true",
+                    help="also time the same workload with the full cache and at 50 % / 10 % / 1 % retention "
+                         "(the quantity the paper's efficiency table reports for attention alone)")
     ap.add_argument("--copy-probe", type=int, default=0, metavar="MB",
                     help="only run a plain device copy of this many MB (reference for the rocprofv3 byte counters)")
     args = ap.parse_args()
@@ -167,55 +170,60 @@ def main():
     dv = to_device(np.stack([d[2] for d in dec_inputs]), dev)
     out = torch.empty((L, w.batch, w.n_q_heads, w.head_dim), dtype=q[0].dtype, device=dev)
 
-    ac = A.AirCache(config_for(w, retention, max_decode_steps=n_dec, seqs=seqs), dev)
-    ev = lambda: torch.cuda.Event(enable_timing=True)  # noqa: E731
-    # host-side marshalling is done once, outside the timed region: descriptor arrays and raw addresses
-    prep_score = ac.prepare(q, k, v, seqs)
-    prep_compact = ac.prepare(None, k, v)
-    esz = dq.element_size()
-    step_q = dq[0].numel() * esz
-    step_kv = dk[0].numel() * esz
-    lay_q = dq[0, 0].numel() * esz
-    lay_kv = dk[0, 0].numel() * esz
-    pq, pk, pv, po = dq.data_ptr(), dk.data_ptr(), dv.data_ptr(), out.data_ptr()
+    def run(retention, steps, warmup):
+        """One context at this retention: `warmup` untimed passes, then `steps` timed ones."""
+        ac = A.AirCache(config_for(w, retention, max_decode_steps=n_dec, seqs=seqs), dev)
+        ev = lambda: torch.cuda.Event(enable_timing=True)  # noqa: E731
+        # host-side marshalling is done once, outside the timed region: descriptor arrays and raw addresses
+        prep_score = ac.prepare(q, k, v, seqs)
+        prep_compact = ac.prepare(None, k, v)
+        esz = dq.element_size()
+        step_q = dq[0].numel() * esz
+        step_kv = dk[0].numel() * esz
+        lay_q = dq[0, 0].numel() * esz
+        lay_kv = dk[0, 0].numel() * esz
+        pq, pk, pv, po = dq.data_ptr(), dk.data_ptr(), dv.data_ptr(), out.data_ptr()
 
-    def one_step(events=None):
-        ac.air_reset()
-        if events is not None:
-            events[0].record()
-        ac.air_score(0, L, prepared=prep_score)
-        if events is not None:
-            events[1].record()
-        ac.air_budget()
-        if events is not None:
-            events[2].record()
-        ac.air_select_compact(0, L, prepared=prep_compact)
-        if events is not None:
-            events[3].record()
-        for t in range(n_dec):
-            if args.per_layer:
-                for l in range(L):
-                    ac.air_decode_attn(l, l + 1, pq + t * step_q + l * lay_q, pk + t * step_kv + l * lay_kv,
-                                       pv + t * step_kv + l * lay_kv, po + l * lay_q)
-            else:
-                ac.air_decode_attn(0, L, pq + t * step_q, pk + t * step_kv, pv + t * step_kv, po)
-        if events is not None:
-            events[4].record()
+        def one_step(events=None):
+            ac.air_reset()
+            if events is not None:
+                events[0].record()
+            ac.air_score(0, L, prepared=prep_score)
+            if events is not None:
+                events[1].record()
+            ac.air_budget()
+            if events is not None:
+                events[2].record()
+            ac.air_select_compact(0, L, prepared=prep_compact)
+            if events is not None:
+                events[3].record()
+            for t in range(n_dec):
+                if args.per_layer:
+                    for l in range(L):
+                        ac.air_decode_attn(l, l + 1, pq + t * step_q + l * lay_q, pk + t * step_kv + l * lay_kv,
+                                           pv + t * step_kv + l * lay_kv, po + l * lay_q)
+                else:
+                    ac.air_decode_attn(0, L, pq + t * step_q, pk + t * step_kv, pv + t * step_kv, po)
+            if events is not None:
+                events[4].record()
 
-    for _ in range(args.warmup):
-        one_step()
-    torch.cuda.synchronize()
-    budgets = ac.air_get_budgets()
-    all_events = [[ev() for _ in range(5)] for _ in range(args.steps)]
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for i in range(args.steps):
-        one_step(all_events[i])
-    torch.cuda.synchronize()
-    wall = time.perf_counter() - t0
+        for _ in range(warmup):
+            one_step()
+        torch.cuda.synchronize()
+        budgets = ac.air_get_budgets()
+        all_events = [[ev() for _ in range(5)] for _ in range(steps)]
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for i in range(steps):
+            one_step(all_events[i])
+        torch.cuda.synchronize()
+        wall = time.perf_counter() - t0
 
-    stage = np.array([[e[i].elapsed_time(e[i + 1]) for i in range(4)] for e in all_events])  # ms
-    score_ms, budget_ms, select_ms, decode_ms = stage.mean(axis=0)
+        stage = np.array([[e[i].elapsed_time(e[i + 1]) for i in range(4)] for e in all_events])  # ms
+        del ac
+        return stage.mean(axis=0), wall, budgets
+
+    (score_ms, budget_ms, select_ms, decode_ms), wall, budgets = run(retention, args.steps, args.warmup)
     compress_ms = score_ms + budget_ms + select_ms
     ms_per_step = wall * 1e3 / args.steps
     ab = algorithmic_bytes(w, seqs, budgets, n_dec)
@@ -262,6 +270,15 @@ def main():
             result["roofline"]["traffic"] = tr["fetch_bytes"] + tr["write_bytes"]
     except (OSError, ValueError):
         pass
+    if args.retention_sweep:
+        sweep = []
+        for r in (1.0, 0.5, 0.1, 0.01):
+            (sc, bu, se, de), _, _ = run(r, 3, 1)
+            sweep.append({"retention": r, "compress_us_per_layer": (sc + bu + se) * 1e3 / L,
+                          "decode_us_per_step": de * 1e3 / n_dec})
+        for e in sweep:
+            e["decode_speedup_vs_full_cache"] = sweep[0]["decode_us_per_step"] / e["decode_us_per_step"]
+        result["retention_sweep"] = sweep
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(w, seqs, retention, host_layers, dec_inputs, n_dec)
     print(json.dumps(result))
