@@ -218,6 +218,19 @@ def test_decode_forced_launch_shapes(monkeypatch, splits, waves, tiles):
     _run_case(w, 0.25, steps=36)
 
 
+def test_maximum_candidate_span():
+    # 4096 text tokens, the largest candidate span the boundary accepts: the elite kernel then keeps
+    # the logits of one head at a time in LDS
+    w = synth.get_workload(2).scaled(n_layers=1, n_vis=300, n_text=4096, decode_steps=1)
+    _run_case(w, 0.10, steps=1)
+
+
+def test_maximum_batch():
+    # 64 ragged sequences, the largest batch the boundary accepts (the sequence table travels as a kernel argument)
+    w = synth.get_workload(3).scaled(batch=64, n_layers=2, n_vis=260, n_text=20, decode_steps=2)
+    _run_case(w, 0.10, steps=2)
+
+
 def test_config2_full_size():
     _run_case(synth.get_workload(2), 0.10, steps=2)
 
