@@ -83,7 +83,7 @@ struct DecodeSteps {
     int32_t appended[kMaxLayersPerLaunch];
 };
 
-template <int NW, int KT>
+template <int NW, int KT, bool SPLIT>
 __global__ __launch_bounds__(64 * NW) void decode_mfma_kernel(Dims dm, DecodeTabs t, int l0, int lbase,
                                                               DecodeSteps ll, const bf16_t *q_new,
                                                               const bf16_t *k_new, const bf16_t *v_new, bf16_t *out,
@@ -359,7 +359,7 @@ __global__ __launch_bounds__(64 * NW) void decode_mfma_kernel(Dims dm, DecodeTab
     }
     constexpr int kTiles = 8 / NW;  // output tiles this wave owns after the merge: j = wave + NW*jj
 
-    if (splits == 1) {  // no partials: normalise and store
+    if (!SPLIT || splits == 1) {  // no partials: normalise and store
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
             const int g = 4 * c + i;
@@ -372,6 +372,7 @@ __global__ __launch_bounds__(64 * NW) void decode_mfma_kernel(Dims dm, DecodeTab
         }
         return;
     }
+    if (!SPLIT) return;  // the instance for one workgroup per unit carries none of what follows
     // ---- partial of this split.  Partials are exchanged between workgroups of one launch, which
     // may run on different XCDs (separate L2s).  They are written and read with system-scope
     // (write-through / L2-bypassing) 16-byte accesses in the accumulators' own lane layout, the
@@ -644,8 +645,16 @@ hipError_t launch_decode(hipStream_t s, const Dims &dm, const DevTables &t, int 
         DecodeSteps ds;
         for (int i = 0; i < kMaxLayersPerLaunch; ++i) ds.appended[i] = ll.appended[i];
 #define AIR_LAUNCH_DECODE(NW, KT)                                                                                  \
-    hipLaunchKernelGGL((decode_mfma_kernel<NW, KT>), grid, dim3(64 * NW), 0, s, dm, dt, l0, lbase, ds,             \
-                       (const bf16_t *)q_new, (const bf16_t *)k_new, (const bf16_t *)v_new, (bf16_t *)out, splits)
+    do {                                                                                                           \
+        if (splits == 1)                                                                                           \
+            hipLaunchKernelGGL((decode_mfma_kernel<NW, KT, false>), grid, dim3(64 * NW), 0, s, dm, dt, l0, lbase,  \
+                               ds, (const bf16_t *)q_new, (const bf16_t *)k_new, (const bf16_t *)v_new,            \
+                               (bf16_t *)out, splits);                                                             \
+        else                                                                                                       \
+            hipLaunchKernelGGL((decode_mfma_kernel<NW, KT, true>), grid, dim3(64 * NW), 0, s, dm, dt, l0, lbase,   \
+                               ds, (const bf16_t *)q_new, (const bf16_t *)k_new, (const bf16_t *)v_new,            \
+                               (bf16_t *)out, splits);                                                             \
+    } while (0)
         if (waves == 8 && tiles == 4) AIR_LAUNCH_DECODE(8, 4);
         else if (waves == 4 && tiles == 4) AIR_LAUNCH_DECODE(4, 4);
         else if (waves == 2 && tiles == 4) AIR_LAUNCH_DECODE(2, 4);
