@@ -101,11 +101,44 @@ def cpu_baseline(w, seqs, retention, host_layers, dec_inputs, decode_steps):
         t_dec += time.perf_counter() - t1
     t_step = t_dec / len(sample)
     total = t_compress + t_step * decode_steps
+    # the same compression pass on ONE host thread (BLAS limited to one thread), for the per-core figure
+    single = None
+    try:
+        from threadpoolctl import threadpool_limits
+
+        with threadpool_limits(limits=1):
+            t1 = time.perf_counter()
+            for b, seg in enumerate(segs):
+                O.compress_sequence(q64[b], k64[b], seg, w.alpha, retention)
+            single = (time.perf_counter() - t1) * 1e6 / w.n_layers
+    except Exception:
+        pass
     return dict(value=w.batch * decode_steps / total, unit="tokens/s", cores=int(cores), kind="oracle",
                 sample=f"full compression pass of all {w.n_layers} layers ({t_compress:.2f} s) + {len(sample)} of "
                        f"{decode_steps} decode steps at their true cache lengths ({t_step * 1e3:.1f} ms/step), "
                        f"numpy fp64",
-                compress_us_per_layer=t_compress * 1e6 / w.n_layers, decode_tokens_per_s=w.batch / t_step)
+                compress_us_per_layer=t_compress * 1e6 / w.n_layers, decode_tokens_per_s=w.batch / t_step,
+                compress_us_per_layer_one_thread=single)
+
+
+def device_copy_reference(result, dev, dec_gbs):
+    """Adds the rate of a plain device-to-device copy of 512 MiB and the rooflines as fractions of it."""
+    import torch
+
+    src = torch.ones(512 << 18, dtype=torch.float32, device=dev)
+    dst = torch.empty_like(src)
+    e0, e1 = (torch.cuda.Event(enable_timing=True) for _ in range(2))
+    for _ in range(2):
+        dst.copy_(src)
+    e0.record()
+    for _ in range(5):
+        dst.copy_(src)
+    e1.record()
+    torch.cuda.synchronize()
+    copy_gbs = 2 * src.numel() * 4 * 5 / (e0.elapsed_time(e1) * 1e-3) / 1e9
+    result["device_copy"] = {"gbs_read_plus_write": copy_gbs, "bytes": src.numel() * 4}
+    result["roofline"]["frac_of_device_copy"] = dec_gbs / copy_gbs
+    result["roofline_compress"]["frac_of_device_copy"] = result["roofline_compress"]["achieved"] / copy_gbs
 
 
 def main():
@@ -118,6 +151,8 @@ def main():
     ap.add_argument("--decode-steps", type=int, default=None)
     ap.add_argument("--per-layer", action="store_true", help="one air_decode_attn call per layer instead of one per step")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-extras", action="store_true",
+                    help="skip the one-launch-per-layer passes and the device-copy reference (profiling runs)")
     ap.add_argument("--retention-sweep", action="store_true",
                     help="also time the same workload with the full cache and at 50 % / 10 % / 1 % retention "
                          "(the quantity the paper's efficiency table reports for attention alone)")
@@ -170,7 +205,7 @@ def main():
     dv = to_device(np.stack([d[2] for d in dec_inputs]), dev)
     out = torch.empty((L, w.batch, w.n_q_heads, w.head_dim), dtype=q[0].dtype, device=dev)
 
-    def run(retention, steps, warmup):
+    def run(retention, steps, warmup, per_layer=args.per_layer, want_stats=False):
         """One context at this retention: `warmup` untimed passes, then `steps` timed ones."""
         ac = A.AirCache(config_for(w, retention, max_decode_steps=n_dec, seqs=seqs), dev)
         ev = lambda: torch.cuda.Event(enable_timing=True)  # noqa: E731
@@ -198,7 +233,7 @@ def main():
             if events is not None:
                 events[3].record()
             for t in range(n_dec):
-                if args.per_layer:
+                if per_layer:
                     for l in range(L):
                         ac.air_decode_attn(l, l + 1, pq + t * step_q + l * lay_q, pk + t * step_kv + l * lay_kv,
                                            pv + t * step_kv + l * lay_kv, po + l * lay_q)
@@ -211,6 +246,7 @@ def main():
             one_step()
         torch.cuda.synchronize()
         budgets = ac.air_get_budgets()
+        stats = ac.air_get_stats() if want_stats else None
         all_events = [[ev() for _ in range(5)] for _ in range(steps)]
         torch.cuda.synchronize()
         t0 = time.perf_counter()
@@ -221,9 +257,10 @@ def main():
 
         stage = np.array([[e[i].elapsed_time(e[i + 1]) for i in range(4)] for e in all_events])  # ms
         del ac
-        return stage.mean(axis=0), wall, budgets
+        return stage, wall, budgets, stats
 
-    (score_ms, budget_ms, select_ms, decode_ms), wall, budgets = run(retention, args.steps, args.warmup)
+    stage, wall, budgets, stats = run(retention, args.steps, args.warmup, want_stats=True)
+    score_ms, budget_ms, select_ms, decode_ms = stage.mean(axis=0)
     compress_ms = score_ms + budget_ms + select_ms
     ms_per_step = wall * 1e3 / args.steps
     ab = algorithmic_bytes(w, seqs, budgets, n_dec)
@@ -261,6 +298,22 @@ def main():
                               "score_frac": ab["score"] / (score_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
                               "bytes": ab["compress"]},
     }
+    # median and minimum over the timed passes
+    comp_iter = stage[:, :3].sum(axis=1)
+    result["compress_us_per_layer_median_min"] = [float(np.median(comp_iter)) * 1e3 / L, float(comp_iter.min()) * 1e3 / L]
+    result["decode_us_per_step_median_min"] = [float(np.median(stage[:, 3])) * 1e3 / n_dec, float(stage[:, 3].min()) * 1e3 / n_dec]
+    # Eq.9-10 per layer of sequence 0 (mean over the KV heads): the spread the budgets follow
+    if stats is not None:
+        result["layer_stats_seq0"] = {"s_t": [round(float(x), 6) for x in stats[0][0]],
+                                      "s_k": [round(float(x), 4) for x in stats[1][0]]}
+    # the same decode steps as one launch per layer on the one stream (a few passes)
+    if not args.per_layer and not args.no_extras:
+        pl = run(retention, 3, 1, per_layer=True)[0].mean(axis=0)
+        result["decode_per_layer_launches"] = {"us_per_step": float(pl[3]) * 1e3 / n_dec,
+                                               "tokens_per_s": w.batch * n_dec / (float(pl[3]) * 1e-3)}
+    # what a plain kernel reaches on this machine: a device-to-device copy of 512 MiB
+    if not args.no_extras:
+        device_copy_reference(result, dev, dec_gbs)
     # measured HBM traffic of the dominant kernel (rocprofv3 byte counters, committed summary), when one
     # exists for this workload and launch shape
     try:
@@ -273,7 +326,7 @@ def main():
     if args.retention_sweep:
         sweep = []
         for r in (1.0, 0.5, 0.1, 0.01):
-            (sc, bu, se, de), _, _ = run(r, 3, 1)
+            sc, bu, se, de = run(r, 3, 1)[0].mean(axis=0)
             sweep.append({"retention": r, "compress_us_per_layer": (sc + bu + se) * 1e3 / L,
                           "decode_us_per_step": de * 1e3 / n_dec})
         for e in sweep:
