@@ -7,14 +7,16 @@
 //   gather_kernel  K' = [K_sys ; K_v[idx] ; K_t], V' likewise, as 16-byte vector copies.
 #include "air_device.h"
 #include "air_internal.h"
+#include <stdlib.h>
 
 namespace air {
 
 constexpr int kSelThreads = 512;
 constexpr int kSelRegs = 32;                         // scores per thread kept in registers
 constexpr int kSelSpan = kSelThreads * kSelRegs;     // 16384 scores per sweep
+constexpr int kSelCand = 1024;                       // scores of the deciding 12-bit bin that are ranked directly
 
-__global__ __launch_bounds__(kSelThreads) void select_kernel(Dims dm, DevTables t, int l0) {
+__global__ __launch_bounds__(kSelThreads) void select_kernel(Dims dm, DevTables t, int l0, int cand_cap) {
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int64_t unit = (int64_t)l0 * dm.B * dm.Hkv + blockIdx.x;
     const int b = (blockIdx.x / dm.Hkv) % dm.B;
@@ -30,7 +32,8 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(Dims dm, DevTables 
     }
 
     __shared__ uint32_t hist[kSelThreads / 64][256];  // one histogram per wave: scores share leading bits, so few bins are hot
-    __shared__ uint32_t s_prefix, s_kk;
+    __shared__ uint32_t s_prefix, s_kk, s_m;
+    __shared__ uint32_t h12[2048], cand[kSelCand];
     __shared__ int s_scan[kSelThreads / 64 + 1];
 
     // A sweep of up to kSelSpan scores stays in registers for all passes: thread t owns the `per`
@@ -49,7 +52,70 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(Dims dm, DevTables 
     if (cached) load_sweep(0);
 
     uint32_t prefix = 0, mask = 0, kk = (uint32_t)k;
-    for (int pass = 0; pass < 4; ++pass) {
+    // Short rows (all scores in registers): one histogram over the leading 12 bits (sign, exponent,
+    // three mantissa bits: 2048 bins for non-negative values) finds the bin of the k-th largest;
+    // when that bin holds at most kSelCand scores they are ranked against each other directly
+    // and the four 8-bit passes below are skipped.
+    bool found = false;
+    if (cached) {
+        for (int i = tid; i < 2048; i += kSelThreads) h12[i] = 0;
+        __syncthreads();
+#pragma unroll
+        for (int j = 0; j < kSelRegs; ++j)
+            if (live(0, j)) atomicAdd(&h12[min(v[j] >> 20, 2047u)], 1u);
+        __syncthreads();
+        // thread t takes the four bins at positions 4t .. 4t+3 from the top
+        uint32_t hb[4];
+        int s4 = 0;
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            hb[q] = h12[2047 - (4 * tid + q)];
+            s4 += (int)hb[q];
+        }
+        int total;
+        int excl = block_excl_scan<kSelThreads / 64>(s4, s_scan, &total);
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            if (hb[q] > 0 && (uint32_t)excl < kk && kk <= (uint32_t)excl + hb[q]) {
+                s_prefix = (uint32_t)(2047 - (4 * tid + q));
+                s_kk = kk - (uint32_t)excl;
+                s_m = hb[q];
+            }
+            excl += (int)hb[q];
+        }
+        __syncthreads();
+        const uint32_t bin = s_prefix, kk2 = s_kk, m = s_m;
+        __syncthreads();  // s_prefix / s_kk are written again below
+        if ((int)m <= cand_cap) {  // uniform over the workgroup
+            int cnt = 0;
+#pragma unroll
+            for (int j = 0; j < kSelRegs; ++j) cnt += (live(0, j) && (v[j] >> 20) == bin) ? 1 : 0;
+            int pos = block_excl_scan<kSelThreads / 64>(cnt, s_scan, &total);
+#pragma unroll
+            for (int j = 0; j < kSelRegs; ++j)
+                if (live(0, j) && (v[j] >> 20) == bin) cand[pos++] = v[j];
+            __syncthreads();
+            // candidate i is the k-th largest iff (#greater) < kk2 <= (#greater) + (#equal)
+            for (int i = tid; i < (int)m; i += kSelThreads) {
+                const uint32_t x = cand[i];
+                uint32_t gt = 0, eq = 0;
+                for (int j = 0; j < (int)m; ++j) {
+                    const uint32_t y = cand[j];
+                    gt += y > x ? 1u : 0u;
+                    eq += y == x ? 1u : 0u;
+                }
+                if (gt < kk2 && kk2 <= gt + eq) {  // every candidate with this value writes the same pair
+                    s_prefix = x;
+                    s_kk = kk2 - gt;
+                }
+            }
+            __syncthreads();
+            prefix = s_prefix;
+            kk = s_kk;
+            found = true;
+        }
+    }
+    for (int pass = 0; pass < 4 && !found; ++pass) {
         const int shift = 24 - 8 * pass;
         for (int i = tid; i < (kSelThreads / 64) * 256; i += kSelThreads) (&hist[0][0])[i] = 0;
         __syncthreads();
@@ -213,7 +279,10 @@ __global__ __launch_bounds__(256) void gather_vt_kernel(Dims dm, DevTables t, in
 }
 
 hipError_t launch_select(hipStream_t s, const Dims &dm, const DevTables &t, int l0, int nl) {
-    hipLaunchKernelGGL(select_kernel, dim3(nl * dm.B * dm.Hkv), dim3(kSelThreads), 0, s, dm, t, l0);
+    // AIR_SELECT_CAND (tuning / test aid): largest deciding bin that is ranked directly, 0 = always take the radix passes
+    int cap = kSelCand;
+    if (const char *e = getenv("AIR_SELECT_CAND")) cap = atoi(e) < kSelCand ? (atoi(e) < 0 ? 0 : atoi(e)) : kSelCand;
+    hipLaunchKernelGGL(select_kernel, dim3(nl * dm.B * dm.Hkv), dim3(kSelThreads), 0, s, dm, t, l0, cap);
     return hipGetLastError();
 }
 

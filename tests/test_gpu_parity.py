@@ -218,6 +218,15 @@ def test_decode_forced_launch_shapes(monkeypatch, splits, waves, tiles):
     _run_case(w, 0.25, steps=36)
 
 
+@pytest.mark.parametrize("cap", [0, 8])
+def test_select_radix_fallback(monkeypatch, cap):
+    # the selection kernel ranks the deciding 12-bit bin directly when it is small; a cap of 0 (or one
+    # that the bin exceeds) sends every row through the four radix passes instead
+    monkeypatch.setenv("AIR_SELECT_CAND", str(cap))
+    w = synth.get_workload(2).scaled(n_layers=3, n_vis=5000, n_text=40, decode_steps=1)
+    _run_case(w, 0.10, steps=1)
+
+
 def test_maximum_candidate_span():
     # 4096 text tokens, the largest candidate span the boundary accepts: the elite kernel then keeps
     # the logits of one head at a time in LDS
