@@ -1,11 +1,12 @@
 // air_decode_attn: Eq.2 append, then softmax(q K'^T / sqrt(d)) V' over the compacted cache.
 //
-//   decode_mfma_kernel bf16, head_dim 128, ONE launch per call: one wavefront per (split, unit).
-//                      The tiled K' and the block-transposed V' go from global memory straight into
-//                      MFMA operands, every load instruction reading 1 KB of consecutive memory; the G query heads of the group are the second MFMA
-//                      dimension.  The wave whose key range holds the new token takes it from
-//                      k_new / v_new and stores it into the cache (Eq.2); the wave of a unit that
-//                      finishes last merges the unit's split-K partials.
+//   decode_mfma_kernel bf16, head_dim 128, ONE launch per call: one workgroup per (split, unit).
+//                      The tiled K' and the block-transposed V' go from global memory straight
+//                      into MFMA operands, every load instruction reading 1 KB of consecutive
+//                      memory; the G query heads of the group are the second MFMA dimension.
+//                      The token the call appends (Eq.2) is scored from k_new / v_new by one wave
+//                      of the split that owns its row, which also stores it into the cache; the
+//                      workgroup of a unit that finishes last merges the unit's split-K partials.
 //   append_kernel, decode_kernel, combine_kernel
 //                      generic fp32-ALU path (fp32 storage, head_dim 64): three launches.
 #include "air_device.h"
