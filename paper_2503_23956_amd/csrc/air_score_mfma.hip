@@ -241,7 +241,7 @@ __global__ __launch_bounds__(256, 4) void score_stream_kernel(Dims dm, DevTables
 // M = max over chunks and the elite-text columns, Z = sum z exp(m - M) in fp64,
 // w = 1 / (R_h G Z).  Units with a stash also get f[row][chunk] = w exp(m_chunk - M), the factor
 // that turns a stashed exponential into its share of Eq.8.
-constexpr int kRowWaves = 16;  // one wave per row: a unit's usual dozen rows are done in one round of loads
+constexpr int kRowWaves = 16;  // up to one wave per row: a unit's usual dozen rows are then done in one round of loads
 __global__ __launch_bounds__(64 * kRowWaves) void score_rows_mfma_kernel(Dims dm, DevTables t, int l0, SeqArgs seqs) {
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
     const int uu = blockIdx.x;
@@ -257,7 +257,7 @@ __global__ __launch_bounds__(64 * kRowWaves) void score_rows_mfma_kernel(Dims dm
     const int R_total = s_pref[G];
     const bool stash = R_total <= kStashRows;
     if (tid == 0) t.unit_R[unit] = R_total;
-    for (int rho = wave; rho < R_total; rho += kRowWaves) {
+    for (int rho = wave; rho < R_total; rho += (int)(blockDim.x >> 6)) {
         const int g = head_of_row(s_pref, G, rho);
         const int64_t slot = (hrow0 + g) * W + (rho - s_pref[g]);
         const float2 *p = t.part + slot * dm.n_chunks;
@@ -330,57 +330,45 @@ __global__ __launch_bounds__(256) void score_finish_kernel(Dims dm, DevTables t,
     if (stash) {
         if (tid < kFinishChunks * kStashRows) s_f[tid / kStashRows][tid % kStashRows] = (tid % kStashRows) < u.R_total ? f_mine : 0.f;
         lds_barrier();
-        // All stashed values of the workgroup's chunks are requested at once when the list is short
-        // (rows past the list re-read its last row against a zero factor, chunks past the end re-read
-        // the last chunk and are not stored); longer lists go chunk by chunk.
+        // One wave per chunk; a lane takes 16 bytes of every stashed row (four keys, 16 apart: see
+        // stash_pos) and all rows are requested at once.  Rows past the list re-read its last row
+        // against a zero factor, a wave past the last chunk re-reads the last chunk and stores nothing.
         auto finish_all = [&](auto rb_tag) __attribute__((always_inline)) {
             constexpr int RB = decltype(rb_tag)::value;
-            float e[kFinishChunks][RB];
+            const int ci = wave, chunk = first + ci;
+            const float *sb = t.stash + ((u.unit * dm.n_chunks + min(chunk, last - 1)) * (int64_t)kStashRows) * kChunkKeys + 4 * lane;
+            f32x4 e[RB];
 #pragma unroll
-            for (int ci = 0; ci < kFinishChunks; ++ci) {
-                const float *sb = t.stash + ((u.unit * dm.n_chunks + min(first + ci, last - 1)) * (int64_t)kStashRows) * kChunkKeys + stash_pos(tid);
+            for (int r = 0; r < RB; ++r)
+                e[r] = *reinterpret_cast<const f32x4 *>(sb + (int64_t)min(r, max(u.R_total - 1, 0)) * kChunkKeys);
+            f32x4 imp = (f32x4){0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-                for (int r = 0; r < RB; ++r) e[ci][r] = sb[(int64_t)min(r, u.R_total - 1) * kChunkKeys];
+            for (int r = 0; r < RB; ++r) {
+                const float f = s_f[ci][r];
+#pragma unroll
+                for (int i = 0; i < 4; ++i) imp[i] = fmaf(f, e[r][i], imp[i]);
             }
+            if (chunk < last) {
 #pragma unroll
-            for (int ci = 0; ci < kFinishChunks; ++ci) {
-                float imp = 0.f;
-#pragma unroll
-                for (int r = 0; r < RB; ++r) imp = fmaf(s_f[ci][r], e[ci][r], imp);
-                const int key = (first + ci) * kChunkKeys + tid;
-                if (first + ci < last && key < u.sq.vis_len) {
-                    t.scores[u.unit * dm.max_vis + key] = imp;
-                    const double x = (double)imp;
-                    m1 += x;
-                    m2 += x * x;
-                    m3 += x * x * x;
+                for (int i = 0; i < 4; ++i) {
+                    const int key = chunk * kChunkKeys + 64 * (lane >> 4) + 16 * i + (lane & 15);
+                    if (key < u.sq.vis_len) {
+                        t.scores[u.unit * dm.max_vis + key] = imp[i];
+                        const double x = (double)imp[i];
+                        m1 += x;
+                        m2 += x * x;
+                        m3 += x * x * x;
+                    }
                 }
             }
         };
-        if (u.R_total <= 8 && u.R_total > 0) {
-            finish_all(std::integral_constant<int, 8>());
-        } else if (u.R_total <= 16 && u.R_total > 0) {
-            finish_all(std::integral_constant<int, 16>());
-        } else {
-            for (int ci = 0; ci < last - first; ++ci) {
-                const float *sb = t.stash + ((u.unit * dm.n_chunks + first + ci) * (int64_t)kStashRows) * kChunkKeys + stash_pos(tid);
-                float e[kStashRows];
-#pragma unroll
-                for (int r = 0; r < kStashRows; ++r) e[r] = r < u.R_total ? sb[(int64_t)r * kChunkKeys] : 0.f;
-                float imp = 0.f;
-#pragma unroll
-                for (int r = 0; r < kStashRows; ++r)
-                    if (r < u.R_total) imp = fmaf(s_f[ci][r], e[r], imp);
-                const int key = (first + ci) * kChunkKeys + tid;
-                if (key < u.sq.vis_len) {
-                    t.scores[u.unit * dm.max_vis + key] = imp;
-                    const double x = (double)imp;
-                    m1 += x;
-                    m2 += x * x;
-                    m3 += x * x * x;
-                }
-            }
-        }
+        static_assert(kFinishChunks == 4, "one wave of the workgroup per chunk");
+        if (u.R_total == 0) {  // no window row: the importance is zero (and so are its power sums)
+            for (int key = first * kChunkKeys + tid; key < min(last * kChunkKeys, u.sq.vis_len); key += 256)
+                t.scores[u.unit * dm.max_vis + key] = 0.f;
+        } else if (u.R_total <= 8) finish_all(std::integral_constant<int, 8>());
+        else if (u.R_total <= 16) finish_all(std::integral_constant<int, 16>());
+        else finish_all(std::integral_constant<int, kStashRows>());
         put_moments();
         return;
     }
@@ -617,7 +605,9 @@ hipError_t launch_score_mfma(hipStream_t s, const Dims &dm, const DevTables &t, 
         hipLaunchKernelGGL(score_stream_kernel, dim3((dm.n_chunks + kStreamChunks - 1) / kStreamChunks, nl * dm.B * dm.Hkv),
                            dim3(256), 0, s, dm, t, l0, ll, st, seqs);
     else {
-        hipLaunchKernelGGL(score_rows_mfma_kernel, dim3(nl * dm.B * dm.Hkv), dim3(64 * kRowWaves), 0, s, dm, t, l0, seqs);
+        // a wave per row when the launch has few units; with many units, 4 waves walk the rows
+        hipLaunchKernelGGL(score_rows_mfma_kernel, dim3(nl * dm.B * dm.Hkv),
+                           dim3(nl * dm.B * dm.Hkv >= 512 ? 256 : 64 * kRowWaves), 0, s, dm, t, l0, seqs);
         hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;
         hipLaunchKernelGGL(score_finish_kernel, dim3((dm.n_chunks + kFinishChunks - 1) / kFinishChunks, nl * dm.B * dm.Hkv),
