@@ -336,8 +336,11 @@ air_status air_budget(air_ctx *ctx, void *stream) {
         if (!ctx->scored[l]) return fail(ctx, AIR_ERR_STATE, "air_budget: not every layer has been scored");
     for (int l = 0; l < ctx->cfg.n_layers; ++l)
         if (ctx->compacted[l]) return fail(ctx, AIR_ERR_STATE, "air_budget: layers already compacted");
+    SeqArgs sa;
+    memset(&sa, 0, sizeof(sa));
+    memcpy(sa.s, ctx->seqs.data(), sizeof(air_seq) * ctx->cfg.batch);
     hipError_t e = launch_budget((hipStream_t)stream, ctx->dm, ctx->tab, ctx->cfg.retention, ctx->cfg.budget_mode,
-                                 ctx->cfg.min_keep, 0, v_transposed(ctx->cfg.dtype, ctx->cfg.head_dim) ? 1 : 0);
+                                 ctx->cfg.min_keep, 0, v_transposed(ctx->cfg.dtype, ctx->cfg.head_dim) ? 1 : 0, sa);
     if (e != hipSuccess) return hip_fail(ctx, e, "air_budget launch");
     ctx->budgets_ready = true;
     return AIR_OK;
@@ -495,10 +498,13 @@ air_status air_set_budgets(air_ctx *ctx, const int32_t *host) {
         }
         if (rows > ctx->dm.pool_rows) return fail(ctx, AIR_ERR_SHAPE, "air_set_budgets: budgets exceed the cache pool");
     }
+    SeqArgs sa;
+    memset(&sa, 0, sizeof(sa));
+    memcpy(sa.s, ctx->seqs.data(), sizeof(air_seq) * ctx->cfg.batch);
     hipError_t e = hipDeviceSynchronize();
     if (e == hipSuccess) e = hipMemcpy(ctx->tab.budgets, host, (size_t)ctx->dm.B * L * 4, hipMemcpyHostToDevice);
     if (e == hipSuccess) e = launch_budget(nullptr, ctx->dm, ctx->tab, ctx->cfg.retention, ctx->cfg.budget_mode,
-                                           ctx->cfg.min_keep, 1, 0);
+                                           ctx->cfg.min_keep, 1, 0, sa);
     if (e == hipSuccess) e = hipDeviceSynchronize();
     if (e != hipSuccess) return hip_fail(ctx, e, "air_set_budgets");
     ctx->budgets_ready = true;

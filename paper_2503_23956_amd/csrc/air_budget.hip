@@ -15,11 +15,11 @@ namespace air {
 constexpr int kBT = 256;  // threads; also the largest layer count (AIR_MAX_LAYERS)
 
 __global__ __launch_bounds__(kBT) void budget_kernel(Dims dm, DevTables t, double retention, int mode, int min_keep,
-                                                     int skip_allocation, int use_moments) {
+                                                     int skip_allocation, int use_moments, SeqArgs seqs) {
     const int tid = threadIdx.x;
     const int b = blockIdx.x;
     const int L = dm.L;
-    const air_seq sq = t.seq_tab[b];
+    const air_seq sq = seqs.s[b];  // from the kernel arguments: no table read in front of the power sums
     const int n_vis = sq.vis_len;
     __shared__ double w[kBT], x[kBT], frac[kBT], sh_t[kBT], sh_k[kBT];
     __shared__ int kk[kBT];
@@ -227,7 +227,7 @@ __global__ __launch_bounds__(kBT) void budget_kernel(Dims dm, DevTables t, doubl
 
     // cache layout: each layer's region holds system + kept + text rows and room for the
     // decode appends, and starts on a multiple of kCacheRowAlign rows
-    if (tid < L) kk[tid] = budgets[tid];
+    if (skip_allocation && tid < L) kk[tid] = budgets[tid];  // otherwise kk still holds what was just written
     __syncthreads();
     const int nonvis = sq.seq_len - sq.vis_len;
     if (tid < L) {
@@ -243,9 +243,9 @@ __global__ __launch_bounds__(kBT) void budget_kernel(Dims dm, DevTables t, doubl
 }
 
 hipError_t launch_budget(hipStream_t s, const Dims &dm, const DevTables &t, double retention, int mode,
-                         int min_keep, int skip_allocation, int use_moments) {
+                         int min_keep, int skip_allocation, int use_moments, const SeqArgs &seqs) {
     hipLaunchKernelGGL(budget_kernel, dim3(dm.B), dim3(kBT), 0, s, dm, t, retention, mode, min_keep, skip_allocation,
-                       use_moments);
+                       use_moments, seqs);
     return hipGetLastError();
 }
 

@@ -16,6 +16,9 @@ constexpr int kSelRegs = 32;                         // scores per thread kept i
 constexpr int kSelSpan = kSelThreads * kSelRegs;     // 16384 scores per sweep
 constexpr int kSelCand = 1024;                       // scores of the deciding 12-bit bin that are ranked directly
 
+// leading 12 bits of a score pattern; importance is non-negative, a set sign bit (never produced) falls into the top bin
+__device__ __forceinline__ uint32_t digit12(uint32_t v) { return min(v >> 20, 2047u); }
+
 __global__ __launch_bounds__(kSelThreads) void select_kernel(Dims dm, DevTables t, int l0, int cand_cap) {
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int64_t unit = (int64_t)l0 * dm.B * dm.Hkv + blockIdx.x;
@@ -62,7 +65,7 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(Dims dm, DevTables 
         __syncthreads();
 #pragma unroll
         for (int j = 0; j < kSelRegs; ++j)
-            if (live(0, j)) atomicAdd(&h12[min(v[j] >> 20, 2047u)], 1u);
+            if (live(0, j)) atomicAdd(&h12[digit12(v[j])], 1u);
         __syncthreads();
         // thread t takes the four bins at positions 4t .. 4t+3 from the top
         uint32_t hb[4];
@@ -89,11 +92,11 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(Dims dm, DevTables 
         if ((int)m <= cand_cap) {  // uniform over the workgroup
             int cnt = 0;
 #pragma unroll
-            for (int j = 0; j < kSelRegs; ++j) cnt += (live(0, j) && (v[j] >> 20) == bin) ? 1 : 0;
+            for (int j = 0; j < kSelRegs; ++j) cnt += (live(0, j) && digit12(v[j]) == bin) ? 1 : 0;
             int pos = block_excl_scan<kSelThreads / 64>(cnt, s_scan, &total);
 #pragma unroll
             for (int j = 0; j < kSelRegs; ++j)
-                if (live(0, j) && (v[j] >> 20) == bin) cand[pos++] = v[j];
+                if (live(0, j) && digit12(v[j]) == bin) cand[pos++] = v[j];
             __syncthreads();
             // candidate i is the k-th largest iff (#greater) < kk2 <= (#greater) + (#equal)
             for (int i = tid; i < (int)m; i += kSelThreads) {
