@@ -448,7 +448,7 @@ __device__ __forceinline__ double dot64_wave(const bf16_t *a, const bf16_t *b, i
 }
 
 __global__ __launch_bounds__(64 * kEliteWaves) void elite_mfma_kernel(Dims dm, DevTables t, int l0, LaunchLayers ll, air_strides st,
-                                                         SeqArgs seqs, double alpha, int gb) {
+                                                         SeqArgs seqs, double alpha, double ln_alpha, int gb) {
     constexpr int D = 128;
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, n = lane & 15, c = lane >> 4;
     const int kvh = blockIdx.x, b = blockIdx.y, li = blockIdx.z;
@@ -463,8 +463,7 @@ __global__ __launch_bounds__(64 * kEliteWaves) void elite_mfma_kernel(Dims dm, D
     extern __shared__ float s_dynf[];  // gb * max_window raw logits, then as many ints (elite lists)
     float *s_logit = s_dynf;
     int *s_elite = reinterpret_cast<int *>(s_dynf + (size_t)gb * W);
-    const double inv_sqrt_d = 1.0 / sqrt((double)D);
-    const double ln_alpha = alpha > 0.0 ? log(alpha) : -INFINITY;
+    const double inv_sqrt_d = 0.08838834764831845;  // 1 / sqrt(128), correctly rounded
     const float scale = 0.08838834764831845f;
 
     for (int g0 = 0; g0 < G; g0 += gb) {
@@ -545,31 +544,42 @@ __global__ __launch_bounds__(64 * kEliteWaves) void elite_mfma_kernel(Dims dm, D
             // (row, key) logit is a 64-lane dot product.  Up to 8 keys are scored in one batch of loads,
             // longer rows are scored twice (maximum, then sum).  The maximum is kept as the RAW dot
             // product (before the 1/sqrt(d) scale), the sum is of exp((a - max) / sqrt(d)).
-            for (int r = 0; r < R; ++r) {
-                const bf16_t *qr = q + (int64_t)(elite[r] - t0) * st.q_t;
-                const uint32_t uq = reinterpret_cast<const uint32_t *>(qr)[lane];
-                const float q0 = __uint_as_float(uq << 16), q1 = __uint_as_float(uq & 0xffff0000u);
-                float m = -INFINITY, z = 0.f;
-                if (R <= 8) {
-                    float a[8];
+            if (R <= 8) {
+                // the usual case: the elite rows' queries and keys are requested in one batch, then the
+                // R x R logits are formed
+                uint32_t uqv[8], ukv[8];
 #pragma unroll
-                    for (int j = 0; j < 8; ++j) {
-                        a[j] = 0.f;
-                        if (j < R) {
-                            const uint32_t uk = reinterpret_cast<const uint32_t *>(k + (int64_t)elite[j] * st.kv_t)[lane];
-                            a[j] = fmaf(q1, __uint_as_float(uk & 0xffff0000u), q0 * __uint_as_float(uk << 16));
-                        }
-                    }
+                for (int j = 0; j < 8; ++j) {
+                    const int tok = elite[min(j, R - 1)];
+                    uqv[j] = reinterpret_cast<const uint32_t *>(q + (int64_t)(tok - t0) * st.q_t)[lane];
+                    ukv[j] = reinterpret_cast<const uint32_t *>(k + (int64_t)tok * st.kv_t)[lane];
+                }
+#pragma unroll
+                for (int r = 0; r < 8; ++r) {
+                    if (r >= R) break;
+                    const float q0 = __uint_as_float(uqv[r] << 16), q1 = __uint_as_float(uqv[r] & 0xffff0000u);
+                    float a[8];
+                    float m = -INFINITY, z = 0.f;
 #pragma unroll
                     for (int j = 0; j < 8; ++j)
                         if (j < R) {
-                            a[j] = wave_sum(a[j]);
+                            a[j] = wave_sum(fmaf(q1, __uint_as_float(ukv[j] & 0xffff0000u), q0 * __uint_as_float(ukv[j] << 16)));
                             m = fmaxf(m, a[j]);
                         }
 #pragma unroll
                     for (int j = 0; j < 8; ++j)
                         if (j < R) z += expf((a[j] - m) * scale);
-                } else {
+                    if (lane == 0) {
+                        t.row_mtext[hrow * W + r] = m;
+                        t.row_ztext[hrow * W + r] = z;
+                    }
+                }
+            } else {
+                for (int r = 0; r < R; ++r) {
+                    const bf16_t *qr = q + (int64_t)(elite[r] - t0) * st.q_t;
+                    const uint32_t uq = reinterpret_cast<const uint32_t *>(qr)[lane];
+                    const float q0 = __uint_as_float(uq << 16), q1 = __uint_as_float(uq & 0xffff0000u);
+                    float m = -INFINITY, z = 0.f;
                     for (int j = 0; j < R; ++j) {
                         const uint32_t uk = reinterpret_cast<const uint32_t *>(k + (int64_t)elite[j] * st.kv_t)[lane];
                         m = fmaxf(m, wave_sum(fmaf(q1, __uint_as_float(uk & 0xffff0000u), q0 * __uint_as_float(uk << 16))));
@@ -578,10 +588,10 @@ __global__ __launch_bounds__(64 * kEliteWaves) void elite_mfma_kernel(Dims dm, D
                         const uint32_t uk = reinterpret_cast<const uint32_t *>(k + (int64_t)elite[j] * st.kv_t)[lane];
                         z += expf((wave_sum(fmaf(q1, __uint_as_float(uk & 0xffff0000u), q0 * __uint_as_float(uk << 16))) - m) * scale);
                     }
-                }
-                if (lane == 0) {
-                    t.row_mtext[hrow * W + r] = m;
-                    t.row_ztext[hrow * W + r] = z;
+                    if (lane == 0) {
+                        t.row_mtext[hrow * W + r] = m;
+                        t.row_ztext[hrow * W + r] = z;
+                    }
                 }
             }
         }
@@ -595,7 +605,7 @@ hipError_t launch_elite_mfma(hipStream_t s, const Dims &dm, const DevTables &t, 
     int gb = (int)(49152 / per_head);  // heads whose logits share the LDS
     gb = gb < 1 ? 1 : (gb > dm.G ? dm.G : gb);
     hipLaunchKernelGGL(elite_mfma_kernel, dim3(dm.Hkv, dm.B, nl), dim3(64 * kEliteWaves), gb * per_head, s, dm, t, l0, ll, st, seqs,
-                       alpha, gb);
+                       alpha, alpha > 0.0 ? log(alpha) : -INFINITY, gb);
     return hipGetLastError();
 }
 
