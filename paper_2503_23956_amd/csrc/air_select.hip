@@ -24,9 +24,24 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(Dims dm, DevTables 
     const int64_t unit = (int64_t)l0 * dm.B * dm.Hkv + blockIdx.x;
     const int b = (blockIdx.x / dm.Hkv) % dm.B;
     const int l = l0 + blockIdx.x / (dm.Hkv * dm.B);
+    const uint32_t *key = reinterpret_cast<const uint32_t *>(t.scores + unit * dm.max_vis);
+    // A sweep of up to kSelSpan scores stays in registers for all passes: thread t owns the `per`
+    // consecutive scores from base + t * per on.  `per` follows the row capacity (a kernel argument),
+    // not the sequence's own length, so that a short row's loads go out before anything has been
+    // read (entries past the sequence's span exist and are never counted).  Rows longer than
+    // kSelSpan are re-read sweep by sweep.
+    const bool cached = dm.max_vis <= kSelSpan;
+    const int per = cached ? (dm.max_vis + kSelThreads - 1) / kSelThreads : kSelRegs;
+    uint32_t v[kSelRegs];
+    if (cached) {
+#pragma unroll
+        for (int j = 0; j < kSelRegs; ++j) {
+            const int i = tid * per + j;
+            v[j] = (j < per && i < dm.max_vis) ? key[i] : 0u;
+        }
+    }
     const int n = t.seq_tab[b].vis_len;
     const int k = t.budgets[(int64_t)b * dm.L + l];
-    const uint32_t *key = reinterpret_cast<const uint32_t *>(t.scores + unit * dm.max_vis);
     int32_t *out = t.indices + unit * dm.max_vis;
     if (k <= 0) return;
     if (k >= n) {
@@ -39,11 +54,6 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(Dims dm, DevTables 
     __shared__ uint32_t h12[2048], cand[kSelCand];
     __shared__ int s_scan[kSelThreads / 64 + 1];
 
-    // A sweep of up to kSelSpan scores stays in registers for all passes: thread t owns the `per`
-    // consecutive scores from base + t * per on.  Rows longer than kSelSpan are re-read sweep by sweep.
-    const bool cached = n <= kSelSpan;
-    const int per = cached ? (n + kSelThreads - 1) / kSelThreads : kSelRegs;
-    uint32_t v[kSelRegs];
     auto load_sweep = [&](int base) {
 #pragma unroll
         for (int j = 0; j < kSelRegs; ++j) {
@@ -52,7 +62,6 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(Dims dm, DevTables 
         }
     };
     auto live = [&](int base, int j) { return j < per && base + tid * per + j < n; };
-    if (cached) load_sweep(0);
 
     uint32_t prefix = 0, mask = 0, kk = (uint32_t)k;
     // Short rows (all scores in registers): one histogram over the leading 12 bits (sign, exponent,
@@ -169,9 +178,12 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(Dims dm, DevTables 
                 c_gt += v[j] > tau ? 1 : 0;
                 c_eq += v[j] == tau ? 1 : 0;
             }
-        int tot_gt, tot_eq;
-        int gt_before = base_gt + block_excl_scan<kSelThreads / 64>(c_gt, s_scan, &tot_gt);
-        int eq_before = base_eq + block_excl_scan<kSelThreads / 64>(c_eq, s_scan, &tot_eq);
+        // both counts in one scan: a sweep has at most 2^14 scores, so each count fits 16 bits
+        int tot;
+        const int before = block_excl_scan<kSelThreads / 64>(c_gt | (c_eq << 16), s_scan, &tot);
+        const int tot_gt = tot & 0xffff, tot_eq = tot >> 16;
+        int gt_before = base_gt + (before & 0xffff);
+        int eq_before = base_eq + (before >> 16);
 #pragma unroll
         for (int j = 0; j < kSelRegs; ++j)
             if (live(base, j)) {
