@@ -153,6 +153,9 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extras", action="store_true",
                     help="skip the one-launch-per-layer passes and the device-copy reference (profiling runs)")
+    ap.add_argument("--budget-divergence", action="store_true",
+                    help="also report the Jensen-Shannon divergence between the layer budgets of the allocation "
+                         "strategies (uniform, strength only, skewness only, both), as the paper's Tab.14 does")
     ap.add_argument("--retention-sweep", action="store_true",
                     help="also time the same workload with the full cache and at 50 % / 10 % / 1 % retention "
                          "(the quantity the paper's efficiency table reports for attention alone)")
@@ -323,6 +326,21 @@ def main():
             result["roofline"]["traffic"] = tr["fetch_bytes"] + tr["write_bytes"]
     except (OSError, ValueError):
         pass
+    if args.budget_divergence:
+        from paper_2503_23956_amd.diagnostics import js_divergence
+
+        names = {0: "strength+skew", 1: "uniform", 2: "strength", 3: "skew"}
+        alloc = {}
+        for mode, name in names.items():
+            ac = A.AirCache(config_for(w, retention, budget_mode=mode, max_decode_steps=n_dec, seqs=seqs), dev)
+            ac.air_score(0, L, prepared=ac.prepare(q, k, v, seqs))
+            ac.air_budget()
+            alloc[name] = ac.air_get_budgets()
+            del ac
+        pairs = [("uniform", "strength"), ("uniform", "skew"), ("strength", "skew"), ("uniform", "strength+skew")]
+        result["budget_js_divergence"] = {
+            f"{a} & {b}": float(np.mean([js_divergence(alloc[a][i], alloc[b][i]) for i in range(w.batch)]))
+            for a, b in pairs}
     if args.retention_sweep:
         sweep = []
         for r in (1.0, 0.5, 0.1, 0.01):
