@@ -127,13 +127,10 @@ __global__ __launch_bounds__(64 * NW) void decode_mfma_kernel(Dims dm, DecodeTab
 
     bf16x8 qb[4];
     {
-        const bf16_t *q = q_new + (((int64_t)(lbase + li) * dm.B + b) * dm.Hq + (int64_t)kvh * G + n) * D;
+        // MFMA columns past the group's heads re-read its last head: their results are never stored
+        const bf16_t *q = q_new + (((int64_t)(lbase + li) * dm.B + b) * dm.Hq + (int64_t)kvh * G + min(n, G - 1)) * D;
 #pragma unroll
-        for (int s = 0; s < 4; ++s) {
-            uint4 x = make_uint4(0, 0, 0, 0);
-            if (n < G) x = *reinterpret_cast<const uint4 *>(q + 32 * s + 8 * c);
-            qb[s] = __builtin_bit_cast(bf16x8, x);
-        }
+        for (int s = 0; s < 4; ++s) qb[s] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4 *>(q + 32 * s + 8 * c));
     }
     constexpr float kScale2 = 0.08838834764831845f * 1.4426950408889634f;  // log2(e) / sqrt(128)
     float m_run = -INFINITY, l_run = 0.f;
