@@ -218,6 +218,27 @@ def test_decode_forced_launch_shapes(monkeypatch, splits, waves, tiles):
     _run_case(w, 0.25, steps=36)
 
 
+@pytest.mark.parametrize("side", [+1, -1])
+def test_elite_threshold_within_fp32_resolution_of_a_candidate(side):
+    # Eq.5 with alpha placed a relative 1e-9 above / below exp(s_j - s_max) of a real candidate: fp32
+    # logits cannot tell the two sides apart, so the kernel has to take the decision from its fp64
+    # recomputation, and the elite sets must still equal the oracle's for every head
+    w = synth.get_workload(2).scaled(n_layers=1, n_vis=300, n_text=48, decode_steps=1)
+    seqs = w.seqs()
+    s = seqs[0]
+    li = synth.layer_inputs(w, 0, seqs)
+    q = synth.storage_to_f64(li.q_text[0])
+    k = synth.storage_to_f64(li.k[0])
+    t0 = s.vis_start + s.vis_len
+    logits = O.last_row_logits(q[0, s.win_start + s.win_len - 1 - t0], k[0, s.win_start:s.win_start + s.win_len])
+    second = np.sort(logits)[-2]
+    alpha = float(np.exp(second - logits.max()) * (1.0 + side * 1e-9))
+    assert 0.0 < alpha < 1.0
+    want = 1 if side > 0 else 2  # the runner-up of head 0 falls just outside / just inside
+    assert len(O.elite_set(logits, alpha)) == want
+    _run_case(w, 0.10, alpha=alpha, steps=0)
+
+
 @pytest.mark.parametrize("cap", [0, 8])
 def test_select_radix_fallback(monkeypatch, cap):
     # the selection kernel ranks the deciding 12-bit bin directly when it is small; a cap of 0 (or one
