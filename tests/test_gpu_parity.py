@@ -239,6 +239,38 @@ def test_elite_threshold_within_fp32_resolution_of_a_candidate(side):
     _run_case(w, 0.10, alpha=alpha, steps=0)
 
 
+def test_topk_exact_ties_go_to_the_lower_index(monkeypatch):
+    # Half of the visual keys are copies of the layer's most important key (one 256-key chunk, so the
+    # copies' scores are equal bit for bit): the budget boundary falls inside the group of equal
+    # scores, and the kept copies must be exactly the ones with the lowest token indices, as in the oracle
+    w = synth.get_workload(2).scaled(n_layers=2, n_vis=200, n_text=24, decode_steps=1)
+    seqs = w.seqs()
+    s = seqs[0]
+    real = synth.layer_inputs
+
+    def with_copies(wl, layer, sq=None):
+        li = real(wl, layer, sq)
+        imp = P.oracle_score_layer(wl, li, seqs, wl.alpha)[0][0]  # [H_kv][vis_len] of sequence 0
+        src = s.vis_start + int(np.argmax(imp.sum(axis=0)))
+        k, v = li.k.copy(), li.v.copy()
+        for i in range(1, 200, 2):  # every odd visual position
+            k[:, :, s.vis_start + i] = k[:, :, src]
+            v[:, :, s.vis_start + i] = v[:, :, src]
+        return type(li)(li.q_text, k, v)
+
+    # the boundary does fall inside the tie group for at least one (layer, KV head)
+    straddles = 0
+    for layer in range(w.n_layers):
+        imp = P.oracle_score_layer(w, with_copies(w, layer, seqs), seqs, w.alpha)[0][0]
+        for h in range(w.n_kv_heads):
+            kth = np.sort(imp[h])[-60]
+            straddles += int(np.sum(imp[h] == kth) > 1 and np.sum(imp[h] > kth) < 60 < np.sum(imp[h] >= kth))
+    assert straddles > 0
+    monkeypatch.setattr(synth, "layer_inputs", with_copies)
+    res = _run_case(w, 0.30, steps=1)
+    assert res["swaps"] == 0
+
+
 @pytest.mark.parametrize("cap", [0, 8])
 def test_select_radix_fallback(monkeypatch, cap):
     # the selection kernel ranks the deciding 12-bit bin directly when it is small; a cap of 0 (or one
