@@ -196,6 +196,15 @@ def test_degenerate_sizes():
     _run_case(w, 0.02, steps=1)
 
 
+def test_degenerate_sizes_bf16_mfma_path():
+    # the same degenerate shapes on the bf16 / head_dim 128 kernels: a cache of a handful of rows that
+    # grows through its first token block, one text token, fewer than three visual tokens
+    w = synth.get_workload(2).scaled(n_layers=2, n_vis=2, n_text=1, n_sys=1, decode_steps=40)
+    _run_case(w, 0.5, steps=40, min_keep=0)
+    w = synth.get_workload(2).scaled(n_layers=1, n_vis=33, n_text=2, n_sys=0, decode_steps=3)
+    _run_case(w, 0.03, steps=3)
+
+
 def test_decode_many_steps_cross_token_blocks():
     # appended tokens cross several 32-token block boundaries of the cache
     w = synth.get_workload(2).scaled(n_layers=2, n_vis=300, n_text=21, decode_steps=70)
