@@ -1,0 +1,76 @@
+"""Error behaviour of the boundary with a live context: every misuse is caught on the host, returns a
+status, and leaves the context usable (no kernel is launched for a rejected call)."""
+import dataclasses
+
+import numpy as np
+import pytest
+
+import synth
+
+pytestmark = pytest.mark.gpu
+
+
+def _setup():
+    import torch
+
+    import paper_2503_23956_amd as A
+    from paper_2503_23956_amd.device_inputs import config_for, to_device
+
+    dev = torch.device("cuda:0")
+    w = synth.get_workload(2).scaled(n_layers=2, n_vis=300, n_text=24, decode_steps=2)
+    seqs = w.seqs()
+    ac = A.AirCache(config_for(w, 0.1, max_decode_steps=2, seqs=seqs), dev)
+    layers = [synth.layer_inputs(w, l, seqs) for l in range(w.n_layers)]
+    q = [to_device(li.q_text, dev) for li in layers]
+    k = [to_device(li.k, dev) for li in layers]
+    v = [to_device(li.v, dev) for li in layers]
+    return A, ac, w, seqs, q, k, v, dev
+
+
+def test_stage_order_shapes_and_capacity_are_enforced():
+    import torch
+
+    A, ac, w, seqs, q, k, v, dev = _setup()
+    B = A.binding
+    L = w.n_layers
+
+    def status(fn, *a, **kw):
+        with pytest.raises(B.AirError) as e:
+            fn(*a, **kw)
+        return e.value.status
+
+    # stages out of order
+    assert status(ac.air_budget) == B.AIR_ERR_STATE                      # nothing scored yet
+    assert status(ac.air_select_compact, 0, L, k=k, v=v) == B.AIR_ERR_STATE  # no budgets yet
+    # an empty visual span, a span past the configured maximum, no text token
+    s0 = seqs[0]
+    for bad in (dataclasses.replace(s0, vis_len=0), dataclasses.replace(s0, vis_len=s0.vis_len + 1),
+                dataclasses.replace(s0, seq_len=s0.vis_start + s0.vis_len)):
+        assert status(ac.air_score, 0, L, q, k, v, [bad]) == B.AIR_ERR_SHAPE
+    assert status(ac.air_score, L, L + 1, q[:1], k[:1], v[:1], seqs) == B.AIR_ERR_INVALID_ARG  # layer range past the end
+    # the context is still usable: the regular sequence of calls goes through
+    ac.air_score(0, 1, q[:1], k[:1], v[:1], seqs)
+    assert status(ac.air_budget) == B.AIR_ERR_STATE                      # one layer still unscored
+    ac.air_score(1, 2, q[1:], k[1:], v[1:], seqs)
+    ac.air_budget()
+    budgets = ac.air_get_budgets()
+    assert budgets.sum() == round(0.1 * 300 * L)
+    too_big = budgets.copy()
+    too_big[0, 0] = 301
+    assert status(ac.air_set_budgets, too_big) == B.AIR_ERR_SHAPE
+    qn = torch.zeros((L, 1, w.n_q_heads, w.head_dim), dtype=q[0].dtype, device=dev)
+    kn = torch.zeros((L, 1, w.n_kv_heads, w.head_dim), dtype=q[0].dtype, device=dev)
+    out = torch.empty_like(qn)
+    assert status(ac.air_decode_attn, 0, L, qn, kn, kn, out) == B.AIR_ERR_STATE  # not compacted yet
+    ac.air_select_compact(0, L, k=k, v=v)
+    assert status(ac.air_score, 0, L, q, k, v, seqs) == B.AIR_ERR_STATE   # already compacted
+    ac.air_decode_attn(0, L, qn, kn, kn, out)
+    ac.air_decode_attn(0, L, qn, kn, kn, out)
+    assert status(ac.air_decode_attn, 0, L, qn, kn, kn, out) == B.AIR_ERR_STATE  # max_decode_steps used up
+    torch.cuda.synchronize()
+    assert np.array_equal(ac.air_get_lengths()[0], ac.air_get_budgets()[0] + (s0.seq_len - s0.vis_len) + 2)
+    # and after a reset the next prompt goes through again
+    ac.air_reset()
+    ac.air_score(0, L, q, k, v, seqs)
+    ac.air_budget()
+    assert np.array_equal(ac.air_get_budgets(), budgets)
