@@ -153,6 +153,9 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extras", action="store_true",
                     help="skip the one-launch-per-layer passes and the device-copy reference (profiling runs)")
+    ap.add_argument("--score-per-layer", action="store_true",
+                    help="also time air_score called one layer at a time, as a caller that scores each layer "
+                         "right after its prefill would")
     ap.add_argument("--budget-divergence", action="store_true",
                     help="also report the Jensen-Shannon divergence between the layer budgets of the allocation "
                          "strategies (uniform, strength only, skewness only, both), as the paper's Tab.14 does")
@@ -326,6 +329,23 @@ def main():
             result["roofline"]["traffic"] = tr["fetch_bytes"] + tr["write_bytes"]
     except (OSError, ValueError):
         pass
+    if args.score_per_layer:
+        ac = A.AirCache(config_for(w, retention, max_decode_steps=n_dec, seqs=seqs), dev)
+        preps = [ac.prepare(q[l:l + 1], k[l:l + 1], v[l:l + 1], seqs) for l in range(L)]
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        times = []
+        for it in range(4):
+            ac.air_reset()
+            e0.record()
+            for l in range(L):
+                ac.air_score(l, l + 1, prepared=preps[l])
+            e1.record()
+            torch.cuda.synchronize()
+            if it:
+                times.append(e0.elapsed_time(e1))
+        result["score_one_layer_per_call"] = {"us_per_layer": float(np.mean(times)) * 1e3 / L,
+                                              "all_layers_in_one_call_us_per_layer": score_ms * 1e3 / L}
+        del ac
     if args.budget_divergence:
         from paper_2503_23956_amd.diagnostics import js_divergence
 
