@@ -188,8 +188,15 @@ __global__ __launch_bounds__(64 * NW) void decode_mfma_kernel(Dims dm, DecodeTab
     }
 
     const int last16 = (kend - 1) & ~15, last32 = (kend - 1) & ~31;  // last tile / block with a cached key
-    const int kb_first = k0 + wave * kIter;
-    constexpr int kStep = NW * kIter;  // distance between two chunks of one wave
+    // The chunks of the range are walked front to back on even steps and back to front on odd ones:
+    // what a step read last is what the next step reads first, so the part of the cache that is
+    // still in the L2 of the XCD (the unit-to-XCD mapping is the same every launch) gets reused
+    // instead of being evicted just before its turn.
+    const bool backward = (ll.appended[li] & 1) != 0;
+    const int n_chunks = (max(kend - k0, 0) + kIter - 1) / kIter;
+    const int kb_first = k0 + (backward ? n_chunks - 1 - wave : wave) * kIter;
+    const int kStep = (backward ? -NW : NW) * kIter;  // distance between two chunks of one wave
+    auto has = [&](int kb) { return kb >= k0 && kb < kend; };
 
     // all loads of a chunk: the KT score tiles of K' and the V' operands of the TB token blocks
     auto load_chunk = [&](uint4(&a)[KT][4], uint4(&vb)[TB][8], int kb) {
@@ -273,28 +280,28 @@ __global__ __launch_bounds__(64 * NW) void decode_mfma_kernel(Dims dm, DecodeTab
     // flight.  Loads are issued only for chunks that exist, and the loop is laid out so that every
     // path reaches a compute step with the same loads behind it (the wait counts stay exact).
     if constexpr (KT > 2) {  // two buffers of this size do not fit the registers: load, then multiply
-        for (int kb = kb_first; kb < kend; kb += kStep) {
+        for (int kb = kb_first; has(kb); kb += kStep) {
             uint4 a0[KT][4], v0[TB][8];
             load_chunk(a0, v0, kb);
             compute_chunk(a0, v0, kb);
         }
-    } else if (kb_first < kend) {
+    } else if (has(kb_first)) {
         uint4 a0[KT][4], v0[TB][8], a1[KT][4], v1[TB][8];
         int kb = kb_first;
         load_chunk(a0, v0, kb);
-        if (kb + kStep >= kend) {
+        if (!has(kb + kStep)) {
             compute_chunk(a0, v0, kb);
         } else {
             load_chunk(a1, v1, kb + kStep);
             while (true) {
                 compute_chunk(a0, v0, kb);
-                if (kb + 2 * kStep >= kend) {
+                if (!has(kb + 2 * kStep)) {
                     compute_chunk(a1, v1, kb + kStep);
                     break;
                 }
                 load_chunk(a0, v0, kb + 2 * kStep);
                 compute_chunk(a1, v1, kb + kStep);
-                if (kb + 3 * kStep >= kend) {
+                if (!has(kb + 3 * kStep)) {
                     compute_chunk(a0, v0, kb + 2 * kStep);
                     break;
                 }
