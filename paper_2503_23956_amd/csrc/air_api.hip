@@ -382,7 +382,7 @@ air_status air_select_compact(air_ctx *ctx, void *stream, int32_t l0, int32_t l1
 // kItersPerWave iterations at the average cache length and the launch is short of workgroups.
 // AIR_DECODE_SPLITS / AIR_DECODE_WAVES / AIR_DECODE_TILES override the choice (tuning aid).
 static void decode_shape(const air_ctx *ctx, int n_layers_in_launch, int appended, int *splits, int *waves, int *tiles) {
-    constexpr int kItersPerWave = 3, kEnoughWorkgroups = 256;
+    constexpr int kItersPerWave = 3, kEnoughWorkgroups = 256, kEnoughWaves = 1536;
     const air_config &c = ctx->cfg;
     double avg_len = 0.0;
     for (int b = 0; b < c.batch; ++b) {
@@ -391,11 +391,17 @@ static void decode_shape(const air_ctx *ctx, int n_layers_in_launch, int appende
     }
     avg_len /= c.batch;
     const int64_t units = (int64_t)n_layers_in_launch * c.batch * c.n_kv_heads;
-    int kt = 4, w = units >= 1024 ? 4 : 8;  // with many short units, smaller workgroups overlap each other's start and end
+    int kt = 4;
     if (ctx->force_tiles > 0) kt = ctx->force_tiles;
+    const int64_t iters = (int64_t)((avg_len + 16.0 * kt - 1.0) / (16.0 * kt));
+    // Waves per workgroup: enough for the launch to hold about 1536 waves, and beyond that one wave per 8
+    // iterations of the unit.  Many short units run fastest with one wave each (no merge, no barrier:
+    // 1792 units of ~600 keys 85 us against 97 us with four waves); few units need all 8 to have
+    // enough loads in flight.
+    int w = 1;
+    while (w < 8 && (units * w < kEnoughWaves || iters >= 16 * w)) w *= 2;
     if (ctx->force_waves > 0) w = ctx->force_waves;
     if (kt == 8 && w == 8) w = 4;
-    const int64_t iters = (int64_t)((avg_len + 16.0 * kt - 1.0) / (16.0 * kt));
     int64_t s = 1;
     while (s < kMaxSplits && iters > (int64_t)kItersPerWave * w * s && units * s < kEnoughWorkgroups) s *= 2;
     if (ctx->force_splits > 0) s = ctx->force_splits;

@@ -216,7 +216,7 @@ def test_decode_long_cache_multiple_iterations_per_split():
     _run_case(w, 1.00, steps=2)
 
 
-@pytest.mark.parametrize("splits,waves,tiles", [(4, 8, 4), (1, 2, 2), (2, 4, 2), (1, 1, 8), (16, 1, 4), (2, 2, 8)])
+@pytest.mark.parametrize("splits,waves,tiles", [(4, 8, 4), (1, 2, 2), (2, 4, 2), (1, 1, 8), (16, 1, 4), (2, 2, 8), (1, 1, 4)])
 def test_decode_forced_launch_shapes(monkeypatch, splits, waves, tiles):
     # every compiled launch shape of the decode kernel (split-K exchange, 32-key double-buffered chunks,
     # 128-key chunks) against the oracle, with appends that cross token-block and split boundaries
