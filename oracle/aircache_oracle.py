@@ -24,7 +24,9 @@ Pins (tests/test_oracle_*.py): row sums and torch.softmax for Eq.7; the alpha=0
 and alpha=1 special cases and the explicit-softmax form of Eq.5; scipy's
 adjusted skewness and closed forms for Eq.10; sum / bound / monotonicity /
 uniform invariants for Eq.11; brute-force and stable-argsort top-k;
-torch scaled_dot_product_attention and the 100 %-retention identity for decode.
+torch scaled_dot_product_attention and the 100 %-retention identity for decode;
+causal scaled_dot_product_attention over the visual span, unit row sums and the
+one-hot closed form for the visual observation window.
 The whole pipeline has no printed worked example in the paper to compare with:
 end-to-end values are "parity unpinned" beyond those per-step pins.
 """
@@ -105,6 +107,50 @@ def head_importance(q_text_h: np.ndarray, k_h: np.ndarray, seg: Segments, alpha:
     if return_attn:
         return imp, elite, a
     return imp, elite
+
+
+def head_importance_visual_window(q_win_h: np.ndarray, k_h: np.ndarray, seg: Segments,
+                                  return_attn: bool = False):
+    """Importance under a visual observation window (the "visual window" row of the ablation
+    table of Sec.4.3: the last continuous visual tokens serve as the reference).
+
+    The candidate span [win_start, win_start + win_len) lies INSIDE the visual span and every
+    token of it is a window row (there is no Eq.5 for this window).  The paper gives no
+    equation for it; the reading taken is the attention these rows had in prefill, restricted
+    to the visual keys as Eq.7 is: row r (visual index p_r) sees the visual keys i <= p_r
+    (causal), no text key (all text comes later), and Eq.8 averages the rows.
+
+    q_win_h: [win_len][d] queries of the window tokens of this query head (row j = token win_start + j).
+    k_h    : [seq_len][d] keys of the KV head this query head reads.
+    Returns I_h [vis_len] (, A [win_len][vis_len]).
+    """
+    d = k_h.shape[-1]
+    k_v = k_h[seg.vis_start:seg.text_start]
+    p_row = np.arange(seg.win_start, seg.win_start + seg.win_len) - seg.vis_start
+    s = (q_win_h[: seg.win_len] @ k_v.T) / math.sqrt(d)
+    s = np.where(np.arange(seg.vis_len)[None, :] <= p_row[:, None], s, -np.inf)
+    s = s - s.max(axis=1, keepdims=True)
+    p = np.exp(s)
+    a = p / p.sum(axis=1, keepdims=True)
+    imp = a.sum(axis=0) / a.shape[0]
+    if return_attn:
+        return imp, a
+    return imp
+
+
+def layer_importance_visual_window(q_win: np.ndarray, k: np.ndarray, seg: Segments):
+    """Per-KV-head importance of one layer of one sequence under the visual observation window:
+    head_importance_visual_window per query head, then the mean over the query heads of a KV head.
+    q_win: [H_q][win_len][d], k: [H_kv][seq_len][d].  Returns (I [H_kv][vis_len], window positions
+    per query head, for symmetry with layer_importance)."""
+    hq, hkv = q_win.shape[0], k.shape[0]
+    g = hq // hkv
+    imp = np.zeros((hkv, seg.vis_len), dtype=np.float64)
+    rows = np.arange(seg.win_start, seg.win_start + seg.win_len)
+    for h in range(hq):
+        imp[h // g] += head_importance_visual_window(q_win[h], k[h // g], seg)
+    imp /= g
+    return imp, [rows.copy() for _ in range(hq)]
 
 
 def layer_importance(q_text: np.ndarray, k: np.ndarray, seg: Segments, alpha: float):

@@ -210,6 +210,68 @@ def test_gqa_grouping_reads_the_right_kv_head():
 
 
 # ---------------------------------------------------------------------------
+# Visual observation window (ablation table of Sec.4.3)
+# ---------------------------------------------------------------------------
+def _vis_seg(n_sys, n_vis, n_text, win_first, win):
+    return O.Segments(n_sys + n_vis + n_text, n_sys, n_vis, n_sys + win_first, win)
+
+
+@pytest.mark.parametrize("win_first,win", [(44, 6), (17, 5), (0, 4), (49, 1)])
+def test_visual_window_matches_causal_sdpa_over_the_visual_span(win_first, win):
+    # library route: causal attention of ALL visual queries over the visual keys with V = identity
+    # returns the attention matrix itself; the window rows of it, averaged, are Eq.8
+    rng = np.random.default_rng(40 + win)
+    n_vis, d = 50, 8
+    seg = _vis_seg(3, n_vis, 7, win_first, win)
+    k = rng.standard_normal((seg.seq_len, d))
+    q_all = rng.standard_normal((n_vis, d))  # queries of every visual token
+    a_full = torch.nn.functional.scaled_dot_product_attention(
+        torch.from_numpy(q_all)[None], torch.from_numpy(k[3:3 + n_vis])[None],
+        torch.eye(n_vis, dtype=torch.float64)[None], is_causal=True)[0].numpy()
+    want = a_full[win_first:win_first + win].mean(axis=0)
+    got, a = O.head_importance_visual_window(q_all[win_first:win_first + win], k, seg, return_attn=True)
+    np.testing.assert_allclose(got, want, rtol=1e-12, atol=1e-15)
+    np.testing.assert_allclose(a.sum(axis=1), 1.0, rtol=1e-13)   # every row is a distribution over visual keys
+    assert np.all(got[win_first + win:] == 0.0)                   # nothing after the window is ever seen
+    assert abs(O.strength(got) - 1.0) < 1e-12                     # Eq.9 is identically 1 for this window
+
+
+def test_visual_window_closed_forms():
+    rng = np.random.default_rng(44)
+    n_vis, d = 36, 4
+    k = rng.standard_normal((2 + n_vis + 5, d))
+    # a single row at the first visual token sees only itself: one-hot importance, skewness sqrt(N_v)
+    imp = O.head_importance_visual_window(rng.standard_normal((1, d)), k, _vis_seg(2, n_vis, 5, 0, 1))
+    assert imp[0] == 1.0 and np.all(imp[1:] == 0.0)
+    assert abs(O.skewness(imp) - math.sqrt(n_vis)) < 1e-12
+    # identical visual keys: row p spreads 1/(p+1) over keys 0..p
+    k[2:2 + n_vis] = k[2]
+    seg = _vis_seg(2, n_vis, 5, n_vis - 3, 3)
+    imp = O.head_importance_visual_window(rng.standard_normal((3, d)), k, seg)
+    want = np.zeros(n_vis)
+    for p in (n_vis - 3, n_vis - 2, n_vis - 1):
+        want[: p + 1] += 1.0 / (p + 1) / 3.0
+    np.testing.assert_allclose(imp, want, rtol=1e-13)
+    # the scale is 1/sqrt(head_dim): two keys, one row at the second, logits (0, ln 3 * sqrt d) -> (1/4, 3/4)
+    k2 = np.zeros((1 + 2 + 1, d)); k2[2, 0] = 1.0
+    q = np.zeros((1, d)); q[0, 0] = math.log(3.0) * math.sqrt(d)
+    imp = O.head_importance_visual_window(q, k2, O.Segments(4, 1, 2, 2, 1))
+    np.testing.assert_allclose(imp, [0.25, 0.75], rtol=1e-13)
+
+
+def test_visual_window_layer_is_mean_over_the_group_and_reads_the_right_kv_head():
+    rng = np.random.default_rng(45)
+    seg = _vis_seg(1, 20, 4, 16, 4)
+    k = rng.standard_normal((2, seg.seq_len, 4))
+    q_win = rng.standard_normal((4, 4, 4))
+    imp, rows = O.layer_importance_visual_window(q_win, k, seg)
+    assert [r.tolist() for r in rows] == [[17, 18, 19, 20]] * 4
+    for kv in range(2):
+        heads = [O.head_importance_visual_window(q_win[h], k[kv], seg) for h in (2 * kv, 2 * kv + 1)]
+        np.testing.assert_allclose(imp[kv], (heads[0] + heads[1]) / 2.0, rtol=1e-13)
+
+
+# ---------------------------------------------------------------------------
 # Eq.9-10
 # ---------------------------------------------------------------------------
 def test_skewness_matches_scipy_adjusted():
