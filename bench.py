@@ -162,6 +162,9 @@ def main():
     ap.add_argument("--retention-sweep", action="store_true",
                     help="also time the same workload with the full cache and at 50 % / 10 % / 1 % retention "
                          "(the quantity the paper's efficiency table reports for attention alone)")
+    ap.add_argument("--window-sweep", action="store_true",
+                    help="also time air_score with the observation windows of the paper's ablation table: elite, "
+                         "continuous last 16 / 32 text tokens, all text tokens, visual window of 32")
     ap.add_argument("--copy-probe", type=int, default=0, metavar="MB",
                     help="only run a plain device copy of this many MB (reference for the rocprofv3 byte counters)")
     args = ap.parse_args()
@@ -361,6 +364,35 @@ def main():
         result["budget_js_divergence"] = {
             f"{a} & {b}": float(np.mean([js_divergence(alloc[a][i], alloc[b][i]) for i in range(w.batch)]))
             for a, b in pairs}
+    if args.window_sweep:
+        import dataclasses
+
+        def text_tail(n):
+            return [dataclasses.replace(s, win_start=s.seq_len - min(n, s.n_text), win_len=min(n, s.n_text)) for s in seqs]
+
+        variants = [("elite", A.AIR_WINDOW_TEXT, w.alpha, seqs),
+                    ("continuous_16", A.AIR_WINDOW_TEXT, 0.0, text_tail(16)),
+                    ("continuous_32", A.AIR_WINDOW_TEXT, 0.0, text_tail(32)),
+                    ("all_text", A.AIR_WINDOW_TEXT, 0.0, text_tail(1 << 30)),
+                    # the generator has no queries for visual tokens: the first 32 text queries stand in for them
+                    ("visual_32", A.AIR_WINDOW_VISUAL, 0.0,
+                     [dataclasses.replace(s, win_start=s.text_start - 32, win_len=32) for s in seqs])]
+        result["window_sweep_score_us_per_layer"] = {}
+        for name, kind, alpha, sq in variants:
+            ac = A.AirCache(config_for(w, retention, alpha=alpha, max_decode_steps=n_dec, seqs=sq, window_kind=kind), dev)
+            prep = ac.prepare(q, k, v, sq)
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            times = []
+            for it in range(4):
+                ac.air_reset()
+                e0.record()
+                ac.air_score(0, L, prepared=prep)
+                e1.record()
+                torch.cuda.synchronize()
+                if it:
+                    times.append(e0.elapsed_time(e1))
+            result["window_sweep_score_us_per_layer"][name] = float(np.mean(times)) * 1e3 / L
+            del ac
     if args.retention_sweep:
         sweep = []
         for r in (1.0, 0.5, 0.1, 0.01):

@@ -59,6 +59,16 @@ typedef enum {
     AIR_BUDGET_SKEW = 3
 } air_budget_mode;
 
+/* Which tokens serve as the observation window (Sec.3.3; window rows of the ablation table, Tab.5). */
+typedef enum {
+    AIR_WINDOW_TEXT = 0,  /* candidate span inside the text span, Eq.5 picks the rows (alpha = 0: all of it) */
+    AIR_WINDOW_VISUAL = 1 /* the "visual window" ablation: the span lies inside the visual span (the paper
+                             takes the last visual tokens) and every token of it is a row; there is no Eq.5
+                             (alpha must be 0).  Row r at visual index p_r is normalised over the visual keys
+                             i <= p_r (the attention it had in prefill, restricted to the visual keys as
+                             Eq.7 is); no text key takes part, so Eq.9 is 1 for every layer.             */
+} air_window_kind;
+
 #define AIR_MAX_BATCH 64   /* sequences per context                       */
 #define AIR_MAX_LAYERS 256 /* layers per context                          */
 #define AIR_MAX_TEXT 4096  /* text tokens per sequence (candidate span)   */
@@ -74,20 +84,24 @@ typedef struct {
     int32_t min_keep;         /* lower bound on kept visual tokens per layer (>= 0)        */
     double alpha;             /* relevance threshold of Eq.5, in [0,1]; the paper uses 0.9 */
     double retention;         /* r: fraction of visual tokens kept overall, in (0,1]       */
+    int32_t window_kind;      /* air_window_kind; 0 = the paper's text windows              */
+    int32_t reserved;         /* must be 0                                                  */
 } air_config;
 
 /* One prompt.  system = [0, vis_start), visual = [vis_start, vis_start+vis_len),
  * text = [vis_start+vis_len, seq_len).  [win_start, win_start+win_len) is the candidate
  * span of Eq.5, inside the text span; its last token is the reference row of Eq.4.
  * win_len == text length and alpha = 0.9 is the paper's elite window; alpha = 0 turns
- * the span into a plain continuous observation window (Tab.5). */
+ * the span into a plain continuous observation window (Tab.5).  With AIR_WINDOW_VISUAL the
+ * span lies inside the visual span instead and all of it is the window. */
 typedef struct {
     int32_t seq_len, vis_start, vis_len, win_start, win_len;
 } air_seq;
 
 /* One layer's tensors (device pointers). */
 typedef struct {
-    const void *q_text; /* [B][H_q ][text][d]: queries of the text span; row j = text token j */
+    const void *q_text; /* [B][H_q ][text][d]: queries of the text span; row j = text token j
+                           (AIR_WINDOW_VISUAL: [B][H_q][win_len][d], row j = token win_start + j) */
     const void *k;      /* [B][H_kv][seq ][d]                                                  */
     const void *v;      /* [B][H_kv][seq ][d]                                                  */
 } air_layer;

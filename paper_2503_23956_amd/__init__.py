@@ -6,6 +6,8 @@ from .binding import (  # noqa: F401
     AIR_BUDGET_STRENGTH_SKEW,
     AIR_BUDGET_UNIFORM,
     AIR_F32,
+    AIR_WINDOW_TEXT,
+    AIR_WINDOW_VISUAL,
     AirCache,
     AirError,
     air_config,

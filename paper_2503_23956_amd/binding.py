@@ -18,6 +18,7 @@ AIR_OK = 0
 AIR_ERR_INVALID_ARG, AIR_ERR_SHAPE, AIR_ERR_WORKSPACE, AIR_ERR_STATE, AIR_ERR_HIP = 1, 2, 3, 4, 5
 AIR_F32, AIR_BF16 = 0, 1
 AIR_BUDGET_STRENGTH_SKEW, AIR_BUDGET_UNIFORM, AIR_BUDGET_STRENGTH, AIR_BUDGET_SKEW = 0, 1, 2, 3
+AIR_WINDOW_TEXT, AIR_WINDOW_VISUAL = 0, 1
 _STATUS_NAMES = {0: "AIR_OK", 1: "AIR_ERR_INVALID_ARG", 2: "AIR_ERR_SHAPE", 3: "AIR_ERR_WORKSPACE",
                  4: "AIR_ERR_STATE", 5: "AIR_ERR_HIP"}
 
@@ -32,7 +33,7 @@ class air_config(C.Structure):
     _fields_ = [(n, C.c_int32) for n in (
         "n_layers", "n_q_heads", "n_kv_heads", "head_dim", "batch", "max_vis_len", "max_nonvis_len",
         "max_window", "max_decode_steps", "dtype", "budget_mode", "min_keep")] + [
-        ("alpha", C.c_double), ("retention", C.c_double)]
+        ("alpha", C.c_double), ("retention", C.c_double), ("window_kind", C.c_int32), ("reserved", C.c_int32)]
 
 
 class air_seq(C.Structure):
@@ -102,9 +103,9 @@ def load_library(path: Optional[str] = None):
 
 def make_config(*, n_layers, n_q_heads, n_kv_heads, head_dim, batch, max_vis_len, max_nonvis_len, max_window,
                 max_decode_steps, dtype, alpha=0.9, retention=0.1, budget_mode=AIR_BUDGET_STRENGTH_SKEW,
-                min_keep=1) -> air_config:
+                min_keep=1, window_kind=AIR_WINDOW_TEXT) -> air_config:
     return air_config(n_layers, n_q_heads, n_kv_heads, head_dim, batch, max_vis_len, max_nonvis_len, max_window,
-                      max_decode_steps, dtype, budget_mode, min_keep, alpha, retention)
+                      max_decode_steps, dtype, budget_mode, min_keep, alpha, retention, window_kind, 0)
 
 
 def _ptr(t) -> int:

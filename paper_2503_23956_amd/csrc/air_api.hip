@@ -20,7 +20,12 @@ static bool config_ok(const air_config &c) {
     if (c.n_q_heads / c.n_kv_heads > 16) return false;
     if (c.head_dim != 64 && c.head_dim != 128) return false;
     if (c.max_vis_len < 1 || c.max_nonvis_len < 1) return false;
-    if (c.max_window < 1 || c.max_window > AIR_MAX_TEXT || c.max_window > c.max_nonvis_len) return false;
+    if (c.window_kind != AIR_WINDOW_TEXT && c.window_kind != AIR_WINDOW_VISUAL) return false;
+    if (c.reserved != 0) return false;
+    const bool vis_window = c.window_kind == AIR_WINDOW_VISUAL;
+    if (c.max_window < 1 || c.max_window > AIR_MAX_TEXT) return false;
+    if (c.max_window > (vis_window ? c.max_vis_len : c.max_nonvis_len)) return false;
+    if (vis_window && c.alpha != 0.0) return false;  // every token of a visual window is a row: no Eq.5
     if (c.max_decode_steps < 0) return false;
     if (c.dtype != AIR_F32 && c.dtype != AIR_BF16) return false;
     if (c.budget_mode < AIR_BUDGET_STRENGTH_SKEW || c.budget_mode > AIR_BUDGET_SKEW) return false;
@@ -143,6 +148,7 @@ air_status air_create(const air_config *cfg, void *workspace, size_t workspace_b
     d.max_window = cfg->max_window;
     d.n_chunks = lay.n_chunks;
     d.max_steps = cfg->max_decode_steps;
+    d.vis_window = cfg->window_kind == AIR_WINDOW_VISUAL ? 1 : 0;
     d.pool_rows = lay.pool_rows;
     DevTables &t = c->tab;
     char *w = c->ws;
@@ -255,7 +261,10 @@ static air_status check_seqs(air_ctx *ctx, const air_seq *seqs) {
             return fail(ctx, AIR_ERR_SHAPE, "air_seq: need vis_len in [1, max_vis_len] and at least one text token");
         if (s.seq_len - s.vis_len > c.max_nonvis_len)
             return fail(ctx, AIR_ERR_SHAPE, "air_seq: system + text tokens exceed max_nonvis_len");
-        if (s.win_len < 1 || s.win_len > c.max_window || s.win_start < text0 || s.win_start + s.win_len > s.seq_len)
+        if (c.window_kind == AIR_WINDOW_VISUAL) {
+            if (s.win_len < 1 || s.win_len > c.max_window || s.win_start < s.vis_start || s.win_start + s.win_len > text0)
+                return fail(ctx, AIR_ERR_SHAPE, "air_seq: a visual window must lie inside the visual span and fit max_window");
+        } else if (s.win_len < 1 || s.win_len > c.max_window || s.win_start < text0 || s.win_start + s.win_len > s.seq_len)
             return fail(ctx, AIR_ERR_SHAPE, "air_seq: candidate span must lie inside the text span and fit max_window");
     }
     return AIR_OK;
@@ -301,8 +310,9 @@ air_status air_score(air_ctx *ctx, void *stream, int32_t l0, int32_t l1, const a
             ll.p[i].k = layers[c0 - l0 + i].k;
             ll.p[i].v = layers[c0 - l0 + i].v;
         }
-        hipError_t e = mfma ? launch_elite_mfma(s, ctx->dm, ctx->tab, c0, nl, ll, *strides, sa, ctx->cfg.alpha)
-                            : launch_elite(s, ctx->dm, ctx->tab, dt, c0, nl, ll, *strides, sa, ctx->cfg.alpha);
+        hipError_t e = ctx->dm.vis_window ? launch_window_rows(s, ctx->dm, ctx->tab, c0, nl, sa)
+                       : mfma             ? launch_elite_mfma(s, ctx->dm, ctx->tab, c0, nl, ll, *strides, sa, ctx->cfg.alpha)
+                                          : launch_elite(s, ctx->dm, ctx->tab, dt, c0, nl, ll, *strides, sa, ctx->cfg.alpha);
         if (e == hipSuccess && !mfma) {
             e = launch_score_pass1(s, ctx->dm, ctx->tab, dt, c0, nl, ll, *strides);
             if (e == hipSuccess) e = launch_score_rows(s, ctx->dm, ctx->tab, c0, nl);

@@ -46,6 +46,7 @@ struct WsLayout {
 struct Dims {
     int32_t L, Hq, Hkv, G, D, B;
     int32_t max_vis, max_window, n_chunks, max_steps;
+    int32_t vis_window;  // 1: the window rows are visual tokens (causal over the visual keys, no text columns)
     int64_t pool_rows;
 };
 
@@ -69,6 +70,7 @@ WsLayout make_layout(const air_config &cfg);
 // ---- kernel launchers (each returns the hipError_t of its launch) ----
 hipError_t launch_elite(hipStream_t s, const Dims &dm, const DevTables &t, int dtype, int l0, int nl,
                         const LaunchLayers &ll, const air_strides &st, const SeqArgs &seqs, double alpha);
+hipError_t launch_window_rows(hipStream_t s, const Dims &dm, const DevTables &t, int l0, int nl, const SeqArgs &seqs);
 hipError_t launch_score_pass1(hipStream_t s, const Dims &dm, const DevTables &t, int dtype, int l0, int nl,
                               const LaunchLayers &ll, const air_strides &st);
 hipError_t launch_score_rows(hipStream_t s, const Dims &dm, const DevTables &t, int l0, int nl);

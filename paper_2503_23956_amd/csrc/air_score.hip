@@ -190,10 +190,36 @@ __global__ __launch_bounds__(256) void elite_kernel(Dims dm, DevTables t, int l0
 }
 
 // ---------------------------------------------------------------------------------------
+// Visual observation window (the "visual window" of the ablation table, Tab.5): every token of the span
+// is a row of every query head and no text key takes part, so the row lists are written out
+// directly and the elite-text columns are empty (maximum -inf, sum 0).  One workgroup per
+// (layer, sequence, query head).
+__global__ __launch_bounds__(64) void window_rows_kernel(Dims dm, DevTables t, int l0, SeqArgs seqs) {
+    const int h = blockIdx.x, b = blockIdx.y, li = blockIdx.z;
+    const air_seq sq = seqs.s[b];
+    if (li == 0 && h == 0 && threadIdx.x == 0) t.seq_tab[b] = sq;
+    const int64_t hrow = ((int64_t)(l0 + li) * dm.B + b) * dm.Hq + h;
+    const int W = dm.max_window;
+    for (int j = threadIdx.x; j < sq.win_len; j += 64) {
+        t.elite_idx[hrow * W + j] = sq.win_start + j;
+        t.row_mtext[hrow * W + j] = -INFINITY;
+        t.row_ztext[hrow * W + j] = 0.f;
+    }
+    if (threadIdx.x == 0) t.elite_cnt[hrow] = sq.win_len;
+}
+
+hipError_t launch_window_rows(hipStream_t s, const Dims &dm, const DevTables &t, int l0, int nl, const SeqArgs &seqs) {
+    hipLaunchKernelGGL(window_rows_kernel, dim3(dm.Hq, dm.B, nl), dim3(64), 0, s, dm, t, l0, seqs);
+    return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------------------
 // Eq.6-7 over the visual keys.  One workgroup per (256-key chunk, unit); a unit is one
 // (layer, sequence, KV head).  Thread i keeps key i of the chunk in registers and scores it
 // against the elite rows of the G query heads of the group, kRowBlock rows at a time.
 // PASS 1 writes per-row (max, sum-exp) of the chunk; PASS 2 accumulates Eq.8.
+// With a visual window a row at visual index p sees the keys i <= p only; a chunk that lies wholly
+// behind a row leaves (max -inf, sum 0) for it.
 // ---------------------------------------------------------------------------------------
 template <typename T, int D, int PASS>
 __global__ __launch_bounds__(256) void score_pass_kernel(Dims dm, DevTables t, int l0, LaunchLayers ll,
@@ -207,7 +233,7 @@ __global__ __launch_bounds__(256) void score_pass_kernel(Dims dm, DevTables t, i
     const int l = l0 + li;
     const air_seq sq = t.seq_tab[b];
     if (chunk * kChunkKeys >= sq.vis_len) return;
-    const int t0 = sq.vis_start + sq.vis_len;
+    const int qbase = dm.vis_window ? sq.win_start : sq.vis_start + sq.vis_len;  // token of row 0 of the query tensor
     const int i = chunk * kChunkKeys + tid;
     const bool valid = i < sq.vis_len;
     const T *q = (const T *)ll.p[li].q + (int64_t)b * st.q_b;
@@ -225,6 +251,7 @@ __global__ __launch_bounds__(256) void score_pass_kernel(Dims dm, DevTables t, i
     __shared__ float s_q[kRowBlock][D];
     __shared__ float s_red[kRowBlock][4];
     __shared__ float s_M[kRowBlock], s_w[kRowBlock];
+    __shared__ int s_lim[kRowBlock];  // last visual index a row sees
     const float scale = 1.0f / sqrtf((float)D);
     float imp = 0.f;
 
@@ -239,8 +266,9 @@ __global__ __launch_bounds__(256) void score_pass_kernel(Dims dm, DevTables t, i
             for (int idx = tid; idx < nb * D; idx += 256) {
                 const int rr = idx / D, c = idx % D;
                 const int tok = t.elite_idx[hrow * W + r0 + rr];
-                s_q[rr][c] = ldf(qh + (int64_t)(tok - t0) * st.q_t + c);
+                s_q[rr][c] = ldf(qh + (int64_t)(tok - qbase) * st.q_t + c);
             }
+            if (tid < nb) s_lim[tid] = dm.vis_window ? t.elite_idx[hrow * W + r0 + tid] - sq.vis_start : 0x7fffffff;
             if (PASS == 2 && tid < nb) {
                 s_M[tid] = t.row_M[hrow * W + r0 + tid];
                 s_w[tid] = t.row_w[hrow * W + r0 + tid];
@@ -256,10 +284,13 @@ __global__ __launch_bounds__(256) void score_pass_kernel(Dims dm, DevTables t, i
                 }
                 s[rr] = acc * scale;
             }
+            bool ok[kRowBlock];
+#pragma unroll
+            for (int rr = 0; rr < kRowBlock; ++rr) ok[rr] = valid && rr < nb && i <= s_lim[rr];
             if (PASS == 1) {
 #pragma unroll
                 for (int rr = 0; rr < kRowBlock; ++rr) {
-                    float m = wave_max(valid ? s[rr] : -INFINITY);
+                    float m = wave_max(ok[rr] ? s[rr] : -INFINITY);
                     if (lane == 0) s_red[rr][wave] = m;
                 }
                 __syncthreads();
@@ -270,7 +301,7 @@ __global__ __launch_bounds__(256) void score_pass_kernel(Dims dm, DevTables t, i
                 __syncthreads();
 #pragma unroll
                 for (int rr = 0; rr < kRowBlock; ++rr) {
-                    float e = (valid && rr < nb) ? expf(s[rr] - mrow[rr]) : 0.f;
+                    float e = ok[rr] ? expf(s[rr] - mrow[rr]) : 0.f;
                     e = wave_sum(e);
                     if (lane == 0) s_red[rr][wave] = e;
                 }
@@ -282,7 +313,7 @@ __global__ __launch_bounds__(256) void score_pass_kernel(Dims dm, DevTables t, i
             } else {
 #pragma unroll
                 for (int rr = 0; rr < kRowBlock; ++rr)
-                    if (rr < nb) imp = fmaf(s_w[rr], expf(s[rr] - s_M[rr]), imp);
+                    if (ok[rr]) imp = fmaf(s_w[rr], expf(s[rr] - s_M[rr]), imp);
             }
         }
     }

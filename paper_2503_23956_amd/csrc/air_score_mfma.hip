@@ -34,6 +34,7 @@ constexpr int kRowsLds = 1024;  // rows whose (M, w) are staged in LDS at a time
 
 struct UnitCtx {
     int kvh, b, li, l, chunk, t0, G, W, R_total;
+    int qbase;  // token that row 0 of the query tensor belongs to (start of the text span, or of a visual window)
     air_seq sq;
     const bf16_t *q, *k;
     int64_t hrow0, unit;
@@ -81,9 +82,9 @@ __device__ __forceinline__ void load_rows(const DevTables &t, const UnitCtx &u, 
     const int rho = rbase + 4 * (n & 3) + (n >> 2);
     const int g = head_of_row(s_pref, u.G, rho);
     const bool have = rho < u.R_total;
-    int tok = u.t0;
+    int tok = u.qbase;
     if (have) tok = t.elite_idx[(u.hrow0 + g) * u.W + (rho - s_pref[g])];
-    const bf16_t *qr = u.q + (int64_t)(u.kvh * u.G + g) * st.q_h + (int64_t)(tok - u.t0) * st.q_t;
+    const bf16_t *qr = u.q + (int64_t)(u.kvh * u.G + g) * st.q_h + (int64_t)(tok - u.qbase) * st.q_t;
 #pragma unroll
     for (int sl = 0; sl < 4; ++sl) {
         qa[sl] = make_uint4(0, 0, 0, 0);
@@ -130,6 +131,7 @@ __device__ __forceinline__ bool unit_setup(const Dims &dm, const SeqArgs &seqs, 
     u.sq = seqs.s[u.b];  // from the kernel arguments: no table read in front of the key loads
     if (u.chunk * kChunkKeys >= u.sq.vis_len) return false;
     u.t0 = u.sq.vis_start + u.sq.vis_len;
+    u.qbase = dm.vis_window ? u.sq.win_start : u.t0;
     u.G = dm.G;
     u.W = dm.max_window;
     u.q = (const bf16_t *)ll.p[u.li].q + (int64_t)u.b * st.q_b;
@@ -151,6 +153,10 @@ __device__ __forceinline__ int stash_pos(int key_in_chunk) {
     return (key_in_chunk & ~63) | ((key_in_chunk & 15) << 2) | ((key_in_chunk >> 4) & 3);
 }
 
+// VIS: the rows are the tokens of a visual window (all heads have the same win_len rows); row rho sits at
+// visual index prow0 + rho % win_len and sees the keys up to itself.  A (row, chunk) pair that lies wholly
+// behind the row leaves the partial (-inf, 0) and zeros in the stash.
+template <bool VIS>
 __global__ __launch_bounds__(256, 4) void score_stream_kernel(Dims dm, DevTables t, int l0, LaunchLayers ll,
                                                               air_strides st, SeqArgs seqs) {
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, n = lane & 15, c = lane >> 4;
@@ -181,6 +187,15 @@ __global__ __launch_bounds__(256, 4) void score_stream_kernel(Dims dm, DevTables
             if (rb == 0) logits_of(qa0, kreg, s);
             else block_logits(t, u, st, s_pref, rb, n, c, kreg, s);
             const int n_i = min(4, (u.R_total - rb + 3) >> 2);  // live values of i (uniform over the workgroup)
+            int lim[4];  // VIS: last key of the lane's tiles that row i sees, relative to the lane's key of tile 0
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+                lim[i] = VIS ? (u.sq.win_start - u.sq.vis_start) + (rb + 4 * i + c) % u.sq.win_len -
+                                   (chunk * kChunkKeys + wave * 64 + n)
+                             : 0;
+            auto live = [&](int tile, int i) __attribute__((always_inline)) {
+                return VIS ? (valid[tile] && 16 * tile <= lim[i]) : valid[tile];
+            };
             float m[4];
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
@@ -188,7 +203,7 @@ __global__ __launch_bounds__(256, 4) void score_stream_kernel(Dims dm, DevTables
                 if (i >= n_i) continue;
                 float mx = -INFINITY;
 #pragma unroll
-                for (int tile = 0; tile < 4; ++tile) mx = fmaxf(mx, valid[tile] ? s[tile][i] : -INFINITY);
+                for (int tile = 0; tile < 4; ++tile) mx = fmaxf(mx, live(tile, i) ? s[tile][i] : -INFINITY);
                 m[i] = max16(mx);
             }
             lds_barrier();
@@ -207,7 +222,7 @@ __global__ __launch_bounds__(256, 4) void score_stream_kernel(Dims dm, DevTables
                 const float M = fmaxf(fmaxf(s_pm[0][r], s_pm[1][r]), fmaxf(s_pm[2][r], s_pm[3][r]));
                 f32x4 e;
 #pragma unroll
-                for (int tile = 0; tile < 4; ++tile) e[tile] = valid[tile] ? exp_key(s[tile][i] - M) : 0.f;
+                for (int tile = 0; tile < 4; ++tile) e[tile] = live(tile, i) ? exp_key(s[tile][i] - M) : 0.f;
                 float zz = (e[0] + e[1]) + (e[2] + e[3]);
                 if (stash && rb + r < u.R_total)
                     *reinterpret_cast<f32x4 *>(stash_base + (int64_t)(rb + r) * kChunkKeys + wave * 64 + 4 * n) = e;
@@ -266,13 +281,15 @@ __global__ __launch_bounds__(64 * kRowWaves) void score_rows_mfma_kernel(Dims dm
         float M = fmaxf(mt, p0.x);
         for (int cc = lane + 64; cc < nch; cc += 64) M = fmaxf(M, p[cc].x);
         M = wave_max(M);
-        double Z = lane < nch ? (double)(p0.y * exp_raw(p0.x - M)) : 0.0;
+        // a partial with sum 0 (a chunk wholly behind a visual-window row; the empty text columns of such a
+        // window) has maximum -inf and takes no part
+        double Z = lane < nch && p0.y > 0.f ? (double)(p0.y * exp_raw(p0.x - M)) : 0.0;
         for (int cc = lane + 64; cc < nch; cc += 64) {
             const float2 x = p[cc];
-            Z += (double)(x.y * exp_raw(x.x - M));
+            if (x.y > 0.f) Z += (double)(x.y * exp_raw(x.x - M));
         }
         Z = wave_sum(Z);
-        Z += (double)(zt * exp_raw(mt - M));
+        if (zt > 0.f) Z += (double)(zt * exp_raw(mt - M));
         const float w = (float)(1.0 / ((double)(s_pref[g + 1] - s_pref[g]) * (double)G * Z));
         if (lane == 0) {
             t.row_M[slot] = M;  // raw units
@@ -280,8 +297,8 @@ __global__ __launch_bounds__(64 * kRowWaves) void score_rows_mfma_kernel(Dims dm
         }
         if (stash) {
             float *f = t.row_f + (unit * kStashRows + rho) * dm.n_chunks;
-            if (lane < nch) f[lane] = w * exp_raw(p0.x - M);
-            for (int cc = lane + 64; cc < nch; cc += 64) f[cc] = w * exp_raw(p[cc].x - M);
+            if (lane < nch) f[lane] = p0.y > 0.f ? w * exp_raw(p0.x - M) : 0.f;
+            for (int cc = lane + 64; cc < nch; cc += 64) f[cc] = p[cc].y > 0.f ? w * exp_raw(p[cc].x - M) : 0.f;
         }
     }
 }
@@ -289,6 +306,7 @@ __global__ __launch_bounds__(64 * kRowWaves) void score_rows_mfma_kernel(Dims dm
 // ---------------------------------------------------------------------------------------
 // One workgroup finishes kFinishChunks consecutive chunks of a unit and leaves one power-sum entry.
 
+template <bool VIS>
 __global__ __launch_bounds__(256) void score_finish_kernel(Dims dm, DevTables t, int l0, LaunchLayers ll,
                                                            air_strides st, SeqArgs seqs) {
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, n = lane & 15, c = lane >> 4;
@@ -405,8 +423,13 @@ __global__ __launch_bounds__(256) void score_finish_kernel(Dims dm, DevTables t,
                     const bool have = rr < rows_here;
                     const float M = have ? s_M[rr] : 0.f;
                     const float w = have ? s_w[rr] : 0.f;
+                    // visual window: the row sees the keys up to its own visual index
+                    const int lim = VIS ? (u.sq.win_start - u.sq.vis_start) + (rs + rr) % u.sq.win_len - (key0 + n) : 0;
 #pragma unroll
-                    for (int tile = 0; tile < 4; ++tile) acc[tile] = fmaf(w, exp_key(s[tile][i] - M), acc[tile]);
+                    for (int tile = 0; tile < 4; ++tile) {
+                        const float e = exp_key(s[tile][i] - M);
+                        acc[tile] = fmaf(w, VIS && 16 * tile > lim ? 0.f : e, acc[tile]);
+                    }
                 }
             }
         }
@@ -575,22 +598,47 @@ __global__ __launch_bounds__(64 * kEliteWaves) void elite_mfma_kernel(Dims dm, D
                     }
                 }
             } else {
-                for (int r = 0; r < R; ++r) {
-                    const bf16_t *qr = q + (int64_t)(elite[r] - t0) * st.q_t;
-                    const uint32_t uq = reinterpret_cast<const uint32_t *>(qr)[lane];
-                    const float q0 = __uint_as_float(uq << 16), q1 = __uint_as_float(uq & 0xffff0000u);
-                    float m = -INFINITY, z = 0.f;
-                    for (int j = 0; j < R; ++j) {
-                        const uint32_t uk = reinterpret_cast<const uint32_t *>(k + (int64_t)elite[j] * st.kv_t)[lane];
-                        m = fmaxf(m, wave_sum(fmaf(q1, __uint_as_float(uk & 0xffff0000u), q0 * __uint_as_float(uk << 16))));
+                // longer windows (alpha = 0 turns the whole span into rows): R x R logits on MFMA, 16 rows
+                // against 16 keys per tile, two passes over the keys (maximum, then sum).  Lane (n, c) of a
+                // tile holds key n and rows 4c .. 4c+3; rows and keys past R re-read the last one.
+                for (int rb = 0; rb < R; rb += 16) {
+                    uint4 qa2[4];
+                    {
+                        const bf16_t *qr = q + (int64_t)(elite[min(rb + n, R - 1)] - t0) * st.q_t;
+#pragma unroll
+                        for (int sl = 0; sl < 4; ++sl) qa2[sl] = *reinterpret_cast<const uint4 *>(qr + 32 * sl + 8 * c);
                     }
-                    for (int j = 0; j < R; ++j) {
-                        const uint32_t uk = reinterpret_cast<const uint32_t *>(k + (int64_t)elite[j] * st.kv_t)[lane];
-                        z += expf((wave_sum(fmaf(q1, __uint_as_float(uk & 0xffff0000u), q0 * __uint_as_float(uk << 16))) - m) * scale);
+                    float m4[4] = {-INFINITY, -INFINITY, -INFINITY, -INFINITY}, z4[4] = {0.f, 0.f, 0.f, 0.f};
+                    for (int pass = 0; pass < 2; ++pass) {
+                        for (int jb = 0; jb < R; jb += 16) {
+                            const bf16_t *kr = k + (int64_t)elite[min(jb + n, R - 1)] * st.kv_t;
+                            f32x4 a4 = (f32x4){0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                            for (int sl = 0; sl < 4; ++sl) {
+                                const uint4 kb2 = *reinterpret_cast<const uint4 *>(kr + 32 * sl + 8 * c);
+                                a4 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, qa2[sl]),
+                                                                             __builtin_bit_cast(bf16x8, kb2), a4, 0, 0, 0);
+                            }
+                            const bool live = jb + n < R;
+#pragma unroll
+                            for (int i = 0; i < 4; ++i) {
+                                if (pass == 0) m4[i] = fmaxf(m4[i], live ? a4[i] : -INFINITY);
+                                else z4[i] += live ? expf((a4[i] - m4[i]) * scale) : 0.f;
+                            }
+                        }
+                        if (pass == 0) {
+#pragma unroll
+                            for (int i = 0; i < 4; ++i) m4[i] = max16(m4[i]);
+                        }
                     }
-                    if (lane == 0) {
-                        t.row_mtext[hrow * W + r] = m;
-                        t.row_ztext[hrow * W + r] = z;
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) {
+                        const float z = sum16(z4[i]);
+                        const int r = rb + 4 * c + i;
+                        if (n == 0 && r < R) {
+                            t.row_mtext[hrow * W + r] = m4[i];
+                            t.row_ztext[hrow * W + r] = z;
+                        }
                     }
                 }
             }
@@ -612,16 +660,18 @@ hipError_t launch_elite_mfma(hipStream_t s, const Dims &dm, const DevTables &t, 
 hipError_t launch_score_mfma(hipStream_t s, const Dims &dm, const DevTables &t, int pass, int l0, int nl,
                              const LaunchLayers &ll, const air_strides &st, const SeqArgs &seqs) {
     if (pass == 1)
-        hipLaunchKernelGGL(score_stream_kernel, dim3((dm.n_chunks + kStreamChunks - 1) / kStreamChunks, nl * dm.B * dm.Hkv),
-                           dim3(256), 0, s, dm, t, l0, ll, st, seqs);
+        hipLaunchKernelGGL(dm.vis_window ? score_stream_kernel<true> : score_stream_kernel<false>,
+                           dim3((dm.n_chunks + kStreamChunks - 1) / kStreamChunks, nl * dm.B * dm.Hkv), dim3(256), 0, s, dm, t, l0,
+                           ll, st, seqs);
     else {
         // a wave per row when the launch has few units; with many units, 4 waves walk the rows
         hipLaunchKernelGGL(score_rows_mfma_kernel, dim3(nl * dm.B * dm.Hkv),
                            dim3(nl * dm.B * dm.Hkv >= 512 ? 256 : 64 * kRowWaves), 0, s, dm, t, l0, seqs);
         hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;
-        hipLaunchKernelGGL(score_finish_kernel, dim3((dm.n_chunks + kFinishChunks - 1) / kFinishChunks, nl * dm.B * dm.Hkv),
-                           dim3(256), 0, s, dm, t, l0, ll, st, seqs);
+        hipLaunchKernelGGL(dm.vis_window ? score_finish_kernel<true> : score_finish_kernel<false>,
+                           dim3((dm.n_chunks + kFinishChunks - 1) / kFinishChunks, nl * dm.B * dm.Hkv), dim3(256), 0, s, dm, t, l0,
+                           ll, st, seqs);
     }
     return hipGetLastError();
 }

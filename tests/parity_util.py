@@ -52,6 +52,21 @@ def oracle_score_layer(w, li, seqs, alpha):
     return out_scores, out_elites, st, sk
 
 
+def oracle_score_layer_visual_window(w, q_win, li, seqs):
+    """The same for the visual observation window; q_win [B][H_q][>=win_len][d] holds the window rows' queries."""
+    out_scores, out_elites, st, sk = [], [], [], []
+    for b, s in enumerate(seqs):
+        q = synth.storage_to_f64(q_win[b][:, : s.win_len])
+        k = synth.storage_to_f64(li.k[b][:, : s.seq_len])
+        imp, rows = O.layer_importance_visual_window(q, k, seg_of(s))
+        a, c = O.layer_stats(imp)
+        out_scores.append(imp)
+        out_elites.append(rows)
+        st.append(a)
+        sk.append(c)
+    return out_scores, out_elites, st, sk
+
+
 def oracle_budgets(s_t, s_k, seqs, retention, mode=0, min_keep=1):
     """[B][L] budgets from [B][L] statistics."""
     return np.array([O.layer_budgets(list(s_t[b]), list(s_k[b]), retention, s.vis_len, mode, min_keep)

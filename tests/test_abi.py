@@ -51,6 +51,14 @@ def test_invalid_configs_are_rejected_on_the_host():
         assert lib.air_workspace_bytes(C.byref(cfg)) == 0, bad
     for kw in (dict(alpha=1.5), dict(retention=0.0), dict(retention=1.2), dict(min_keep=-1), dict(budget_mode=9)):
         assert lib.air_workspace_bytes(C.byref(A.make_config(**good, **kw))) == 0, kw
+    # visual observation window: no Eq.5, so alpha must be 0; the span may then be as long as the visual span
+    assert lib.air_workspace_bytes(C.byref(A.make_config(**good, window_kind=A.AIR_WINDOW_VISUAL))) == 0  # alpha 0.9
+    assert lib.air_workspace_bytes(C.byref(A.make_config(**good, window_kind=A.AIR_WINDOW_VISUAL, alpha=0.0))) > 0
+    assert lib.air_workspace_bytes(C.byref(A.make_config(**{**good, "max_window": 100}, window_kind=A.AIR_WINDOW_VISUAL,
+                                                         alpha=0.0))) > 0
+    assert lib.air_workspace_bytes(C.byref(A.make_config(**{**good, "max_window": 600}, window_kind=A.AIR_WINDOW_VISUAL,
+                                                         alpha=0.0))) == 0
+    assert lib.air_workspace_bytes(C.byref(A.make_config(**good, window_kind=2, alpha=0.0))) == 0
     h = C.c_void_p()
     cfg = A.make_config(**good)
     assert lib.air_create(C.byref(cfg), None, 1 << 30, C.byref(h)) == A.binding.AIR_ERR_WORKSPACE

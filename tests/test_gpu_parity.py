@@ -12,11 +12,15 @@ pytestmark = pytest.mark.gpu
 
 
 def _run_case(w, retention, *, alpha=None, steps=2, layer_chunk=None, token_major=False, budget_mode=0,
-              min_keep=1, check_decode_units=None, verbose=True):
+              min_keep=1, check_decode_units=None, verbose=True, visual_window=None):
     """Full pipeline on the GPU, checked stage by stage against the oracle.
 
     Stages after the budget are fed the oracle's budgets when the GPU's differ from them (the
     difference itself is checked separately), so that every stage is compared on equal inputs.
+
+    visual_window = (first, length): the visual observation window of the ablation table; the span
+    starts `first` tokens into the visual span (negative: counted from its end).  The generator has no
+    queries for visual tokens, so the first `length` rows of its text queries stand in for them.
     """
     import torch
 
@@ -26,8 +30,16 @@ def _run_case(w, retention, *, alpha=None, steps=2, layer_chunk=None, token_majo
     dev = torch.device("cuda:0")
     alpha = w.alpha if alpha is None else alpha
     seqs = w.seqs()
+    if visual_window is not None:
+        import dataclasses
+        first, length = visual_window
+        assert all(length <= s.n_text and length <= s.vis_len for s in seqs)
+        seqs = [dataclasses.replace(s, win_start=s.vis_start + (first if first >= 0 else s.vis_len + first), win_len=length)
+                for s in seqs]
+        alpha = 0.0
     L, B, Hkv, G, d = w.n_layers, w.batch, w.n_kv_heads, w.group, w.head_dim
-    cfg = config_for(w, retention, alpha=alpha, budget_mode=budget_mode, min_keep=min_keep, max_decode_steps=max(steps, 1))
+    cfg = config_for(w, retention, alpha=alpha, budget_mode=budget_mode, min_keep=min_keep, max_decode_steps=max(steps, 1),
+                     seqs=seqs, window_kind=0 if visual_window is None else A.AIR_WINDOW_VISUAL)
     ac = A.AirCache(cfg, dev)
     tag = f"[{w.name} r={retention} alpha={alpha}]"
 
@@ -46,7 +58,10 @@ def _run_case(w, retention, *, alpha=None, steps=2, layer_chunk=None, token_majo
             q_dev.append(to_device(li.q_text, dev))
             k_dev.append(to_device(li.k, dev))
             v_dev.append(to_device(li.v, dev))
-        sc, el, a, c = P.oracle_score_layer(w, li, seqs, alpha)
+        if visual_window is None:
+            sc, el, a, c = P.oracle_score_layer(w, li, seqs, alpha)
+        else:
+            sc, el, a, c = P.oracle_score_layer_visual_window(w, li.q_text, li, seqs)
         orc.scores.append(sc)
         orc.elites.append(el)
         s_t[:, l] = a
@@ -186,6 +201,31 @@ def test_all_text_window_alpha_zero():
     # every text token is a window row (Tab.5 "all text tokens"): many rows per head
     w = synth.get_workload(2).scaled(n_layers=2, n_vis=520, n_text=24)
     _run_case(w, 0.10, alpha=0.0, steps=1)
+
+
+@pytest.mark.parametrize("first,length", [(-32, 32), (-4, 4), (200, 40), (0, 3)])
+def test_visual_window_bf16(first, length):
+    # "Visual window (32)" of the ablation table on the MFMA kernels: G * 32 rows take the recompute path,
+    # G * 4 = 28 rows the stash path; a window in the middle of the span (200..239 of 1500, across no chunk
+    # boundary but with five chunks wholly behind it) and one at its very start (rows that see 1-3 keys)
+    # exercise the empty partials.  Eq.9 is 1 for every layer, so the budgets rest on the skewness alone.
+    w = synth.get_workload(2).scaled(n_layers=3, n_vis=1500, n_text=48, decode_steps=1)
+    r = _run_case(w, 0.10, steps=1, visual_window=(first, length))
+    assert r["score_err"] <= P.SCORE_RTOL
+
+
+def test_visual_window_across_a_chunk_boundary_and_ragged_batch():
+    # rows 750 .. 773 of 780 straddle the chunk boundary at 768: the last chunk is empty for the first 18 rows
+    w = synth.get_workload(2).scaled(n_layers=2, n_vis=780, n_text=48, decode_steps=1)
+    _run_case(w, 0.10, steps=1, visual_window=(-30, 24))
+    # visual spans of different lengths in one batch
+    w = synth.get_workload(3).scaled(batch=3, n_layers=2, n_vis=780, n_text=48)
+    _run_case(w, 0.10, steps=1, visual_window=(-30, 24))
+
+
+def test_visual_window_fp32_generic_path():
+    _run_case(synth.get_workload(1), 0.10, steps=1, visual_window=(-16, 16))
+    _run_case(synth.get_workload(1).scaled(n_vis=300), 0.10, steps=1, visual_window=(250, 12))
 
 
 def test_degenerate_sizes():
