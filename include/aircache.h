@@ -162,6 +162,12 @@ air_status air_get_budgets(air_ctx *ctx, int32_t *host);
 air_status air_set_budgets(air_ctx *ctx, const int32_t *host);
 /* kept visual indices of layer l: host [B][H_kv][max_vis_len], ascending, first k[b][l] valid */
 air_status air_get_indices(air_ctx *ctx, int32_t l, int32_t *host);
+/* Fix the kept visual indices of layer l instead of selecting them (same layout as air_get_indices;
+ * the first k[b][l] entries of every row must be strictly ascending and inside [0, vis_len of b]):
+ * air_select_compact then only gathers that layer.  With budgets of 1 this keeps the single token of
+ * a chosen importance rank, the one-token-at-a-time study of Sec.4.3 (Fig.4); it also isolates the
+ * gather for tests.  Needs budgets; computing or setting budgets again forgets the fixed indices. */
+air_status air_set_indices(air_ctx *ctx, int32_t l, const int32_t *host);
 /* current cache length (system + kept + text + appended) per (b, l): host [B][L] */
 air_status air_get_lengths(air_ctx *ctx, int32_t *host);
 /* rows [0, length) of the compacted cache of (layer l, sequence b, KV head h) in token

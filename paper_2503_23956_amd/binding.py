@@ -51,7 +51,7 @@ class air_strides(C.Structure):
 EXPORTS = (
     "air_version", "air_workspace_bytes", "air_create", "air_destroy", "air_reset", "air_score", "air_budget",
     "air_select_compact", "air_decode_attn", "air_get_scores", "air_get_elite", "air_get_stats",
-    "air_get_budgets", "air_set_budgets", "air_get_indices", "air_get_lengths", "air_get_cache",
+    "air_get_budgets", "air_set_budgets", "air_get_indices", "air_set_indices", "air_get_lengths", "air_get_cache",
     "air_last_error",
 )
 
@@ -88,6 +88,7 @@ def load_library(path: Optional[str] = None):
     lib.air_get_stats.argtypes = [vp, vp, vp]
     lib.air_get_budgets.argtypes = [vp, vp]
     lib.air_set_budgets.argtypes = [vp, vp]
+    lib.air_set_indices.argtypes = [vp, C.c_int32, vp]
     lib.air_get_indices.argtypes = [vp, i32, vp]
     lib.air_get_lengths.argtypes = [vp, vp]
     lib.air_get_cache.argtypes = [vp, i32, i32, i32, vp, vp, i32]
@@ -256,6 +257,12 @@ class AirCache:
         out = np.empty((c.batch, c.n_kv_heads, c.max_vis_len), dtype=np.int32)
         self._check(self.lib.air_get_indices(self.handle, l, out.ctypes.data))
         return out
+
+    def air_set_indices(self, l: int, indices: np.ndarray):
+        c = self.cfg
+        idx = np.ascontiguousarray(indices, dtype=np.int32)
+        assert idx.shape == (c.batch, c.n_kv_heads, c.max_vis_len)
+        self._check(self.lib.air_set_indices(self.handle, l, idx.ctypes.data))
 
     def air_get_lengths(self) -> np.ndarray:
         c = self.cfg

@@ -103,7 +103,7 @@ struct air_ctx {
     bool have_seqs;
     bool budgets_ready;
     std::vector<air_seq> seqs;
-    std::vector<char> scored, compacted;
+    std::vector<char> scored, compacted, fixed_idx;  // fixed_idx: the layer's kept indices were set by the caller
     std::vector<int32_t> appended;
     int force_splits, force_waves, force_tiles;  // AIR_DECODE_SPLITS / _WAVES / _TILES, 0 = automatic
     int score_block_mb;             // bytes of K_v scored per pair of passes (AIR_SCORE_BLOCK_MB)
@@ -201,6 +201,7 @@ air_status air_create(const air_config *cfg, void *workspace, size_t workspace_b
     }
     c->scored.assign(d.L, 0);
     c->compacted.assign(d.L, 0);
+    c->fixed_idx.assign(d.L, 0);
     c->appended.assign(d.L, 0);
     // scores past a sequence's visual span and the small tables start at zero
     hipError_t e = hipMemset(w + lay.scores, 0, lay.unit_st - lay.scores);
@@ -228,6 +229,7 @@ air_status air_reset(air_ctx *ctx) {
     ctx->seqs.clear();
     ctx->scored.assign(ctx->dm.L, 0);
     ctx->compacted.assign(ctx->dm.L, 0);
+    ctx->fixed_idx.assign(ctx->dm.L, 0);
     ctx->appended.assign(ctx->dm.L, 0);
     return AIR_OK;
 }
@@ -352,6 +354,7 @@ air_status air_budget(air_ctx *ctx, void *stream) {
     hipError_t e = launch_budget((hipStream_t)stream, ctx->dm, ctx->tab, ctx->cfg.retention, ctx->cfg.budget_mode,
                                  ctx->cfg.min_keep, 0, v_transposed(ctx->cfg.dtype, ctx->cfg.head_dim) ? 1 : 0, sa);
     if (e != hipSuccess) return hip_fail(ctx, e, "air_budget launch");
+    ctx->fixed_idx.assign(ctx->dm.L, 0);
     ctx->budgets_ready = true;
     return AIR_OK;
 }
@@ -375,7 +378,18 @@ air_status air_select_compact(air_ctx *ctx, void *stream, int32_t l0, int32_t l1
             ll.p[i].k = layers[c0 - l0 + i].k;
             ll.p[i].v = layers[c0 - l0 + i].v;
         }
-        hipError_t e = launch_select(s, ctx->dm, ctx->tab, c0, nl);
+        // selection over each run of layers whose indices the caller has not fixed
+        hipError_t e = hipSuccess;
+        for (int a = 0; a < nl && e == hipSuccess;) {
+            if (ctx->fixed_idx[c0 + a]) {
+                ++a;
+                continue;
+            }
+            int z = a;
+            while (z < nl && !ctx->fixed_idx[c0 + z]) ++z;
+            e = launch_select(s, ctx->dm, ctx->tab, c0 + a, z - a);
+            a = z;
+        }
         if (e == hipSuccess) e = launch_gather(s, ctx->dm, ctx->tab, ctx->cfg.dtype, c0, nl, ll, *strides);
         if (e != hipSuccess) return hip_fail(ctx, e, "air_select_compact launch");
     }
@@ -523,6 +537,7 @@ air_status air_set_budgets(air_ctx *ctx, const int32_t *host) {
                                            ctx->cfg.min_keep, 1, 0, sa);
     if (e == hipSuccess) e = hipDeviceSynchronize();
     if (e != hipSuccess) return hip_fail(ctx, e, "air_set_budgets");
+    ctx->fixed_idx.assign(ctx->dm.L, 0);
     ctx->budgets_ready = true;
     return AIR_OK;
 }
@@ -533,6 +548,31 @@ air_status air_get_indices(air_ctx *ctx, int32_t l, int32_t *host) {
     if (!ctx->compacted[l]) return fail(ctx, AIR_ERR_STATE, "layer not compacted");
     const size_t n = (size_t)ctx->dm.B * ctx->dm.Hkv * ctx->dm.max_vis;
     return d2h(ctx, host, ctx->tab.indices + (size_t)l * n, n * 4);
+}
+
+air_status air_set_indices(air_ctx *ctx, int32_t l, const int32_t *host) {
+    if (!ctx || !host) return AIR_ERR_INVALID_ARG;
+    if (l < 0 || l >= ctx->cfg.n_layers) return fail(ctx, AIR_ERR_INVALID_ARG, "bad layer");
+    if (!ctx->budgets_ready) return fail(ctx, AIR_ERR_STATE, "air_set_indices: budgets not computed");
+    if (ctx->compacted[l]) return fail(ctx, AIR_ERR_STATE, "air_set_indices: layer already compacted");
+    const int L = ctx->dm.L, B = ctx->dm.B, Hkv = ctx->dm.Hkv, NV = ctx->dm.max_vis;
+    std::vector<int32_t> budgets((size_t)B * L);
+    air_status st = d2h(ctx, budgets.data(), ctx->tab.budgets, budgets.size() * 4);
+    if (st != AIR_OK) return st;
+    for (int b = 0; b < B; ++b) {
+        const int k = budgets[(size_t)b * L + l], n = ctx->seqs[b].vis_len;
+        for (int h = 0; h < Hkv; ++h) {
+            const int32_t *row = host + ((size_t)b * Hkv + h) * NV;
+            for (int i = 0; i < k; ++i)
+                if (row[i] < 0 || row[i] >= n || (i > 0 && row[i] <= row[i - 1]))
+                    return fail(ctx, AIR_ERR_INVALID_ARG, "air_set_indices: indices must be strictly ascending inside the visual span");
+        }
+    }
+    const size_t n = (size_t)B * Hkv * NV;
+    hipError_t e = hipMemcpy(ctx->tab.indices + (size_t)l * n, host, n * 4, hipMemcpyHostToDevice);
+    if (e != hipSuccess) return hip_fail(ctx, e, "air_set_indices");
+    ctx->fixed_idx[l] = 1;
+    return AIR_OK;
 }
 
 air_status air_get_lengths(air_ctx *ctx, int32_t *host) {

@@ -4,7 +4,8 @@ import math
 import numpy as np
 import pytest
 
-from paper_2503_23956_amd.diagnostics import js_divergence
+from oracle import aircache_oracle as O
+from paper_2503_23956_amd.diagnostics import importance_ranking, js_divergence, single_rank_indices
 
 
 def test_identical_and_rescaled_budgets_have_zero_divergence():
@@ -39,3 +40,28 @@ def test_bad_inputs_are_rejected():
         js_divergence([0, 0], [1, 1])
     with pytest.raises(ValueError):
         js_divergence([-1, 2], [1, 1])
+
+
+def test_importance_ranking_is_the_order_top_k_takes_tokens():
+    # the oracle's top-(j+1) set minus its top-j set is the token of rank j, ties to the lower index
+    rng = np.random.default_rng(3)
+    x = rng.random(40).astype(np.float32)
+    x[[5, 17, 30]] = x[9]  # a four-way tie
+    rank = importance_ranking(x)
+    assert sorted(rank.tolist()) == list(range(40))
+    for j in range(40):
+        (tok,) = set(O.select_topk(x.astype(np.float64), j + 1).tolist()) - set(O.select_topk(x.astype(np.float64), j).tolist())
+        assert rank[j] == tok
+    pos = {int(t): j for j, t in enumerate(rank)}
+    assert pos[5] < pos[9] < pos[17] < pos[30]
+
+
+def test_single_rank_indices_layout_and_errors():
+    sc = np.zeros((2, 3, 8), dtype=np.float32)
+    sc[0, :, :5] = [0.1, 0.5, 0.2, 0.5, 0.05]
+    sc[1, :, :8] = np.arange(8)
+    idx = single_rank_indices(sc, [5, 8], 1)
+    assert idx.shape == sc.shape and idx.dtype == np.int32
+    assert idx[0, :, 0].tolist() == [3, 3, 3] and idx[1, :, 0].tolist() == [6, 6, 6]
+    with pytest.raises(ValueError):
+        single_rank_indices(sc, [5, 8], 5)

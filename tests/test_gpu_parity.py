@@ -228,6 +228,82 @@ def test_visual_window_fp32_generic_path():
     _run_case(synth.get_workload(1).scaled(n_vis=300), 0.10, steps=1, visual_window=(250, 12))
 
 
+def test_one_token_at_a_time_harness_and_fixed_indices():
+    """Sec.4.3, Fig.4 as a mechanism: keep only the visual token of importance rank j in every layer
+    (budgets of 1, indices fixed by the caller), decode over [system ; that token ; text].  One layer keeps
+    the library's own selection, to check that fixed and selected layers mix in one call."""
+    import torch
+
+    import paper_2503_23956_amd as A
+    from paper_2503_23956_amd.device_inputs import config_for, to_device, to_host
+    from paper_2503_23956_amd.diagnostics import importance_ranking, single_rank_indices
+
+    dev = torch.device("cuda:0")
+    w = synth.get_workload(2).scaled(n_layers=3, n_vis=700, n_text=32, decode_steps=1)
+    seqs = w.seqs()
+    L, B, Hkv, G, d = w.n_layers, w.batch, w.n_kv_heads, w.group, w.head_dim
+    layers = [synth.layer_inputs(w, l, seqs) for l in range(L)]
+    q = [to_device(li.q_text, dev) for li in layers]
+    k = [to_device(li.k, dev) for li in layers]
+    v = [to_device(li.v, dev) for li in layers]
+    oracle_imp = [P.oracle_score_layer(w, li, seqs, w.alpha)[0] for li in layers]  # [l][b] -> [H_kv][vis_len]
+    qs, ks, vs = zip(*[synth.decode_inputs(w, l, 0) for l in range(L)])
+    qn, kn, vn = np.stack(qs), np.stack(ks), np.stack(vs)
+    ac = A.AirCache(config_for(w, 0.10, max_decode_steps=1, seqs=seqs), dev)
+    for rank in (0, 1, 7, 699):
+        ac.air_reset()
+        ac.air_score(0, L, q, k, v, seqs)
+        ac.air_budget()
+        ac.air_set_budgets(np.ones((B, L), dtype=np.int32))
+        want_tok = np.zeros((L, B, Hkv), dtype=np.int64)
+        for l in range(L):
+            for b in range(B):
+                for h in range(Hkv):  # the oracle's token of this rank: its top-(j+1) set minus its top-j set
+                    imp = oracle_imp[l][b][h]
+                    (tok,) = set(O.select_topk(imp, rank + 1).tolist()) - set(O.select_topk(imp, rank).tolist())
+                    want_tok[l, b, h] = tok
+            if l != 1:  # layer 1 is left to the library's own top-1 selection
+                idx = np.zeros((B, Hkv, ac.cfg.max_vis_len), dtype=np.int32)
+                idx[:, :, 0] = want_tok[l]
+                ac.air_set_indices(l, idx)
+            if rank < 2:  # well-separated ranks: the GPU's scores rank the same token there
+                got = single_rank_indices(ac.air_get_scores(l), [s.vis_len for s in seqs], rank)
+                assert np.array_equal(got[:, :, 0], want_tok[l])
+        ac.air_select_compact(0, L, k, v)
+        out = torch.empty((L, B, w.n_q_heads, d), dtype=q[0].dtype, device=dev)
+        ac.air_decode_attn(0, L, to_device(qn, dev), to_device(kn, dev), to_device(vn, dev), out)
+        got_out = synth.storage_to_f64(to_host(out))
+        for l in range(L):
+            gi = ac.air_get_indices(l)
+            for b, s in enumerate(seqs):
+                for h in range(Hkv):
+                    tok = int(want_tok[l, b, h]) if l != 1 else int(O.select_topk(oracle_imp[l][b][h], 1)[0])
+                    assert gi[b, h, 0] == tok
+                    rows = O.compact_rows(P.seg_of(s), np.array([tok]))
+                    kk, vv = ac.air_get_cache(l, b, h, len(rows) + 1)  # the decode step has appended one row
+                    assert np.array_equal(kk[:-1], layers[l].k[b, h][rows]) and np.array_equal(vv[:-1], layers[l].v[b, h][rows])
+                    assert np.array_equal(kk[-1], kn[l, b, h]) and np.array_equal(vv[-1], vn[l, b, h])
+                    kc, vc = synth.storage_to_f64(kk), synth.storage_to_f64(vv)
+                    want = O.decode_attn(synth.storage_to_f64(qn[l, b, h * G:(h + 1) * G]), kc, vc)
+                    assert np.abs(got_out[l, b, h * G:(h + 1) * G] - want).max() <= P.DECODE_ATOL[w.dtype]
+    # misuse is caught on the host
+    ac.air_reset()
+    ac.air_score(0, L, q, k, v, seqs)
+    with pytest.raises(A.AirError) as e:
+        ac.air_set_indices(0, np.zeros((B, Hkv, ac.cfg.max_vis_len), dtype=np.int32))  # no budgets yet
+    assert e.value.status == A.binding.AIR_ERR_STATE
+    ac.air_budget()
+    bad = np.zeros((B, Hkv, ac.cfg.max_vis_len), dtype=np.int32)  # budgets > 1: zeros are not ascending
+    with pytest.raises(A.AirError) as e:
+        ac.air_set_indices(0, bad)
+    assert e.value.status == A.binding.AIR_ERR_INVALID_ARG
+    bad[:, :, :] = np.arange(ac.cfg.max_vis_len) + 699  # ascending, but the second entry is past the visual span
+    with pytest.raises(A.AirError) as e:
+        ac.air_set_indices(0, bad)
+    assert e.value.status == A.binding.AIR_ERR_INVALID_ARG
+    ac.close()
+
+
 def test_degenerate_sizes():
     # fewer than three visual tokens (skewness 0), one text token, one-token window, min_keep 0
     w = synth.get_workload(1).scaled(n_vis=2, n_text=1, window=1, n_sys=1)
