@@ -162,6 +162,9 @@ def main():
     ap.add_argument("--retention-sweep", action="store_true",
                     help="also time the same workload with the full cache and at 50 % / 10 % / 1 % retention "
                          "(the quantity the paper's efficiency table reports for attention alone)")
+    ap.add_argument("--graph-decode", action="store_true",
+                    help="also time the decode loop replayed from a HIP graph (device-counted steps): one recorded "
+                         "step of one launch per layer, as a model that calls the attention layer by layer would hold it")
     ap.add_argument("--window-sweep", action="store_true",
                     help="also time air_score with the observation windows of the paper's ablation table: elite, "
                          "continuous last 16 / 32 text tokens, all text tokens, visual window of 32")
@@ -364,6 +367,43 @@ def main():
         result["budget_js_divergence"] = {
             f"{a} & {b}": float(np.mean([js_divergence(alloc[a][i], alloc[b][i]) for i in range(w.batch)]))
             for a, b in pairs}
+    if args.graph_decode:
+        res = {}
+        for name, per_layer in (("one_launch_per_layer", True), ("all_layers_in_one_launch", False)):
+            ac = A.AirCache(config_for(w, retention, max_decode_steps=n_dec, seqs=seqs, device_steps=1), dev)
+            prep_score, prep_compact = ac.prepare(q, k, v, seqs), ac.prepare(None, k, v)
+            sq, sk, sv = torch.empty_like(dq[0]), torch.empty_like(dk[0]), torch.empty_like(dv[0])
+            g = torch.cuda.CUDAGraph()
+            ac.air_score(0, L, prepared=prep_score)
+            ac.air_budget()
+            ac.air_select_compact(0, L, prepared=prep_compact)
+            with torch.cuda.graph(g):
+                if per_layer:
+                    for l in range(L):
+                        ac.air_decode_attn(l, l + 1, sq[l:l + 1], sk[l:l + 1], sv[l:l + 1], out[l:l + 1])
+                else:
+                    ac.air_decode_attn(0, L, sq, sk, sv, out)
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            times = []
+            for it in range(4):
+                ac.air_reset()
+                ac.air_score(0, L, prepared=prep_score)
+                ac.air_budget()
+                ac.air_select_compact(0, L, prepared=prep_compact)
+                sq.copy_(dq[0]), sk.copy_(dk[0]), sv.copy_(dv[0])
+                e0.record()
+                for _ in range(n_dec):
+                    g.replay()
+                e1.record()
+                torch.cuda.synchronize()
+                if it:
+                    times.append(e0.elapsed_time(e1))
+            s0 = seqs[0]
+            want_len = (s0.seq_len - s0.vis_len) + int(budgets[0, 0]) + n_dec
+            assert int(ac.air_get_lengths()[0, 0]) == want_len, "replayed steps did not advance the cache"
+            res[name] = float(np.mean(times)) * 1e3 / n_dec
+            del ac, g
+        result["decode_graph_replay_us_per_step"] = res
     if args.window_sweep:
         import dataclasses
 

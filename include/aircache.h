@@ -85,7 +85,10 @@ typedef struct {
     double alpha;             /* relevance threshold of Eq.5, in [0,1]; the paper uses 0.9 */
     double retention;         /* r: fraction of visual tokens kept overall, in (0,1]       */
     int32_t window_kind;      /* air_window_kind; 0 = the paper's text windows              */
-    int32_t reserved;         /* must be 0                                                  */
+    int32_t device_steps;     /* 0: the host counts the tokens air_decode_attn has appended and passes the
+                                 count with every launch.  1 (bf16, head_dim 128 only): the count lives in
+                                 device memory and advances with every decode launch that RUNS, so that a
+                                 decode step captured in a HIP graph can be replayed; see air_decode_attn */
 } air_config;
 
 /* One prompt.  system = [0, vis_start), visual = [vis_start, vis_start+vis_len),
@@ -145,7 +148,12 @@ air_status air_select_compact(air_ctx *ctx, void *stream, int32_t l0, int32_t l1
 /* One decode step for layers [l0, l1): appends k_new / v_new to each layer's compacted
  * cache (Eq.2), then out[h] = softmax(q_h K'^T / sqrt(d)) V' over the whole cache
  * including the new token.  All tensors dense: q_new, out [l1-l0][B][H_q][d];
- * k_new, v_new [l1-l0][B][H_kv][d].  At most max_decode_steps calls per layer. */
+ * k_new, v_new [l1-l0][B][H_kv][d].  At most max_decode_steps calls per layer.
+ * The call enqueues kernel launches only (no copy, no memset, no allocation, no host wait), so it
+ * can be recorded into a HIP graph.  With cfg.device_steps the recorded step advances the cache by
+ * itself on every replay; the host then cannot check the capacity: a step that runs with the cache
+ * full appends nothing, leaves `out` as it is and raises a flag that makes air_get_lengths fail
+ * with AIR_ERR_STATE.  air_select_compact starts a layer's count at zero again. */
 air_status air_decode_attn(air_ctx *ctx, void *stream, int32_t l0, int32_t l1, const void *q_new,
                            const void *k_new, const void *v_new, void *out);
 

@@ -21,7 +21,8 @@ static bool config_ok(const air_config &c) {
     if (c.head_dim != 64 && c.head_dim != 128) return false;
     if (c.max_vis_len < 1 || c.max_nonvis_len < 1) return false;
     if (c.window_kind != AIR_WINDOW_TEXT && c.window_kind != AIR_WINDOW_VISUAL) return false;
-    if (c.reserved != 0) return false;
+    if (c.device_steps != 0 && c.device_steps != 1) return false;
+    if (c.device_steps && !(c.dtype == AIR_BF16 && c.head_dim == 128)) return false;
     const bool vis_window = c.window_kind == AIR_WINDOW_VISUAL;
     if (c.max_window < 1 || c.max_window > AIR_MAX_TEXT) return false;
     if (c.max_window > (vis_window ? c.max_vis_len : c.max_nonvis_len)) return false;
@@ -76,6 +77,7 @@ WsLayout make_layout(const air_config &c) {
     w.base_len = take(B * L * 4);
     w.layer_off = take(B * L * 4);
     w.dec_cnt = take(L * B * Hkv * 4);
+    w.dec_steps = take((L * B * Hkv + 1) * 4);
     w.moments = take(L * B * Hkv * (size_t)w.n_chunks * 3 * 8);
     w.indices = take(L * B * Hkv * NV * 4);
     w.kcache = take(B * Hkv * (size_t)w.pool_rows * D * esz);
@@ -103,6 +105,7 @@ struct air_ctx {
     bool have_seqs;
     bool budgets_ready;
     std::vector<air_seq> seqs;
+    std::vector<char> decoded;  // device_steps: air_decode_attn has been called on the layer since its compaction
     std::vector<char> scored, compacted, fixed_idx;  // fixed_idx: the layer's kept indices were set by the caller
     std::vector<int32_t> appended;
     int force_splits, force_waves, force_tiles;  // AIR_DECODE_SPLITS / _WAVES / _TILES, 0 = automatic
@@ -179,6 +182,7 @@ air_status air_create(const air_config *cfg, void *workspace, size_t workspace_b
     t.row_f = (float *)(w + lay.row_f);
     t.unit_R = (int32_t *)(w + lay.unit_R);
     t.len_off = (int2 *)(w + lay.len_off);
+    t.dec_steps = cfg->device_steps ? (int32_t *)(w + lay.dec_steps) : nullptr;
     c->have_seqs = false;
     c->budgets_ready = false;
     c->force_splits = c->force_waves = c->force_tiles = 0;
@@ -203,6 +207,7 @@ air_status air_create(const air_config *cfg, void *workspace, size_t workspace_b
     c->compacted.assign(d.L, 0);
     c->fixed_idx.assign(d.L, 0);
     c->appended.assign(d.L, 0);
+    c->decoded.assign(d.L, 0);
     // scores past a sequence's visual span and the small tables start at zero
     hipError_t e = hipMemset(w + lay.scores, 0, lay.unit_st - lay.scores);
     if (e == hipSuccess) e = hipMemset(w + lay.seq_tab, 0, lay.part - lay.seq_tab);
@@ -231,6 +236,7 @@ air_status air_reset(air_ctx *ctx) {
     ctx->compacted.assign(ctx->dm.L, 0);
     ctx->fixed_idx.assign(ctx->dm.L, 0);
     ctx->appended.assign(ctx->dm.L, 0);
+    ctx->decoded.assign(ctx->dm.L, 0);
     return AIR_OK;
 }
 
@@ -366,7 +372,7 @@ air_status air_select_compact(air_ctx *ctx, void *stream, int32_t l0, int32_t l1
     if (!range_ok(ctx, l0, l1)) return fail(ctx, AIR_ERR_INVALID_ARG, "air_select_compact: bad layer range");
     if (!ctx->budgets_ready) return fail(ctx, AIR_ERR_STATE, "air_select_compact: budgets not computed");
     for (int l = l0; l < l1; ++l)
-        if (ctx->appended[l]) return fail(ctx, AIR_ERR_STATE, "air_select_compact: layer already decoded on");
+        if (ctx->appended[l] || ctx->decoded[l]) return fail(ctx, AIR_ERR_STATE, "air_select_compact: layer already decoded on");
     air_status st = check_strides(ctx, strides, layers, l1 - l0, false);
     if (st != AIR_OK) return st;
     hipStream_t s = (hipStream_t)stream;
@@ -443,7 +449,8 @@ air_status air_decode_attn(air_ctx *ctx, void *stream, int32_t l0, int32_t l1, c
     if (!range_ok(ctx, l0, l1)) return fail(ctx, AIR_ERR_INVALID_ARG, "air_decode_attn: bad layer range");
     for (int l = l0; l < l1; ++l) {
         if (!ctx->compacted[l]) return fail(ctx, AIR_ERR_STATE, "air_decode_attn: layer not compacted");
-        if (ctx->appended[l] >= ctx->cfg.max_decode_steps)
+        // with device-counted steps the kernel guards the capacity itself
+        if (!ctx->cfg.device_steps && ctx->appended[l] >= ctx->cfg.max_decode_steps)
             return fail(ctx, AIR_ERR_STATE, "air_decode_attn: max_decode_steps exhausted");
     }
     hipStream_t s = (hipStream_t)stream;
@@ -453,12 +460,32 @@ air_status air_decode_attn(air_ctx *ctx, void *stream, int32_t l0, int32_t l1, c
         memset(&ll, 0, sizeof(ll));
         for (int i = 0; i < nl; ++i) ll.appended[i] = ctx->appended[c0 + i];
         int splits = 1, waves = 1, tiles = 4;
-        decode_shape(ctx, nl, ctx->appended[c0], &splits, &waves, &tiles);
+        // a recorded launch is replayed at every cache length: its shape is chosen for the middle of the decode
+        decode_shape(ctx, nl, ctx->cfg.device_steps ? ctx->cfg.max_decode_steps / 2 : ctx->appended[c0], &splits, &waves, &tiles);
         hipError_t e = launch_decode(s, ctx->dm, ctx->tab, ctx->cfg.dtype, c0, nl, c0 - l0, ll, q_new, k_new, v_new,
                                      out, splits, waves, tiles);
         if (e != hipSuccess) return hip_fail(ctx, e, "air_decode_attn launch");
     }
-    for (int l = l0; l < l1; ++l) ctx->appended[l] += 1;
+    for (int l = l0; l < l1; ++l) {
+        if (ctx->cfg.device_steps) ctx->decoded[l] = 1;
+        else ctx->appended[l] += 1;
+    }
+    return AIR_OK;
+}
+
+static air_status d2h(air_ctx *ctx, void *dst, const void *src, size_t bytes);
+
+// tokens appended so far to every layer of sequence b = 0..B-1 (device-counted steps): host [B][L];
+// fails when a step ran with the cache full
+static air_status device_steps(air_ctx *ctx, std::vector<int32_t> &steps) {
+    const int L = ctx->dm.L, B = ctx->dm.B, Hkv = ctx->dm.Hkv;
+    std::vector<int32_t> raw((size_t)L * B * Hkv + 1);
+    air_status st = d2h(ctx, raw.data(), ctx->tab.dec_steps, raw.size() * 4);
+    if (st != AIR_OK) return st;
+    if (raw.back() != 0) return fail(ctx, AIR_ERR_STATE, "a decode step ran with the cache full (max_decode_steps exhausted)");
+    steps.assign((size_t)B * L, 0);
+    for (int l = 0; l < L; ++l)
+        for (int b = 0; b < B; ++b) steps[(size_t)b * L + l] = raw[((size_t)l * B + b) * Hkv];  // the same for every KV head
     return AIR_OK;
 }
 
@@ -581,8 +608,14 @@ air_status air_get_lengths(air_ctx *ctx, int32_t *host) {
     const int L = ctx->dm.L;
     air_status st = d2h(ctx, host, ctx->tab.base_len, (size_t)ctx->dm.B * L * 4);
     if (st != AIR_OK) return st;
+    std::vector<int32_t> steps;
+    if (ctx->cfg.device_steps) {
+        st = device_steps(ctx, steps);
+        if (st != AIR_OK) return st;
+    }
     for (int b = 0; b < ctx->dm.B; ++b)
-        for (int l = 0; l < L; ++l) host[(size_t)b * L + l] += ctx->appended[l];
+        for (int l = 0; l < L; ++l)
+            host[(size_t)b * L + l] += ctx->cfg.device_steps ? steps[(size_t)b * L + l] : ctx->appended[l];
     return AIR_OK;
 }
 
@@ -596,7 +629,12 @@ air_status air_get_cache(air_ctx *ctx, int32_t l, int32_t b, int32_t h, void *k_
     if (st != AIR_OK) return st;
     st = d2h(ctx, &off, ctx->tab.layer_off + (size_t)b * ctx->dm.L + l, 4);
     if (st != AIR_OK) return st;
-    const int32_t len = base + ctx->appended[l];
+    int32_t app = ctx->appended[l];
+    if (ctx->cfg.device_steps) {
+        st = d2h(ctx, &app, ctx->tab.dec_steps + ((size_t)l * ctx->dm.B + b) * ctx->dm.Hkv + h, 4);
+        if (st != AIR_OK) return st;
+    }
+    const int32_t len = base + app;
     if (len > max_rows) return fail(ctx, AIR_ERR_SHAPE, "air_get_cache: max_rows too small");
     const size_t esz = ctx->cfg.dtype == AIR_BF16 ? 2 : 4;
     const size_t row0 = ((size_t)b * ctx->dm.Hkv + h) * (size_t)ctx->dm.pool_rows + off;

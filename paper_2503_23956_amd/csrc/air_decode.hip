@@ -79,6 +79,8 @@ struct DecodeTabs {
     float *dec_o;
     float2 *dec_ml;
     int32_t *dec_cnt;
+    int32_t *dec_steps;  // null: the host passes the count of appended tokens (DecodeSteps)
+    int32_t n_units;     // units of the whole context: dec_steps[n_units] is the cache-full flag
 };
 struct DecodeSteps {
     int32_t appended[kMaxLayersPerLaunch];
@@ -114,7 +116,19 @@ __global__ __launch_bounds__(64 * NW) void decode_mfma_kernel(Dims dm, DecodeTab
     vcol[0] = v_new[new_src + lane];
     vcol[1] = v_new[new_src + 64 + lane];
     const int2 len_off = t.len_off[(int64_t)b * dm.L + l];
-    const int len = len_off.x + ll.appended[li] + 1;
+    const int64_t unit = ((int64_t)l * dm.B + b) * dm.Hkv + kvh;
+    // tokens appended so far: from the host with the launch, or counted on the device (a recorded launch
+    // that is replayed): the workgroup that finishes the unit advances the count, after every workgroup
+    // of the unit has read it
+    int appended = ll.appended[li];
+    if (t.dec_steps) {
+        appended = t.dec_steps[unit];
+        if (appended >= dm.max_steps) {  // cache full: nothing is appended or written
+            if (threadIdx.x == 0) t.dec_steps[t.n_units] = 1;
+            return;
+        }
+    }
+    const int len = len_off.x + appended + 1;
     const int newrow = len - 1;  // the token appended by this call (Eq.2): scored from k_new / v_new, stored to the cache
     int k0, k1;
     split_range(len, splits, split, k0, k1);
@@ -122,7 +136,6 @@ __global__ __launch_bounds__(64 * NW) void decode_mfma_kernel(Dims dm, DecodeTab
     const int64_t row0 = ((int64_t)b * dm.Hkv + kvh) * dm.pool_rows + len_off.y;
     bf16_t *kc = (bf16_t *)t.kcache + row0 * D;
     bf16_t *vc = (bf16_t *)t.vcache + row0 * D;
-    const int64_t unit = ((int64_t)l * dm.B + b) * dm.Hkv + kvh;
     bf16_t *o_unit = out + (((int64_t)(lbase + li) * dm.B + b) * dm.Hq + (int64_t)kvh * G) * D;
 
     bf16x8 qb[4];
@@ -192,7 +205,7 @@ __global__ __launch_bounds__(64 * NW) void decode_mfma_kernel(Dims dm, DecodeTab
     // what a step read last is what the next step reads first, so the part of the cache that is
     // still in the L2 of the XCD (the unit-to-XCD mapping is the same every launch) gets reused
     // instead of being evicted just before its turn.
-    const bool backward = (ll.appended[li] & 1) != 0;
+    const bool backward = (appended & 1) != 0;
     const int n_chunks = (max(kend - k0, 0) + kIter - 1) / kIter;
     const int kb_first = k0 + (backward ? n_chunks - 1 - wave : wave) * kIter;
     const int kStep = (backward ? -NW : NW) * kIter;  // distance between two chunks of one wave
@@ -375,6 +388,7 @@ __global__ __launch_bounds__(64 * NW) void decode_mfma_kernel(Dims dm, DecodeTab
                     o_unit[g * D + 16 * (wave + NW * jj) + n] = float_to_bf16_bits(acc[jj][i] * inv);
             }
         }
+        if (t.dec_steps && threadIdx.x == 0) t.dec_steps[unit] = appended + 1;
         return;
     }
     if (!SPLIT) return;  // the instance for one workgroup per unit carries none of what follows
@@ -472,6 +486,7 @@ __global__ __launch_bounds__(64 * NW) void decode_mfma_kernel(Dims dm, DecodeTab
                 o_unit[g * D + 16 * (wave + NW * jj) + n] = float_to_bf16_bits(num[jj][i] * inv);
         }
     }
+    if (t.dec_steps && threadIdx.x == 0) t.dec_steps[unit] = appended + 1;
 }
 
 // ---------------------------------------------------------------------------------------
@@ -647,6 +662,8 @@ hipError_t launch_decode(hipStream_t s, const Dims &dm, const DevTables &t, int 
         dt.dec_o = t.dec_o;
         dt.dec_ml = t.dec_ml;
         dt.dec_cnt = t.dec_cnt;
+        dt.dec_steps = t.dec_steps;
+        dt.n_units = dm.L * dm.B * dm.Hkv;
         DecodeSteps ds;
         for (int i = 0; i < kMaxLayersPerLaunch; ++i) ds.appended[i] = ll.appended[i];
 #define AIR_LAUNCH_DECODE(NW, KT)                                                                                  \

@@ -36,7 +36,7 @@ struct SeqArgs {
 struct WsLayout {
     size_t seq_tab, elite_cnt, elite_idx, row_mtext, row_ztext, row_M, row_w, part, scores;
     size_t unit_st, unit_sk, s_t, s_k, budgets, base_len, layer_off, dec_cnt, moments, indices;
-    size_t kcache, vcache, dec_o, dec_ml, stash, row_f, unit_R, len_off;
+    size_t kcache, vcache, dec_o, dec_ml, stash, row_f, unit_R, len_off, dec_steps;
     size_t total;
     int32_t n_chunks;     // ceil(max_vis_len / kChunkKeys)
     int64_t pool_rows;    // rows of one (sequence, KV head) cache pool
@@ -63,6 +63,7 @@ struct DevTables {
     int2 *len_off;    // (base_len, layer_off) of a (sequence, layer) side by side: one read for the decode kernel
     int32_t *unit_R;  // window rows of a unit (all heads of the group), left by the row-parameter kernel
     float2 *dec_ml;
+    int32_t *dec_steps;  // tokens appended so far per unit when the device counts them (else null); one overflow flag after the last unit
 };
 
 WsLayout make_layout(const air_config &cfg);

@@ -255,6 +255,10 @@ __global__ __launch_bounds__(256) void gather_vt_kernel(Dims dm, DevTables t, in
     const int64_t dst_row0 = ((int64_t)b * dm.Hkv + kvh) * dm.pool_rows + t.layer_off[(int64_t)b * dm.L + l];
     T *kdst = (T *)t.kcache + dst_row0 * D;
     T *vdst = (T *)t.vcache + dst_row0 * D;
+    if (t.dec_steps && blockIdx.x == 0 && threadIdx.x == 0) {  // a fresh cache: nothing appended yet, cache-full flag down
+        t.dec_steps[unit] = 0;
+        if (blockIdx.y == 0) t.dec_steps[(int64_t)dm.L * dm.B * dm.Hkv] = 0;
+    }
     __shared__ bf16_t tile[32][D + 8];   // V rows, indexed [slot][column]; +8 keeps the 16-byte row alignment and spreads banks
     __shared__ bf16_t ktile[32][D + 8];  // K rows, indexed [row][column]
     for (int r0 = blockIdx.x * 32; r0 < n_rows; r0 += gridDim.x * 32) {
