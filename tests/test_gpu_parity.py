@@ -412,6 +412,15 @@ def test_maximum_candidate_span():
     _run_case(w, 0.10, steps=1)
 
 
+def test_visual_span_beyond_one_selection_sweep():
+    # 40000 visual tokens (a long video): the selection kernel walks the row in three sweeps of 16384
+    # scores instead of keeping it in registers, and a window row has 157 chunk partials (more than one
+    # per lane of the wave that combines them)
+    w = synth.get_workload(2).scaled(n_layers=2, n_vis=40000, n_text=32, decode_steps=2)
+    units = [(0, 0, 0), (1, 0, w.n_kv_heads - 1)]
+    _run_case(w, 0.05, steps=2, check_decode_units=units)
+
+
 def test_maximum_batch():
     # 64 ragged sequences, the largest batch the boundary accepts (the sequence table travels as a kernel argument)
     w = synth.get_workload(3).scaled(batch=64, n_layers=2, n_vis=260, n_text=20, decode_steps=2)
