@@ -304,6 +304,21 @@ def test_one_token_at_a_time_harness_and_fixed_indices():
     ac.close()
 
 
+def test_generic_path_other_storage_combinations():
+    # the fp32-ALU kernels serve every storage type / head_dim pair that the MFMA kernels do not:
+    # fp32 with head_dim 128, bf16 with head_dim 64 (G = 7, several key chunks, decode across a split)
+    _run_case(synth.get_workload(1).scaled(head_dim=128), 0.10, alpha=0.9, steps=2)
+    w = synth.get_workload(2).scaled(n_layers=2, n_vis=700, n_text=40, head_dim=64, decode_steps=3)
+    _run_case(w, 0.10, steps=3)
+
+
+def test_all_text_window_with_more_rows_than_one_staging_round():
+    # 7 heads x 160 text tokens = 1120 window rows per unit: the finish kernel stages its row parameters
+    # in rounds of 1024, and the elite-text block of Eq.7 is 160 x 160 per head
+    w = synth.get_workload(2).scaled(n_layers=1, n_vis=600, n_text=160, decode_steps=1)
+    _run_case(w, 0.10, alpha=0.0, steps=1)
+
+
 def test_degenerate_sizes():
     # fewer than three visual tokens (skewness 0), one text token, one-token window, min_keep 0
     w = synth.get_workload(1).scaled(n_vis=2, n_text=1, window=1, n_sys=1)
