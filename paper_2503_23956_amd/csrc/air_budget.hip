@@ -6,7 +6,8 @@
 // layer shares by left-to-right sums, proportional allocation clamped to [min_keep, N_v] by
 // repeatedly pinning the side with the larger total violation, floor + largest remainder
 // (ties to the lower layer).  Independent per-layer work is spread over the threads; the
-// order-dependent sums stay serial in thread 0.
+// order-dependent sums stay serial in thread 0.  Threads exchange data through LDS only, so the
+// barriers order LDS traffic and do not wait for the global stores of the statistics and budgets.
 #include "air_device.h"
 #include "air_internal.h"
 
@@ -70,7 +71,8 @@ __global__ __launch_bounds__(kBT) void budget_kernel(Dims dm, DevTables t, doubl
                     u_sk[p] = sk;
                 }
             }
-            __syncthreads();
+            if (stage) lds_barrier();  // the statistics cross in LDS: no wait for the global stores above
+            else __syncthreads();
         }
         if (tid < L) {  // mean over the KV heads, left to right
             double a = 0.0, c = 0.0;
@@ -85,7 +87,7 @@ __global__ __launch_bounds__(kBT) void budget_kernel(Dims dm, DevTables t, doubl
             s_t[tid] = sh_t[tid];
             s_k[tid] = sh_k[tid];
         }
-        __syncthreads();
+        lds_barrier();
         const int lo_i = min(min_keep, n_vis);
         const double lo = (double)lo_i, hi = (double)n_vis;
         if (tid == 0) {
@@ -103,7 +105,7 @@ __global__ __launch_bounds__(kBT) void budget_kernel(Dims dm, DevTables t, doubl
             s_elig = 0;
             s_npin = 0;
         }
-        __syncthreads();
+        lds_barrier();
         if (tid < L) {
             const double a = s_sum_t > 0.0 ? sh_t[tid] / s_sum_t : 1.0 / (double)L;
             const double c = s_sum_k > 0.0 ? fmax(sh_k[tid], 0.0) / s_sum_k : 1.0 / (double)L;
@@ -116,13 +118,13 @@ __global__ __launch_bounds__(kBT) void budget_kernel(Dims dm, DevTables t, doubl
             x[tid] = 0.0;
             is_free[tid] = 1;
         }
-        __syncthreads();
+        lds_barrier();
         // proportional allocation with clamping.  Per round: thread 0 sums the free weights in layer
         // order, every layer forms its own x_l (the divisions run in parallel), thread 0 sums the
         // violations in layer order and picks the side to pin.
         if (tid == 0) s_kfree = (double)s_ktot;
         for (int it = 0; it < L + 1; ++it) {
-            __syncthreads();
+            lds_barrier();
             if (tid == 0) {
                 double w_free = 0.0;
                 int n_free = 0;
@@ -135,7 +137,7 @@ __global__ __launch_bounds__(kBT) void budget_kernel(Dims dm, DevTables t, doubl
                 s_wfree = w_free;
                 s_nfree = n_free;
             }
-            __syncthreads();
+            lds_barrier();
             if (s_nfree == 0) break;
             if (tid < L) {
                 double vo = 0.0, vu = 0.0;
@@ -148,7 +150,7 @@ __global__ __launch_bounds__(kBT) void budget_kernel(Dims dm, DevTables t, doubl
                 v_over[tid] = vo;
                 v_under[tid] = vu;
             }
-            __syncthreads();
+            lds_barrier();
             if (tid == 0) {
                 double over = 0.0, under = 0.0;
 #pragma unroll 4
@@ -158,7 +160,7 @@ __global__ __launch_bounds__(kBT) void budget_kernel(Dims dm, DevTables t, doubl
                 }
                 s_pin = (over == 0.0 && under == 0.0) ? 0 : (over >= under ? 1 : 2);
             }
-            __syncthreads();
+            lds_barrier();
             const int pin = s_pin;
             if (pin == 0) break;
             int pinned = 0;
@@ -176,14 +178,14 @@ __global__ __launch_bounds__(kBT) void budget_kernel(Dims dm, DevTables t, doubl
             // k_free stays an integer-valued double: subtracting the bound once per pinned layer is exact in any order
             const unsigned long long any = __ballot(pinned);
             if (any && (tid & 63) == 0) atomicAdd(&s_npin, __popcll(any));
-            __syncthreads();
+            lds_barrier();
             if (tid == 0) {
                 const double bound = pin == 1 ? hi : lo;
                 for (int q = 0; q < s_npin; ++q) s_kfree -= bound;
                 s_npin = 0;
             }
         }
-        __syncthreads();
+        lds_barrier();
         if (tid < L) {
             int fl = (int)floor(x[tid]);
             fl = max(lo_i, min(fl, n_vis));
@@ -192,7 +194,7 @@ __global__ __launch_bounds__(kBT) void budget_kernel(Dims dm, DevTables t, doubl
             atomicAdd(&s_tot, fl);
             if (fl < n_vis) atomicAdd(&s_elig, 1);
         }
-        __syncthreads();
+        lds_barrier();
         const long long left = s_ktot - (long long)s_tot;
         if (left > 0 && left <= (long long)s_elig) {
             // largest remainder: the `left` eligible layers that come first by (fraction descending, layer ascending)
@@ -204,7 +206,7 @@ __global__ __launch_bounds__(kBT) void budget_kernel(Dims dm, DevTables t, doubl
                     if (kk[j] < n_vis && (frac[j] > frac[tid] || (frac[j] == frac[tid] && j < tid))) ++rank;
                 add = rank < (int)left ? 1 : 0;
             }
-            __syncthreads();
+            lds_barrier();
             if (tid < L) kk[tid] += add;
         } else if (left > 0) {
             if (tid == 0) {  // more leftovers than eligible layers: hand them out one by one
@@ -220,15 +222,15 @@ __global__ __launch_bounds__(kBT) void budget_kernel(Dims dm, DevTables t, doubl
                 }
             }
         }
-        __syncthreads();
+        lds_barrier();
         if (tid < L) budgets[tid] = kk[tid];
-        __syncthreads();
+        lds_barrier();
     }
 
     // cache layout: each layer's region holds system + kept + text rows and room for the
     // decode appends, and starts on a multiple of kCacheRowAlign rows
     if (skip_allocation && tid < L) kk[tid] = budgets[tid];  // otherwise kk still holds what was just written
-    __syncthreads();
+    lds_barrier();
     const int nonvis = sq.seq_len - sq.vis_len;
     if (tid < L) {
         int off = 0;
