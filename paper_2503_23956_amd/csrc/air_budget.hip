@@ -128,12 +128,11 @@ __global__ __launch_bounds__(kBT) void budget_kernel(Dims dm, DevTables t, doubl
             if (tid == 0) {
                 double w_free = 0.0;
                 int n_free = 0;
-#pragma unroll 4
-                for (int l = 0; l < L; ++l)
-                    if (is_free[l]) {
-                        w_free += w[l];
-                        ++n_free;
-                    }
+#pragma unroll 8
+                for (int l = 0; l < L; ++l) {  // branch-free: a pinned layer adds an exact zero
+                    w_free += is_free[l] ? w[l] : 0.0;
+                    n_free += is_free[l];
+                }
                 s_wfree = w_free;
                 s_nfree = n_free;
             }
@@ -201,9 +200,12 @@ __global__ __launch_bounds__(kBT) void budget_kernel(Dims dm, DevTables t, doubl
             int add = 0;
             if (tid < L && kk[tid] < n_vis) {
                 int rank = 0;
-#pragma unroll 4
-                for (int j = 0; j < L; ++j)
-                    if (kk[j] < n_vis && (frac[j] > frac[tid] || (frac[j] == frac[tid] && j < tid))) ++rank;
+                const double mine = frac[tid];
+#pragma unroll 8
+                for (int j = 0; j < L; ++j) {  // branch-free, so that the LDS reads of several layers are in flight together
+                    const double fj = frac[j];
+                    rank += (int)(kk[j] < n_vis) & ((int)(fj > mine) | ((int)(fj == mine) & (int)(j < tid)));
+                }
                 add = rank < (int)left ? 1 : 0;
             }
             lds_barrier();
@@ -234,6 +236,7 @@ __global__ __launch_bounds__(kBT) void budget_kernel(Dims dm, DevTables t, doubl
     const int nonvis = sq.seq_len - sq.vis_len;
     if (tid < L) {
         int off = 0;
+#pragma unroll 8
         for (int l = 0; l < tid; ++l) {
             const int cap = nonvis + kk[l] + dm.max_steps;
             off += (cap + kCacheRowAlign - 1) / kCacheRowAlign * kCacheRowAlign;
