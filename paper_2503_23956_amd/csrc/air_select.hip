@@ -50,7 +50,7 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(Dims dm, DevTables 
     }
 
     __shared__ uint32_t hist[kSelThreads / 64][256];  // one histogram per wave: scores share leading bits, so few bins are hot
-    __shared__ uint32_t s_prefix, s_kk, s_m;
+    __shared__ uint32_t s_prefix, s_kk, s_m, s_ncand, s_tau, s_ktau;
     __shared__ uint32_t h12[2048], cand[kSelCand];
     __shared__ int s_scan[kSelThreads / 64 + 1];
 
@@ -71,6 +71,7 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(Dims dm, DevTables 
     bool found = false;
     if (cached) {
         for (int i = tid; i < 2048; i += kSelThreads) h12[i] = 0;
+        if (tid == 0) s_ncand = 0;
         __syncthreads();
 #pragma unroll
         for (int j = 0; j < kSelRegs; ++j)
@@ -97,15 +98,11 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(Dims dm, DevTables 
         }
         __syncthreads();
         const uint32_t bin = s_prefix, kk2 = s_kk, m = s_m;
-        __syncthreads();  // s_prefix / s_kk are written again below
         if ((int)m <= cand_cap) {  // uniform over the workgroup
-            int cnt = 0;
-#pragma unroll
-            for (int j = 0; j < kSelRegs; ++j) cnt += (live(0, j) && digit12(v[j]) == bin) ? 1 : 0;
-            int pos = block_excl_scan<kSelThreads / 64>(cnt, s_scan, &total);
+            // the bin's scores are collected in any order (their ranks do not depend on it)
 #pragma unroll
             for (int j = 0; j < kSelRegs; ++j)
-                if (live(0, j) && digit12(v[j]) == bin) cand[pos++] = v[j];
+                if (live(0, j) && digit12(v[j]) == bin) cand[atomicAdd(&s_ncand, 1u)] = v[j];
             __syncthreads();
             // candidate i is the k-th largest iff (#greater) < kk2 <= (#greater) + (#equal)
             for (int i = tid; i < (int)m; i += kSelThreads) {
@@ -117,13 +114,13 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(Dims dm, DevTables 
                     eq += y == x ? 1u : 0u;
                 }
                 if (gt < kk2 && kk2 <= gt + eq) {  // every candidate with this value writes the same pair
-                    s_prefix = x;
-                    s_kk = kk2 - gt;
+                    s_tau = x;
+                    s_ktau = kk2 - gt;
                 }
             }
             __syncthreads();
-            prefix = s_prefix;
-            kk = s_kk;
+            prefix = s_tau;
+            kk = s_ktau;
             found = true;
         }
     }
