@@ -332,6 +332,23 @@ def test_budget_hand_worked_cases():
     assert O.layer_budgets([0.3, 0.3], [1.0, 4.0], 0.2, 100) == [14, 26]
 
 
+def test_budget_hand_worked_fixture():
+    # tests/golden/eq11_hand_worked.txt: allocations derived on paper from Eq.11 (the derivation is in the file)
+    import os
+
+    path = os.path.join(os.path.dirname(__file__), "golden", "eq11_hand_worked.txt")
+    n = 0
+    for line in open(path):
+        if not line.strip() or line.startswith("#"):
+            continue
+        s_t, s_k, r, n_vis, min_keep, want, _ = [f.strip() for f in line.split("|")]
+        got = O.layer_budgets([float(x) for x in s_t.split(",")], [float(x) for x in s_k.split(",")], float(r), int(n_vis),
+                              O.BUDGET_STRENGTH_SKEW, int(min_keep))
+        assert got == [int(x) for x in want.split(",")], line
+        n += 1
+    assert n == 8
+
+
 def test_budget_modes():
     s_t, s_k = [0.1, 0.3], [3.0, 1.0]
     assert O.layer_budgets(s_t, s_k, 0.1, 100, O.BUDGET_UNIFORM) == [10, 10]
@@ -480,3 +497,30 @@ def test_compress_sequence_recovers_planted_salient_tokens():
         assert set(res.indices[1][h]).issubset(set(planted[1]))   # 60 planted, fewer kept
         assert len(res.indices[0][h]) == res.budgets[0]
         assert np.all(np.diff(res.indices[1][h]) > 0)
+
+
+def test_oracle_answer_for_the_tiny_workload_has_not_drifted():
+    # tests/golden/tiny_pipeline.txt is written by tests/golden/make_tiny_pipeline.py from the oracle alone;
+    # it guards the oracle against unintended changes (it is not a pin against the paper, which prints no example)
+    import importlib.util
+    import os
+
+    here = os.path.join(os.path.dirname(__file__), "golden")
+    spec = importlib.util.spec_from_file_location("make_tiny_pipeline", os.path.join(here, "make_tiny_pipeline.py"))
+    mod = importlib.util.module_from_spec(spec)
+    spec.loader.exec_module(mod)
+    stored = open(os.path.join(here, "tiny_pipeline.txt")).read().splitlines()
+    now = mod.tiny_pipeline_lines()
+    assert len(stored) == len(now)
+    for a, b in zip(stored, now):
+        ta, tb = a.split(), b.split()
+        assert len(ta) == len(tb), (a, b)
+        for x, y in zip(ta, tb):
+            if ":" in x and "e" in x:  # index:score pairs
+                assert x.split(":")[0] == y.split(":")[0], (a, b)
+                assert float(x.split(":")[1]) == pytest.approx(float(y.split(":")[1]), rel=1e-10), (a, b)
+            elif "e-" in x or "e+" in x:
+                assert float(x) == pytest.approx(float(y), rel=1e-10), (a, b)
+            else:
+                assert x == y, (a, b)
+
