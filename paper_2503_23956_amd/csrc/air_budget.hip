@@ -26,7 +26,7 @@ __global__ __launch_bounds__(kBT) void budget_kernel(Dims dm, DevTables t, doubl
     __shared__ int kk[kBT];
     __shared__ unsigned char is_free[kBT];
     __shared__ double s_sum_t, s_sum_k;
-    __shared__ long long s_ktot, s_left;
+    __shared__ long long s_ktot;
     __shared__ int s_tot, s_elig, s_nfree, s_pin, s_npin;
     __shared__ double s_wfree, s_kfree, v_over[kBT], v_under[kBT];
     __shared__ double u_st[AIR_MAX_LAYERS * 16], u_sk[AIR_MAX_LAYERS * 16];  // per (layer, KV head), H_kv <= 16 staged

@@ -439,7 +439,7 @@ __global__ __launch_bounds__(64 * NW) void decode_mfma_kernel(Dims dm, DecodeTab
         s_l[p / G][p % G] = __hip_atomic_load(ml + 2 * p + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
     __syncthreads();
-    if (threadIdx.x < G) {
+    if ((int)threadIdx.x < G) {
         const int g = threadIdx.x;
         float M = -INFINITY;
         for (int s2 = 0; s2 < splits; ++s2) M = fmaxf(M, s_m[s2][g]);

@@ -472,7 +472,6 @@ __device__ __forceinline__ double dot64_wave(const bf16_t *a, const bf16_t *b, i
 
 __global__ __launch_bounds__(64 * kEliteWaves) void elite_mfma_kernel(Dims dm, DevTables t, int l0, LaunchLayers ll, air_strides st,
                                                          SeqArgs seqs, double alpha, double ln_alpha, int gb) {
-    constexpr int D = 128;
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, n = lane & 15, c = lane >> 4;
     const int kvh = blockIdx.x, b = blockIdx.y, li = blockIdx.z;
     const int l = l0 + li;

@@ -20,7 +20,7 @@ constexpr int kSelCand = 1024;                       // scores of the deciding 1
 __device__ __forceinline__ uint32_t digit12(uint32_t v) { return min(v >> 20, 2047u); }
 
 __global__ __launch_bounds__(kSelThreads) void select_kernel(Dims dm, DevTables t, int l0, int cand_cap) {
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, wave = tid >> 6;
     const int64_t unit = (int64_t)l0 * dm.B * dm.Hkv + blockIdx.x;
     const int b = (blockIdx.x / dm.Hkv) % dm.B;
     const int l = l0 + blockIdx.x / (dm.Hkv * dm.B);
