@@ -21,7 +21,7 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0  # MI355X HBM3E, published
-METRIC = "compress us/layer + compacted decode attn tokens/s; achieved HBM GB/s vs peak"
+METRIC = "compress \u00b5s/layer + compacted decode attn tokens/s; achieved HBM GB/s vs peak"
 
 
 def _esize(w):

@@ -4,6 +4,7 @@ import sys
 from pathlib import Path
 
 import numpy as np
+import pytest
 
 ROOT = Path(__file__).resolve().parent.parent
 sys.path.insert(0, str(ROOT))
@@ -37,3 +38,14 @@ def test_algorithmic_bytes_match_the_per_unit_formulas():
     # the figures quoted for this workload: 49.9 -> 57.3 MB per decode step, ~316 MB per compression pass
     assert abs(ab["decode_first"] / 1e6 - 50.0) < 0.3 and abs(ab["decode_last"] / 1e6 - 57.3) < 0.3
     assert abs(ab["compress"] / 1e6 - 316) < 2
+
+
+def test_metric_string_is_the_one_the_baseline_file_names():
+    import json
+    import os
+
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    path = os.path.join(root, "BASELINE.json")
+    if not os.path.exists(path):
+        pytest.skip("no BASELINE.json beside the repository")
+    assert bench.METRIC == json.load(open(path))["metric"]
