@@ -11,27 +11,29 @@
 
 namespace air {
 
-constexpr int kSelThreads = 512;
+constexpr int kSelThreads = 512;                     // threads of the selection kernel for long rows (256 for rows up to 8192 scores)
 constexpr int kSelRegs = 32;                         // scores per thread kept in registers
-constexpr int kSelSpan = kSelThreads * kSelRegs;     // 16384 scores per sweep
 constexpr int kSelCand = 1024;                       // scores of the deciding 12-bit bin that are ranked directly
 
 // leading 12 bits of a score pattern; importance is non-negative, a set sign bit (never produced) falls into the top bin
 __device__ __forceinline__ uint32_t digit12(uint32_t v) { return min(v >> 20, 2047u); }
 
-__global__ __launch_bounds__(kSelThreads) void select_kernel(Dims dm, DevTables t, int l0, int cand_cap) {
+template <int NT>
+__global__ __launch_bounds__(NT) void select_kernel(Dims dm, DevTables t, int l0, int cand_cap) {
+    constexpr int kSpan = NT * kSelRegs;  // scores per sweep
+    constexpr int kBinsPer = 2048 / NT;   // bins of the 12-bit histogram per thread
     const int tid = threadIdx.x, wave = tid >> 6;
     const int64_t unit = (int64_t)l0 * dm.B * dm.Hkv + blockIdx.x;
     const int b = (blockIdx.x / dm.Hkv) % dm.B;
     const int l = l0 + blockIdx.x / (dm.Hkv * dm.B);
     const uint32_t *key = reinterpret_cast<const uint32_t *>(t.scores + unit * dm.max_vis);
-    // A sweep of up to kSelSpan scores stays in registers for all passes: thread t owns the `per`
+    // A sweep of up to kSpan scores stays in registers for all passes: thread t owns the `per`
     // consecutive scores from base + t * per on.  `per` follows the row capacity (a kernel argument),
     // not the sequence's own length, so that a short row's loads go out before anything has been
     // read (entries past the sequence's span exist and are never counted).  Rows longer than
-    // kSelSpan are re-read sweep by sweep.
-    const bool cached = dm.max_vis <= kSelSpan;
-    const int per = cached ? (dm.max_vis + kSelThreads - 1) / kSelThreads : kSelRegs;
+    // kSpan are re-read sweep by sweep.
+    const bool cached = dm.max_vis <= kSpan;
+    const int per = cached ? (dm.max_vis + NT - 1) / NT : kSelRegs;
     uint32_t v[kSelRegs];
     if (cached) {
 #pragma unroll
@@ -45,14 +47,14 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(Dims dm, DevTables 
     int32_t *out = t.indices + unit * dm.max_vis;
     if (k <= 0) return;
     if (k >= n) {
-        for (int i = tid; i < n; i += kSelThreads) out[i] = i;
+        for (int i = tid; i < n; i += NT) out[i] = i;
         return;
     }
 
-    __shared__ uint32_t hist[kSelThreads / 64][256];  // one histogram per wave: scores share leading bits, so few bins are hot
+    __shared__ uint32_t hist[NT / 64][256];  // one histogram per wave: scores share leading bits, so few bins are hot
     __shared__ uint32_t s_prefix, s_kk, s_m, s_ncand, s_tau, s_ktau;
     __shared__ uint32_t h12[2048], cand[kSelCand];
-    __shared__ int s_scan[kSelThreads / 64 + 1];
+    __shared__ int s_scan[NT / 64 + 1];
 
     auto load_sweep = [&](int base) {
 #pragma unroll
@@ -70,27 +72,27 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(Dims dm, DevTables 
     // and the four 8-bit passes below are skipped.
     bool found = false;
     if (cached) {
-        for (int i = tid; i < 2048; i += kSelThreads) h12[i] = 0;
+        for (int i = tid; i < 2048; i += NT) h12[i] = 0;
         if (tid == 0) s_ncand = 0;
         __syncthreads();
 #pragma unroll
         for (int j = 0; j < kSelRegs; ++j)
             if (live(0, j)) atomicAdd(&h12[digit12(v[j])], 1u);
         __syncthreads();
-        // thread t takes the four bins at positions 4t .. 4t+3 from the top
-        uint32_t hb[4];
+        // thread t takes the kBinsPer bins at positions kBinsPer t .. from the top
+        uint32_t hb[kBinsPer];
         int s4 = 0;
 #pragma unroll
-        for (int q = 0; q < 4; ++q) {
-            hb[q] = h12[2047 - (4 * tid + q)];
+        for (int q = 0; q < kBinsPer; ++q) {
+            hb[q] = h12[2047 - (kBinsPer * tid + q)];
             s4 += (int)hb[q];
         }
         int total;
-        int excl = block_excl_scan<kSelThreads / 64>(s4, s_scan, &total);
+        int excl = block_excl_scan<NT / 64>(s4, s_scan, &total);
 #pragma unroll
-        for (int q = 0; q < 4; ++q) {
+        for (int q = 0; q < kBinsPer; ++q) {
             if (hb[q] > 0 && (uint32_t)excl < kk && kk <= (uint32_t)excl + hb[q]) {
-                s_prefix = (uint32_t)(2047 - (4 * tid + q));
+                s_prefix = (uint32_t)(2047 - (kBinsPer * tid + q));
                 s_kk = kk - (uint32_t)excl;
                 s_m = hb[q];
             }
@@ -105,7 +107,7 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(Dims dm, DevTables 
                 if (live(0, j) && digit12(v[j]) == bin) cand[atomicAdd(&s_ncand, 1u)] = v[j];
             __syncthreads();
             // candidate i is the k-th largest iff (#greater) < kk2 <= (#greater) + (#equal)
-            for (int i = tid; i < (int)m; i += kSelThreads) {
+            for (int i = tid; i < (int)m; i += NT) {
                 const uint32_t x = cand[i];
                 uint32_t gt = 0, eq = 0;
                 for (int j = 0; j < (int)m; ++j) {
@@ -126,9 +128,9 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(Dims dm, DevTables 
     }
     for (int pass = 0; pass < 4 && !found; ++pass) {
         const int shift = 24 - 8 * pass;
-        for (int i = tid; i < (kSelThreads / 64) * 256; i += kSelThreads) (&hist[0][0])[i] = 0;
+        for (int i = tid; i < (NT / 64) * 256; i += NT) (&hist[0][0])[i] = 0;
         __syncthreads();
-        for (int base = 0; base < n; base += kSelSpan) {
+        for (int base = 0; base < n; base += kSpan) {
             if (!cached) load_sweep(base);
             // Scores share their leading bits, so in the first passes most of a thread's scores fall
             // into one bin and whole waves collide on it: each thread counts the scores that share
@@ -149,10 +151,10 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(Dims dm, DevTables 
         int h = 0;
         if (tid < 256) {
 #pragma unroll
-            for (int w = 0; w < kSelThreads / 64; ++w) h += (int)hist[w][255 - tid];
+            for (int w = 0; w < NT / 64; ++w) h += (int)hist[w][255 - tid];
         }
         int total;
-        const int excl = block_excl_scan<kSelThreads / 64>(h, s_scan, &total);
+        const int excl = block_excl_scan<NT / 64>(h, s_scan, &total);
         if (tid < 256 && h > 0 && (uint32_t)excl < kk && kk <= (uint32_t)(excl + h)) {
             s_prefix = prefix | ((uint32_t)(255 - tid) << shift);
             s_kk = kk - (uint32_t)excl;
@@ -166,7 +168,7 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(Dims dm, DevTables 
 
     // ordered compaction: count per thread, one scan per sweep, then each thread writes its slice in order
     int base_gt = 0, base_eq = 0;
-    for (int base = 0; base < n; base += kSelSpan) {
+    for (int base = 0; base < n; base += kSpan) {
         if (!cached) load_sweep(base);
         int c_gt = 0, c_eq = 0;
 #pragma unroll
@@ -177,7 +179,7 @@ __global__ __launch_bounds__(kSelThreads) void select_kernel(Dims dm, DevTables 
             }
         // both counts in one scan: a sweep has at most 2^14 scores, so each count fits 16 bits
         int tot;
-        const int before = block_excl_scan<kSelThreads / 64>(c_gt | (c_eq << 16), s_scan, &tot);
+        const int before = block_excl_scan<NT / 64>(c_gt | (c_eq << 16), s_scan, &tot);
         const int tot_gt = tot & 0xffff, tot_eq = tot >> 16;
         int gt_before = base_gt + (before & 0xffff);
         int eq_before = base_eq + (before >> 16);
@@ -298,7 +300,13 @@ hipError_t launch_select(hipStream_t s, const Dims &dm, const DevTables &t, int 
     // AIR_SELECT_CAND (tuning / test aid): largest deciding bin that is ranked directly, 0 = always take the radix passes
     int cap = kSelCand;
     if (const char *e = getenv("AIR_SELECT_CAND")) cap = atoi(e) < kSelCand ? (atoi(e) < 0 ? 0 : atoi(e)) : kSelCand;
-    hipLaunchKernelGGL(select_kernel, dim3(nl * dm.B * dm.Hkv), dim3(kSelThreads), 0, s, dm, t, l0, cap);
+    // Many short rows take workgroups of 256 threads (cheaper barriers and scans, more workgroups per CU:
+    // 1792 rows of ~2500 scores 23 us against 38 us); few long rows are faster with 512 (112 rows of 7290
+    // scores 13.7 us against 16.3 us).  AIR_SELECT_THREADS = 256 | 512 overrides (tuning aid).
+    int nt = (dm.max_vis <= 4096 && nl * dm.B * dm.Hkv >= 256) ? 256 : kSelThreads;
+    if (const char *e = getenv("AIR_SELECT_THREADS")) nt = atoi(e) == 256 ? 256 : (atoi(e) == 512 ? 512 : nt);
+    if (nt == 256) hipLaunchKernelGGL(select_kernel<256>, dim3(nl * dm.B * dm.Hkv), dim3(256), 0, s, dm, t, l0, cap);
+    else hipLaunchKernelGGL(select_kernel<kSelThreads>, dim3(nl * dm.B * dm.Hkv), dim3(kSelThreads), 0, s, dm, t, l0, cap);
     return hipGetLastError();
 }
 

@@ -420,6 +420,17 @@ def test_select_radix_fallback(monkeypatch, cap):
     _run_case(w, 0.10, steps=1)
 
 
+@pytest.mark.parametrize("threads,n_vis,cap", [(256, 1500, None), (256, 9000, None), (256, 5000, 0), (512, 1500, None)])
+def test_select_workgroup_sizes(monkeypatch, threads, n_vis, cap):
+    # both workgroup sizes of the selection kernel, whatever the launch would choose by itself: rows kept
+    # in registers (1500, 5000 scores), a row walked in sweeps (9000 scores with 256 threads), the radix passes
+    monkeypatch.setenv("AIR_SELECT_THREADS", str(threads))
+    if cap is not None:
+        monkeypatch.setenv("AIR_SELECT_CAND", str(cap))
+    w = synth.get_workload(2).scaled(n_layers=2, n_vis=n_vis, n_text=40, decode_steps=1)
+    _run_case(w, 0.10, steps=1)
+
+
 def test_maximum_candidate_span():
     # 4096 text tokens, the largest candidate span the boundary accepts: the elite kernel then keeps
     # the logits of one head at a time in LDS
