@@ -454,16 +454,23 @@ air_status air_decode_attn(air_ctx *ctx, void *stream, int32_t l0, int32_t l1, c
             return fail(ctx, AIR_ERR_STATE, "air_decode_attn: max_decode_steps exhausted");
     }
     hipStream_t s = (hipStream_t)stream;
-    for (int c0 = l0; c0 < l1; c0 += kMaxLayersPerLaunch) {
-        const int nl = (l1 - c0 < kMaxLayersPerLaunch) ? l1 - c0 : kMaxLayersPerLaunch;
+    // The MFMA kernel takes any number of layers per launch when they have all appended the same number of
+    // tokens (the usual case: the layers decode in step), as long as the grid fits; otherwise the per-layer
+    // counts travel with the launch, kMaxLayersPerLaunch layers at a time.
+    bool in_step = v_transposed(ctx->cfg.dtype, ctx->cfg.head_dim);
+    for (int l = l0 + 1; l < l1 && in_step; ++l) in_step = ctx->appended[l] == ctx->appended[l0];
+    const int64_t units_per_layer = (int64_t)ctx->dm.B * ctx->dm.Hkv;
+    const int max_nl = in_step ? (int)(65535 / units_per_layer) : kMaxLayersPerLaunch;  // grid.y <= 65535
+    for (int c0 = l0; c0 < l1; c0 += max_nl) {
+        const int nl = (l1 - c0 < max_nl) ? l1 - c0 : max_nl;
         LaunchLayers ll;
         memset(&ll, 0, sizeof(ll));
-        for (int i = 0; i < nl; ++i) ll.appended[i] = ctx->appended[c0 + i];
+        for (int i = 0; i < nl && !in_step; ++i) ll.appended[i] = ctx->appended[c0 + i];
         int splits = 1, waves = 1, tiles = 4;
         // a recorded launch is replayed at every cache length: its shape is chosen for the middle of the decode
         decode_shape(ctx, nl, ctx->cfg.device_steps ? ctx->cfg.max_decode_steps / 2 : ctx->appended[c0], &splits, &waves, &tiles);
         hipError_t e = launch_decode(s, ctx->dm, ctx->tab, ctx->cfg.dtype, c0, nl, c0 - l0, ll, q_new, k_new, v_new,
-                                     out, splits, waves, tiles);
+                                     out, splits, waves, tiles, in_step ? ctx->appended[l0] : -1);
         if (e != hipSuccess) return hip_fail(ctx, e, "air_decode_attn launch");
     }
     for (int l = l0; l < l1; ++l) {

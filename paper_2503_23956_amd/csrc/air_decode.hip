@@ -83,6 +83,7 @@ struct DecodeTabs {
     int32_t n_units;     // units of the whole context: dec_steps[n_units] is the cache-full flag
 };
 struct DecodeSteps {
+    int32_t uniform;  // >= 0: every layer of the launch has appended this many tokens (any number of layers per launch)
     int32_t appended[kMaxLayersPerLaunch];
 };
 
@@ -120,7 +121,7 @@ __global__ __launch_bounds__(64 * NW) void decode_mfma_kernel(Dims dm, DecodeTab
     // tokens appended so far: from the host with the launch, or counted on the device (a recorded launch
     // that is replayed): the workgroup that finishes the unit advances the count, after every workgroup
     // of the unit has read it
-    int appended = ll.appended[li];
+    int appended = ll.uniform >= 0 ? ll.uniform : ll.appended[li];
     if (t.dec_steps) {
         appended = t.dec_steps[unit];
         if (appended >= dm.max_steps) {  // cache full: nothing is appended or written
@@ -652,7 +653,7 @@ static hipError_t decode_launch(hipStream_t s, const Dims &dm, const DevTables &
 // Generic path: append, split-K attention, combine (three launches).
 hipError_t launch_decode(hipStream_t s, const Dims &dm, const DevTables &t, int dtype, int l0, int nl, int lbase,
                          const LaunchLayers &ll, const void *q_new, const void *k_new, const void *v_new, void *out,
-                         int splits, int waves, int tiles) {
+                         int splits, int waves, int tiles, int uniform_appended) {
     if (v_transposed(dtype, dm.D)) {  // one launch: append, attention and merge of the partials
         const dim3 grid(splits, nl * dm.B * dm.Hkv);
         DecodeTabs dt;
@@ -665,6 +666,7 @@ hipError_t launch_decode(hipStream_t s, const Dims &dm, const DevTables &t, int 
         dt.dec_steps = t.dec_steps;
         dt.n_units = dm.L * dm.B * dm.Hkv;
         DecodeSteps ds;
+        ds.uniform = uniform_appended;
         for (int i = 0; i < kMaxLayersPerLaunch; ++i) ds.appended[i] = ll.appended[i];
 #define AIR_LAUNCH_DECODE(NW, KT)                                                                                  \
     do {                                                                                                           \

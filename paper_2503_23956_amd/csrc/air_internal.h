@@ -89,7 +89,7 @@ hipError_t launch_gather(hipStream_t s, const Dims &dm, const DevTables &t, int 
                          const LaunchLayers &ll, const air_strides &st);
 hipError_t launch_decode(hipStream_t s, const Dims &dm, const DevTables &t, int dtype, int l0, int nl, int lbase,
                          const LaunchLayers &ll, const void *q_new, const void *k_new, const void *v_new, void *out,
-                         int splits, int waves, int tiles);
+                         int splits, int waves, int tiles, int uniform_appended);
 
 // The bf16 / head_dim 128 cache is laid out so that the decode kernel can feed it to MFMA straight
 // from global memory, every load instruction of a wave reading 1 KB of consecutive memory, and so

@@ -138,3 +138,39 @@ def test_device_counted_steps_without_a_graph_and_config_limits():
     assert lib.air_workspace_bytes(C.byref(bad)) == 0
     eager.close()
     counted.close()
+
+
+def test_layers_out_of_step_in_one_call():
+    """A call whose layers have appended different numbers of tokens (layer 0 was decoded on once more than the
+    rest) carries the per-layer counts with the launch; it must give what layer-by-layer calls give."""
+    import torch
+
+    from paper_2503_23956_amd.device_inputs import to_device
+
+    dev = torch.device("cuda:0")
+    w = synth.get_workload(2).scaled(n_layers=3, n_vis=500, n_text=24, decode_steps=4)
+    A, one, ref, compress, seqs, layers = _contexts(w, 4, dev)  # `ref` counts on the device; used layer by layer here
+    L = w.n_layers
+    steps = []
+    for step in range(2):
+        qs, ks, vs = zip(*[synth.decode_inputs(w, l, step) for l in range(L)])
+        steps.append(tuple(to_device(np.stack(x), dev) for x in (qs, ks, vs)))
+    shape = (L, w.batch, w.n_q_heads, w.head_dim)
+    out_a = torch.zeros(shape, dtype=torch.bfloat16, device=dev)
+    out_b = torch.zeros(shape, dtype=torch.bfloat16, device=dev)
+    # layer 0 alone first, then all layers in one call: layer 0 gets its second token, the others their first
+    one.air_decode_attn(0, 1, steps[0][0][:1], steps[0][1][:1], steps[0][2][:1], out_a[:1])
+    mixed = tuple(torch.cat([steps[1][i][:1], steps[0][i][1:]]) for i in range(3))
+    one.air_decode_attn(0, L, *mixed, out_a)
+    # reference: the same tokens layer by layer
+    ref.air_decode_attn(0, 1, steps[0][0][:1], steps[0][1][:1], steps[0][2][:1], out_b[:1])
+    for l in range(L):
+        ref.air_decode_attn(l, l + 1, mixed[0][l:l + 1], mixed[1][l:l + 1], mixed[2][l:l + 1], out_b[l:l + 1])
+    torch.cuda.synchronize()
+    assert (out_a.float() - out_b.float()).abs().max().item() <= 1e-2
+    la, lb = one.air_get_lengths(), ref.air_get_lengths()
+    s0 = seqs[0]
+    appended = la[0] - (s0.seq_len - s0.vis_len) - one.air_get_budgets()[0]
+    assert np.array_equal(la, lb) and appended.tolist() == [2, 1, 1]
+    one.close()
+    ref.close()
