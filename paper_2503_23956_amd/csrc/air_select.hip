@@ -260,23 +260,40 @@ __global__ __launch_bounds__(256) void gather_vt_kernel(Dims dm, DevTables t, in
     }
     __shared__ bf16_t tile[32][D + 8];   // V rows, indexed [slot][column]; +8 keeps the 16-byte row alignment and spreads banks
     __shared__ bf16_t ktile[32][D + 8];  // K rows, indexed [row][column]
-    for (int r0 = blockIdx.x * 32; r0 < n_rows; r0 += gridDim.x * 32) {
-        for (int v = threadIdx.x; v < 32 * 16; v += 256) {
+    // Two 16-byte pieces of K and of V per thread and block of 32 rows.  The rows of the workgroup's next block are
+    // requested before the current block is written out, so that its index and row reads (two dependent
+    // round trips) run under the stores.
+    uint4 kx[2], vx[2];
+    auto fetch = [&](int r0) __attribute__((always_inline)) {
+#pragma unroll
+        for (int it = 0; it < 2; ++it) {
+            const int v = threadIdx.x + 256 * it;
             const int row = v >> 4, c = (v & 15) * 8;
             const int j = r0 + row;
-            uint4 vx = make_uint4(0, 0, 0, 0), kx = vx;
+            kx[it] = make_uint4(0, 0, 0, 0);
+            vx[it] = kx[it];
             if (j < n_rows) {
                 int tok;
                 if (j < sq.vis_start) tok = j;
                 else if (j < sq.vis_start + kl) tok = sq.vis_start + idx[j - sq.vis_start];
                 else tok = sq.vis_start + sq.vis_len + (j - sq.vis_start - kl);
-                kx = *reinterpret_cast<const uint4 *>(ksrc + (int64_t)tok * st.kv_t + c);
-                vx = *reinterpret_cast<const uint4 *>(vsrc + (int64_t)tok * st.kv_t + c);
+                kx[it] = *reinterpret_cast<const uint4 *>(ksrc + (int64_t)tok * st.kv_t + c);
+                vx[it] = *reinterpret_cast<const uint4 *>(vsrc + (int64_t)tok * st.kv_t + c);
             }
-            *reinterpret_cast<uint4 *>(&ktile[row][c]) = kx;
-            *reinterpret_cast<uint4 *>(&tile[v_slot(row)][c]) = vx;
         }
-        __syncthreads();
+    };
+    const int stride = gridDim.x * 32;
+    if ((int)blockIdx.x * 32 < n_rows) fetch(blockIdx.x * 32);
+    for (int r0 = blockIdx.x * 32; r0 < n_rows; r0 += stride) {
+#pragma unroll
+        for (int it = 0; it < 2; ++it) {
+            const int v = threadIdx.x + 256 * it;
+            const int row = v >> 4, c = (v & 15) * 8;
+            *reinterpret_cast<uint4 *>(&ktile[row][c]) = kx[it];
+            *reinterpret_cast<uint4 *>(&tile[v_slot(row)][c]) = vx[it];
+        }
+        if (r0 + stride < n_rows) fetch(r0 + stride);
+        lds_barrier();  // LDS traffic only: the requested rows of the next block stay in flight
         // K': the two 16-token tiles of the block in k_tiled order, 16 bytes per thread, consecutive in memory
         for (int v = threadIdx.x; v < 32 * 16; v += 256) {
             const int tl = v >> 8, sl = (v >> 6) & 3, n = (v >> 2) & 15, c = v & 3;
@@ -292,7 +309,7 @@ __global__ __launch_bounds__(256) void gather_vt_kernel(Dims dm, DevTables t, in
                 w[i] = (uint32_t)tile[8 * c + 2 * i][col] | ((uint32_t)tile[8 * c + 2 * i + 1][col] << 16);
             *reinterpret_cast<uint4 *>(vdst + (int64_t)r0 * D + (int64_t)v * 8) = make_uint4(w[0], w[1], w[2], w[3]);
         }
-        __syncthreads();
+        lds_barrier();  // LDS traffic only: the requested rows of the next block stay in flight
     }
 }
 
@@ -320,7 +337,13 @@ static hipError_t gather_launch(hipStream_t s, const Dims &dm, const DevTables &
 hipError_t launch_gather(hipStream_t s, const Dims &dm, const DevTables &t, int dtype, int l0, int nl,
                          const LaunchLayers &ll, const air_strides &st) {
     if (v_transposed(dtype, dm.D)) {
-        hipLaunchKernelGGL(gather_vt_kernel, dim3(32, nl * dm.B * dm.Hkv), dim3(256), 0, s, dm, t, l0, ll, st);
+        // workgroups per unit: about 4096 in the launch, so that with many units each workgroup walks several
+        // blocks of 32 rows (the next block's reads run under the current block's stores); AIR_GATHER_WGS overrides
+        const int units = nl * dm.B * dm.Hkv;
+        int gx = (4096 + units - 1) / units;
+        gx = gx < 2 ? 2 : (gx > 32 ? 32 : gx);
+        if (const char *e = getenv("AIR_GATHER_WGS")) gx = atoi(e) >= 1 && atoi(e) <= 64 ? atoi(e) : gx;
+        hipLaunchKernelGGL(gather_vt_kernel, dim3(gx, units), dim3(256), 0, s, dm, t, l0, ll, st);
         return hipGetLastError();
     }
     if (dtype == AIR_BF16)
