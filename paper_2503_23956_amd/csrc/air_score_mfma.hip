@@ -307,7 +307,7 @@ __global__ __launch_bounds__(64 * kRowWaves) void score_rows_mfma_kernel(Dims dm
 // One workgroup finishes kFinishChunks consecutive chunks of a unit and leaves one power-sum entry.
 
 template <bool VIS>
-__global__ __launch_bounds__(256) void score_finish_kernel(Dims dm, DevTables t, int l0, LaunchLayers ll,
+__global__ __launch_bounds__(256, 4) void score_finish_kernel(Dims dm, DevTables t, int l0, LaunchLayers ll,
                                                            air_strides st, SeqArgs seqs) {
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, n = lane & 15, c = lane >> 4;
     UnitCtx u;
@@ -351,21 +351,33 @@ __global__ __launch_bounds__(256) void score_finish_kernel(Dims dm, DevTables t,
         // One wave per chunk; a lane takes 16 bytes of every stashed row (four keys, 16 apart: see
         // stash_pos) and all rows are requested at once.  Rows past the list re-read its last row
         // against a zero factor, a wave past the last chunk re-reads the last chunk and stores nothing.
-        auto finish_all = [&](auto rb_tag) __attribute__((always_inline)) {
+        // rows r0 .. r0 + RB - 1 of the stash into the lane's four keys
+        const int ci = wave, chunk = first + ci;
+        const float *sb = t.stash + ((u.unit * dm.n_chunks + min(chunk, last - 1)) * (int64_t)kStashRows) * kChunkKeys + 4 * lane;
+        f32x4 imp = (f32x4){0.f, 0.f, 0.f, 0.f};
+        auto add_rows = [&](auto rb_tag, int r0) __attribute__((always_inline)) {
             constexpr int RB = decltype(rb_tag)::value;
-            const int ci = wave, chunk = first + ci;
-            const float *sb = t.stash + ((u.unit * dm.n_chunks + min(chunk, last - 1)) * (int64_t)kStashRows) * kChunkKeys + 4 * lane;
             f32x4 e[RB];
 #pragma unroll
             for (int r = 0; r < RB; ++r)
-                e[r] = *reinterpret_cast<const f32x4 *>(sb + (int64_t)min(r, max(u.R_total - 1, 0)) * kChunkKeys);
-            f32x4 imp = (f32x4){0.f, 0.f, 0.f, 0.f};
+                e[r] = *reinterpret_cast<const f32x4 *>(sb + (int64_t)min(r0 + r, max(u.R_total - 1, 0)) * kChunkKeys);
 #pragma unroll
             for (int r = 0; r < RB; ++r) {
-                const float f = s_f[ci][r];
+                const float f = s_f[ci][r0 + r];
 #pragma unroll
                 for (int i = 0; i < 4; ++i) imp[i] = fmaf(f, e[r][i], imp[i]);
             }
+        };
+        static_assert(kFinishChunks == 4, "one wave of the workgroup per chunk");
+        static_assert(kStashRows == 32, "rows beyond 16 are taken in a second round of 16");
+        if (u.R_total == 0) {  // no window row: the importance is zero (and so are its power sums)
+            for (int key = first * kChunkKeys + tid; key < min(last * kChunkKeys, u.sq.vis_len); key += 256)
+                t.scores[u.unit * dm.max_vis + key] = 0.f;
+        } else {
+            // 16 rows in flight at most: 32 at once would cost the kernel half of its occupancy
+            if (u.R_total <= 8) add_rows(std::integral_constant<int, 8>(), 0);
+            else add_rows(std::integral_constant<int, 16>(), 0);
+            if (u.R_total > 16) add_rows(std::integral_constant<int, 16>(), 16);
             if (chunk < last) {
 #pragma unroll
                 for (int i = 0; i < 4; ++i) {
@@ -379,14 +391,7 @@ __global__ __launch_bounds__(256) void score_finish_kernel(Dims dm, DevTables t,
                     }
                 }
             }
-        };
-        static_assert(kFinishChunks == 4, "one wave of the workgroup per chunk");
-        if (u.R_total == 0) {  // no window row: the importance is zero (and so are its power sums)
-            for (int key = first * kChunkKeys + tid; key < min(last * kChunkKeys, u.sq.vis_len); key += 256)
-                t.scores[u.unit * dm.max_vis + key] = 0.f;
-        } else if (u.R_total <= 8) finish_all(std::integral_constant<int, 8>());
-        else if (u.R_total <= 16) finish_all(std::integral_constant<int, 16>());
-        else finish_all(std::integral_constant<int, kStashRows>());
+        }
         put_moments();
         return;
     }
