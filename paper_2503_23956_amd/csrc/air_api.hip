@@ -18,6 +18,7 @@ static bool config_ok(const air_config &c) {
     if (c.batch < 1 || c.batch > AIR_MAX_BATCH) return false;
     if (c.n_kv_heads < 1 || c.n_q_heads < c.n_kv_heads || c.n_q_heads % c.n_kv_heads) return false;
     if (c.n_q_heads / c.n_kv_heads > 16) return false;
+    if ((int64_t)c.batch * c.n_kv_heads > 65535) return false;  // one layer's units must fit a grid dimension
     if (c.head_dim != 64 && c.head_dim != 128) return false;
     if (c.max_vis_len < 1 || c.max_nonvis_len < 1) return false;
     if (c.window_kind != AIR_WINDOW_TEXT && c.window_kind != AIR_WINDOW_VISUAL) return false;
@@ -242,6 +243,12 @@ air_status air_reset(air_ctx *ctx) {
 
 const char *air_last_error(const air_ctx *ctx) { return ctx ? ctx->err.c_str() : "null context"; }
 
+// layers per launch of the kernels that take per-layer tensor pointers: the units of a launch are one grid dimension (<= 65535)
+static int layers_per_launch(const air_ctx *c) {
+    const int64_t fit = 65535 / ((int64_t)c->dm.B * c->dm.Hkv);
+    return (int)(fit < kMaxLayersPerLaunch ? fit : kMaxLayersPerLaunch);
+}
+
 static bool range_ok(const air_ctx *c, int32_t l0, int32_t l1) { return l0 >= 0 && l1 > l0 && l1 <= c->cfg.n_layers; }
 
 static air_status check_strides(air_ctx *ctx, const air_strides *st, const air_layer *layers, int nl, bool need_q) {
@@ -297,7 +304,8 @@ air_status air_score(air_ctx *ctx, void *stream, int32_t l0, int32_t l1, const a
     memcpy(sa.s, seqs, sizeof(air_seq) * ctx->cfg.batch);
     const int dt = ctx->cfg.dtype;
     const bool mfma = v_transposed(dt, ctx->cfg.head_dim);  // bf16, head_dim 128
-    int group = kMaxLayersPerLaunch;
+    const int lpl = layers_per_launch(ctx);
+    int group = lpl;
     // Windows that are known to exceed the stash (alpha = 0 turns the whole candidate span into rows)
     // read K_v twice: run the two kernels over groups of layers whose keys fit the memory-side cache.
     if (mfma && ctx->cfg.alpha == 0.0 && (int64_t)ctx->dm.G * ctx->cfg.max_window > kStashRows) {
@@ -307,10 +315,10 @@ air_status air_score(air_ctx *ctx, void *stream, int32_t l0, int32_t l1, const a
         const int n_groups = (int)ceil(layer_bytes * (l1 - l0) / block);
         group = (l1 - l0 + (n_groups > 0 ? n_groups : 1) - 1) / (n_groups > 0 ? n_groups : 1);
         if (group < 1) group = 1;
-        if (group > kMaxLayersPerLaunch) group = kMaxLayersPerLaunch;
+        if (group > lpl) group = lpl;
     }
-    for (int c0 = l0; c0 < l1; c0 += kMaxLayersPerLaunch) {
-        const int nl = (l1 - c0 < kMaxLayersPerLaunch) ? l1 - c0 : kMaxLayersPerLaunch;
+    for (int c0 = l0; c0 < l1; c0 += lpl) {
+        const int nl = (l1 - c0 < lpl) ? l1 - c0 : lpl;
         LaunchLayers ll;
         memset(&ll, 0, sizeof(ll));
         for (int i = 0; i < nl; ++i) {
@@ -376,8 +384,9 @@ air_status air_select_compact(air_ctx *ctx, void *stream, int32_t l0, int32_t l1
     air_status st = check_strides(ctx, strides, layers, l1 - l0, false);
     if (st != AIR_OK) return st;
     hipStream_t s = (hipStream_t)stream;
-    for (int c0 = l0; c0 < l1; c0 += kMaxLayersPerLaunch) {
-        const int nl = (l1 - c0 < kMaxLayersPerLaunch) ? l1 - c0 : kMaxLayersPerLaunch;
+    const int lpl = layers_per_launch(ctx);
+    for (int c0 = l0; c0 < l1; c0 += lpl) {
+        const int nl = (l1 - c0 < lpl) ? l1 - c0 : lpl;
         LaunchLayers ll;
         memset(&ll, 0, sizeof(ll));
         for (int i = 0; i < nl; ++i) {
@@ -460,7 +469,7 @@ air_status air_decode_attn(air_ctx *ctx, void *stream, int32_t l0, int32_t l1, c
     bool in_step = v_transposed(ctx->cfg.dtype, ctx->cfg.head_dim);
     for (int l = l0 + 1; l < l1 && in_step; ++l) in_step = ctx->appended[l] == ctx->appended[l0];
     const int64_t units_per_layer = (int64_t)ctx->dm.B * ctx->dm.Hkv;
-    const int max_nl = in_step ? (int)(65535 / units_per_layer) : kMaxLayersPerLaunch;  // grid.y <= 65535
+    const int max_nl = in_step ? (int)(65535 / units_per_layer) : layers_per_launch(ctx);  // grid.y <= 65535
     for (int c0 = l0; c0 < l1; c0 += max_nl) {
         const int nl = (l1 - c0 < max_nl) ? l1 - c0 : max_nl;
         LaunchLayers ll;

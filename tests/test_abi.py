@@ -51,6 +51,8 @@ def test_invalid_configs_are_rejected_on_the_host():
         assert lib.air_workspace_bytes(C.byref(cfg)) == 0, bad
     for kw in (dict(alpha=1.5), dict(retention=0.0), dict(retention=1.2), dict(min_keep=-1), dict(budget_mode=9)):
         assert lib.air_workspace_bytes(C.byref(A.make_config(**good, **kw))) == 0, kw
+    # the units of one layer (batch x KV heads) must fit a grid dimension
+    assert lib.air_workspace_bytes(C.byref(A.make_config(**{**good, "batch": 64, "n_q_heads": 1024, "n_kv_heads": 1024}))) == 0
     # visual observation window: no Eq.5, so alpha must be 0; the span may then be as long as the visual span
     assert lib.air_workspace_bytes(C.byref(A.make_config(**good, window_kind=A.AIR_WINDOW_VISUAL))) == 0  # alpha 0.9
     assert lib.air_workspace_bytes(C.byref(A.make_config(**good, window_kind=A.AIR_WINDOW_VISUAL, alpha=0.0))) > 0

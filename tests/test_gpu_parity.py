@@ -453,6 +453,15 @@ def test_maximum_batch():
     _run_case(w, 0.10, steps=2)
 
 
+def test_more_units_per_layer_than_a_launch_of_32_layers_can_hold():
+    # 64 sequences x 40 KV heads = 2560 units per layer: a grid dimension holds 25 layers of them, so the 27
+    # layers go out in two launches per kernel (one query head per KV head on the way)
+    w = synth.get_workload(3).scaled(batch=64, n_layers=27, n_q_heads=40, n_kv_heads=40, n_vis=40, n_text=4,
+                                     decode_steps=1)
+    units = [(0, 0, 0), (26, 63, 39), (25, 31, 7)]
+    _run_case(w, 0.25, steps=1, check_decode_units=units, verbose=True)
+
+
 def test_config2_full_size():
     _run_case(synth.get_workload(2), 0.10, steps=2)
 
