@@ -24,6 +24,9 @@
  *     launched, so an error return implies that no device memory was written.
  *     air_last_error() gives a text for the last failure on that context.
  *   - Same inputs give bitwise the same outputs (no floating-point atomics anywhere).
+ *   - A context is not thread-safe: the caller serialises the calls on one context.  Contexts are
+ *     independent of each other.  Calls that overlap on the device (different streams) must not
+ *     touch the same layers of one context.
  *   - Token layout of a prompt: [system | visual | text] (Eq.3; the system prompt is never
  *     scored and always kept).  Query head h reads KV head h / (n_q_heads / n_kv_heads).
  *   - head_dim is 64 or 128; the innermost (head_dim) axis of every tensor is contiguous.
