@@ -430,7 +430,11 @@ static void decode_shape(const air_ctx *ctx, int n_layers_in_launch, int appende
     }
     avg_len /= c.batch;
     const int64_t units = (int64_t)n_layers_in_launch * c.batch * c.n_kv_heads;
-    int kt = 4;
+    // A launch of a handful of units (one layer of one sequence) is bound by what one CU can stream
+    // (about 100 GB/s): the unit is cut into splits of about one 32-key chunk per wave, which beats the
+    // exchange of the partials (4 units of ~900 keys: 8.4 us against 9.9 us as single workgroups).
+    const bool tiny_launch = units <= 16;
+    int kt = tiny_launch ? 2 : 4;
     if (ctx->force_tiles > 0) kt = ctx->force_tiles;
     const int64_t iters = (int64_t)((avg_len + 16.0 * kt - 1.0) / (16.0 * kt));
     // Waves per workgroup: enough for the launch to hold about 1536 waves, and beyond that one wave per 8
@@ -442,7 +446,11 @@ static void decode_shape(const air_ctx *ctx, int n_layers_in_launch, int appende
     if (ctx->force_waves > 0) w = ctx->force_waves;
     if (kt == 8 && w == 8) w = 4;
     int64_t s = 1;
-    while (s < kMaxSplits && iters > (int64_t)kItersPerWave * w * s && units * s < kEnoughWorkgroups) s *= 2;
+    if (tiny_launch) {
+        while (s < kMaxSplits && iters > 4 * s && units * s * 2 <= kEnoughWorkgroups) s *= 2;
+    } else {
+        while (s < kMaxSplits && iters > (int64_t)kItersPerWave * w * s && units * s < kEnoughWorkgroups) s *= 2;
+    }
     if (ctx->force_splits > 0) s = ctx->force_splits;
     *splits = (int)s;
     *waves = w;
