@@ -506,7 +506,10 @@ static air_status device_steps(air_ctx *ctx, std::vector<int32_t> &steps) {
     std::vector<int32_t> raw((size_t)L * B * Hkv + 1);
     air_status st = d2h(ctx, raw.data(), ctx->tab.dec_steps, raw.size() * 4);
     if (st != AIR_OK) return st;
-    if (raw.back() != 0) return fail(ctx, AIR_ERR_STATE, "a decode step ran with the cache full (max_decode_steps exhausted)");
+    bool any_compacted = false;  // until a layer is compacted again the flag is the previous prompt's
+    for (int l = 0; l < L; ++l) any_compacted = any_compacted || ctx->compacted[l];
+    if (any_compacted && raw.back() != 0)
+        return fail(ctx, AIR_ERR_STATE, "a decode step ran with the cache full (max_decode_steps exhausted)");
     steps.assign((size_t)B * L, 0);
     for (int l = 0; l < L; ++l)
         for (int b = 0; b < B; ++b) steps[(size_t)b * L + l] = raw[((size_t)l * B + b) * Hkv];  // the same for every KV head
@@ -639,7 +642,8 @@ air_status air_get_lengths(air_ctx *ctx, int32_t *host) {
     }
     for (int b = 0; b < ctx->dm.B; ++b)
         for (int l = 0; l < L; ++l)
-            host[(size_t)b * L + l] += ctx->cfg.device_steps ? steps[(size_t)b * L + l] : ctx->appended[l];
+            // a layer that is not compacted yet has appended nothing (its device count is from the prompt before)
+            host[(size_t)b * L + l] += !ctx->cfg.device_steps ? ctx->appended[l] : (ctx->compacted[l] ? steps[(size_t)b * L + l] : 0);
     return AIR_OK;
 }
 

@@ -23,11 +23,12 @@ def _contexts(w, steps, dev):
     eager = A.AirCache(config_for(w, 0.10, max_decode_steps=steps, seqs=seqs), dev)
     counted = A.AirCache(config_for(w, 0.10, max_decode_steps=steps, seqs=seqs, device_steps=1), dev)
 
-    def compress(ac):
+    def compress(ac, compact=True):
         ac.air_reset()
         ac.air_score(0, L, q, k, v, seqs)
         ac.air_budget()
-        ac.air_select_compact(0, L, k, v)
+        if compact:
+            ac.air_select_compact(0, L, k, v)
 
     compress(eager)
     compress(counted)
@@ -96,6 +97,10 @@ def test_replayed_decode_step_matches_eager_calls(monkeypatch, shape):
         counted.air_get_lengths()
     assert e.value.status == A.binding.AIR_ERR_STATE
 
+    # a new prompt: before its compaction the lengths are the bare ones (the old counts and the flag are not its own)
+    compress(eager, compact=False)
+    compress(counted, compact=False)
+    assert np.array_equal(counted.air_get_lengths(), eager.air_get_lengths())
     # compacting again starts the count at zero and lowers the flag; the same recorded step serves the new cache
     compress(eager)
     compress(counted)
