@@ -329,7 +329,7 @@ def main():
     # measured HBM traffic of the dominant kernel (rocprofv3 byte counters, committed summary), when one
     # exists for this workload and launch shape
     try:
-        with open(os.path.join(ROOT, "profiles", "hbm_traffic.json")) as f:
+        with open(os.path.join(ROOT, "profiles", "hbm_traffic_config2.txt")) as f:
             tr = json.load(f).get(result["config"]["workload"], {}).get("air_decode_attn")
         if tr and not args.per_layer:
             result["roofline"]["traffic"] = tr["fetch_bytes"] + tr["write_bytes"]
