@@ -81,11 +81,8 @@ def cpu_baseline(w, seqs, retention, host_layers, dec_inputs, decode_steps):
                               for h in range(w.n_kv_heads)])
         caches.append(per_layer)
     t_compress = time.perf_counter() - t0
-    n_sample = min(decode_steps, 8)
-    sample = sorted(set(int(round(i * (decode_steps - 1) / max(n_sample - 1, 1))) for i in range(n_sample)))
-    t_dec = 0.0
-    G = w.group
-    for step in sample:
+
+    def one_decode_step(step):
         qn, kn, vn = dec_inputs[step]
         q, k, v = synth.storage_to_f64(qn), synth.storage_to_f64(kn), synth.storage_to_f64(vn)
         t1 = time.perf_counter()
@@ -94,11 +91,19 @@ def cpu_baseline(w, seqs, retention, host_layers, dec_inputs, decode_steps):
                 kcs, vcs = [], []
                 for h in range(w.n_kv_heads):
                     kc, vc = caches[b][l][h]
-                    # cache length of this step: the sample skips steps, so pad with the new token repeated
+                    # cache length of this step: pad with the new token repeated
                     kcs.append(np.concatenate([kc, np.repeat(k[l, b, h][None], step + 1, axis=0)]))
                     vcs.append(np.concatenate([vc, np.repeat(v[l, b, h][None], step + 1, axis=0)]))
                 O.decode_layer(q[l, b], kcs, vcs)
-        t_dec += time.perf_counter() - t1
+        return time.perf_counter() - t1
+
+    # every decode step when that stays within about 20 s of host time, else 8 steps spread over the run
+    probe = one_decode_step(decode_steps // 2)
+    n_sample = decode_steps if probe * decode_steps <= 20.0 else min(decode_steps, 8)
+    sample = sorted(set(int(round(i * (decode_steps - 1) / max(n_sample - 1, 1))) for i in range(n_sample)))
+    t_dec = 0.0
+    for step in sample:
+        t_dec += one_decode_step(step)
     t_step = t_dec / len(sample)
     total = t_compress + t_step * decode_steps
     # the same compression pass on ONE host thread (BLAS limited to one thread), for the per-core figure
