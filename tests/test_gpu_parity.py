@@ -462,6 +462,23 @@ def test_more_units_per_layer_than_a_launch_of_32_layers_can_hold():
     _run_case(w, 0.25, steps=1, check_decode_units=units, verbose=True)
 
 
+def test_seeded_random_shapes():
+    # a seeded sweep over other input seeds, sizes, batches, retentions and thresholds than the named cases use
+    import dataclasses
+
+    rng = np.random.default_rng(12345)
+    for it in range(16):
+        n_vis, n_text, L = int(rng.integers(200, 5000)), int(rng.integers(4, 200)), int(rng.integers(1, 5))
+        ret = float(rng.choice([0.01, 0.05, 0.1, 0.25, 0.5, 1.0]))
+        alpha = float(rng.choice([0.9, 0.9, 0.5, 0.99, 0.0]))
+        base = int(rng.choice([2, 3]))
+        B = 1 if base == 2 else int(rng.integers(1, 5))
+        w = synth.get_workload(base).scaled(cfg_id=100 + it, batch=B, n_layers=L, n_vis=n_vis, n_text=n_text, decode_steps=3)
+        if alpha == 0.0 and n_text > 64:
+            w = dataclasses.replace(w, window=32)
+        _run_case(w, ret, alpha=alpha, steps=3, verbose=False)
+
+
 def test_config2_full_size():
     _run_case(synth.get_workload(2), 0.10, steps=2)
 
