@@ -53,41 +53,6 @@ __device__ __forceinline__ void load_row(const bf16_t *p, float (&r)[D]) {
     }
 }
 
-__device__ __forceinline__ float wave_max(float v) {
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 64));
-    return v;
-}
-__device__ __forceinline__ float wave_sum(float v) {
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
-    return v;
-}
-__device__ __forceinline__ double wave_sum(double v) {
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
-    return v;
-}
-__device__ __forceinline__ double wave_max(double v) {
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) v = fmax(v, __shfl_xor(v, o, 64));
-    return v;
-}
-
-// Sum over a workgroup of NW waves in a fixed order; every thread gets the result.
-// `scratch` holds NW doubles; the call contains two barriers.
-template <int NW>
-__device__ __forceinline__ double block_sum(double v, double *scratch) {
-    v = wave_sum(v);
-    __syncthreads();
-    if ((threadIdx.x & 63) == 0) scratch[threadIdx.x >> 6] = v;
-    __syncthreads();
-    double r = 0.0;
-#pragma unroll
-    for (int w = 0; w < NW; ++w) r += scratch[w];
-    return r;
-}
-
 // All-reduce over each group of 16 consecutive lanes with DPP modifiers (no LDS traffic):
 // quad_perm [1,0,3,2], quad_perm [2,3,0,1], row_half_mirror, row_mirror.
 #define AIR_DPP_STEP(OP, v, ctrl) OP((v), __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, (v)), (ctrl), 0xf, 0xf, false)))
@@ -105,6 +70,60 @@ __device__ __forceinline__ float sum16(float v) {
     v = AIR_DPP_STEP(add_f, v, 0x141);
     v = AIR_DPP_STEP(add_f, v, 0x140);
     return v;
+}
+
+// The same for doubles: the DPP move is applied to the two halves.
+#define AIR_DPP_STEP64(OP, v, ctrl)                                                                             \
+    {                                                                                                           \
+        const unsigned long long u_ = __builtin_bit_cast(unsigned long long, (v));                              \
+        const int lo_ = __builtin_amdgcn_update_dpp(0, (int)(unsigned)u_, (ctrl), 0xf, 0xf, false);              \
+        const int hi_ = __builtin_amdgcn_update_dpp(0, (int)(unsigned)(u_ >> 32), (ctrl), 0xf, 0xf, false);      \
+        (v) = OP((v), __builtin_bit_cast(double, ((unsigned long long)(unsigned)hi_ << 32) | (unsigned)lo_));    \
+    }
+__device__ __forceinline__ double add_d(double a, double b) { return a + b; }
+__device__ __forceinline__ double max_d(double a, double b) { return fmax(a, b); }
+
+// All-reduce over the 64 lanes of a wave: four DPP steps inside each row of 16 lanes, then the two
+// cross-row steps through the permute unit (a third of the latency of six permutes).
+__device__ __forceinline__ float wave_max(float v) {
+    v = max16(v);
+    v = fmaxf(v, __shfl_xor(v, 16, 64));
+    return fmaxf(v, __shfl_xor(v, 32, 64));
+}
+__device__ __forceinline__ float wave_sum(float v) {
+    v = sum16(v);
+    v += __shfl_xor(v, 16, 64);
+    return v + __shfl_xor(v, 32, 64);
+}
+__device__ __forceinline__ double wave_sum(double v) {
+    AIR_DPP_STEP64(add_d, v, 0xB1)
+    AIR_DPP_STEP64(add_d, v, 0x4E)
+    AIR_DPP_STEP64(add_d, v, 0x141)
+    AIR_DPP_STEP64(add_d, v, 0x140)
+    v += __shfl_xor(v, 16, 64);
+    return v + __shfl_xor(v, 32, 64);
+}
+__device__ __forceinline__ double wave_max(double v) {
+    AIR_DPP_STEP64(max_d, v, 0xB1)
+    AIR_DPP_STEP64(max_d, v, 0x4E)
+    AIR_DPP_STEP64(max_d, v, 0x141)
+    AIR_DPP_STEP64(max_d, v, 0x140)
+    v = fmax(v, __shfl_xor(v, 16, 64));
+    return fmax(v, __shfl_xor(v, 32, 64));
+}
+
+// Sum over a workgroup of NW waves in a fixed order; every thread gets the result.
+// `scratch` holds NW doubles; the call contains two barriers.
+template <int NW>
+__device__ __forceinline__ double block_sum(double v, double *scratch) {
+    v = wave_sum(v);
+    __syncthreads();
+    if ((threadIdx.x & 63) == 0) scratch[threadIdx.x >> 6] = v;
+    __syncthreads();
+    double r = 0.0;
+#pragma unroll
+    for (int w = 0; w < NW; ++w) r += scratch[w];
+    return r;
 }
 
 // exp(d * c / log2(e)) = 2^(d * c) for d <= 0 and a constant c given as a hi/lo pair (c_hi + c_lo = c to
