@@ -151,12 +151,16 @@ __device__ __forceinline__ void lds_barrier() {
 template <int NW>
 __device__ __forceinline__ int block_excl_scan(int v, int *scratch, int *total) {
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    // inclusive scan over the wave: shifts inside each row of 16 lanes on DPP (lanes shifted in from outside the
+    // row read 0), then the totals of the rows in front are added from lanes 15, 31 and 47
     int incl = v;
-#pragma unroll
-    for (int o = 1; o < 64; o <<= 1) {
-        const int y = __shfl_up(incl, o, 64);
-        if (lane >= o) incl += y;
-    }
+    incl += __builtin_amdgcn_update_dpp(0, incl, 0x111, 0xf, 0xf, true);  // row_shr:1
+    incl += __builtin_amdgcn_update_dpp(0, incl, 0x112, 0xf, 0xf, true);  // row_shr:2
+    incl += __builtin_amdgcn_update_dpp(0, incl, 0x114, 0xf, 0xf, true);  // row_shr:4
+    incl += __builtin_amdgcn_update_dpp(0, incl, 0x118, 0xf, 0xf, true);  // row_shr:8
+    const int t0 = __builtin_amdgcn_readlane(incl, 15), t1 = __builtin_amdgcn_readlane(incl, 31),
+              t2 = __builtin_amdgcn_readlane(incl, 47);
+    incl += (lane >= 16 ? t0 : 0) + (lane >= 32 ? t1 : 0) + (lane >= 48 ? t2 : 0);
     __syncthreads();
     if (lane == 63) scratch[wave] = incl;
     __syncthreads();
