@@ -193,7 +193,7 @@ __global__ __launch_bounds__(64 * NW) void decode_mfma_kernel(Dims dm, DecodeTab
         sn += __shfl_xor(sn, 16, 64);
         sn += __shfl_xor(sn, 32, 64);
         m_run = sn * kScale2;
-        l_run = 1.f;
+        l_run = c == 0 ? 1.f : 0.f;  // l_run is a per-lane partial of the head's sum: the token counts once
 #pragma unroll
         for (int j = 0; j < 8; ++j) {
             const float v = bf16_bits_to_float(vnew[j]);
@@ -244,38 +244,45 @@ __global__ __launch_bounds__(64 * NW) void decode_mfma_kernel(Dims dm, DecodeTab
                 for (int i = 0; i < 4; ++i)
                     if (kb + 16 * tile + 4 * c + i >= kend) s[tile][i] = -INFINITY;
         }
-        // ---- online softmax for head n over the keys this lane holds (4c+i of each tile)
-        float mb = s[0][0];
+        // ---- online softmax for head n over the keys this lane holds (4c+i of each tile).  The four lanes of a
+        // head share one reference maximum m_run; it is raised (and the accumulators rescaled) only when some
+        // score of the chunk lies more than kSlack above it, so most chunks need no cross-lane step at all:
+        // probabilities may then be as large as 2^kSlack, which fp32 sums and bf16 operands hold without loss.
+        // The sum l_run stays a per-lane partial and is added up over the four lanes after the last chunk.
+        constexpr float kSlack = 8.0f;
+        float mloc = s[0][0];
 #pragma unroll
         for (int tile = 0; tile < KT; ++tile)
 #pragma unroll
-            for (int i = 0; i < 4; ++i) mb = fmaxf(mb, s[tile][i]);
-        mb = fmaxf(mb, __shfl_xor(mb, 16, 64));
-        mb = fmaxf(mb, __shfl_xor(mb, 32, 64));
-        const float m_new = fmaxf(m_run, mb * kScale2);  // finite: key kb is valid
-        const float corr = __builtin_amdgcn_exp2f(m_run - m_new);
+            for (int i = 0; i < 4; ++i) mloc = fmaxf(mloc, s[tile][i]);
+        mloc *= kScale2;
+        if (__ballot(mloc > m_run + kSlack) != 0ull) {  // uniform over the wave; always taken on a wave's first chunk
+            float mb = fmaxf(mloc, __shfl_xor(mloc, 16, 64));
+            mb = fmaxf(mb, __shfl_xor(mb, 32, 64));
+            const float m_new = fmaxf(m_run, mb);  // finite: key kb is valid
+            const float corr = __builtin_amdgcn_exp2f(m_run - m_new);
+            l_run *= corr;
+            m_run = m_new;
+            // accumulator rows are heads 4c..4c+3: fetch their rescale factors from lanes 4c+i
+            if ((owns_new || kb != kb_first) && __ballot(corr != 1.0f) != 0ull) {
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    const float f = __shfl(corr, 4 * c + i, 64);
+#pragma unroll
+                    for (int j = 0; j < 8; ++j) acc[j][i] *= f;
+                }
+            }
+        }
         float lb = 0.f;
 #pragma unroll
         for (int tile = 0; tile < KT; ++tile)
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
-                const float p = __builtin_amdgcn_exp2f(fmaf(s[tile][i], kScale2, -m_new));
+                const float p = __builtin_amdgcn_exp2f(fmaf(s[tile][i], kScale2, -m_run));
                 s[tile][i] = p;
                 lb += p;
             }
-        lb += __shfl_xor(lb, 16, 64);
-        lb += __shfl_xor(lb, 32, 64);
-        l_run = fmaf(l_run, corr, lb);
-        m_run = m_new;
-        // accumulator rows are heads 4c..4c+3: fetch their rescale factors from lanes 4c+i
-        if ((owns_new || kb != kb_first) && __ballot(corr != 1.0f) != 0ull) {
-#pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                const float f = __shfl(corr, 4 * c + i, 64);
-#pragma unroll
-                for (int j = 0; j < 8; ++j) acc[j][i] *= f;
-            }
-        }
+        l_run += lb;
         // ---- P * V
 #pragma unroll
         for (int tb = 0; tb < TB; ++tb) {
@@ -324,6 +331,10 @@ __global__ __launch_bounds__(64 * NW) void decode_mfma_kernel(Dims dm, DecodeTab
             }
         }
     }
+
+    // the head's sum over the four lanes that hold its keys
+    l_run += __shfl_xor(l_run, 16, 64);
+    l_run += __shfl_xor(l_run, 32, 64);
 
     // ---- merge the NW waves of the workgroup through LDS.  Every wave first rescales its partial
     // to the workgroup's maximum, so that the merge is a plain sum: wave w ends up with output
