@@ -567,82 +567,52 @@ __global__ __launch_bounds__(64 * kEliteWaves) void elite_mfma_kernel(Dims dm, D
                 R += __popcll(bal);
             }
             if (lane == 0) t.elite_cnt[hrow] = R;
-            // elite-text columns of Eq.7: (max, sum-exp) of every elite row over the elite text keys; each
-            // (row, key) logit is a 64-lane dot product.  Up to 8 keys are scored in one batch of loads,
-            // longer rows are scored twice (maximum, then sum).  The maximum is kept as the RAW dot
-            // product (before the 1/sqrt(d) scale), the sum is of exp((a - max) / sqrt(d)).
-            if (R <= 8) {
-                // the usual case: the elite rows' queries and keys are requested in one batch, then the
-                // R x R logits are formed
-                uint32_t uqv[8], ukv[8];
+            // elite-text columns of Eq.7: (max, sum-exp) of every elite row over the elite text keys.  The
+            // R x R logits are formed on MFMA, 16 rows against 16 keys per tile; lane (n, c) of a tile holds
+            // key n and rows 4c .. 4c+3, rows and keys past R re-read the last one.  Windows of more than 16
+            // rows (alpha = 0 turns the whole span into rows) go over the keys twice (maximum, then sum);
+            // up to 16 rows the one tile is kept.  The maximum is kept as the RAW dot product (before the
+            // 1/sqrt(d) scale), the sum is of exp((a - max) / sqrt(d)).
+            for (int rb = 0; rb < R; rb += 16) {
+                uint4 qa2[4];
+                {
+                    const bf16_t *qr = q + (int64_t)(elite[min(rb + n, R - 1)] - t0) * st.q_t;
 #pragma unroll
-                for (int j = 0; j < 8; ++j) {
-                    const int tok = elite[min(j, R - 1)];
-                    uqv[j] = reinterpret_cast<const uint32_t *>(q + (int64_t)(tok - t0) * st.q_t)[lane];
-                    ukv[j] = reinterpret_cast<const uint32_t *>(k + (int64_t)tok * st.kv_t)[lane];
+                    for (int sl = 0; sl < 4; ++sl) qa2[sl] = *reinterpret_cast<const uint4 *>(qr + 32 * sl + 8 * c);
                 }
-#pragma unroll
-                for (int r = 0; r < 8; ++r) {
-                    if (r >= R) break;
-                    const float q0 = __uint_as_float(uqv[r] << 16), q1 = __uint_as_float(uqv[r] & 0xffff0000u);
-                    float a[8];
-                    float m = -INFINITY, z = 0.f;
-#pragma unroll
-                    for (int j = 0; j < 8; ++j)
-                        if (j < R) {
-                            a[j] = wave_sum(fmaf(q1, __uint_as_float(ukv[j] & 0xffff0000u), q0 * __uint_as_float(ukv[j] << 16)));
-                            m = fmaxf(m, a[j]);
-                        }
-#pragma unroll
-                    for (int j = 0; j < 8; ++j)
-                        if (j < R) z += expf((a[j] - m) * scale);
-                    if (lane == 0) {
-                        t.row_mtext[hrow * W + r] = m;
-                        t.row_ztext[hrow * W + r] = z;
-                    }
-                }
-            } else {
-                // longer windows (alpha = 0 turns the whole span into rows): R x R logits on MFMA, 16 rows
-                // against 16 keys per tile, two passes over the keys (maximum, then sum).  Lane (n, c) of a
-                // tile holds key n and rows 4c .. 4c+3; rows and keys past R re-read the last one.
-                for (int rb = 0; rb < R; rb += 16) {
-                    uint4 qa2[4];
-                    {
-                        const bf16_t *qr = q + (int64_t)(elite[min(rb + n, R - 1)] - t0) * st.q_t;
-#pragma unroll
-                        for (int sl = 0; sl < 4; ++sl) qa2[sl] = *reinterpret_cast<const uint4 *>(qr + 32 * sl + 8 * c);
-                    }
-                    float m4[4] = {-INFINITY, -INFINITY, -INFINITY, -INFINITY}, z4[4] = {0.f, 0.f, 0.f, 0.f};
-                    for (int pass = 0; pass < 2; ++pass) {
-                        for (int jb = 0; jb < R; jb += 16) {
+                float m4[4] = {-INFINITY, -INFINITY, -INFINITY, -INFINITY}, z4[4] = {0.f, 0.f, 0.f, 0.f};
+                f32x4 a4 = (f32x4){0.f, 0.f, 0.f, 0.f};
+                for (int pass = 0; pass < 2; ++pass) {
+                    for (int jb = 0; jb < R; jb += 16) {
+                        if (pass == 0 || R > 16) {
                             const bf16_t *kr = k + (int64_t)elite[min(jb + n, R - 1)] * st.kv_t;
-                            f32x4 a4 = (f32x4){0.f, 0.f, 0.f, 0.f};
+                            a4 = (f32x4){0.f, 0.f, 0.f, 0.f};
 #pragma unroll
                             for (int sl = 0; sl < 4; ++sl) {
                                 const uint4 kb2 = *reinterpret_cast<const uint4 *>(kr + 32 * sl + 8 * c);
                                 a4 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, qa2[sl]),
                                                                              __builtin_bit_cast(bf16x8, kb2), a4, 0, 0, 0);
                             }
-                            const bool live = jb + n < R;
-#pragma unroll
-                            for (int i = 0; i < 4; ++i) {
-                                if (pass == 0) m4[i] = fmaxf(m4[i], live ? a4[i] : -INFINITY);
-                                else z4[i] += live ? expf((a4[i] - m4[i]) * scale) : 0.f;
-                            }
                         }
-                        if (pass == 0) {
+                        const bool live = jb + n < R;
 #pragma unroll
-                            for (int i = 0; i < 4; ++i) m4[i] = max16(m4[i]);
+                        for (int i = 0; i < 4; ++i) {
+                            if (pass == 0) m4[i] = fmaxf(m4[i], live ? a4[i] : -INFINITY);
+                            else z4[i] += live ? expf((a4[i] - m4[i]) * scale) : 0.f;
                         }
                     }
+                    if (pass == 0) {
 #pragma unroll
-                    for (int i = 0; i < 4; ++i) {
-                        const float z = sum16(z4[i]);
-                        const int r = rb + 4 * c + i;
-                        if (n == 0 && r < R) {
-                            t.row_mtext[hrow * W + r] = m4[i];
-                            t.row_ztext[hrow * W + r] = z;
-                        }
+                        for (int i = 0; i < 4; ++i) m4[i] = max16(m4[i]);
+                    }
+                }
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    const float z = sum16(z4[i]);
+                    const int r = rb + 4 * c + i;
+                    if (n == 0 && r < R) {
+                        t.row_mtext[hrow * W + r] = m4[i];
+                        t.row_ztext[hrow * W + r] = z;
                     }
                 }
             }
