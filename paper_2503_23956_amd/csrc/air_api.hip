@@ -111,6 +111,7 @@ struct air_ctx {
     std::vector<int32_t> appended;
     int force_splits, force_waves, force_tiles;  // AIR_DECODE_SPLITS / _WAVES / _TILES, 0 = automatic
     int score_block_mb;             // bytes of K_v scored per pair of passes (AIR_SCORE_BLOCK_MB)
+    bool rows_kernel;               // row parameters by their own kernel also for the elite window (AIR_SCORE_ROWS_KERNEL=1)
     std::string err;
 };
 
@@ -200,6 +201,8 @@ air_status air_create(const air_config *cfg, void *workspace, size_t workspace_b
         const int v = atoi(e);
         if (v >= 1 && v <= 65536) c->score_block_mb = v;
     }
+    c->rows_kernel = false;
+    if (const char *e = getenv("AIR_SCORE_ROWS_KERNEL")) c->rows_kernel = atoi(e) == 1;
     if (const char *e = getenv("AIR_DECODE_WAVES")) {
         const int v = atoi(e);
         if (v == 1 || v == 2 || v == 4 || v == 8) c->force_waves = v;
@@ -306,6 +309,9 @@ air_status air_score(air_ctx *ctx, void *stream, int32_t l0, int32_t l1, const a
     const bool mfma = v_transposed(dt, ctx->cfg.head_dim);  // bf16, head_dim 128
     const int lpl = layers_per_launch(ctx);
     int group = lpl;
+    // The elite window (alpha > 0) leaves a unit a handful of rows: the finish kernel forms their
+    // parameters itself.  A window that turns its whole span into rows gets the row-parameter kernel.
+    const int inline_rows = ctx->cfg.alpha > 0.0 && !ctx->dm.vis_window && !ctx->rows_kernel;
     // Windows that are known to exceed the stash (alpha = 0 turns the whole candidate span into rows)
     // read K_v twice: run the two kernels over groups of layers whose keys fit the memory-side cache.
     if (mfma && ctx->cfg.alpha == 0.0 && (int64_t)ctx->dm.G * ctx->cfg.max_window > kStashRows) {
@@ -342,8 +348,8 @@ air_status air_score(air_ctx *ctx, void *stream, int32_t l0, int32_t l1, const a
             LaunchLayers lg;
             memset(&lg, 0, sizeof(lg));
             for (int i = 0; i < gn; ++i) lg.p[i] = ll.p[g0 + i];
-            e = launch_score_mfma(s, ctx->dm, ctx->tab, 1, c0 + g0, gn, lg, *strides, sa);
-            if (e == hipSuccess) e = launch_score_mfma(s, ctx->dm, ctx->tab, 2, c0 + g0, gn, lg, *strides, sa);
+            e = launch_score_mfma(s, ctx->dm, ctx->tab, 1, c0 + g0, gn, lg, *strides, sa, inline_rows);
+            if (e == hipSuccess) e = launch_score_mfma(s, ctx->dm, ctx->tab, 2, c0 + g0, gn, lg, *strides, sa, inline_rows);
         }
         if (e != hipSuccess) return hip_fail(ctx, e, "air_score launch");
     }

@@ -95,11 +95,15 @@ __device__ __forceinline__ float wave_sum(float v) {
     v += __shfl_xor(v, 16, 64);
     return v + __shfl_xor(v, 32, 64);
 }
-__device__ __forceinline__ double wave_sum(double v) {
+__device__ __forceinline__ double sum16(double v) {  // over each row of 16 lanes
     AIR_DPP_STEP64(add_d, v, 0xB1)
     AIR_DPP_STEP64(add_d, v, 0x4E)
     AIR_DPP_STEP64(add_d, v, 0x141)
     AIR_DPP_STEP64(add_d, v, 0x140)
+    return v;
+}
+__device__ __forceinline__ double wave_sum(double v) {
+    v = sum16(v);
     v += __shfl_xor(v, 16, 64);
     return v + __shfl_xor(v, 32, 64);
 }

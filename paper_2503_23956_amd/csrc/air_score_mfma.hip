@@ -252,6 +252,33 @@ __global__ __launch_bounds__(256, 4) void score_stream_kernel(Dims dm, DevTables
 }
 
 // ---------------------------------------------------------------------------------------
+// Parameters of one window row, by one wave (every lane gets the result): M = max over the chunk
+// partials and the elite-text columns (raw units), Z = sum z exp(m - M) in fp64, w = 1 / (R_h G Z).
+// p0 returns the lane's own partial of the first 64 chunks.  A partial with sum 0 (a chunk wholly
+// behind a visual-window row; the empty text columns of such a window) has maximum -inf and takes no part.
+__device__ __forceinline__ void row_params(const DevTables &t, int64_t slot, int nch, int n_chunks, int rows_of_head, int G,
+                                           int lane, float &M, float &w, float2 &p0) {
+    const float2 *p = t.part + slot * n_chunks;
+    const float mt = t.row_mtext[slot], zt = t.row_ztext[slot];
+    p0 = lane < nch ? p[lane] : make_float2(-INFINITY, 0.f);  // the first 64 chunks stay in registers
+    M = fmaxf(mt, p0.x);
+    for (int cc = lane + 64; cc < nch; cc += 64) M = fmaxf(M, p[cc].x);
+    M = wave_max(M);
+    double Z = lane < nch && p0.y > 0.f ? (double)(p0.y * exp_raw(p0.x - M)) : 0.0;
+    for (int cc = lane + 64; cc < nch; cc += 64) {
+        const float2 x = p[cc];
+        if (x.y > 0.f) Z += (double)(x.y * exp_raw(x.x - M));
+    }
+    Z = wave_sum(Z);
+    if (zt > 0.f) Z += (double)(zt * exp_raw(mt - M));
+    w = (float)(1.0 / ((double)rows_of_head * (double)G * Z));
+}
+// the factor that turns a stashed exponential of a chunk into its share of Eq.8
+__device__ __forceinline__ float chunk_factor(float2 part, float M, float w) {
+    return part.y > 0.f ? w * exp_raw(part.x - M) : 0.f;
+}
+
+// ---------------------------------------------------------------------------------------
 // Row parameters, once per unit: one wave per window row, lanes over the chunk partials.
 // M = max over chunks and the elite-text columns, Z = sum z exp(m - M) in fp64,
 // w = 1 / (R_h G Z).  Units with a stash also get f[row][chunk] = w exp(m_chunk - M), the factor
@@ -276,37 +303,27 @@ __global__ __launch_bounds__(64 * kRowWaves) void score_rows_mfma_kernel(Dims dm
         const int g = head_of_row(s_pref, G, rho);
         const int64_t slot = (hrow0 + g) * W + (rho - s_pref[g]);
         const float2 *p = t.part + slot * dm.n_chunks;
-        const float mt = t.row_mtext[slot], zt = t.row_ztext[slot];
-        const float2 p0 = lane < nch ? p[lane] : make_float2(-INFINITY, 0.f);  // the first 64 chunks stay in registers
-        float M = fmaxf(mt, p0.x);
-        for (int cc = lane + 64; cc < nch; cc += 64) M = fmaxf(M, p[cc].x);
-        M = wave_max(M);
-        // a partial with sum 0 (a chunk wholly behind a visual-window row; the empty text columns of such a
-        // window) has maximum -inf and takes no part
-        double Z = lane < nch && p0.y > 0.f ? (double)(p0.y * exp_raw(p0.x - M)) : 0.0;
-        for (int cc = lane + 64; cc < nch; cc += 64) {
-            const float2 x = p[cc];
-            if (x.y > 0.f) Z += (double)(x.y * exp_raw(x.x - M));
-        }
-        Z = wave_sum(Z);
-        if (zt > 0.f) Z += (double)(zt * exp_raw(mt - M));
-        const float w = (float)(1.0 / ((double)(s_pref[g + 1] - s_pref[g]) * (double)G * Z));
+        float M, w;
+        float2 p0;
+        row_params(t, slot, nch, dm.n_chunks, s_pref[g + 1] - s_pref[g], G, lane, M, w, p0);
         if (lane == 0) {
             t.row_M[slot] = M;  // raw units
             t.row_w[slot] = w;
         }
         if (stash) {
             float *f = t.row_f + (unit * kStashRows + rho) * dm.n_chunks;
-            if (lane < nch) f[lane] = p0.y > 0.f ? w * exp_raw(p0.x - M) : 0.f;
-            for (int cc = lane + 64; cc < nch; cc += 64) f[cc] = p[cc].y > 0.f ? w * exp_raw(p[cc].x - M) : 0.f;
+            if (lane < nch) f[lane] = chunk_factor(p0, M, w);
+            for (int cc = lane + 64; cc < nch; cc += 64) f[cc] = chunk_factor(p[cc], M, w);
         }
     }
 }
 
 // ---------------------------------------------------------------------------------------
 // One workgroup finishes kFinishChunks consecutive chunks of a unit and leaves one power-sum entry.
+// INLINE: no row-parameter kernel has run; every workgroup forms the parameters of the unit's rows
+// itself from the chunk partials (the elite window's handful of rows: cheaper than a launch).
 
-template <bool VIS>
+template <bool VIS, bool INLINE>
 __global__ __launch_bounds__(256, 4) void score_finish_kernel(Dims dm, DevTables t, int l0, LaunchLayers ll,
                                                            air_strides st, SeqArgs seqs) {
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, n = lane & 15, c = lane >> 4;
@@ -321,11 +338,16 @@ __global__ __launch_bounds__(256, 4) void score_finish_kernel(Dims dm, DevTables
     const int first = u.chunk, last = min(nch, first + kFinishChunks);
     // factor table of the stash path goes out before anything else; rows past R_total are never used
     float f_mine = 0.f;
-    if (tid < kFinishChunks * kStashRows && first + tid / kStashRows < last)
-        f_mine = t.row_f[(u.unit * kStashRows + (tid % kStashRows)) * dm.n_chunks + first + tid / kStashRows];
-    u.R_total = t.unit_R[u.unit];
+    if (!INLINE) {
+        if (tid < kFinishChunks * kStashRows && first + tid / kStashRows < last)
+            f_mine = t.row_f[(u.unit * kStashRows + (tid % kStashRows)) * dm.n_chunks + first + tid / kStashRows];
+        u.R_total = t.unit_R[u.unit];
+    } else {
+        head_prefix(t, u.hrow0, u.G, s_pref);
+        u.R_total = s_pref[u.G];
+    }
     const bool stash = u.R_total <= kStashRows;
-    if (!stash) head_prefix(t, u.hrow0, u.G, s_pref);
+    if (!INLINE && !stash) head_prefix(t, u.hrow0, u.G, s_pref);
 
     // fp64 power sums of I over the workgroup's chunks, summed in a fixed order; one entry per workgroup
     double m1 = 0.0, m2 = 0.0, m3 = 0.0;
@@ -346,21 +368,61 @@ __global__ __launch_bounds__(256, 4) void score_finish_kernel(Dims dm, DevTables
     };
 
     if (stash) {
-        if (tid < kFinishChunks * kStashRows) s_f[tid / kStashRows][tid % kStashRows] = (tid % kStashRows) < u.R_total ? f_mine : 0.f;
-        lds_barrier();
+        // factors f[chunk][row] into LDS: read from the table the row-parameter kernel left, or formed
+        // here, a wave per row (rows past the list get zero)
+        auto put_factors = [&]() __attribute__((always_inline)) {
+            if (!INLINE) {
+                if (tid < kFinishChunks * kStashRows) s_f[tid / kStashRows][tid % kStashRows] = (tid % kStashRows) < u.R_total ? f_mine : 0.f;
+            } else {
+                // a row of 16 lanes per window row (16 rows at a time), a lane takes every 16th chunk
+                // partial: all loads of a round go out together and the reductions stay inside the row
+                if (tid < kFinishChunks * kStashRows && (tid % kStashRows) >= u.R_total) s_f[tid / kStashRows][tid % kStashRows] = 0.f;
+                const int grp = tid >> 4, gl = tid & 15;
+                for (int r0 = 0; r0 < u.R_total; r0 += 16) {
+                    const int rho = min(r0 + grp, u.R_total - 1);  // a row group past the list repeats the last row and stores nothing
+                    const int g = head_of_row(s_pref, u.G, rho);
+                    const int64_t slot = (u.hrow0 + g) * u.W + (rho - s_pref[g]);
+                    const float2 *p = t.part + slot * dm.n_chunks;
+                    const float mt = t.row_mtext[slot], zt = t.row_ztext[slot];
+                    const float2 pf = p[min(first + gl, nch - 1)];  // the partial a factor is made of (lanes 0 .. 3)
+                    float2 pc[4];
+#pragma unroll
+                    for (int k = 0; k < 4; ++k) pc[k] = gl + 16 * k < nch ? p[gl + 16 * k] : make_float2(-INFINITY, 0.f);
+                    float M = mt;
+#pragma unroll
+                    for (int k = 0; k < 4; ++k) M = fmaxf(M, pc[k].x);
+                    for (int cc = gl + 64; cc < nch; cc += 16) M = fmaxf(M, p[cc].x);
+                    M = max16(M);
+                    double Z = 0.0;
+#pragma unroll
+                    for (int k = 0; k < 4; ++k) Z += pc[k].y > 0.f ? (double)(pc[k].y * exp_raw(pc[k].x - M)) : 0.0;
+                    for (int cc = gl + 64; cc < nch; cc += 16) {
+                        const float2 x = p[cc];
+                        if (x.y > 0.f) Z += (double)(x.y * exp_raw(x.x - M));
+                    }
+                    Z = sum16(Z);
+                    if (zt > 0.f) Z += (double)(zt * exp_raw(mt - M));
+                    const float w = (float)(1.0 / ((double)(s_pref[g + 1] - s_pref[g]) * (double)u.G * Z));
+                    if (r0 + grp < u.R_total && gl < kFinishChunks) s_f[gl][rho] = first + gl < last ? chunk_factor(pf, M, w) : 0.f;
+                }
+            }
+            lds_barrier();
+        };
         // One wave per chunk; a lane takes 16 bytes of every stashed row (four keys, 16 apart: see
-        // stash_pos) and all rows are requested at once.  Rows past the list re-read its last row
-        // against a zero factor, a wave past the last chunk re-reads the last chunk and stores nothing.
-        // rows r0 .. r0 + RB - 1 of the stash into the lane's four keys
+        // stash_pos) and all rows of a round are requested at once, in front of the factors.  Rows past
+        // the list re-read its last row against a zero factor, a wave past the last chunk re-reads the
+        // last chunk and stores nothing.
         const int ci = wave, chunk = first + ci;
         const float *sb = t.stash + ((u.unit * dm.n_chunks + min(chunk, last - 1)) * (int64_t)kStashRows) * kChunkKeys + 4 * lane;
         f32x4 imp = (f32x4){0.f, 0.f, 0.f, 0.f};
-        auto add_rows = [&](auto rb_tag, int r0) __attribute__((always_inline)) {
-            constexpr int RB = decltype(rb_tag)::value;
-            f32x4 e[RB];
+        auto get_rows = [&](auto &e, int r0) __attribute__((always_inline)) {
+            constexpr int RB = sizeof(e) / sizeof(e[0]);
 #pragma unroll
             for (int r = 0; r < RB; ++r)
                 e[r] = *reinterpret_cast<const f32x4 *>(sb + (int64_t)min(r0 + r, max(u.R_total - 1, 0)) * kChunkKeys);
+        };
+        auto add_rows = [&](const auto &e, int r0) __attribute__((always_inline)) {
+            constexpr int RB = sizeof(e) / sizeof(e[0]);
 #pragma unroll
             for (int r = 0; r < RB; ++r) {
                 const float f = s_f[ci][r0 + r];
@@ -375,9 +437,21 @@ __global__ __launch_bounds__(256, 4) void score_finish_kernel(Dims dm, DevTables
                 t.scores[u.unit * dm.max_vis + key] = 0.f;
         } else {
             // 16 rows in flight at most: 32 at once would cost the kernel half of its occupancy
-            if (u.R_total <= 8) add_rows(std::integral_constant<int, 8>(), 0);
-            else add_rows(std::integral_constant<int, 16>(), 0);
-            if (u.R_total > 16) add_rows(std::integral_constant<int, 16>(), 16);
+            if (u.R_total <= 8) {
+                f32x4 e[8];
+                get_rows(e, 0);
+                put_factors();
+                add_rows(e, 0);
+            } else {
+                f32x4 e[16];
+                get_rows(e, 0);
+                put_factors();
+                add_rows(e, 0);
+                if (u.R_total > 16) {
+                    get_rows(e, 16);
+                    add_rows(e, 16);
+                }
+            }
             if (chunk < last) {
 #pragma unroll
                 for (int i = 0; i < 4; ++i) {
@@ -398,12 +472,27 @@ __global__ __launch_bounds__(256, 4) void score_finish_kernel(Dims dm, DevTables
     // recompute path: (M, w) of a block of rows staged from the row tables
     auto stage_rows = [&](int rs, int rows) {
         __syncthreads();
-        for (int rr = tid; rr < rows; rr += 256) {
-            const int rho = rs + rr;
-            const int g = head_of_row(s_pref, u.G, rho);
-            const int64_t slot = (u.hrow0 + g) * u.W + (rho - s_pref[g]);
-            s_M[rr] = t.row_M[slot];
-            s_w[rr] = t.row_w[slot];
+        if (!INLINE) {
+            for (int rr = tid; rr < rows; rr += 256) {
+                const int rho = rs + rr;
+                const int g = head_of_row(s_pref, u.G, rho);
+                const int64_t slot = (u.hrow0 + g) * u.W + (rho - s_pref[g]);
+                s_M[rr] = t.row_M[slot];
+                s_w[rr] = t.row_w[slot];
+            }
+        } else {
+            for (int rr = wave; rr < rows; rr += 4) {
+                const int rho = rs + rr;
+                const int g = head_of_row(s_pref, u.G, rho);
+                const int64_t slot = (u.hrow0 + g) * u.W + (rho - s_pref[g]);
+                float M, w;
+                float2 p0;
+                row_params(t, slot, nch, dm.n_chunks, s_pref[g + 1] - s_pref[g], u.G, lane, M, w, p0);
+                if (lane == 0) {
+                    s_M[rr] = M;
+                    s_w[rr] = w;
+                }
+            }
         }
         __syncthreads();
     };
@@ -632,20 +721,26 @@ hipError_t launch_elite_mfma(hipStream_t s, const Dims &dm, const DevTables &t, 
 }
 
 hipError_t launch_score_mfma(hipStream_t s, const Dims &dm, const DevTables &t, int pass, int l0, int nl,
-                             const LaunchLayers &ll, const air_strides &st, const SeqArgs &seqs) {
+                             const LaunchLayers &ll, const air_strides &st, const SeqArgs &seqs, int inline_rows) {
     if (pass == 1)
         hipLaunchKernelGGL(dm.vis_window ? score_stream_kernel<true> : score_stream_kernel<false>,
                            dim3((dm.n_chunks + kStreamChunks - 1) / kStreamChunks, nl * dm.B * dm.Hkv), dim3(256), 0, s, dm, t, l0,
                            ll, st, seqs);
     else {
+        const dim3 grid((dm.n_chunks + kFinishChunks - 1) / kFinishChunks, nl * dm.B * dm.Hkv);
+        if (inline_rows && !dm.vis_window) {
+            hipLaunchKernelGGL((score_finish_kernel<false, true>), grid, dim3(256), 0, s, dm, t, l0, ll, st, seqs);
+            return hipGetLastError();
+        }
         // a wave per row when the launch has few units; with many units, 4 waves walk the rows
         hipLaunchKernelGGL(score_rows_mfma_kernel, dim3(nl * dm.B * dm.Hkv),
                            dim3(nl * dm.B * dm.Hkv >= 512 ? 256 : 64 * kRowWaves), 0, s, dm, t, l0, seqs);
         hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;
-        hipLaunchKernelGGL(dm.vis_window ? score_finish_kernel<true> : score_finish_kernel<false>,
-                           dim3((dm.n_chunks + kFinishChunks - 1) / kFinishChunks, nl * dm.B * dm.Hkv), dim3(256), 0, s, dm, t, l0,
-                           ll, st, seqs);
+        if (dm.vis_window)
+            hipLaunchKernelGGL((score_finish_kernel<true, false>), grid, dim3(256), 0, s, dm, t, l0, ll, st, seqs);
+        else
+            hipLaunchKernelGGL((score_finish_kernel<false, false>), grid, dim3(256), 0, s, dm, t, l0, ll, st, seqs);
     }
     return hipGetLastError();
 }

@@ -319,6 +319,35 @@ def test_all_text_window_with_more_rows_than_one_staging_round():
     _run_case(w, 0.10, alpha=0.0, steps=1)
 
 
+def test_elite_window_row_parameters_by_their_own_kernel(monkeypatch):
+    """The elite window's row parameters are formed inside the finish kernel; the separate row-parameter
+    kernel (the path of the windows that turn their whole span into rows) must give the same on it, with the
+    rows in the stash (alpha 0.9) and beyond it (alpha 0.05: most text tokens are elite)."""
+    monkeypatch.setenv("AIR_SCORE_ROWS_KERNEL", "1")
+    w = synth.get_workload(2).scaled(n_layers=2, n_vis=1100, n_text=48, decode_steps=1)
+    _run_case(w, 0.10, steps=1)
+    _run_case(w, 0.10, alpha=0.05, steps=1)
+
+
+def test_elite_window_with_more_rows_than_the_stash_holds():
+    # a low threshold makes most text tokens elite: the finish kernel recomputes the logits and forms the
+    # parameters of several hundred rows itself
+    w = synth.get_workload(2).scaled(n_layers=2, n_vis=1100, n_text=48, decode_steps=1)
+    _run_case(w, 0.10, alpha=0.05, steps=1)
+
+
+def test_unified_span_without_a_modality_distinction():
+    """The unified variant of the paper's vision-only / unified comparison (Sec.4.3): every prompt token in
+    front of the observation window is a candidate.  Nothing in the path looks at a token's modality, so
+    the variant is a sequence descriptor whose compressible span starts at token 0 and ends where the
+    window starts (no system tokens, the whole text span as the window)."""
+    w = synth.get_workload(2).scaled(n_layers=2, n_sys=0, n_vis=1500, n_text=48, window=0, decode_steps=2)
+    s = w.seqs()[0]
+    assert s.vis_start == 0 and s.vis_start + s.vis_len == s.win_start and s.win_start + s.win_len == s.seq_len
+    _run_case(w, 0.25, steps=2)             # elite rows of the window
+    _run_case(w, 0.10, alpha=0.0, steps=1)  # every window token a row, as the continuous-window baselines do
+
+
 def test_degenerate_sizes():
     # fewer than three visual tokens (skewness 0), one text token, one-token window, min_keep 0
     w = synth.get_workload(1).scaled(n_vis=2, n_text=1, window=1, n_sys=1)
