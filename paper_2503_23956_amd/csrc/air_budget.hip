@@ -5,15 +5,161 @@
 // contraction off): per-layer strength / skewness as the left-to-right mean over KV heads,
 // layer shares by left-to-right sums, proportional allocation clamped to [min_keep, N_v] by
 // repeatedly pinning the side with the larger total violation, floor + largest remainder
-// (ties to the lower layer).  Independent per-layer work is spread over the threads; the
-// order-dependent sums stay serial in thread 0.  Threads exchange data through LDS only, so the
-// barriers order LDS traffic and do not wait for the global stores of the statistics and budgets.
+// (ties to the lower layer).  Up to 64 layers are done by one wave, a layer per lane, whose lanes
+// read each other's registers: no LDS, no barriers.  Beyond that the per-layer work is spread over
+// the threads of the workgroup and the order-dependent sums stay serial in thread 0; the threads
+// exchange data through LDS only, so the barriers order LDS traffic and do not wait for the
+// global stores of the statistics and budgets.
 #include "air_device.h"
 #include "air_internal.h"
 
 namespace air {
 
 constexpr int kBT = 256;  // threads; also the largest layer count (AIR_MAX_LAYERS)
+
+// Value that lane `l` (the same for every lane of the wave) holds, handed to all lanes through a scalar register.
+__device__ __forceinline__ double lane_value(double v, int l) {
+    const unsigned long long u = __builtin_bit_cast(unsigned long long, v);
+    const unsigned lo = (unsigned)__builtin_amdgcn_readlane((int)(unsigned)u, l);
+    const unsigned hi = (unsigned)__builtin_amdgcn_readlane((int)(unsigned)(u >> 32), l);
+    return __builtin_bit_cast(double, ((unsigned long long)hi << 32) | lo);
+}
+
+// Eq.11 and the cache layout for up to 64 layers by ONE wave, a layer per lane.  The order-dependent
+// sums run left to right over the lanes (every lane forms the same sum from scalar reads of the other
+// lanes' registers), so the wave needs neither LDS nor barriers; the arithmetic and its order are
+// those of the many-layer path below.
+__device__ __forceinline__ void allocate_one_wave(const Dims &dm, const DevTables &t, double retention, int mode, int min_keep,
+                                                  int skip_allocation, bool stats_in_lds, const air_seq &sq, int b,
+                                                  const double *u_st, const double *u_sk) {
+    const int lane = threadIdx.x, L = dm.L, n_vis = sq.vis_len;
+    const bool mine = lane < L;
+    int32_t *budgets = t.budgets + (int64_t)b * L;
+    int kk = 0;
+    if (skip_allocation) {
+        if (mine) kk = budgets[lane];
+    } else {
+        double st = 0.0, sk = 0.0;
+        if (mine) {  // mean over the KV heads, left to right
+            double a = 0.0, c = 0.0;
+            for (int h = 0; h < dm.Hkv; ++h) {
+                const int64_t unit = ((int64_t)lane * dm.B + b) * dm.Hkv + h;
+                a += stats_in_lds ? u_st[lane * dm.Hkv + h] : t.unit_st[unit];
+                c += stats_in_lds ? u_sk[lane * dm.Hkv + h] : t.unit_sk[unit];
+            }
+            st = a / (double)dm.Hkv;
+            sk = c / (double)dm.Hkv;
+            t.s_t[(int64_t)b * L + lane] = st;
+            t.s_k[(int64_t)b * L + lane] = sk;
+        }
+        const int lo_i = min(min_keep, n_vis);
+        const double lo = (double)lo_i, hi = (double)n_vis;
+        const double skp = fmax(sk, 0.0);
+        double sum_t = 0.0, sum_k = 0.0;
+        for (int l = 0; l < L; ++l) {
+            sum_t += lane_value(st, l);
+            sum_k += lane_value(skp, l);
+        }
+        long long k_tot = (long long)floor(retention * (double)n_vis * (double)L + 0.5);
+        const long long k_lo = (long long)L * lo_i, k_hi = (long long)L * n_vis;
+        k_tot = k_tot < k_lo ? k_lo : (k_tot > k_hi ? k_hi : k_tot);
+        const double a = sum_t > 0.0 ? st / sum_t : 1.0 / (double)L;
+        const double c = sum_k > 0.0 ? skp / sum_k : 1.0 / (double)L;
+        double wl;
+        if (mode == AIR_BUDGET_UNIFORM) wl = 1.0 / (double)L;
+        else if (mode == AIR_BUDGET_STRENGTH) wl = a;
+        else if (mode == AIR_BUDGET_SKEW) wl = c;
+        else wl = 0.5 * (a + c);
+        // proportional allocation with clamping: pin the side with the larger total violation, repeat
+        bool is_free = mine;
+        double x = 0.0, k_free = (double)k_tot;
+        for (int it = 0; it < L + 1; ++it) {
+            const int n_free = __popcll(__ballot(is_free));
+            if (n_free == 0) break;
+            const double w_mine = is_free ? wl : 0.0;  // a pinned layer adds an exact zero
+            double w_free = 0.0;
+            for (int l = 0; l < L; ++l) w_free += lane_value(w_mine, l);
+            double vo = 0.0, vu = 0.0;
+            if (is_free) {
+                x = w_free > 0.0 ? (wl / w_free) * k_free : k_free / (double)n_free;
+                if (x > hi) vo = x - hi;
+                else if (x < lo) vu = lo - x;
+            }
+            double over = 0.0, under = 0.0;
+            for (int l = 0; l < L; ++l) {
+                over += lane_value(vo, l);
+                under += lane_value(vu, l);
+            }
+            const int pin = (over == 0.0 && under == 0.0) ? 0 : (over >= under ? 1 : 2);
+            if (pin == 0) break;
+            bool pinned = false;
+            if (is_free && pin == 1 && x > hi) {
+                x = hi;
+                pinned = true;
+            } else if (is_free && pin == 2 && x < lo) {
+                x = lo;
+                pinned = true;
+            }
+            is_free = is_free && !pinned;
+            // k_free stays an integer-valued double: the bound is subtracted once per pinned layer
+            const int n_pin = __popcll(__ballot(pinned));
+            const double bound = pin == 1 ? hi : lo;
+            for (int q = 0; q < n_pin; ++q) k_free -= bound;
+        }
+        double frac = -1.0;
+        if (mine) {
+            kk = max(lo_i, min((int)floor(x), n_vis));
+            frac = x - (double)kk;
+        }
+        int tot = 0;
+        for (int l = 0; l < L; ++l) tot += __builtin_amdgcn_readlane(kk, l);
+        unsigned long long elig = __ballot(mine && kk < n_vis);
+        const long long left = k_tot - (long long)tot;
+        if (left > 0 && left <= (long long)__popcll(elig)) {
+            // largest remainder: the `left` eligible layers that come first by (fraction descending, layer ascending)
+            int rank = 0;
+            for (int j = 0; j < L; ++j) {
+                const double fj = lane_value(frac, j);
+                rank += (int)((elig >> j) & 1ull) & ((int)(fj > frac) | ((int)(fj == frac) & (int)(j < lane)));
+            }
+            if (((elig >> lane) & 1ull) && rank < (int)left) kk += 1;
+        } else if (left > 0) {
+            // more leftovers than eligible layers: hand them out one by one, each to the eligible layer
+            // with the largest fraction (the lowest such layer), which then counts as served
+            for (long long rem = left; rem > 0 && elig != 0ull; --rem) {
+                int best = -1;
+                double fbest = 0.0;
+                for (int l = 0; l < L; ++l) {
+                    const double fl = lane_value(frac, l);
+                    if (((elig >> l) & 1ull) && (best < 0 || fl > fbest)) {
+                        best = l;
+                        fbest = fl;
+                    }
+                }
+                if (lane == best) {
+                    kk += 1;
+                    frac = -1.0;
+                }
+                elig = __ballot(mine && kk < n_vis);
+            }
+        }
+        if (mine) budgets[lane] = kk;
+    }
+    // cache layout: each layer's region holds system + kept + text rows and room for the decode
+    // appends, and starts on a multiple of kCacheRowAlign rows
+    const int nonvis = sq.seq_len - sq.vis_len;
+    const int cap = (nonvis + kk + dm.max_steps + kCacheRowAlign - 1) / kCacheRowAlign * kCacheRowAlign;
+    int off = 0;
+    for (int l = 0; l < L; ++l) {
+        const int cl = __builtin_amdgcn_readlane(cap, l);
+        off += l < lane ? cl : 0;
+    }
+    if (mine) {
+        t.base_len[(int64_t)b * L + lane] = nonvis + kk;
+        t.layer_off[(int64_t)b * L + lane] = off;
+        t.len_off[(int64_t)b * L + lane] = make_int2(nonvis + kk, off);
+    }
+}
 
 __global__ __launch_bounds__(kBT) void budget_kernel(Dims dm, DevTables t, double retention, int mode, int min_keep,
                                                      int skip_allocation, int use_moments, SeqArgs seqs) {
@@ -73,6 +219,10 @@ __global__ __launch_bounds__(kBT) void budget_kernel(Dims dm, DevTables t, doubl
             }
             if (stage) lds_barrier();  // the statistics cross in LDS: no wait for the global stores above
             else __syncthreads();
+        }
+        if (L <= 64) {  // the usual depth: one wave takes it from here
+            if (tid < 64) allocate_one_wave(dm, t, retention, mode, min_keep, 0, use_moments && stage, sq, b, u_st, u_sk);
+            return;
         }
         if (tid < L) {  // mean over the KV heads, left to right
             double a = 0.0, c = 0.0;
@@ -229,6 +379,10 @@ __global__ __launch_bounds__(kBT) void budget_kernel(Dims dm, DevTables t, doubl
         lds_barrier();
     }
 
+    if (L <= 64) {  // only the layout is left (the budgets were set by the caller)
+        if (tid < 64) allocate_one_wave(dm, t, retention, mode, min_keep, 1, false, sq, b, u_st, u_sk);
+        return;
+    }
     // cache layout: each layer's region holds system + kept + text rows and room for the
     // decode appends, and starts on a multiple of kCacheRowAlign rows
     if (skip_allocation && tid < L) kk[tid] = budgets[tid];  // otherwise kk still holds what was just written
