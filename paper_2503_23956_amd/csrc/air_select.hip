@@ -12,15 +12,15 @@
 namespace air {
 
 constexpr int kSelThreads = 512;                     // threads of the selection kernel for long rows (256 for rows up to 8192 scores)
-constexpr int kSelRegs = 32;                         // scores per thread kept in registers
+constexpr int kSelRegs = 32;                         // scores per thread kept in registers, at most (compiled for 8, 16 and 32)
 constexpr int kSelCand = 1024;                       // scores of the deciding 12-bit bin that are ranked directly
 
 // leading 12 bits of a score pattern; importance is non-negative, a set sign bit (never produced) falls into the top bin
 __device__ __forceinline__ uint32_t digit12(uint32_t v) { return min(v >> 20, 2047u); }
 
-template <int NT>
+template <int NT, int REGS>
 __global__ __launch_bounds__(NT) void select_kernel(Dims dm, DevTables t, int l0, int cand_cap) {
-    constexpr int kSpan = NT * kSelRegs;  // scores per sweep
+    constexpr int kSpan = NT * REGS;  // scores per sweep
     constexpr int kBinsPer = 2048 / NT;   // bins of the 12-bit histogram per thread
     const int tid = threadIdx.x, wave = tid >> 6;
     const int64_t unit = (int64_t)l0 * dm.B * dm.Hkv + blockIdx.x;
@@ -32,18 +32,19 @@ __global__ __launch_bounds__(NT) void select_kernel(Dims dm, DevTables t, int l0
     // not the sequence's own length, so that a short row's loads go out before anything has been
     // read (entries past the sequence's span exist and are never counted).  Rows longer than
     // kSpan are re-read sweep by sweep.
+    // the two table entries are requested in front of the scores, so that they are not waited for behind them
+    const int n = t.seq_tab[b].vis_len;
+    const int k = t.budgets[(int64_t)b * dm.L + l];
     const bool cached = dm.max_vis <= kSpan;
-    const int per = cached ? (dm.max_vis + NT - 1) / NT : kSelRegs;
-    uint32_t v[kSelRegs];
+    const int per = cached ? (dm.max_vis + NT - 1) / NT : REGS;
+    uint32_t v[REGS];
     if (cached) {
 #pragma unroll
-        for (int j = 0; j < kSelRegs; ++j) {
+        for (int j = 0; j < REGS; ++j) {
             const int i = tid * per + j;
             v[j] = (j < per && i < dm.max_vis) ? key[i] : 0u;
         }
     }
-    const int n = t.seq_tab[b].vis_len;
-    const int k = t.budgets[(int64_t)b * dm.L + l];
     int32_t *out = t.indices + unit * dm.max_vis;
     if (k <= 0) return;
     if (k >= n) {
@@ -58,7 +59,7 @@ __global__ __launch_bounds__(NT) void select_kernel(Dims dm, DevTables t, int l0
 
     auto load_sweep = [&](int base) {
 #pragma unroll
-        for (int j = 0; j < kSelRegs; ++j) {
+        for (int j = 0; j < REGS; ++j) {
             const int i = base + tid * per + j;
             v[j] = (j < per && i < n) ? key[i] : 0u;
         }
@@ -76,7 +77,7 @@ __global__ __launch_bounds__(NT) void select_kernel(Dims dm, DevTables t, int l0
         if (tid == 0) s_ncand = 0;
         __syncthreads();
 #pragma unroll
-        for (int j = 0; j < kSelRegs; ++j)
+        for (int j = 0; j < REGS; ++j)
             if (live(0, j)) atomicAdd(&h12[digit12(v[j])], 1u);
         __syncthreads();
         // thread t takes the kBinsPer bins at positions kBinsPer t .. from the top
@@ -103,7 +104,7 @@ __global__ __launch_bounds__(NT) void select_kernel(Dims dm, DevTables t, int l0
         if ((int)m <= cand_cap) {  // uniform over the workgroup
             // the bin's scores are collected in any order (their ranks do not depend on it)
 #pragma unroll
-            for (int j = 0; j < kSelRegs; ++j)
+            for (int j = 0; j < REGS; ++j)
                 if (live(0, j) && digit12(v[j]) == bin) cand[atomicAdd(&s_ncand, 1u)] = v[j];
             __syncthreads();
             // candidate i is the k-th largest iff (#greater) < kk2 <= (#greater) + (#equal)
@@ -137,7 +138,7 @@ __global__ __launch_bounds__(NT) void select_kernel(Dims dm, DevTables t, int l0
             // the digit of its first candidate itself and adds them once; the others add one by one.
             int d0 = -1, c0 = 0;
 #pragma unroll
-            for (int j = 0; j < kSelRegs; ++j)
+            for (int j = 0; j < REGS; ++j)
                 if (live(base, j) && (v[j] & mask) == prefix) {
                     const int dgt = (int)((v[j] >> shift) & 255u);
                     if (d0 < 0) d0 = dgt;
@@ -172,7 +173,7 @@ __global__ __launch_bounds__(NT) void select_kernel(Dims dm, DevTables t, int l0
         if (!cached) load_sweep(base);
         int c_gt = 0, c_eq = 0;
 #pragma unroll
-        for (int j = 0; j < kSelRegs; ++j)
+        for (int j = 0; j < REGS; ++j)
             if (live(base, j)) {
                 c_gt += v[j] > tau ? 1 : 0;
                 c_eq += v[j] == tau ? 1 : 0;
@@ -184,7 +185,7 @@ __global__ __launch_bounds__(NT) void select_kernel(Dims dm, DevTables t, int l0
         int gt_before = base_gt + (before & 0xffff);
         int eq_before = base_eq + (before >> 16);
 #pragma unroll
-        for (int j = 0; j < kSelRegs; ++j)
+        for (int j = 0; j < REGS; ++j)
             if (live(base, j)) {
                 const bool gt = v[j] > tau, eq = v[j] == tau;
                 if (gt || (eq && eq_before < (int)kk)) out[gt_before + min(eq_before, (int)kk)] = base + tid * per + j;
@@ -322,8 +323,22 @@ hipError_t launch_select(hipStream_t s, const Dims &dm, const DevTables &t, int 
     // scores 13.7 us against 16.3 us).  AIR_SELECT_THREADS = 256 | 512 overrides (tuning aid).
     int nt = (dm.max_vis <= 4096 && nl * dm.B * dm.Hkv >= 256) ? 256 : kSelThreads;
     if (const char *e = getenv("AIR_SELECT_THREADS")) nt = atoi(e) == 256 ? 256 : (atoi(e) == 512 ? 512 : nt);
-    if (nt == 256) hipLaunchKernelGGL(select_kernel<256>, dim3(nl * dm.B * dm.Hkv), dim3(256), 0, s, dm, t, l0, cap);
-    else hipLaunchKernelGGL(select_kernel<kSelThreads>, dim3(nl * dm.B * dm.Hkv), dim3(kSelThreads), 0, s, dm, t, l0, cap);
+    // registers per thread: the smallest compiled count that holds a whole row (every pass walks all of a
+    // thread's slots, so unused ones cost instructions); longer rows are swept 32 per thread at a time
+    const int per = (dm.max_vis + nt - 1) / nt;
+    const int regs = per <= 8 ? 8 : (per <= 16 ? 16 : kSelRegs);
+    const dim3 grid(nl * dm.B * dm.Hkv);
+#define AIR_SELECT_LAUNCH(NT_, REGS_) hipLaunchKernelGGL((select_kernel<NT_, REGS_>), grid, dim3(NT_), 0, s, dm, t, l0, cap)
+    if (nt == 256) {
+        if (regs == 8) AIR_SELECT_LAUNCH(256, 8);
+        else if (regs == 16) AIR_SELECT_LAUNCH(256, 16);
+        else AIR_SELECT_LAUNCH(256, kSelRegs);
+    } else {
+        if (regs == 8) AIR_SELECT_LAUNCH(kSelThreads, 8);
+        else if (regs == 16) AIR_SELECT_LAUNCH(kSelThreads, 16);
+        else AIR_SELECT_LAUNCH(kSelThreads, kSelRegs);
+    }
+#undef AIR_SELECT_LAUNCH
     return hipGetLastError();
 }
 
