@@ -91,18 +91,20 @@ template <int NW, int KT, bool SPLIT>
 __global__ __launch_bounds__(64 * NW) void decode_mfma_kernel(Dims dm, DecodeTabs t, int l0, int lbase,
                                                               DecodeSteps ll, const bf16_t *q_new,
                                                               const bf16_t *k_new, const bf16_t *v_new, bf16_t *out,
-                                                              int splits) {
+                                                              int splits, int lg_splits) {
     constexpr int D = 128;
     constexpr int kIter = 16 * KT;  // keys per loop iteration of one wave (KT score tiles, KT/2 token blocks)
     constexpr int TB = KT / 2;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, n = lane & 15, c = lane >> 4;
-    const int split = blockIdx.x;
-    const int u = blockIdx.y;
-    const int kvh = u % dm.Hkv;
-    const int b = (u / dm.Hkv) % dm.B;
-    const int li = u / (dm.Hkv * dm.B);
+    // grid (split + splits * KV head, sequence, layer): the linear order of the workgroups is (split, unit) and
+    // no index needs a division (the number of splits is a power of two)
+    const int split = SPLIT ? (int)blockIdx.x & (splits - 1) : 0;
+    const int kvh = SPLIT ? (int)blockIdx.x >> lg_splits : (int)blockIdx.x;
+    const int b = blockIdx.y, li = blockIdx.z;
     const int l = l0 + li;
     const int G = dm.G;
+    // the unit's cache length and offset first: everything that touches the cache waits for them
+    const int2 len_off = t.len_off[(int64_t)b * dm.L + l];
     // The token this call appends (Eq.2): every wave fetches its k_new / v_new values first thing (the
     // addresses depend on the block index only), so they are long there when the wave that owns the
     // token needs them.
@@ -116,7 +118,6 @@ __global__ __launch_bounds__(64 * NW) void decode_mfma_kernel(Dims dm, DecodeTab
     for (int j = 0; j < 8; ++j) vnew[j] = v_new[new_src + 16 * j + n];
     vcol[0] = v_new[new_src + lane];
     vcol[1] = v_new[new_src + 64 + lane];
-    const int2 len_off = t.len_off[(int64_t)b * dm.L + l];
     const int64_t unit = ((int64_t)l * dm.B + b) * dm.Hkv + kvh;
     // tokens appended so far: from the host with the launch, or counted on the device (a recorded launch
     // that is replayed): the workgroup that finishes the unit advances the count, after every workgroup
@@ -131,8 +132,12 @@ __global__ __launch_bounds__(64 * NW) void decode_mfma_kernel(Dims dm, DecodeTab
     }
     const int len = len_off.x + appended + 1;
     const int newrow = len - 1;  // the token appended by this call (Eq.2): scored from k_new / v_new, stored to the cache
-    int k0, k1;
-    split_range(len, splits, split, k0, k1);
+    int k0 = 0, k1 = len;
+    if (SPLIT) {  // ceil(len / splits) rounded up to whole 32-token blocks, as split_range
+        const int cs = (((len + splits - 1) >> lg_splits) + 31) & ~31;
+        k0 = split * cs;
+        k1 = min(len, k0 + cs);
+    }
     const int kend = min(k1, newrow);  // the split's keys that are in the cache: [k0, kend)
     const int64_t row0 = ((int64_t)b * dm.Hkv + kvh) * dm.pool_rows + len_off.y;
     bf16_t *kc = (bf16_t *)t.kcache + row0 * D;
@@ -666,7 +671,10 @@ hipError_t launch_decode(hipStream_t s, const Dims &dm, const DevTables &t, int 
                          const LaunchLayers &ll, const void *q_new, const void *k_new, const void *v_new, void *out,
                          int splits, int waves, int tiles, int uniform_appended) {
     if (v_transposed(dtype, dm.D)) {  // one launch: append, attention and merge of the partials
-        const dim3 grid(splits, nl * dm.B * dm.Hkv);
+        if (splits < 1 || (splits & (splits - 1)) != 0) return hipErrorInvalidValue;  // the kernel shifts by log2(splits)
+        int lg_splits = 0;
+        while ((1 << lg_splits) < splits) ++lg_splits;
+        const dim3 grid(splits * dm.Hkv, dm.B, nl);
         DecodeTabs dt;
         dt.len_off = t.len_off;
         dt.kcache = t.kcache;
@@ -684,11 +692,11 @@ hipError_t launch_decode(hipStream_t s, const Dims &dm, const DevTables &t, int 
         if (splits == 1)                                                                                           \
             hipLaunchKernelGGL((decode_mfma_kernel<NW, KT, false>), grid, dim3(64 * NW), 0, s, dm, dt, l0, lbase,  \
                                ds, (const bf16_t *)q_new, (const bf16_t *)k_new, (const bf16_t *)v_new,            \
-                               (bf16_t *)out, splits);                                                             \
+                               (bf16_t *)out, splits, lg_splits);                                                  \
         else                                                                                                       \
             hipLaunchKernelGGL((decode_mfma_kernel<NW, KT, true>), grid, dim3(64 * NW), 0, s, dm, dt, l0, lbase,   \
                                ds, (const bf16_t *)q_new, (const bf16_t *)k_new, (const bf16_t *)v_new,            \
-                               (bf16_t *)out, splits);                                                             \
+                               (bf16_t *)out, splits, lg_splits);                                                  \
     } while (0)
         if (waves == 8 && tiles == 4) AIR_LAUNCH_DECODE(8, 4);
         else if (waves == 4 && tiles == 4) AIR_LAUNCH_DECODE(4, 4);
