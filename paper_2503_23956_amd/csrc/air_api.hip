@@ -154,6 +154,7 @@ air_status air_create(const air_config *cfg, void *workspace, size_t workspace_b
     d.n_chunks = lay.n_chunks;
     d.max_steps = cfg->max_decode_steps;
     d.vis_window = cfg->window_kind == AIR_WINDOW_VISUAL ? 1 : 0;
+    d.inv_B = cfg->batch > 1 ? (uint32_t)(0x100000000ull / (uint64_t)cfg->batch) + 1u : 0u;
     d.pool_rows = lay.pool_rows;
     DevTables &t = c->tab;
     char *w = c->ws;

@@ -116,6 +116,15 @@ __device__ __forceinline__ double wave_max(double v) {
     return fmax(v, __shfl_xor(v, 32, 64));
 }
 
+// Sequence b and layer li of a workgroup whose grid index is z = b + B * li (z < 2^16, B <= 64): the quotient
+// is the high word of z * (floor(2^32 / B) + 1), exact in that range, instead of an integer division in
+// front of the kernel's first loads.
+template <typename DimsT>
+__device__ __forceinline__ void seq_layer_of(const DimsT &dm, int z, int &b, int &li) {
+    li = dm.B == 1 ? z : (int)__umulhi((unsigned)z, dm.inv_B);
+    b = z - li * dm.B;
+}
+
 // Sum over a workgroup of NW waves in a fixed order; every thread gets the result.
 // `scratch` holds NW doubles; the call contains two barriers.
 template <int NW>

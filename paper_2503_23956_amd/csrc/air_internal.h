@@ -47,6 +47,7 @@ struct Dims {
     int32_t L, Hq, Hkv, G, D, B;
     int32_t max_vis, max_window, n_chunks, max_steps;
     int32_t vis_window;  // 1: the window rows are visual tokens (causal over the visual keys, no text columns)
+    uint32_t inv_B;      // floor(2^32 / B) + 1 (unused for B = 1): division of a 16-bit index by B as one multiply
     int64_t pool_rows;
 };
 

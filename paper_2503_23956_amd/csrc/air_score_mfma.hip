@@ -123,10 +123,8 @@ __device__ __forceinline__ void block_logits(const DevTables &t, const UnitCtx &
 __device__ __forceinline__ bool unit_setup(const Dims &dm, const SeqArgs &seqs, int l0, const LaunchLayers &ll,
                                            const air_strides &st, UnitCtx &u, int chunks_per_wg) {
     u.chunk = blockIdx.x * chunks_per_wg;  // first chunk of this workgroup
-    const int uu = blockIdx.y;
-    u.kvh = uu % dm.Hkv;
-    u.b = (uu / dm.Hkv) % dm.B;
-    u.li = uu / (dm.Hkv * dm.B);
+    u.kvh = blockIdx.y;  // grid (chunk group, KV head, sequence + B * layer)
+    seq_layer_of(dm, (int)blockIdx.z, u.b, u.li);
     u.l = l0 + u.li;
     u.sq = seqs.s[u.b];  // from the kernel arguments: no table read in front of the key loads
     if (u.chunk * kChunkKeys >= u.sq.vis_len) return false;
@@ -286,10 +284,7 @@ __device__ __forceinline__ float chunk_factor(float2 part, float M, float w) {
 constexpr int kRowWaves = 16;  // up to one wave per row: a unit's usual dozen rows are then done in one round of loads
 __global__ __launch_bounds__(64 * kRowWaves) void score_rows_mfma_kernel(Dims dm, DevTables t, int l0, SeqArgs seqs) {
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
-    const int uu = blockIdx.x;
-    const int kvh = uu % dm.Hkv;
-    const int b = (uu / dm.Hkv) % dm.B;
-    const int l = l0 + uu / (dm.Hkv * dm.B);
+    const int kvh = blockIdx.x, b = blockIdx.y, l = l0 + (int)blockIdx.z;  // grid (KV head, sequence, layer)
     const int G = dm.G, W = dm.max_window;
     const int64_t hrow0 = ((int64_t)l * dm.B + b) * dm.Hq + (int64_t)kvh * G;
     const int64_t unit = ((int64_t)l * dm.B + b) * dm.Hkv + kvh;
@@ -724,16 +719,16 @@ hipError_t launch_score_mfma(hipStream_t s, const Dims &dm, const DevTables &t, 
                              const LaunchLayers &ll, const air_strides &st, const SeqArgs &seqs, int inline_rows) {
     if (pass == 1)
         hipLaunchKernelGGL(dm.vis_window ? score_stream_kernel<true> : score_stream_kernel<false>,
-                           dim3((dm.n_chunks + kStreamChunks - 1) / kStreamChunks, nl * dm.B * dm.Hkv), dim3(256), 0, s, dm, t, l0,
+                           dim3((dm.n_chunks + kStreamChunks - 1) / kStreamChunks, dm.Hkv, nl * dm.B), dim3(256), 0, s, dm, t, l0,
                            ll, st, seqs);
     else {
-        const dim3 grid((dm.n_chunks + kFinishChunks - 1) / kFinishChunks, nl * dm.B * dm.Hkv);
+        const dim3 grid((dm.n_chunks + kFinishChunks - 1) / kFinishChunks, dm.Hkv, nl * dm.B);
         if (inline_rows && !dm.vis_window) {
             hipLaunchKernelGGL((score_finish_kernel<false, true>), grid, dim3(256), 0, s, dm, t, l0, ll, st, seqs);
             return hipGetLastError();
         }
         // a wave per row when the launch has few units; with many units, 4 waves walk the rows
-        hipLaunchKernelGGL(score_rows_mfma_kernel, dim3(nl * dm.B * dm.Hkv),
+        hipLaunchKernelGGL(score_rows_mfma_kernel, dim3(dm.Hkv, dm.B, nl),
                            dim3(nl * dm.B * dm.Hkv >= 512 ? 256 : 64 * kRowWaves), 0, s, dm, t, l0, seqs);
         hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;

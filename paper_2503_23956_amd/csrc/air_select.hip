@@ -23,9 +23,8 @@ __global__ __launch_bounds__(NT) void select_kernel(Dims dm, DevTables t, int l0
     constexpr int kSpan = NT * REGS;  // scores per sweep
     constexpr int kBinsPer = 2048 / NT;   // bins of the 12-bit histogram per thread
     const int tid = threadIdx.x, wave = tid >> 6;
-    const int64_t unit = (int64_t)l0 * dm.B * dm.Hkv + blockIdx.x;
-    const int b = (blockIdx.x / dm.Hkv) % dm.B;
-    const int l = l0 + blockIdx.x / (dm.Hkv * dm.B);
+    const int b = blockIdx.y, l = l0 + (int)blockIdx.z;  // grid (KV head, sequence, layer)
+    const int64_t unit = ((int64_t)l * dm.B + b) * dm.Hkv + blockIdx.x;
     const uint32_t *key = reinterpret_cast<const uint32_t *>(t.scores + unit * dm.max_vis);
     // A sweep of up to kSpan scores stays in registers for all passes: thread t owns the `per`
     // consecutive scores from base + t * per on.  `per` follows the row capacity (a kernel argument),
@@ -240,10 +239,9 @@ __global__ __launch_bounds__(256) void gather_kernel(Dims dm, DevTables t, int l
 __global__ __launch_bounds__(256) void gather_vt_kernel(Dims dm, DevTables t, int l0, LaunchLayers ll, air_strides st) {
     constexpr int D = 128;
     typedef bf16_t T;
-    const int u = blockIdx.y;
-    const int kvh = u % dm.Hkv;
-    const int b = (u / dm.Hkv) % dm.B;
-    const int li = u / (dm.Hkv * dm.B);
+    const int kvh = blockIdx.y;  // grid (workgroup of the unit, KV head, sequence + B * layer)
+    int b, li;
+    seq_layer_of(dm, (int)blockIdx.z, b, li);
     const int l = l0 + li;
     const air_seq sq = t.seq_tab[b];
     const int kl = t.budgets[(int64_t)b * dm.L + l];
@@ -257,7 +255,7 @@ __global__ __launch_bounds__(256) void gather_vt_kernel(Dims dm, DevTables t, in
     T *vdst = (T *)t.vcache + dst_row0 * D;
     if (t.dec_steps && blockIdx.x == 0 && threadIdx.x == 0) {  // a fresh cache: nothing appended yet, cache-full flag down
         t.dec_steps[unit] = 0;
-        if (blockIdx.y == 0) t.dec_steps[(int64_t)dm.L * dm.B * dm.Hkv] = 0;
+        if (blockIdx.y == 0 && blockIdx.z == 0) t.dec_steps[(int64_t)dm.L * dm.B * dm.Hkv] = 0;
     }
     __shared__ bf16_t tile[32][D + 8];   // V rows, indexed [slot][column]; +8 keeps the 16-byte row alignment and spreads banks
     __shared__ bf16_t ktile[32][D + 8];  // K rows, indexed [row][column]
@@ -327,7 +325,7 @@ hipError_t launch_select(hipStream_t s, const Dims &dm, const DevTables &t, int 
     // thread's slots, so unused ones cost instructions); longer rows are swept 32 per thread at a time
     const int per = (dm.max_vis + nt - 1) / nt;
     const int regs = per <= 8 ? 8 : (per <= 16 ? 16 : kSelRegs);
-    const dim3 grid(nl * dm.B * dm.Hkv);
+    const dim3 grid(dm.Hkv, dm.B, nl);
 #define AIR_SELECT_LAUNCH(NT_, REGS_) hipLaunchKernelGGL((select_kernel<NT_, REGS_>), grid, dim3(NT_), 0, s, dm, t, l0, cap)
     if (nt == 256) {
         if (regs == 8) AIR_SELECT_LAUNCH(256, 8);
@@ -358,7 +356,7 @@ hipError_t launch_gather(hipStream_t s, const Dims &dm, const DevTables &t, int 
         int gx = (4096 + units - 1) / units;
         gx = gx < 2 ? 2 : (gx > 32 ? 32 : gx);
         if (const char *e = getenv("AIR_GATHER_WGS")) gx = atoi(e) >= 1 && atoi(e) <= 64 ? atoi(e) : gx;
-        hipLaunchKernelGGL(gather_vt_kernel, dim3(gx, units), dim3(256), 0, s, dm, t, l0, ll, st);
+        hipLaunchKernelGGL(gather_vt_kernel, dim3(gx, dm.Hkv, nl * dm.B), dim3(256), 0, s, dm, t, l0, ll, st);
         return hipGetLastError();
     }
     if (dtype == AIR_BF16)

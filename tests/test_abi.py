@@ -78,3 +78,14 @@ def test_missing_library_fails_loudly(tmp_path):
 
     with pytest.raises(FileNotFoundError):
         A.load_library(str(tmp_path / "libaircache.so"))
+
+
+def test_index_division_by_batch_as_one_multiply():
+    """The kernels split a grid index z = b + B * layer (z < 2^16, B <= 64) with the high word of
+    z * (floor(2^32 / B) + 1); the quotient must be exact over the whole range."""
+    import numpy as np
+
+    z = np.arange(1 << 16, dtype=np.uint64)
+    for B in range(2, 65):
+        inv = np.uint64((1 << 32) // B + 1)
+        assert np.array_equal((z * inv) >> np.uint64(32), z // np.uint64(B)), B
