@@ -1,6 +1,7 @@
 // air_decode_attn: Eq.2 append, then softmax(q K'^T / sqrt(d)) V' over the compacted cache.
 //
-//   decode_mfma_kernel bf16, head_dim 128, ONE launch per call: one workgroup per (split, unit).
+//   decode_mfma_kernel bf16, head_dim 128, ONE launch per call: one workgroup per (split, unit), the
+//                      grid laid out so that no block index needs an integer division.
 //                      The tiled K' and the block-transposed V' go from global memory straight
 //                      into MFMA operands, every load instruction reading 1 KB of consecutive
 //                      memory; the G query heads of the group are the second MFMA dimension.

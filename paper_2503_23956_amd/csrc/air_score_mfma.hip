@@ -16,7 +16,8 @@
 //       rows per head) it also stashes e = exp(s - m) per (row, key) in fp32, 4 bytes per row
 //       and key against the 256 bytes of the key itself.
 //   score_rows_mfma_kernel  per row: M = max over chunks (and over the elite-text columns),
-//       Z = sum z exp(m - M), weight w = 1 / (R_h G Z).
+//       Z = sum z exp(m - M), weight w = 1 / (R_h G Z).  Launched for the windows that turn their
+//       whole span into rows; the elite window's few rows are done inside the finish kernel.
 //   score_finish_kernel  units with a stash never touch K again:
 //       I[key] = sum_rows e[row][key] * (w exp(m_chunk - M)).  Units with more rows (continuous
 //       or all-text windows) recompute their logits from K_v: I[key] = sum_rows w exp(s - M).
