@@ -192,8 +192,8 @@ __global__ __launch_bounds__(kBT) void budget_kernel(Dims dm, DevTables t, doubl
                 const int64_t unit = ((int64_t)l * dm.B + b) * dm.Hkv + h;
                 const double *mo = t.moments + unit * dm.n_chunks * 3;
                 double S1 = 0.0, S2 = 0.0, S3 = 0.0;
-#pragma unroll 8
-                for (int c = 0; c < nch; ++c) {  // ordered sums; unrolled so that the loads of 8 chunks are in flight together
+#pragma unroll 4
+                for (int c = 0; c < nch; ++c) {  // ordered sums; unrolled so that the loads of 4 entries are in flight together
                     S1 += mo[3 * c + 0];
                     S2 += mo[3 * c + 1];
                     S3 += mo[3 * c + 2];
