@@ -96,7 +96,8 @@ __global__ __launch_bounds__(64 * NW) void decode_mfma_kernel(Dims dm, DecodeTab
     constexpr int D = 128;
     constexpr int kIter = 16 * KT;  // keys per loop iteration of one wave (KT score tiles, KT/2 token blocks)
     constexpr int TB = KT / 2;
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, n = lane & 15, c = lane >> 4;
+    const int lane = threadIdx.x & 63, n = lane & 15, c = lane >> 4;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);  // a scalar: the wave's chunk walk and its branches stay off the vector unit
     // grid (split + splits * KV head, sequence, layer): the linear order of the workgroups is (split, unit) and
     // no index needs a division (the number of splits is a power of two)
     const int split = SPLIT ? (int)blockIdx.x & (splits - 1) : 0;
