@@ -158,7 +158,7 @@ __device__ __forceinline__ int stash_pos(int key_in_chunk) {
 template <bool VIS>
 __global__ __launch_bounds__(256, 4) void score_stream_kernel(Dims dm, DevTables t, int l0, LaunchLayers ll,
                                                               air_strides st, SeqArgs seqs) {
-    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, n = lane & 15, c = lane >> 4;
+    const int tid = threadIdx.x, wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63, n = lane & 15, c = lane >> 4;
     UnitCtx u;
     if (!unit_setup(dm, seqs, l0, ll, st, u, kStreamChunks)) return;
     __shared__ int s_pref[17];
@@ -284,7 +284,7 @@ __device__ __forceinline__ float chunk_factor(float2 part, float M, float w) {
 // that turns a stashed exponential into its share of Eq.8.
 constexpr int kRowWaves = 16;  // up to one wave per row: a unit's usual dozen rows are then done in one round of loads
 __global__ __launch_bounds__(64 * kRowWaves) void score_rows_mfma_kernel(Dims dm, DevTables t, int l0, SeqArgs seqs) {
-    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+    const int tid = threadIdx.x, wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63;
     const int kvh = blockIdx.x, b = blockIdx.y, l = l0 + (int)blockIdx.z;  // grid (KV head, sequence, layer)
     const int G = dm.G, W = dm.max_window;
     const int64_t hrow0 = ((int64_t)l * dm.B + b) * dm.Hq + (int64_t)kvh * G;
@@ -322,7 +322,7 @@ __global__ __launch_bounds__(64 * kRowWaves) void score_rows_mfma_kernel(Dims dm
 template <bool VIS, bool INLINE>
 __global__ __launch_bounds__(256, 4) void score_finish_kernel(Dims dm, DevTables t, int l0, LaunchLayers ll,
                                                            air_strides st, SeqArgs seqs) {
-    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, n = lane & 15, c = lane >> 4;
+    const int tid = threadIdx.x, wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63, n = lane & 15, c = lane >> 4;
     UnitCtx u;
     if (!unit_setup(dm, seqs, l0, ll, st, u, kFinishChunks)) return;
     __shared__ int s_pref[17];
@@ -562,7 +562,7 @@ __device__ __forceinline__ double dot64_wave(const bf16_t *a, const bf16_t *b, i
 
 __global__ __launch_bounds__(64 * kEliteWaves) void elite_mfma_kernel(Dims dm, DevTables t, int l0, LaunchLayers ll, air_strides st,
                                                          SeqArgs seqs, double alpha, double ln_alpha, int gb) {
-    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, n = lane & 15, c = lane >> 4;
+    const int tid = threadIdx.x, wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63, n = lane & 15, c = lane >> 4;
     const int kvh = blockIdx.x, b = blockIdx.y, li = blockIdx.z;
     const int l = l0 + li;
     const air_seq sq = seqs.s[b];

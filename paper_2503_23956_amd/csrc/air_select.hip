@@ -22,7 +22,7 @@ template <int NT, int REGS>
 __global__ __launch_bounds__(NT) void select_kernel(Dims dm, DevTables t, int l0, int cand_cap) {
     constexpr int kSpan = NT * REGS;  // scores per sweep
     constexpr int kBinsPer = 2048 / NT;   // bins of the 12-bit histogram per thread
-    const int tid = threadIdx.x, wave = tid >> 6;
+    const int tid = threadIdx.x, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int b = blockIdx.y, l = l0 + (int)blockIdx.z;  // grid (KV head, sequence, layer)
     const int64_t unit = ((int64_t)l * dm.B + b) * dm.Hkv + blockIdx.x;
     const uint32_t *key = reinterpret_cast<const uint32_t *>(t.scores + unit * dm.max_vis);
