@@ -508,6 +508,22 @@ def test_seeded_random_shapes():
         _run_case(w, ret, alpha=alpha, steps=3, verbose=False)
 
 
+def test_budget_allocation_random_configurations():
+    """Eq.11 with its clamps under seeded random depths, retentions, floors and allocation modes (the clamp at N_v
+    at high retention, the floor at low retention with a large min_keep, both in one allocation): the budgets
+    must be the oracle's allocation of the same statistics in every case."""
+    rng = np.random.default_rng(4242)
+    for it in range(24):
+        base = int(rng.choice([1, 2]))
+        n_vis, n_text, L = int(rng.integers(8, 700)), int(rng.integers(2, 40)), int(rng.integers(1, 20))
+        ret = float(rng.choice([0.005, 0.02, 0.1, 0.3, 0.6, 0.9, 0.97, 1.0]))
+        mode, min_keep = int(rng.integers(0, 4)), int(rng.choice([0, 1, 1, 5, 50]))
+        B = int(rng.integers(1, 4))
+        w = synth.get_workload(base).scaled(cfg_id=500 + it, batch=B, n_layers=L, n_vis=n_vis, n_text=n_text, window=0,
+                                            decode_steps=1, jitter=0.2 if B > 1 else 0.0)
+        _run_case(w, ret, steps=1, budget_mode=mode, min_keep=min_keep, verbose=False)
+
+
 def test_config2_full_size():
     _run_case(synth.get_workload(2), 0.10, steps=2)
 
