@@ -522,6 +522,10 @@ def test_budget_allocation_random_configurations():
         w = synth.get_workload(base).scaled(cfg_id=500 + it, batch=B, n_layers=L, n_vis=n_vis, n_text=n_text, window=0,
                                             decode_steps=1, jitter=0.2 if B > 1 else 0.0)
         _run_case(w, ret, steps=1, budget_mode=mode, min_keep=min_keep, verbose=False)
+    # deeper than one wave has lanes: the workgroup-wide form of the allocation
+    for L, ret, min_keep in ((70, 0.1, 1), (100, 0.97, 0), (129, 0.02, 5)):
+        w = synth.get_workload(1).scaled(cfg_id=600 + L, n_layers=L, n_vis=96, n_text=6, window=0, decode_steps=1)
+        _run_case(w, ret, steps=1, min_keep=min_keep, verbose=False)
 
 
 def test_config2_full_size():
