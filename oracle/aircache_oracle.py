@@ -16,6 +16,8 @@ heads are scored per query head and averaged over the query heads that share a
 KV head; the scale is 1/sqrt(head_dim); Eq.7's softmax runs over the visual
 keys plus that head's elite text keys with no mask; system-prompt tokens are
 never scored and always kept; Eq.10 uses the sample standard deviation; the
+a row whose
+standard deviation is at most 1e-6 of its mean has zero spread (skewness 0); the
 cross-layer normalisation is by shares; budgets are integerised by largest
 remainder after clamping to [min_keep, N_v]; ties in top-k go to the lower
 token index and kept tokens stay in position order.
@@ -181,10 +183,20 @@ def strength(imp: np.ndarray) -> float:
     return float(np.sum(imp))
 
 
+# Relative resolution below which a row's spread counts as zero in Eq.10 (see skewness).
+ZERO_SPREAD_REL = 1e-6
+
+
 def skewness(imp: np.ndarray) -> float:
     """Eq.10: adjusted sample skewness with the sample (n-1) standard deviation.
 
-    Fewer than three tokens, or zero spread, give 0.
+    Fewer than three tokens, or zero spread, give 0.  Eq.10 divides by sigma^3 and the paper
+    does not say what a layer whose visual tokens all score alike gets; the reading taken is
+    0, and "alike" is taken at the resolution at which two scores count as equal anywhere
+    else in the method's contract (1e-6 relative): sigma <= 1e-6 |mu| is zero spread.  An
+    exact test (sigma > 0) would not do: the mean of n equal values is in general not that
+    value in floating point, so a constant row would get +-1 instead of 0, and the skewness
+    of rounding noise is not a property of the layer.
     """
     n = imp.shape[0]
     if n < 3:
@@ -192,9 +204,9 @@ def skewness(imp: np.ndarray) -> float:
     mu = float(np.sum(imp)) / n
     c = imp - mu
     var = float(np.sum(c * c)) / (n - 1)
-    if not var > 0.0:
-        return 0.0
     sigma = math.sqrt(var)
+    if not sigma > ZERO_SPREAD_REL * abs(mu):
+        return 0.0
     z = c / sigma
     return n / ((n - 1.0) * (n - 2.0)) * float(np.sum(z * z * z))
 

@@ -305,6 +305,40 @@ def test_skewness_invariances_and_degenerate_cases():
     assert O.skewness(np.array([1.0, 2.0])) == 0.0
 
 
+def test_skewness_zero_spread_is_taken_at_the_resolution_of_the_scores():
+    # Eq.10 at sigma -> 0 (reading: 0).  A constant row must give 0 whatever its value and length: the mean of
+    # n equal values is not that value in floating point for most values, and an exact "sigma > 0" test then
+    # returns +-1 (the skewness of n copies of one rounding error)
+    for n in (3, 576, 1000, 2304, 7290, 16384):
+        for val in (0.9 / n, 0.37 / n, 1.0 / 3.0, 1e-30):
+            assert O.skewness(np.full(n, val)) == 0.0
+    # spreads below 1e-6 of the mean are zero spread; above it the definition applies unchanged
+    rng = np.random.default_rng(23)
+    base = 0.9 / 7290
+    noise = rng.standard_normal(7290)
+    for rel in (1e-12, 1e-9, 1e-7):
+        assert O.skewness(base * (1.0 + rel * noise)) == 0.0
+    for rel in (1e-5, 1e-3, 1e-1):
+        x = base * (1.0 + rel * rng.exponential(size=7290))
+        assert O.skewness(x) == pytest.approx(scipy.stats.skew(x, bias=False), rel=1e-6)
+        assert O.skewness(x) > 1.0  # an exponential tail: the skewness is 2 in the limit, and it is not cut off
+
+
+def test_identical_visual_keys_give_uniform_importance_and_zero_skewness():
+    # all visual keys equal: every row of Eq.7 spreads its visual mass evenly, I_v = s_t / N_v, Eq.10 -> 0
+    rng = np.random.default_rng(24)
+    d, hq, hkv, ns, nv, nt = 32, 4, 2, 3, 700, 12
+    k = rng.standard_normal((hkv, ns + nv + nt, d))
+    k[:, ns:ns + nv] = k[:, ns:ns + 1]
+    q = rng.standard_normal((hq, nt, d))
+    seg = O.Segments(ns + nv + nt, ns, nv, ns + nv, nt)
+    imp, _ = O.layer_importance(q, k, seg, 0.9)
+    s_t, s_k = O.layer_stats(imp)
+    assert s_k == 0.0
+    assert 0.0 < s_t < 1.0
+    np.testing.assert_allclose(imp, np.broadcast_to(imp.sum(axis=1, keepdims=True) / nv, imp.shape), rtol=1e-12)
+
+
 def test_layer_stats_is_mean_over_kv_heads():
     rng = np.random.default_rng(22)
     imp = rng.gamma(0.4, size=(3, 40)) / 100
