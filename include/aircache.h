@@ -127,6 +127,25 @@ size_t air_workspace_bytes(const air_config *cfg);
 air_status air_create(const air_config *cfg, void *workspace, size_t workspace_bytes, air_ctx **out);
 air_status air_destroy(air_ctx *ctx);
 
+/* Launch-shape overrides for tests and tuning.  They change how the work is cut into workgroups and
+ * never a result; every shape they can force is a shape the library may choose by itself.  A field left
+ * at 0 (select_direct_max: at -1) leaves that choice to the library, which is the state after air_create.
+ * Not part of the method: no passage of the paper stands behind this call.  Nothing in the library reads
+ * the environment. */
+typedef struct {
+    int32_t decode_splits;     /* workgroups per (layer, sequence, KV head) of air_decode_attn: 1, 2, 4, 8 or 16 */
+    int32_t decode_waves;      /* wavefronts per workgroup of air_decode_attn: 1, 2, 4 or 8                     */
+    int32_t decode_tiles;      /* 16-key tiles per loop iteration of a wave: 2, 4 or 8                          */
+    int32_t score_block_mb;    /* MB of K_v scored per pair of passes when a window needs two passes: 1..65536   */
+    int32_t score_rows_kernel; /* 1: the elite window's row parameters by their own kernel                       */
+    int32_t select_threads;    /* workgroup size of the selection kernel: 256 or 512                             */
+    int32_t select_direct_max; /* largest deciding bin that is ranked directly, 0..1024 (0: always the radix
+                                  passes); -1: the library's default                                            */
+    int32_t gather_wgs;        /* workgroups per unit of the compaction gather: 1..64                            */
+} air_tuning;
+/* AIR_ERR_INVALID_ARG (and no change) if a field holds a value outside its list. */
+air_status air_set_tuning(air_ctx *ctx, const air_tuning *tuning);
+
 /* Forget the prompt: the context returns to its state after air_create (no layer scored,
  * no budgets, empty caches) so that the next prompt of the same shape can be compressed.
  * Host bookkeeping only; nothing is enqueued and device memory is left as it is. */
@@ -161,7 +180,8 @@ air_status air_decode_attn(air_ctx *ctx, void *stream, int32_t l0, int32_t l1, c
                            const void *k_new, const void *v_new, void *out);
 
 /* ---- inspection (tests, debugging): these synchronise the device ---- */
-/* importance scores of layer l: host [B][H_kv][max_vis_len] (entries past vis_len are 0) */
+/* importance scores of layer l: host [B][H_kv][max_vis_len], the device buffer as it is (entries past a
+ * sequence's vis_len are never written by the library: zero on a context that has seen one prompt) */
 air_status air_get_scores(air_ctx *ctx, int32_t l, float *host);
 /* elite window of layer l: counts host [B][H_q]; indices host [B][H_q][max_window] (absolute token positions) */
 air_status air_get_elite(air_ctx *ctx, int32_t l, int32_t *counts, int32_t *indices);

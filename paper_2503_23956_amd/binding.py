@@ -44,13 +44,18 @@ class air_layer(C.Structure):
     _fields_ = [("q_text", C.c_void_p), ("k", C.c_void_p), ("v", C.c_void_p)]
 
 
+class air_tuning(C.Structure):
+    _fields_ = [(n, C.c_int32) for n in ("decode_splits", "decode_waves", "decode_tiles", "score_block_mb",
+                                         "score_rows_kernel", "select_threads", "select_direct_max", "gather_wgs")]
+
+
 class air_strides(C.Structure):
     _fields_ = [(n, C.c_int64) for n in ("q_b", "q_h", "q_t", "kv_b", "kv_h", "kv_t")]
 
 
 EXPORTS = (
-    "air_version", "air_workspace_bytes", "air_create", "air_destroy", "air_reset", "air_score", "air_budget",
-    "air_select_compact", "air_decode_attn", "air_get_scores", "air_get_elite", "air_get_stats",
+    "air_version", "air_workspace_bytes", "air_create", "air_destroy", "air_reset", "air_set_tuning", "air_score",
+    "air_budget", "air_select_compact", "air_decode_attn", "air_get_scores", "air_get_elite", "air_get_stats",
     "air_get_budgets", "air_set_budgets", "air_get_indices", "air_set_indices", "air_get_lengths", "air_get_cache",
     "air_last_error",
 )
@@ -83,6 +88,7 @@ def load_library(path: Optional[str] = None):
     lib.air_budget.argtypes = [vp, vp]
     lib.air_select_compact.argtypes = [vp, vp, i32, i32, C.POINTER(air_layer), C.POINTER(air_strides)]
     lib.air_decode_attn.argtypes = [vp, vp, i32, i32, vp, vp, vp, vp]
+    lib.air_set_tuning.argtypes = [vp, C.POINTER(air_tuning)]
     lib.air_get_scores.argtypes = [vp, i32, vp]
     lib.air_get_elite.argtypes = [vp, i32, vp, vp]
     lib.air_get_stats.argtypes = [vp, vp, vp]
@@ -207,6 +213,12 @@ class AirCache:
 
     def air_reset(self):
         self._check(self.lib.air_reset(self.handle))
+
+    def air_set_tuning(self, *, decode_splits=0, decode_waves=0, decode_tiles=0, score_block_mb=0, score_rows_kernel=0,
+                       select_threads=0, select_direct_max=-1, gather_wgs=0):
+        tn = air_tuning(decode_splits, decode_waves, decode_tiles, score_block_mb, score_rows_kernel, select_threads,
+                        select_direct_max, gather_wgs)
+        self._check(self.lib.air_set_tuning(self.handle, C.byref(tn)))
 
     def air_select_compact(self, l0: int, l1: int, k=None, v=None, strides=None, prepared=None):
         p = prepared or self.prepare(None, k, v)

@@ -4,6 +4,7 @@
 #include <stdlib.h>
 #include <string.h>
 
+#include <initializer_list>
 #include <string>
 #include <vector>
 
@@ -79,7 +80,7 @@ WsLayout make_layout(const air_config &c) {
     w.layer_off = take(B * L * 4);
     w.dec_cnt = take(L * B * Hkv * 4);
     w.dec_steps = take((L * B * Hkv + 1) * 4);
-    w.moments = take(L * B * Hkv * (size_t)w.n_chunks * 3 * 8);
+    w.moments = take(L * B * Hkv * (size_t)((w.n_chunks + kFinishChunks - 1) / kFinishChunks) * 4 * 8);
     w.indices = take(L * B * Hkv * NV * 4);
     w.kcache = take(B * Hkv * (size_t)w.pool_rows * D * esz);
     w.vcache = take(B * Hkv * (size_t)w.pool_rows * D * esz);
@@ -109,9 +110,7 @@ struct air_ctx {
     std::vector<char> decoded;  // device_steps: air_decode_attn has been called on the layer since its compaction
     std::vector<char> scored, compacted, fixed_idx;  // fixed_idx: the layer's kept indices were set by the caller
     std::vector<int32_t> appended;
-    int force_splits, force_waves, force_tiles;  // AIR_DECODE_SPLITS / _WAVES / _TILES, 0 = automatic
-    int score_block_mb;             // bytes of K_v scored per pair of passes (AIR_SCORE_BLOCK_MB)
-    bool rows_kernel;               // row parameters by their own kernel also for the elite window (AIR_SCORE_ROWS_KERNEL=1)
+    air_tuning tune;  // launch-shape overrides (air_set_tuning); all automatic after air_create
     std::string err;
 };
 
@@ -152,6 +151,7 @@ air_status air_create(const air_config *cfg, void *workspace, size_t workspace_b
     d.max_vis = cfg->max_vis_len;
     d.max_window = cfg->max_window;
     d.n_chunks = lay.n_chunks;
+    d.n_entries = (lay.n_chunks + kFinishChunks - 1) / kFinishChunks;
     d.max_steps = cfg->max_decode_steps;
     d.vis_window = cfg->window_kind == AIR_WINDOW_VISUAL ? 1 : 0;
     d.inv_B = cfg->batch > 1 ? (uint32_t)(0x100000000ull / (uint64_t)cfg->batch) + 1u : 0u;
@@ -188,26 +188,8 @@ air_status air_create(const air_config *cfg, void *workspace, size_t workspace_b
     t.dec_steps = cfg->device_steps ? (int32_t *)(w + lay.dec_steps) : nullptr;
     c->have_seqs = false;
     c->budgets_ready = false;
-    c->force_splits = c->force_waves = c->force_tiles = 0;
-    if (const char *e = getenv("AIR_DECODE_TILES")) {
-        const int v = atoi(e);
-        if (v == 2 || v == 4 || v == 8) c->force_tiles = v;
-    }
-    if (const char *e = getenv("AIR_DECODE_SPLITS")) {
-        const int v = atoi(e);
-        if (v == 1 || v == 2 || v == 4 || v == 8 || v == 16) c->force_splits = v;
-    }
-    c->score_block_mb = 160;
-    if (const char *e = getenv("AIR_SCORE_BLOCK_MB")) {
-        const int v = atoi(e);
-        if (v >= 1 && v <= 65536) c->score_block_mb = v;
-    }
-    c->rows_kernel = false;
-    if (const char *e = getenv("AIR_SCORE_ROWS_KERNEL")) c->rows_kernel = atoi(e) == 1;
-    if (const char *e = getenv("AIR_DECODE_WAVES")) {
-        const int v = atoi(e);
-        if (v == 1 || v == 2 || v == 4 || v == 8) c->force_waves = v;
-    }
+    memset(&c->tune, 0, sizeof(c->tune));
+    c->tune.select_direct_max = -1;
     c->scored.assign(d.L, 0);
     c->compacted.assign(d.L, 0);
     c->fixed_idx.assign(d.L, 0);
@@ -312,13 +294,13 @@ air_status air_score(air_ctx *ctx, void *stream, int32_t l0, int32_t l1, const a
     int group = lpl;
     // The elite window (alpha > 0) leaves a unit a handful of rows: the finish kernel forms their
     // parameters itself.  A window that turns its whole span into rows gets the row-parameter kernel.
-    const int inline_rows = ctx->cfg.alpha > 0.0 && !ctx->dm.vis_window && !ctx->rows_kernel;
+    const int inline_rows = ctx->cfg.alpha > 0.0 && !ctx->dm.vis_window && ctx->tune.score_rows_kernel != 1;
     // Windows that are known to exceed the stash (alpha = 0 turns the whole candidate span into rows)
     // read K_v twice: run the two kernels over groups of layers whose keys fit the memory-side cache.
     if (mfma && ctx->cfg.alpha == 0.0 && (int64_t)ctx->dm.G * ctx->cfg.max_window > kStashRows) {
         double layer_bytes = 0.0;
         for (int b = 0; b < ctx->cfg.batch; ++b) layer_bytes += (double)seqs[b].vis_len * ctx->cfg.n_kv_heads * 128 * 2;
-        const double block = (double)ctx->score_block_mb * 1048576.0;
+        const double block = (double)(ctx->tune.score_block_mb > 0 ? ctx->tune.score_block_mb : 160) * 1048576.0;
         const int n_groups = (int)ceil(layer_bytes * (l1 - l0) / block);
         group = (l1 - l0 + (n_groups > 0 ? n_groups : 1) - 1) / (n_groups > 0 ? n_groups : 1);
         if (group < 1) group = 1;
@@ -386,8 +368,12 @@ air_status air_select_compact(air_ctx *ctx, void *stream, int32_t l0, int32_t l1
     if (!layers || !strides) return fail(ctx, AIR_ERR_INVALID_ARG, "air_select_compact: null argument");
     if (!range_ok(ctx, l0, l1)) return fail(ctx, AIR_ERR_INVALID_ARG, "air_select_compact: bad layer range");
     if (!ctx->budgets_ready) return fail(ctx, AIR_ERR_STATE, "air_select_compact: budgets not computed");
-    for (int l = l0; l < l1; ++l)
+    for (int l = l0; l < l1; ++l) {
         if (ctx->appended[l] || ctx->decoded[l]) return fail(ctx, AIR_ERR_STATE, "air_select_compact: layer already decoded on");
+        // budgets set by the caller do not need every layer scored, selecting a layer does
+        if (!ctx->scored[l] && !ctx->fixed_idx[l])
+            return fail(ctx, AIR_ERR_STATE, "air_select_compact: layer neither scored nor given fixed indices");
+    }
     air_status st = check_strides(ctx, strides, layers, l1 - l0, false);
     if (st != AIR_OK) return st;
     hipStream_t s = (hipStream_t)stream;
@@ -409,10 +395,10 @@ air_status air_select_compact(air_ctx *ctx, void *stream, int32_t l0, int32_t l1
             }
             int z = a;
             while (z < nl && !ctx->fixed_idx[c0 + z]) ++z;
-            e = launch_select(s, ctx->dm, ctx->tab, c0 + a, z - a);
+            e = launch_select(s, ctx->dm, ctx->tab, c0 + a, z - a, ctx->tune.select_threads, ctx->tune.select_direct_max);
             a = z;
         }
-        if (e == hipSuccess) e = launch_gather(s, ctx->dm, ctx->tab, ctx->cfg.dtype, c0, nl, ll, *strides);
+        if (e == hipSuccess) e = launch_gather(s, ctx->dm, ctx->tab, ctx->cfg.dtype, c0, nl, ll, *strides, ctx->tune.gather_wgs);
         if (e != hipSuccess) return hip_fail(ctx, e, "air_select_compact launch");
     }
     for (int l = l0; l < l1; ++l) ctx->compacted[l] = 1;
@@ -426,7 +412,7 @@ air_status air_select_compact(air_ctx *ctx, void *stream, int32_t l0, int32_t l1
 // through memory (merged by the last workgroup to finish), which costs about as much as two
 // more iterations per wave, so they are added only while a wave would otherwise run more than
 // kItersPerWave iterations at the average cache length and the launch is short of workgroups.
-// AIR_DECODE_SPLITS / AIR_DECODE_WAVES / AIR_DECODE_TILES override the choice (tuning aid).
+// air_set_tuning overrides the choice (tests, tuning).
 static void decode_shape(const air_ctx *ctx, int n_layers_in_launch, int appended, int *splits, int *waves, int *tiles) {
     constexpr int kItersPerWave = 3, kEnoughWorkgroups = 256, kEnoughWaves = 1536;
     const air_config &c = ctx->cfg;
@@ -442,7 +428,7 @@ static void decode_shape(const air_ctx *ctx, int n_layers_in_launch, int appende
     // exchange of the partials (4 units of ~900 keys: 8.4 us against 9.9 us as single workgroups).
     const bool tiny_launch = units <= 16;
     int kt = tiny_launch ? 2 : 4;
-    if (ctx->force_tiles > 0) kt = ctx->force_tiles;
+    if (ctx->tune.decode_tiles > 0) kt = ctx->tune.decode_tiles;
     const int64_t iters = (int64_t)((avg_len + 16.0 * kt - 1.0) / (16.0 * kt));
     // Waves per workgroup: enough for the launch to hold about 1536 waves, and beyond that one wave per 8
     // iterations of the unit.  Many short units run fastest with one wave each (no merge, no barrier:
@@ -450,7 +436,7 @@ static void decode_shape(const air_ctx *ctx, int n_layers_in_launch, int appende
     // enough loads in flight.
     int w = 1;
     while (w < 8 && (units * w < kEnoughWaves || iters >= 16 * w)) w *= 2;
-    if (ctx->force_waves > 0) w = ctx->force_waves;
+    if (ctx->tune.decode_waves > 0) w = ctx->tune.decode_waves;
     if (kt == 8 && w == 8) w = 4;
     int64_t s = 1;
     if (tiny_launch) {
@@ -458,7 +444,7 @@ static void decode_shape(const air_ctx *ctx, int n_layers_in_launch, int appende
     } else {
         while (s < kMaxSplits && iters > (int64_t)kItersPerWave * w * s && units * s < kEnoughWorkgroups) s *= 2;
     }
-    if (ctx->force_splits > 0) s = ctx->force_splits;
+    if (ctx->tune.decode_splits > 0) s = ctx->tune.decode_splits;
     *splits = (int)s;
     *waves = w;
     *tiles = kt;
@@ -478,6 +464,12 @@ air_status air_decode_attn(air_ctx *ctx, void *stream, int32_t l0, int32_t l1, c
             return fail(ctx, AIR_ERR_STATE, "air_decode_attn: max_decode_steps exhausted");
     }
     hipStream_t s = (hipStream_t)stream;
+    DecodeExchange xch;
+    xch.o = ctx->tab.dec_o;
+    xch.ml = ctx->tab.dec_ml;
+    xch.cnt = ctx->tab.dec_cnt;
+    xch.local = 0;
+    xch.stride = kMaxSplits;
     // The MFMA kernel takes any number of layers per launch when they have all appended the same number of
     // tokens (the usual case: the layers decode in step), as long as the grid fits; otherwise the per-layer
     // counts travel with the launch, kMaxLayersPerLaunch layers at a time.
@@ -493,14 +485,30 @@ air_status air_decode_attn(air_ctx *ctx, void *stream, int32_t l0, int32_t l1, c
         int splits = 1, waves = 1, tiles = 4;
         // a recorded launch is replayed at every cache length: its shape is chosen for the middle of the decode
         decode_shape(ctx, nl, ctx->cfg.device_steps ? ctx->cfg.max_decode_steps / 2 : ctx->appended[c0], &splits, &waves, &tiles);
-        hipError_t e = launch_decode(s, ctx->dm, ctx->tab, ctx->cfg.dtype, c0, nl, c0 - l0, ll, q_new, k_new, v_new,
-                                     out, splits, waves, tiles, in_step ? ctx->appended[l0] : -1);
+        hipError_t e = launch_decode(s, ctx->dm, ctx->tab, xch, ctx->cfg.dtype, c0, nl, c0 - l0, ll, q_new, k_new, v_new, out,
+                                     splits, waves, tiles, in_step ? ctx->appended[l0] : -1);
         if (e != hipSuccess) return hip_fail(ctx, e, "air_decode_attn launch");
     }
     for (int l = l0; l < l1; ++l) {
         if (ctx->cfg.device_steps) ctx->decoded[l] = 1;
         else ctx->appended[l] += 1;
     }
+    return AIR_OK;
+}
+
+air_status air_set_tuning(air_ctx *ctx, const air_tuning *tn) {
+    if (!ctx || !tn) return AIR_ERR_INVALID_ARG;
+    auto one_of = [](int v, std::initializer_list<int> ok) {
+        for (int x : ok)
+            if (v == x) return true;
+        return false;
+    };
+    if (!one_of(tn->decode_splits, {0, 1, 2, 4, 8, 16}) || !one_of(tn->decode_waves, {0, 1, 2, 4, 8}) ||
+        !one_of(tn->decode_tiles, {0, 2, 4, 8}) || tn->score_block_mb < 0 || tn->score_block_mb > 65536 ||
+        !one_of(tn->score_rows_kernel, {0, 1}) || !one_of(tn->select_threads, {0, 256, 512}) ||
+        tn->select_direct_max < -1 || tn->select_direct_max > 1024 || tn->gather_wgs < 0 || tn->gather_wgs > 64)
+        return fail(ctx, AIR_ERR_INVALID_ARG, "air_set_tuning: a field holds a value outside its list");
+    ctx->tune = *tn;
     return AIR_OK;
 }
 
@@ -538,13 +546,7 @@ air_status air_get_scores(air_ctx *ctx, int32_t l, float *host) {
     if (l < 0 || l >= ctx->cfg.n_layers) return fail(ctx, AIR_ERR_INVALID_ARG, "bad layer");
     if (!ctx->scored[l]) return fail(ctx, AIR_ERR_STATE, "layer not scored");
     const size_t n = (size_t)ctx->dm.B * ctx->dm.Hkv * ctx->dm.max_vis;
-    air_status st = d2h(ctx, host, ctx->tab.scores + (size_t)l * n, n * 4);
-    if (st != AIR_OK) return st;
-    for (int b = 0; b < ctx->dm.B; ++b)  // entries past a sequence's visual span read as 0
-        for (int h = 0; h < ctx->dm.Hkv; ++h)
-            for (int i = ctx->seqs[b].vis_len; i < ctx->dm.max_vis; ++i)
-                host[((size_t)b * ctx->dm.Hkv + h) * ctx->dm.max_vis + i] = 0.f;
-    return AIR_OK;
+    return d2h(ctx, host, ctx->tab.scores + (size_t)l * n, n * 4);  // the device's own buffer, padding included
 }
 
 air_status air_get_elite(air_ctx *ctx, int32_t l, int32_t *counts, int32_t *indices) {

@@ -166,7 +166,7 @@ __global__ __launch_bounds__(kBT) void budget_kernel(Dims dm, DevTables t, doubl
     const int tid = threadIdx.x;
     const int b = blockIdx.x;
     const int L = dm.L;
-    const air_seq sq = seqs.s[b];  // from the kernel arguments: no table read in front of the power sums
+    const air_seq sq = seqs.s[b];  // from the kernel arguments: no table read in front of the moment entries
     const int n_vis = sq.vis_len;
     __shared__ double w[kBT], x[kBT], frac[kBT], sh_t[kBT], sh_k[kBT];
     __shared__ int kk[kBT];
@@ -184,31 +184,35 @@ __global__ __launch_bounds__(kBT) void budget_kernel(Dims dm, DevTables t, doubl
     const bool stage = L * dm.Hkv <= AIR_MAX_LAYERS * 16;  // unit statistics fit the LDS staging arrays
     if (!skip_allocation) {
         if (use_moments) {
-            // Eq.9-10 of every (layer, KV head) from the power sums of the importance row (one entry per
-            // kFinishChunks chunks)
-            const int nch = ((n_vis + kChunkKeys - 1) / kChunkKeys + kFinishChunks - 1) / kFinishChunks;  // entries per unit
+            // Eq.9-10 of every (layer, KV head) from the moment entries of its importance row: entry c holds
+            // the sum S1_c, the mean m_c and the moments M2_c, M3_c about m_c of the n_c scores of kFinishChunks
+            // chunks.  With d_c = m_c - mu the central moments of the row are
+            //   sum (x - mu)^2 = sum_c M2_c + n_c d_c^2,   sum (x - mu)^3 = sum_c M3_c + 3 d_c M2_c + n_c d_c^3,
+            // sums of terms no larger than their result (raw power sums would cancel on rows of little spread).
+            constexpr int kEntryKeys = kFinishChunks * kChunkKeys;
+            const int nch = (n_vis + kEntryKeys - 1) / kEntryKeys;  // entries per unit
             for (int p = tid; p < L * dm.Hkv; p += kBT) {
                 const int l = p / dm.Hkv, h = p % dm.Hkv;
                 const int64_t unit = ((int64_t)l * dm.B + b) * dm.Hkv + h;
-                const double *mo = t.moments + unit * dm.n_chunks * 3;
-                double S1 = 0.0, S2 = 0.0, S3 = 0.0;
+                const double *mo = t.moments + unit * dm.n_entries * 4;
+                double S1 = 0.0;
 #pragma unroll 4
-                for (int c = 0; c < nch; ++c) {  // ordered sums; unrolled so that the loads of 4 entries are in flight together
-                    S1 += mo[3 * c + 0];
-                    S2 += mo[3 * c + 1];
-                    S3 += mo[3 * c + 2];
-                }
+                for (int c = 0; c < nch; ++c) S1 += mo[4 * c];  // ordered sum; unrolled so that the loads of 4 entries are in flight together
                 double sk = 0.0;
                 if (n_vis >= 3) {
                     const double n = (double)n_vis;
                     const double mu = S1 / n;
-                    const double c2 = S2 - S1 * mu;                           // sum (x - mu)^2
-                    const double c3 = S3 - 3.0 * mu * S2 + 2.0 * mu * mu * S1;  // sum (x - mu)^3
-                    const double var = c2 / (n - 1.0);
-                    if (var > 0.0) {
-                        const double sigma = sqrt(var);
-                        sk = n / ((n - 1.0) * (n - 2.0)) * (c3 / (sigma * sigma * sigma));
+                    double c2 = 0.0, c3 = 0.0;
+#pragma unroll 4
+                    for (int c = 0; c < nch; ++c) {
+                        const double nc = (double)min(kEntryKeys, n_vis - c * kEntryKeys);
+                        const double dl = mo[4 * c + 1] - mu, M2 = mo[4 * c + 2], M3 = mo[4 * c + 3];
+                        c2 += M2 + nc * (dl * dl);
+                        c3 += (M3 + 3.0 * dl * M2) + nc * (dl * dl * dl);
                     }
+                    const double sigma = sqrt(c2 / (n - 1.0));
+                    // zero spread (Eq.10 undefined; taken as 0): a standard deviation at most 1e-6 of the mean
+                    if (sigma > 1e-6 * fabs(mu)) sk = n / ((n - 1.0) * (n - 2.0)) * (c3 / (sigma * sigma * sigma));
                 }
                 t.unit_st[unit] = S1;
                 t.unit_sk[unit] = sk;

@@ -82,6 +82,8 @@ struct DecodeTabs {
     int32_t *dec_cnt;
     int32_t *dec_steps;  // null: the host passes the count of appended tokens (DecodeSteps)
     int32_t n_units;     // units of the whole context: dec_steps[n_units] is the cache-full flag
+    int32_t x_local;     // 1: the exchange slots (dec_o, dec_ml, dec_cnt) are indexed by the unit inside the launch (0 for the workspace's area)
+    int32_t x_stride;    // exchange slots per unit
 };
 struct DecodeSteps {
     int32_t uniform;  // >= 0: every layer of the launch has appended this many tokens (any number of layers per launch)
@@ -417,9 +419,10 @@ __global__ __launch_bounds__(64 * NW) void decode_mfma_kernel(Dims dm, DecodeTab
     // writers wait for their stores to complete before the workgroup counts itself, and the
     // workgroup that counts last reads them.  This keeps the exchange off the whole-L2 write-back
     // that a release fence would cost.  Layout of one partial: [tile j][lane][4] floats.
-    const int64_t part = unit * kMaxSplits + split;
-    float *pu = t.dec_o + unit * kMaxSplits * (int64_t)kMaxGroup * D;
-    const __amdgpu_buffer_rsrc_t prs = __builtin_amdgcn_make_buffer_rsrc(pu, 0, kMaxSplits * kMaxGroup * D * 4, 0x00020000);
+    const int64_t xu = t.x_local ? ((int64_t)li * dm.B + b) * dm.Hkv + kvh : unit;  // the unit's exchange slots
+    const int64_t part = xu * t.x_stride + split;
+    float *pu = t.dec_o + xu * t.x_stride * (int64_t)kMaxGroup * D;
+    const __amdgpu_buffer_rsrc_t prs = __builtin_amdgcn_make_buffer_rsrc(pu, 0, t.x_stride * kMaxGroup * D * 4, 0x00020000);
     if (4 * c < G) {
 #pragma unroll
         for (int jj = 0; jj < kTiles; ++jj)
@@ -440,16 +443,16 @@ __global__ __launch_bounds__(64 * NW) void decode_mfma_kernel(Dims dm, DecodeTab
     }
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();
-    if (threadIdx.x == 0) s_prev = __hip_atomic_fetch_add(&t.dec_cnt[unit], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    if (threadIdx.x == 0) s_prev = __hip_atomic_fetch_add(&t.dec_cnt[xu], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     __syncthreads();
     if (s_prev != splits - 1) return;
-    if (threadIdx.x == 0) __hip_atomic_store(&t.dec_cnt[unit], 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);  // next launch
+    if (threadIdx.x == 0) __hip_atomic_store(&t.dec_cnt[xu], 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);  // next launch
 
     // merge of the splits: every wave loads the partial tiles it owns (one round of loads), the
     // (max, sum) pairs go through LDS
     __shared__ float s_m[kMaxSplits][kMaxGroup], s_l[kMaxSplits][kMaxGroup], s_w[kMaxSplits][kMaxGroup];
     __shared__ float s_inv[kMaxGroup];
-    const float *ml = reinterpret_cast<const float *>(t.dec_ml + unit * kMaxSplits * G);
+    const float *ml = reinterpret_cast<const float *>(t.dec_ml + xu * t.x_stride * G);
     f32x4 num[kTiles];
 #pragma unroll
     for (int jj = 0; jj < kTiles; ++jj) num[jj] = (f32x4){0.f, 0.f, 0.f, 0.f};
@@ -513,8 +516,8 @@ __global__ __launch_bounds__(64 * NW) void decode_mfma_kernel(Dims dm, DecodeTab
 // per output column for P.V', online softmax over blocks of 256 keys.
 // ---------------------------------------------------------------------------------------
 template <typename T, int D>
-__global__ __launch_bounds__(256) void decode_kernel(Dims dm, DevTables t, int l0, int lbase, LaunchLayers ll,
-                                                     const T *q_new, int splits) {
+__global__ __launch_bounds__(256) void decode_kernel(Dims dm, DevTables t, DecodeExchange x, int l0, int lbase,
+                                                     LaunchLayers ll, const T *q_new, int splits) {
     constexpr int NP = 256 / D;  // key-parallel parts in the P*V phase
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
     const int split = blockIdx.x;
@@ -602,8 +605,8 @@ __global__ __launch_bounds__(256) void decode_kernel(Dims dm, DevTables t, int l
     for (int g = 0; g < kMaxGroup; ++g)
         if (g < G) s_o[part][g][dcol] = acc[g];
     __syncthreads();
-    const int64_t pidx = unit * kMaxSplits + split;
-    float *po = t.dec_o + pidx * (int64_t)G * D;
+    const int64_t pidx = (x.local ? (int64_t)u : unit) * x.stride + split;
+    float *po = x.o + pidx * (int64_t)G * D;
     for (int idx = tid; idx < G * D; idx += 256) {
         const int g = idx / D, cc = idx % D;
         float o = 0.f;
@@ -611,11 +614,11 @@ __global__ __launch_bounds__(256) void decode_kernel(Dims dm, DevTables t, int l
         for (int p = 0; p < NP; ++p) o += s_o[p][g][cc];
         po[idx] = o;
     }
-    if (tid < G) t.dec_ml[pidx * G + tid] = make_float2(s_m[tid], s_l[tid]);
+    if (tid < G) x.ml[pidx * G + tid] = make_float2(s_m[tid], s_l[tid]);
 }
 
 template <typename T, int D>
-__global__ __launch_bounds__(256) void combine_kernel(Dims dm, DevTables t, int l0, int lbase, T *out, int splits) {
+__global__ __launch_bounds__(256) void combine_kernel(Dims dm, DecodeExchange x, int l0, int lbase, T *out, int splits) {
     const int u = blockIdx.x;
     const int kvh = u % dm.Hkv;
     const int b = (u / dm.Hkv) % dm.B;
@@ -623,8 +626,9 @@ __global__ __launch_bounds__(256) void combine_kernel(Dims dm, DevTables t, int 
     const int l = l0 + li;
     const int G = dm.G;
     const int64_t unit = ((int64_t)l * dm.B + b) * dm.Hkv + kvh;
-    const float2 *ml = t.dec_ml + unit * kMaxSplits * G;
-    const float *po = t.dec_o + unit * kMaxSplits * (int64_t)G * D;
+    const int64_t xu = x.local ? (int64_t)u : unit;
+    const float2 *ml = x.ml + xu * x.stride * G;
+    const float *po = x.o + xu * x.stride * (int64_t)G * D;
     T *o = out + (((int64_t)(lbase + li) * dm.B + b) * dm.Hq + (int64_t)kvh * G) * D;
     for (int idx = threadIdx.x; idx < G * D; idx += 256) {
         const int g = idx / D;
@@ -657,21 +661,21 @@ static hipError_t launch_append(hipStream_t s, const Dims &dm, const DevTables &
 }
 
 template <typename T, int D>
-static hipError_t decode_launch(hipStream_t s, const Dims &dm, const DevTables &t, int l0, int nl, int lbase,
-                                const LaunchLayers &ll, const void *q_new, void *out, int splits) {
+static hipError_t decode_launch(hipStream_t s, const Dims &dm, const DevTables &t, const DecodeExchange &x, int l0, int nl,
+                                int lbase, const LaunchLayers &ll, const void *q_new, void *out, int splits) {
     const int units = nl * dm.B * dm.Hkv;
-    hipLaunchKernelGGL((decode_kernel<T, D>), dim3(splits, units), dim3(256), 0, s, dm, t, l0, lbase, ll,
+    hipLaunchKernelGGL((decode_kernel<T, D>), dim3(splits, units), dim3(256), 0, s, dm, t, x, l0, lbase, ll,
                        (const T *)q_new, splits);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL((combine_kernel<T, D>), dim3(units), dim3(256), 0, s, dm, t, l0, lbase, (T *)out, splits);
+    hipLaunchKernelGGL((combine_kernel<T, D>), dim3(units), dim3(256), 0, s, dm, x, l0, lbase, (T *)out, splits);
     return hipGetLastError();
 }
 
 // Generic path: append, split-K attention, combine (three launches).
-hipError_t launch_decode(hipStream_t s, const Dims &dm, const DevTables &t, int dtype, int l0, int nl, int lbase,
-                         const LaunchLayers &ll, const void *q_new, const void *k_new, const void *v_new, void *out,
-                         int splits, int waves, int tiles, int uniform_appended) {
+hipError_t launch_decode(hipStream_t s, const Dims &dm, const DevTables &t, const DecodeExchange &x, int dtype, int l0,
+                         int nl, int lbase, const LaunchLayers &ll, const void *q_new, const void *k_new,
+                         const void *v_new, void *out, int splits, int waves, int tiles, int uniform_appended) {
     if (v_transposed(dtype, dm.D)) {  // one launch: append, attention and merge of the partials
         if (splits < 1 || (splits & (splits - 1)) != 0) return hipErrorInvalidValue;  // the kernel shifts by log2(splits)
         int lg_splits = 0;
@@ -681,9 +685,11 @@ hipError_t launch_decode(hipStream_t s, const Dims &dm, const DevTables &t, int 
         dt.len_off = t.len_off;
         dt.kcache = t.kcache;
         dt.vcache = t.vcache;
-        dt.dec_o = t.dec_o;
-        dt.dec_ml = t.dec_ml;
-        dt.dec_cnt = t.dec_cnt;
+        dt.dec_o = x.o;
+        dt.dec_ml = x.ml;
+        dt.dec_cnt = x.cnt;
+        dt.x_local = x.local;
+        dt.x_stride = x.stride;
         dt.dec_steps = t.dec_steps;
         dt.n_units = dm.L * dm.B * dm.Hkv;
         DecodeSteps ds;
@@ -716,9 +722,9 @@ hipError_t launch_decode(hipStream_t s, const Dims &dm, const DevTables &t, int 
     }
     hipError_t e = launch_append(s, dm, t, dtype, l0, nl, lbase, ll, k_new, v_new);
     if (e != hipSuccess) return e;
-    if (dtype == AIR_BF16) return decode_launch<bf16_t, 64>(s, dm, t, l0, nl, lbase, ll, q_new, out, splits);
-    return dm.D == 128 ? decode_launch<float, 128>(s, dm, t, l0, nl, lbase, ll, q_new, out, splits)
-                       : decode_launch<float, 64>(s, dm, t, l0, nl, lbase, ll, q_new, out, splits);
+    if (dtype == AIR_BF16) return decode_launch<bf16_t, 64>(s, dm, t, x, l0, nl, lbase, ll, q_new, out, splits);
+    return dm.D == 128 ? decode_launch<float, 128>(s, dm, t, x, l0, nl, lbase, ll, q_new, out, splits)
+                       : decode_launch<float, 64>(s, dm, t, x, l0, nl, lbase, ll, q_new, out, splits);
 }
 
 }  // namespace air

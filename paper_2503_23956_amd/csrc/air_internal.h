@@ -14,7 +14,7 @@ constexpr int kMaxLayersPerLaunch = 32;
 constexpr int kMaxSplits = 16;        // largest split-K factor of the decode attention
 constexpr int kCacheRowAlign = 32;    // layer regions of the compacted cache start on multiples of this
 constexpr int kGatherRows = 32;       // rows copied per workgroup in the compaction gather
-constexpr int kFinishChunks = 4;      // chunks finished (and summed into one power-sum entry) per workgroup of air_score's last kernel
+constexpr int kFinishChunks = 4;      // chunks finished (and summed into one moment entry) per workgroup of air_score's last kernel
 constexpr int kStashRows = 32;        // window rows per unit up to which air_score stashes exponentials (one pass over K_v)
 
 struct LayerPtrs {
@@ -46,6 +46,7 @@ struct WsLayout {
 struct Dims {
     int32_t L, Hq, Hkv, G, D, B;
     int32_t max_vis, max_window, n_chunks, max_steps;
+    int32_t n_entries;   // moment entries per unit: one per workgroup of air_score's last kernel, ceil(n_chunks / kFinishChunks)
     int32_t vis_window;  // 1: the window rows are visual tokens (causal over the visual keys, no text columns)
     uint32_t inv_B;      // floor(2^32 / B) + 1 (unused for B = 1): division of a 16-bit index by B as one multiply
     int64_t pool_rows;
@@ -67,6 +68,18 @@ struct DevTables {
     int32_t *dec_steps;  // tokens appended so far per unit when the device counts them (else null); one overflow flag after the last unit
 };
 
+// Where the workgroups of a decode launch exchange their split-K partials: per unit `stride` slots of
+// (16 x head_dim partial outputs, (max, sum) per head) and one arrival counter.  The workspace's area is
+// indexed by the context-wide unit (calls on different layers may overlap); an area shared between
+// contexts would be indexed by the unit inside the launch.
+struct DecodeExchange {
+    float *o;
+    float2 *ml;
+    int32_t *cnt;
+    int32_t local;   // 1: slots indexed by the unit inside the launch
+    int32_t stride;  // slots per unit
+};
+
 WsLayout make_layout(const air_config &cfg);
 
 // ---- kernel launchers (each returns the hipError_t of its launch) ----
@@ -85,12 +98,13 @@ hipError_t launch_score_mfma(hipStream_t s, const Dims &dm, const DevTables &t, 
                              const LaunchLayers &ll, const air_strides &st, const SeqArgs &seqs, int inline_rows);
 hipError_t launch_budget(hipStream_t s, const Dims &dm, const DevTables &t, double retention, int mode,
                          int min_keep, int skip_allocation, int use_moments, const SeqArgs &seqs);
-hipError_t launch_select(hipStream_t s, const Dims &dm, const DevTables &t, int l0, int nl);
+hipError_t launch_select(hipStream_t s, const Dims &dm, const DevTables &t, int l0, int nl, int threads, int direct_max);
 hipError_t launch_gather(hipStream_t s, const Dims &dm, const DevTables &t, int dtype, int l0, int nl,
-                         const LaunchLayers &ll, const air_strides &st);
-hipError_t launch_decode(hipStream_t s, const Dims &dm, const DevTables &t, int dtype, int l0, int nl, int lbase,
-                         const LaunchLayers &ll, const void *q_new, const void *k_new, const void *v_new, void *out,
-                         int splits, int waves, int tiles, int uniform_appended);
+                         const LaunchLayers &ll, const air_strides &st, int wgs_per_unit);
+hipError_t launch_decode(hipStream_t s, const Dims &dm, const DevTables &t, const DecodeExchange &x, int dtype, int l0,
+                         int nl, int lbase, const LaunchLayers &ll, const void *q_new, const void *k_new,
+                         const void *v_new, void *out, int splits, int waves, int tiles, int uniform_appended);
+
 
 // The bf16 / head_dim 128 cache is laid out so that the decode kernel can feed it to MFMA straight
 // from global memory, every load instruction of a wave reading 1 KB of consecutive memory, and so

@@ -367,11 +367,10 @@ __global__ __launch_bounds__(256) void stats_kernel(Dims dm, DevTables t, int l0
     if (threadIdx.x == 0) {
         double sk = 0.0;
         if (n >= 3) {
-            const double var = s2 / (double)(n - 1);
-            if (var > 0.0) {
-                const double sigma = sqrt(var);
+            const double sigma = sqrt(s2 / (double)(n - 1));
+            // zero spread (Eq.10 undefined; taken as 0): a standard deviation at most 1e-6 of the mean
+            if (sigma > 1e-6 * fabs(mu))
                 sk = (double)n / (((double)n - 1.0) * ((double)n - 2.0)) * (s3 / (sigma * sigma * sigma));
-            }
         }
         t.unit_st[unit] = s_t;
         t.unit_sk[unit] = sk;

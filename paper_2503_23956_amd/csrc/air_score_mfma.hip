@@ -21,7 +21,9 @@
 //   score_finish_kernel  units with a stash never touch K again:
 //       I[key] = sum_rows e[row][key] * (w exp(m_chunk - M)).  Units with more rows (continuous
 //       or all-text windows) recompute their logits from K_v: I[key] = sum_rows w exp(s - M).
-//       Epilogue: fp64 power sums of I over the chunk, from which the budget kernel forms Eq.9-10.
+//       Epilogue: the workgroup's sum of I and its second and third moments about the workgroup's own
+//       mean (fp64), which the budget kernel shifts to the row mean and adds up for Eq.9-10.  Raw power
+//       sums would cancel on rows of little spread: S2 - S1 mu loses (mu / sigma)^2 of its digits.
 #include "air_device.h"
 #include "air_internal.h"
 #include <type_traits>
@@ -315,7 +317,7 @@ __global__ __launch_bounds__(64 * kRowWaves) void score_rows_mfma_kernel(Dims dm
 }
 
 // ---------------------------------------------------------------------------------------
-// One workgroup finishes kFinishChunks consecutive chunks of a unit and leaves one power-sum entry.
+// One workgroup finishes kFinishChunks consecutive chunks of a unit and leaves one moment entry.
 // INLINE: no row-parameter kernel has run; every workgroup forms the parameters of the unit's rows
 // itself from the chunk partials (the elite window's handful of rows: cheaper than a launch).
 
@@ -345,21 +347,40 @@ __global__ __launch_bounds__(256, 4) void score_finish_kernel(Dims dm, DevTables
     const bool stash = u.R_total <= kStashRows;
     if (!INLINE && !stash) head_prefix(t, u.hrow0, u.G, s_pref);
 
-    // fp64 power sums of I over the workgroup's chunks, summed in a fixed order; one entry per workgroup
-    double m1 = 0.0, m2 = 0.0, m3 = 0.0;
-    auto put_moments = [&]() {
-        m1 = wave_sum(m1);
+    // Moments of the workgroup's scores, every sum in a fixed order: S1 = sum x, the workgroup mean S1 / n, then
+    // M2 = sum (x - mean)^2 and M3 = sum (x - mean)^3 in fp64.  One entry (S1, mean, M2, M3) per workgroup.
+    const int n_wg = min(u.sq.vis_len, last * kChunkKeys) - first * kChunkKeys;  // scores of this workgroup
+    auto wg_sum = [&](double v, int slot) {
+        v = wave_sum(v);
+        if (lane == 0) s_mom[wave][slot] = v;
+        lds_barrier();
+        return ((s_mom[0][slot] + s_mom[1][slot]) + s_mom[2][slot]) + s_mom[3][slot];
+    };
+    auto put_moments = [&](const auto &x, const auto &ok) __attribute__((always_inline)) {
+        constexpr int NX = sizeof(x) / sizeof(x[0]);
+        double s1 = 0.0;
+#pragma unroll
+        for (int i = 0; i < NX; ++i) s1 += ok[i] ? (double)x[i] : 0.0;
+        const double S1 = wg_sum(s1, 0);
+        const double mean = S1 / (double)n_wg;
+        double m2 = 0.0, m3 = 0.0;
+#pragma unroll
+        for (int i = 0; i < NX; ++i) {
+            const double dlt = ok[i] ? (double)x[i] - mean : 0.0;
+            m2 += dlt * dlt;
+            m3 += dlt * dlt * dlt;
+        }
         m2 = wave_sum(m2);
         m3 = wave_sum(m3);
         if (lane == 0) {
-            s_mom[wave][0] = m1;
             s_mom[wave][1] = m2;
             s_mom[wave][2] = m3;
         }
         lds_barrier();
-        if (tid < 3) {
-            double *mo = t.moments + (u.unit * dm.n_chunks + blockIdx.x) * 3;
-            mo[tid] = ((s_mom[0][tid] + s_mom[1][tid]) + s_mom[2][tid]) + s_mom[3][tid];
+        if (tid < 4) {
+            double *mo = t.moments + (u.unit * dm.n_entries + blockIdx.x) * 4;
+            const double r = tid == 0 ? S1 : (tid == 1 ? mean : ((s_mom[0][tid - 1] + s_mom[1][tid - 1]) + s_mom[2][tid - 1]) + s_mom[3][tid - 1]);
+            mo[tid] = r;
         }
     };
 
@@ -428,7 +449,8 @@ __global__ __launch_bounds__(256, 4) void score_finish_kernel(Dims dm, DevTables
         };
         static_assert(kFinishChunks == 4, "one wave of the workgroup per chunk");
         static_assert(kStashRows == 32, "rows beyond 16 are taken in a second round of 16");
-        if (u.R_total == 0) {  // no window row: the importance is zero (and so are its power sums)
+        bool ok[4] = {false, false, false, false};
+        if (u.R_total == 0) {  // no window row: the importance is zero (and so are its moments)
             for (int key = first * kChunkKeys + tid; key < min(last * kChunkKeys, u.sq.vis_len); key += 256)
                 t.scores[u.unit * dm.max_vis + key] = 0.f;
         } else {
@@ -452,17 +474,13 @@ __global__ __launch_bounds__(256, 4) void score_finish_kernel(Dims dm, DevTables
 #pragma unroll
                 for (int i = 0; i < 4; ++i) {
                     const int key = chunk * kChunkKeys + 64 * (lane >> 4) + 16 * i + (lane & 15);
-                    if (key < u.sq.vis_len) {
-                        t.scores[u.unit * dm.max_vis + key] = imp[i];
-                        const double x = (double)imp[i];
-                        m1 += x;
-                        m2 += x * x;
-                        m3 += x * x * x;
-                    }
+                    ok[i] = key < u.sq.vis_len;
+                    if (ok[i]) t.scores[u.unit * dm.max_vis + key] = imp[i];
                 }
             }
         }
-        put_moments();
+        const float xs[4] = {imp[0], imp[1], imp[2], imp[3]};
+        put_moments(xs, ok);
         return;
     }
     // recompute path: (M, w) of a block of rows staged from the row tables
@@ -528,16 +546,21 @@ __global__ __launch_bounds__(256, 4) void score_finish_kernel(Dims dm, DevTables
             float v = acc[tile];
             v += __shfl_xor(v, 16, 64);
             v += __shfl_xor(v, 32, 64);
-            if (c == 0 && valid[tile]) {
-                t.scores[u.unit * dm.max_vis + key0 + 16 * tile + n] = v;
-                const double x = (double)v;
-                m1 += x;
-                m2 += x * x;
-                m3 += x * x * x;
-            }
+            if (c == 0 && valid[tile]) t.scores[u.unit * dm.max_vis + key0 + 16 * tile + n] = v;
         }
     }
-    put_moments();
+    // the moments need every score of the workgroup at once: each lane reads back the ones it stored itself
+    float xs[kFinishChunks * 4];
+    bool ok[kFinishChunks * 4];
+#pragma unroll
+    for (int ci = 0; ci < kFinishChunks; ++ci)
+#pragma unroll
+        for (int tile = 0; tile < 4; ++tile) {
+            const int key = (first + ci) * kChunkKeys + wave * 64 + 16 * tile + n;
+            ok[4 * ci + tile] = c == 0 && first + ci < last && key < u.sq.vis_len;
+            xs[4 * ci + tile] = ok[4 * ci + tile] ? t.scores[u.unit * dm.max_vis + key] : 0.f;
+        }
+    put_moments(xs, ok);
 }
 
 // ---------------------------------------------------------------------------------------

@@ -7,7 +7,6 @@
 //   gather_kernel  K' = [K_sys ; K_v[idx] ; K_t], V' likewise, as 16-byte vector copies.
 #include "air_device.h"
 #include "air_internal.h"
-#include <stdlib.h>
 
 namespace air {
 
@@ -312,15 +311,15 @@ __global__ __launch_bounds__(256) void gather_vt_kernel(Dims dm, DevTables t, in
     }
 }
 
-hipError_t launch_select(hipStream_t s, const Dims &dm, const DevTables &t, int l0, int nl) {
-    // AIR_SELECT_CAND (tuning / test aid): largest deciding bin that is ranked directly, 0 = always take the radix passes
-    int cap = kSelCand;
-    if (const char *e = getenv("AIR_SELECT_CAND")) cap = atoi(e) < kSelCand ? (atoi(e) < 0 ? 0 : atoi(e)) : kSelCand;
+// threads: 256 | 512, 0 = chosen here; direct_max: largest deciding bin that is ranked directly (0 = always the radix
+// passes), negative = kSelCand
+hipError_t launch_select(hipStream_t s, const Dims &dm, const DevTables &t, int l0, int nl, int threads, int direct_max) {
+    const int cap = direct_max < 0 || direct_max > kSelCand ? kSelCand : direct_max;
     // Many short rows take workgroups of 256 threads (cheaper barriers and scans, more workgroups per CU:
     // 1792 rows of ~2500 scores 23 us against 38 us); few long rows are faster with 512 (112 rows of 7290
-    // scores 13.7 us against 16.3 us).  AIR_SELECT_THREADS = 256 | 512 overrides (tuning aid).
+    // scores 13.7 us against 16.3 us).
     int nt = (dm.max_vis <= 4096 && nl * dm.B * dm.Hkv >= 256) ? 256 : kSelThreads;
-    if (const char *e = getenv("AIR_SELECT_THREADS")) nt = atoi(e) == 256 ? 256 : (atoi(e) == 512 ? 512 : nt);
+    if (threads == 256 || threads == 512) nt = threads;
     // registers per thread: the smallest compiled count that holds a whole row (every pass walks all of a
     // thread's slots, so unused ones cost instructions); longer rows are swept 32 per thread at a time
     const int per = (dm.max_vis + nt - 1) / nt;
@@ -348,14 +347,14 @@ static hipError_t gather_launch(hipStream_t s, const Dims &dm, const DevTables &
 }
 
 hipError_t launch_gather(hipStream_t s, const Dims &dm, const DevTables &t, int dtype, int l0, int nl,
-                         const LaunchLayers &ll, const air_strides &st) {
+                         const LaunchLayers &ll, const air_strides &st, int wgs_per_unit) {
     if (v_transposed(dtype, dm.D)) {
         // workgroups per unit: about 4096 in the launch, so that with many units each workgroup walks several
-        // blocks of 32 rows (the next block's reads run under the current block's stores); AIR_GATHER_WGS overrides
+        // blocks of 32 rows (the next block's reads run under the current block's stores); wgs_per_unit > 0 overrides
         const int units = nl * dm.B * dm.Hkv;
         int gx = (4096 + units - 1) / units;
         gx = gx < 2 ? 2 : (gx > 32 ? 32 : gx);
-        if (const char *e = getenv("AIR_GATHER_WGS")) gx = atoi(e) >= 1 && atoi(e) <= 64 ? atoi(e) : gx;
+        if (wgs_per_unit >= 1 && wgs_per_unit <= 64) gx = wgs_per_unit;
         hipLaunchKernelGGL(gather_vt_kernel, dim3(gx, dm.Hkv, nl * dm.B), dim3(256), 0, s, dm, t, l0, ll, st);
         return hipGetLastError();
     }

@@ -74,3 +74,20 @@ def test_stage_order_shapes_and_capacity_are_enforced():
     ac.air_score(0, L, q, k, v, seqs)
     ac.air_budget()
     assert np.array_equal(ac.air_get_budgets(), budgets)
+    # budgets handed in by the caller do not need every layer scored, but selecting a layer does: an unscored
+    # layer is refused (its score rows would be the previous prompt's), a scored one and one with fixed indices go through
+    ac.air_reset()
+    ac.air_score(0, 1, q[:1], k[:1], v[:1], seqs)
+    ac.air_set_budgets(budgets)
+    assert status(ac.air_select_compact, 0, L, k=k, v=v) == B.AIR_ERR_STATE
+    assert status(ac.air_select_compact, 1, 2, k=k[1:], v=v[1:]) == B.AIR_ERR_STATE
+    idx = np.zeros((1, w.n_kv_heads, ac.cfg.max_vis_len), dtype=np.int32)
+    idx[:, :, :] = np.arange(ac.cfg.max_vis_len)
+    ac.air_set_indices(1, idx)
+    ac.air_select_compact(0, L, k=k, v=v)
+    assert np.array_equal(ac.air_get_indices(1)[0, 0, : budgets[0, 1]], np.arange(budgets[0, 1]))
+    # launch-shape overrides outside their lists are refused and change nothing
+    assert status(ac.air_set_tuning, decode_splits=3) == B.AIR_ERR_INVALID_ARG
+    assert status(ac.air_set_tuning, select_threads=128) == B.AIR_ERR_INVALID_ARG
+    ac.air_set_tuning(decode_splits=2, decode_waves=4)
+    ac.close()

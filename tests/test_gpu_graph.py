@@ -36,18 +36,18 @@ def _contexts(w, steps, dev):
 
 
 @pytest.mark.parametrize("shape", [(1, 8, 4), (4, 4, 4), None])
-def test_replayed_decode_step_matches_eager_calls(monkeypatch, shape):
+def test_replayed_decode_step_matches_eager_calls(shape):
     import torch
 
     from paper_2503_23956_amd.device_inputs import to_device, to_host
 
-    if shape is not None:  # the same launch shape on both sides makes the outputs bitwise comparable
-        for name, val in zip(("AIR_DECODE_SPLITS", "AIR_DECODE_WAVES", "AIR_DECODE_TILES"), shape):
-            monkeypatch.setenv(name, str(val))
     dev = torch.device("cuda:0")
     steps = 37  # crosses a 32-token block of the cache
     w = synth.get_workload(2).scaled(n_layers=3, n_vis=900, n_text=40, decode_steps=steps)
     A, eager, counted, compress, seqs, layers = _contexts(w, steps, dev)
+    if shape is not None:  # the same launch shape on both sides makes the outputs bitwise comparable
+        for ac in (eager, counted):
+            ac.air_set_tuning(decode_splits=shape[0], decode_waves=shape[1], decode_tiles=shape[2])
     L, B, Hkv, G, d = w.n_layers, w.batch, w.n_kv_heads, w.group, w.head_dim
     ins = []
     for step in range(steps):

@@ -12,7 +12,7 @@ pytestmark = pytest.mark.gpu
 
 
 def _run_case(w, retention, *, alpha=None, steps=2, layer_chunk=None, token_major=False, budget_mode=0,
-              min_keep=1, check_decode_units=None, verbose=True, visual_window=None):
+              min_keep=1, check_decode_units=None, verbose=True, visual_window=None, tuning=None, oracle_steps=None):
     """Full pipeline on the GPU, checked stage by stage against the oracle.
 
     Stages after the budget are fed the oracle's budgets when the GPU's differ from them (the
@@ -41,6 +41,8 @@ def _run_case(w, retention, *, alpha=None, steps=2, layer_chunk=None, token_majo
     cfg = config_for(w, retention, alpha=alpha, budget_mode=budget_mode, min_keep=min_keep, max_decode_steps=max(steps, 1),
                      seqs=seqs, window_kind=0 if visual_window is None else A.AIR_WINDOW_VISUAL)
     ac = A.AirCache(cfg, dev)
+    if tuning:
+        ac.air_set_tuning(**tuning)  # launch shapes the library would not pick for this size by itself
     tag = f"[{w.name} r={retention} alpha={alpha}]"
 
     # ---- inputs: generate layer by layer, upload, run the oracle's first loop on the host copy
@@ -319,14 +321,13 @@ def test_all_text_window_with_more_rows_than_one_staging_round():
     _run_case(w, 0.10, alpha=0.0, steps=1)
 
 
-def test_elite_window_row_parameters_by_their_own_kernel(monkeypatch):
+def test_elite_window_row_parameters_by_their_own_kernel():
     """The elite window's row parameters are formed inside the finish kernel; the separate row-parameter
     kernel (the path of the windows that turn their whole span into rows) must give the same on it, with the
     rows in the stash (alpha 0.9) and beyond it (alpha 0.05: most text tokens are elite)."""
-    monkeypatch.setenv("AIR_SCORE_ROWS_KERNEL", "1")
     w = synth.get_workload(2).scaled(n_layers=2, n_vis=1100, n_text=48, decode_steps=1)
-    _run_case(w, 0.10, steps=1)
-    _run_case(w, 0.10, alpha=0.05, steps=1)
+    _run_case(w, 0.10, steps=1, tuning=dict(score_rows_kernel=1))
+    _run_case(w, 0.10, alpha=0.05, steps=1, tuning=dict(score_rows_kernel=1))
 
 
 def test_elite_window_with_more_rows_than_the_stash_holds():
@@ -377,14 +378,11 @@ def test_decode_long_cache_multiple_iterations_per_split():
 
 
 @pytest.mark.parametrize("splits,waves,tiles", [(4, 8, 4), (1, 2, 2), (2, 4, 2), (1, 1, 8), (16, 1, 4), (2, 2, 8), (1, 1, 4)])
-def test_decode_forced_launch_shapes(monkeypatch, splits, waves, tiles):
+def test_decode_forced_launch_shapes(splits, waves, tiles):
     # every compiled launch shape of the decode kernel (split-K exchange, 32-key double-buffered chunks,
     # 128-key chunks) against the oracle, with appends that cross token-block and split boundaries
-    monkeypatch.setenv("AIR_DECODE_SPLITS", str(splits))
-    monkeypatch.setenv("AIR_DECODE_WAVES", str(waves))
-    monkeypatch.setenv("AIR_DECODE_TILES", str(tiles))
     w = synth.get_workload(2).scaled(n_layers=2, n_vis=900, n_text=37, decode_steps=36)
-    _run_case(w, 0.25, steps=36)
+    _run_case(w, 0.25, steps=36, tuning=dict(decode_splits=splits, decode_waves=waves, decode_tiles=tiles))
 
 
 @pytest.mark.parametrize("side", [+1, -1])
@@ -441,23 +439,19 @@ def test_topk_exact_ties_go_to_the_lower_index(monkeypatch):
 
 
 @pytest.mark.parametrize("cap", [0, 8])
-def test_select_radix_fallback(monkeypatch, cap):
+def test_select_radix_fallback(cap):
     # the selection kernel ranks the deciding 12-bit bin directly when it is small; a cap of 0 (or one
     # that the bin exceeds) sends every row through the four radix passes instead
-    monkeypatch.setenv("AIR_SELECT_CAND", str(cap))
     w = synth.get_workload(2).scaled(n_layers=3, n_vis=5000, n_text=40, decode_steps=1)
-    _run_case(w, 0.10, steps=1)
+    _run_case(w, 0.10, steps=1, tuning=dict(select_direct_max=cap))
 
 
 @pytest.mark.parametrize("threads,n_vis,cap", [(256, 1500, None), (256, 9000, None), (256, 5000, 0), (512, 1500, None)])
-def test_select_workgroup_sizes(monkeypatch, threads, n_vis, cap):
+def test_select_workgroup_sizes(threads, n_vis, cap):
     # both workgroup sizes of the selection kernel, whatever the launch would choose by itself: rows kept
     # in registers (1500, 5000 scores), a row walked in sweeps (9000 scores with 256 threads), the radix passes
-    monkeypatch.setenv("AIR_SELECT_THREADS", str(threads))
-    if cap is not None:
-        monkeypatch.setenv("AIR_SELECT_CAND", str(cap))
     w = synth.get_workload(2).scaled(n_layers=2, n_vis=n_vis, n_text=40, decode_steps=1)
-    _run_case(w, 0.10, steps=1)
+    _run_case(w, 0.10, steps=1, tuning=dict(select_threads=threads, select_direct_max=-1 if cap is None else cap))
 
 
 def test_maximum_candidate_span():
@@ -562,3 +556,92 @@ def test_config5_72b_stress_full_size():
 def test_config5_shape_retention_extremes(retention):
     w = synth.get_workload(5).scaled(n_layers=6)
     _run_case(w, retention, steps=2, check_decode_units=_sample_units(w, 24, 6))
+
+
+# ---------------------------------------------------------------------------------------
+# Eq.10 on importance rows of little or no spread
+# ---------------------------------------------------------------------------------------
+def _low_spread_layers(w, seqs, kinds):
+    """Layer inputs whose visual keys are, per layer kind:
+         "normal"    the generator's
+         "equal"     copies of one key                         -> importance exactly uniform, zero spread
+         "sub"       copies + k 2^-21 in one element, k = 0..3 -> spread of a few 1e-8 of the mean (below what fp32 scores resolve)
+         "small"     copies + k 2^-6 in that element           -> spread of about 1e-3 of the mean
+    (bf16 and fp32 both hold these values exactly)."""
+    out = []
+    for l, kind in enumerate(kinds):
+        li = synth.layer_inputs(w, l, seqs)
+        if kind != "normal":
+            k = synth.storage_to_f64(li.k)
+            rng = np.random.default_rng([77, l])
+            for b, s in enumerate(seqs):
+                vis = slice(s.vis_start, s.vis_start + s.vis_len)
+                k[b, :, vis] = k[b, :, s.vis_start:s.vis_start + 1]
+                k[b, :, vis, 5] = 0.0
+                if kind != "equal":
+                    step = 2.0 ** -21 if kind == "sub" else 2.0 ** -6
+                    k[b, :, vis, 5] = step * rng.integers(0, 4, size=(k.shape[1], s.vis_len))
+            kk = synth.f32_to_bf16_bits(k.astype(np.float32)) if w.dtype == "bf16" else k.astype(np.float32)
+            assert np.array_equal(synth.storage_to_f64(kk)[~np.isnan(k)], k[~np.isnan(k)])  # exactly representable
+            li = type(li)(li.q_text, kk, li.v)
+        out.append(li)
+    return out
+
+
+@pytest.mark.parametrize("base,n_vis,batch", [(2, 3000, 1), (3, 2500, 3), (1, 900, 1)])
+def test_skewness_of_rows_with_little_or_no_spread(base, n_vis, batch):
+    """Eq.10 where its sums cancel: layers whose visual keys are all equal, equal up to differences the fp32 scores
+    cannot resolve, and equal up to a relative 1e-3, next to ordinary layers (skewness 15-40).  Checked: the
+    skewness the library reports against (i) Eq.10 evaluated by the oracle on the library's own fp32 scores, to
+    fp64 rounding, (ii) the oracle's own value within what the score tolerance allows, and the budgets that follow
+    (a skewness off by orders of magnitude would hand one layer the whole skewness share of Eq.11)."""
+    import torch
+
+    import paper_2503_23956_amd as A
+    from paper_2503_23956_amd.device_inputs import config_for, to_device
+
+    dev = torch.device("cuda:0")
+    kinds = ["normal", "equal", "sub", "small", "normal", "equal"]
+    w = synth.get_workload(base).scaled(cfg_id=800 + base, batch=batch, n_layers=len(kinds), n_vis=n_vis, n_text=40,
+                                        window=0, decode_steps=1, jitter=0.1 if batch > 1 else 0.0)
+    seqs = w.seqs()
+    L, B, Hkv = w.n_layers, w.batch, w.n_kv_heads
+    layers = _low_spread_layers(w, seqs, kinds)
+    ac = A.AirCache(config_for(w, 0.10, seqs=seqs, max_decode_steps=1), dev)
+    q = [to_device(li.q_text, dev) for li in layers]
+    k = [to_device(li.k, dev) for li in layers]
+    v = [to_device(li.v, dev) for li in layers]
+    ac.air_score(0, L, q, k, v, seqs)
+    ac.air_budget()
+    g_st, g_sk = ac.air_get_stats()
+    o_st, o_sk, own_sk = np.zeros((B, L)), np.zeros((B, L)), np.zeros((B, L))
+    bound = np.zeros((B, L))
+    for l in range(L):
+        sc, _, a, c = P.oracle_score_layer(w, layers[l], seqs, w.alpha)
+        o_st[:, l], o_sk[:, l] = a, c
+        g = ac.air_get_scores(l)
+        eps = P.check_scores(g, sc, seqs, f"layer {l} ({kinds[l]})")  # worst relative score error, <= 1e-5
+        for b, s in enumerate(seqs):
+            rows = g[b][:, : s.vis_len].astype(np.float64)
+            own_sk[b, l] = np.mean([O.skewness(r) for r in rows])
+            # a relative score error eps moves z = (x - mu) / sigma by eps mu / sigma, and Eq.10 by 3 times that
+            # per unit of mean z^2 (and of the skewness itself through sigma)
+            rel_spread = min(max(r.std() / r.mean(), 1e-300) for r in synth.storage_to_f64(np.asarray(sc[b])))
+            bound[b, l] = 3.0 * eps / rel_spread * (1.0 + abs(c[b])) + P.STAT_RTOL * abs(c[b]) + 1e-9
+    np.testing.assert_allclose(g_st, o_st, rtol=P.STAT_RTOL)
+    # (i) Eq.10 itself, on equal inputs: only the order of the fp64 sums differs
+    np.testing.assert_allclose(g_sk, own_sk, rtol=1e-7, atol=1e-7)
+    for l, kind in enumerate(kinds):
+        if kind in ("equal", "sub"):  # zero spread on both sides, exactly
+            assert np.all(g_sk[:, l] == 0.0) and np.all(o_sk[:, l] == 0.0), (kind, g_sk[:, l], o_sk[:, l])
+        else:
+            assert np.all(np.abs(g_sk[:, l] - o_sk[:, l]) <= bound[:, l]), (kind, g_sk[:, l], o_sk[:, l], bound[:, l])
+        if kind == "small":  # a real, small spread: the value is the definition's, not noise
+            assert np.all(np.abs(g_sk[:, l] - o_sk[:, l]) <= 0.05 * (1.0 + np.abs(o_sk[:, l]))), (g_sk[:, l], o_sk[:, l])
+    g_bud = ac.air_get_budgets()
+    assert np.array_equal(g_bud, P.oracle_budgets(g_st, g_sk, seqs, 0.10))
+    o_bud = P.oracle_budgets(o_st, o_sk, seqs, 0.10)
+    assert np.array_equal(g_bud.sum(axis=1), o_bud.sum(axis=1)) and np.abs(g_bud - o_bud).max() <= 1, (g_bud, o_bud)
+    print(f"[low spread base={base}] s_k gpu {np.round(g_sk[0], 6).tolist()} oracle {np.round(o_sk[0], 6).tolist()} "
+          f"budgets {g_bud[0].tolist()}", flush=True)
+    ac.close()
