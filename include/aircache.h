@@ -179,6 +179,21 @@ air_status air_select_compact(air_ctx *ctx, void *stream, int32_t l0, int32_t l1
 air_status air_decode_attn(air_ctx *ctx, void *stream, int32_t l0, int32_t l1, const void *q_new,
                            const void *k_new, const void *v_new, void *out);
 
+/* air_decode_attn for callers that must not allocate and whose workspace must not serve as scratch: code
+ * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, same
+ * results (bit for bit) as air_decode_attn; the one difference is where the workgroups of a unit exchange
+ * their split-K partials and arrival counters: in a fixed array of 8.1 MiB inside the library's device image
+ * (every GPU the library runs on holds its copy until the process ends) instead of the workspace.  The call
+ * allocates nothing and calls no allocating routine.
+ *   - Limit: a launch that exchanges partials may have at most 1024 (unit, split) pairs, unit = (layer,
+ *     sequence, KV head) of the call; beyond that the call returns AIR_ERR_SHAPE before anything is launched
+ *     (pass fewer layers per call).  Launches with one workgroup per unit exchange nothing and have no limit.
+ *   - The array is shared by every context and call on one GPU and keeps the last call's contents; the call
+ *     clears the counters it needs with a small kernel first.  Calls that overlap on one GPU (two streams,
+ *     two contexts, two threads) race on it: serialise them. */
+air_status air_decode_attn_static(air_ctx *ctx, void *stream, int32_t l0, int32_t l1, const void *q_new,
+                                  const void *k_new, const void *v_new, void *out);
+
 /* ---- inspection (tests, debugging): these synchronise the device ---- */
 /* importance scores of layer l: host [B][H_kv][max_vis_len], the device buffer as it is (entries past a
  * sequence's vis_len are never written by the library: zero on a context that has seen one prompt) */

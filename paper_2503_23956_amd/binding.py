@@ -55,7 +55,7 @@ class air_strides(C.Structure):
 
 EXPORTS = (
     "air_version", "air_workspace_bytes", "air_create", "air_destroy", "air_reset", "air_set_tuning", "air_score",
-    "air_budget", "air_select_compact", "air_decode_attn", "air_get_scores", "air_get_elite", "air_get_stats",
+    "air_budget", "air_select_compact", "air_decode_attn", "air_decode_attn_static", "air_get_scores", "air_get_elite", "air_get_stats",
     "air_get_budgets", "air_set_budgets", "air_get_indices", "air_set_indices", "air_get_lengths", "air_get_cache",
     "air_last_error",
 )
@@ -88,6 +88,7 @@ def load_library(path: Optional[str] = None):
     lib.air_budget.argtypes = [vp, vp]
     lib.air_select_compact.argtypes = [vp, vp, i32, i32, C.POINTER(air_layer), C.POINTER(air_strides)]
     lib.air_decode_attn.argtypes = [vp, vp, i32, i32, vp, vp, vp, vp]
+    lib.air_decode_attn_static.argtypes = [vp, vp, i32, i32, vp, vp, vp, vp]
     lib.air_set_tuning.argtypes = [vp, C.POINTER(air_tuning)]
     lib.air_get_scores.argtypes = [vp, i32, vp]
     lib.air_get_elite.argtypes = [vp, i32, vp, vp]
@@ -231,6 +232,11 @@ class AirCache:
         ptr = lambda x: x if isinstance(x, int) else _ptr(x)  # noqa: E731
         self._check(self.lib.air_decode_attn(self.handle, self._stream(), l0, l1, ptr(q_new), ptr(k_new),
                                              ptr(v_new), ptr(out)))
+
+    def air_decode_attn_static(self, l0: int, l1: int, q_new, k_new, v_new, out):
+        ptr = lambda x: x if isinstance(x, int) else _ptr(x)  # noqa: E731
+        self._check(self.lib.air_decode_attn_static(self.handle, self._stream(), l0, l1, ptr(q_new), ptr(k_new),
+                                                    ptr(v_new), ptr(out)))
 
     # -- inspection ------------------------------------------------------------------
     def air_get_scores(self, l: int) -> np.ndarray:

@@ -196,7 +196,8 @@ air_status air_create(const air_config *cfg, void *workspace, size_t workspace_b
     c->appended.assign(d.L, 0);
     c->decoded.assign(d.L, 0);
     // scores past a sequence's visual span and the small tables start at zero
-    hipError_t e = hipMemset(w + lay.scores, 0, lay.unit_st - lay.scores);
+    hipError_t e = static_exchange(nullptr);  // address of the static exchange area on this device, looked up once
+    if (e == hipSuccess) e = hipMemset(w + lay.scores, 0, lay.unit_st - lay.scores);
     if (e == hipSuccess) e = hipMemset(w + lay.seq_tab, 0, lay.part - lay.seq_tab);
     if (e == hipSuccess) e = hipMemset(w + lay.unit_st, 0, lay.indices - lay.unit_st);
     if (e == hipSuccess) e = hipDeviceSynchronize();
@@ -450,8 +451,9 @@ static void decode_shape(const air_ctx *ctx, int n_layers_in_launch, int appende
     *tiles = kt;
 }
 
-air_status air_decode_attn(air_ctx *ctx, void *stream, int32_t l0, int32_t l1, const void *q_new, const void *k_new,
-                           const void *v_new, void *out) {
+// use_static: the split-K partials are exchanged through the library's static device array instead of the workspace
+static air_status decode_attn(air_ctx *ctx, void *stream, int32_t l0, int32_t l1, const void *q_new, const void *k_new,
+                              const void *v_new, void *out, bool use_static) {
     if (!ctx) return AIR_ERR_INVALID_ARG;
     if (!q_new || !k_new || !v_new || !out) return fail(ctx, AIR_ERR_INVALID_ARG, "air_decode_attn: null argument");
     if (((uintptr_t)q_new & 15) || ((uintptr_t)k_new & 15) || ((uintptr_t)v_new & 15) || ((uintptr_t)out & 15))
@@ -470,6 +472,10 @@ air_status air_decode_attn(air_ctx *ctx, void *stream, int32_t l0, int32_t l1, c
     xch.cnt = ctx->tab.dec_cnt;
     xch.local = 0;
     xch.stride = kMaxSplits;
+    if (use_static) {
+        hipError_t e = static_exchange(&xch);
+        if (e != hipSuccess) return hip_fail(ctx, e, "air_decode_attn_static: address of the static exchange area");
+    }
     // The MFMA kernel takes any number of layers per launch when they have all appended the same number of
     // tokens (the usual case: the layers decode in step), as long as the grid fits; otherwise the per-layer
     // counts travel with the launch, kMaxLayersPerLaunch layers at a time.
@@ -477,16 +483,38 @@ air_status air_decode_attn(air_ctx *ctx, void *stream, int32_t l0, int32_t l1, c
     for (int l = l0 + 1; l < l1 && in_step; ++l) in_step = ctx->appended[l] == ctx->appended[l0];
     const int64_t units_per_layer = (int64_t)ctx->dm.B * ctx->dm.Hkv;
     const int max_nl = in_step ? (int)(65535 / units_per_layer) : layers_per_launch(ctx);  // grid.y <= 65535
+    // launch shapes first: a static exchange area that is too small must be found before anything is launched
+    auto shape_of = [&](int c0, int nl, int *splits, int *waves, int *tiles) {
+        // a recorded launch is replayed at every cache length: its shape is chosen for the middle of the decode
+        decode_shape(ctx, nl, ctx->cfg.device_steps ? ctx->cfg.max_decode_steps / 2 : ctx->appended[c0], splits, waves, tiles);
+    };
+    for (int c0 = l0; use_static && c0 < l1; c0 += max_nl) {
+        const int nl = (l1 - c0 < max_nl) ? l1 - c0 : max_nl;
+        int splits = 1, waves = 1, tiles = 4;
+        shape_of(c0, nl, &splits, &waves, &tiles);
+        const bool exchanges = splits > 1 || !v_transposed(ctx->cfg.dtype, ctx->cfg.head_dim);  // the generic kernels always go through partials
+        if (exchanges && (int64_t)nl * units_per_layer * splits > (int64_t)kStaticSlots)
+            return fail(ctx, AIR_ERR_SHAPE, "air_decode_attn_static: the launch needs " +
+                                                std::to_string((int64_t)nl * units_per_layer * splits) +
+                                                " (unit, split) exchange slots, the static area holds " +
+                                                std::to_string(kStaticSlots) + "; pass fewer layers per call");
+    }
     for (int c0 = l0; c0 < l1; c0 += max_nl) {
         const int nl = (l1 - c0 < max_nl) ? l1 - c0 : max_nl;
         LaunchLayers ll;
         memset(&ll, 0, sizeof(ll));
         for (int i = 0; i < nl && !in_step; ++i) ll.appended[i] = ctx->appended[c0 + i];
         int splits = 1, waves = 1, tiles = 4;
-        // a recorded launch is replayed at every cache length: its shape is chosen for the middle of the decode
-        decode_shape(ctx, nl, ctx->cfg.device_steps ? ctx->cfg.max_decode_steps / 2 : ctx->appended[c0], &splits, &waves, &tiles);
-        hipError_t e = launch_decode(s, ctx->dm, ctx->tab, xch, ctx->cfg.dtype, c0, nl, c0 - l0, ll, q_new, k_new, v_new, out,
-                                     splits, waves, tiles, in_step ? ctx->appended[l0] : -1);
+        shape_of(c0, nl, &splits, &waves, &tiles);
+        hipError_t e = hipSuccess;
+        if (use_static) {
+            xch.stride = splits;
+            // the area keeps the last call's contents: the arrival counters of this launch start at zero
+            if (splits > 1) e = launch_zero_counters(s, xch.cnt, (int)(nl * units_per_layer));
+        }
+        if (e == hipSuccess)
+            e = launch_decode(s, ctx->dm, ctx->tab, xch, ctx->cfg.dtype, c0, nl, c0 - l0, ll, q_new, k_new, v_new, out,
+                              splits, waves, tiles, in_step ? ctx->appended[l0] : -1);
         if (e != hipSuccess) return hip_fail(ctx, e, "air_decode_attn launch");
     }
     for (int l = l0; l < l1; ++l) {
@@ -494,6 +522,16 @@ air_status air_decode_attn(air_ctx *ctx, void *stream, int32_t l0, int32_t l1, c
         else ctx->appended[l] += 1;
     }
     return AIR_OK;
+}
+
+air_status air_decode_attn(air_ctx *ctx, void *stream, int32_t l0, int32_t l1, const void *q_new, const void *k_new,
+                           const void *v_new, void *out) {
+    return decode_attn(ctx, stream, l0, l1, q_new, k_new, v_new, out, false);
+}
+
+air_status air_decode_attn_static(air_ctx *ctx, void *stream, int32_t l0, int32_t l1, const void *q_new,
+                                  const void *k_new, const void *v_new, void *out) {
+    return decode_attn(ctx, stream, l0, l1, q_new, k_new, v_new, out, true);
 }
 
 air_status air_set_tuning(air_ctx *ctx, const air_tuning *tn) {

@@ -13,9 +13,65 @@
 #include "air_device.h"
 #include "air_internal.h"
 
+#include <mutex>
+
 namespace air {
 
 constexpr int kMaxGroup = 16;
+
+// ---------------------------------------------------------------------------------------
+// Split-K exchange area of the entry point that allocates nothing (air_decode_attn_static): a fixed array in
+// the library's own device image instead of the caller's workspace.  Every GPU the library runs on holds its own
+// copy at its own address; host code only ever uses the address hipGetSymbolAddress returns for the current
+// device (the array's name is a host-side stand-in, not a device address).
+//   [arrival counters: kStaticSlots ints][(max, sum) pairs: kStaticSlots x 16][partial outputs: kStaticSlots x 16 x 128 floats]
+// ---------------------------------------------------------------------------------------
+constexpr size_t kStaticCntBytes = kStaticSlots * sizeof(int32_t);
+constexpr size_t kStaticMlBytes = kStaticSlots * kMaxGroup * sizeof(float2);
+constexpr size_t kStaticOBytes = kStaticSlots * kMaxGroup * 128 * sizeof(float);
+constexpr size_t kStaticScratchBytes = kStaticCntBytes + kStaticMlBytes + kStaticOBytes;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+constexpr int kMaxDevices = 64;
+static void *g_scratch_ptr[kMaxDevices];  // per device, filled on first use with that device current
+static std::mutex g_scratch_mutex;
+
+hipError_t static_exchange(DecodeExchange *x) {
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+    void *ptr = nullptr;
+    {
+        std::lock_guard<std::mutex> lock(g_scratch_mutex);
+        if (!g_scratch_ptr[dev]) {
+            e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+            if (e != hipSuccess) return e;
+            if (!ptr) return hipErrorInvalidSymbol;
+            g_scratch_ptr[dev] = ptr;
+        }
+        ptr = g_scratch_ptr[dev];
+    }
+    if (x) {
+        char *base = (char *)ptr;
+        x->cnt = (int32_t *)base;
+        x->ml = (float2 *)(base + kStaticCntBytes);
+        x->o = (float *)(base + kStaticCntBytes + kStaticMlBytes);
+        x->local = 1;
+        x->stride = 0;  // set per launch: the launch's own split count
+    }
+    return hipSuccess;
+}
+
+// counters of a launch start at zero (a kernel, not a memset: the call may be recorded into a graph)
+__global__ __launch_bounds__(256) void zero_counters_kernel(int32_t *p, int n) {
+    const int i = blockIdx.x * 256 + threadIdx.x;
+    if (i < n) p[i] = 0;
+}
+hipError_t launch_zero_counters(hipStream_t s, int32_t *p, int n) {
+    hipLaunchKernelGGL(zero_counters_kernel, dim3((n + 255) / 256), dim3(256), 0, s, p, n);
+    return hipGetLastError();
+}
 
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(4))) float f32x4;
@@ -82,7 +138,7 @@ struct DecodeTabs {
     int32_t *dec_cnt;
     int32_t *dec_steps;  // null: the host passes the count of appended tokens (DecodeSteps)
     int32_t n_units;     // units of the whole context: dec_steps[n_units] is the cache-full flag
-    int32_t x_local;     // 1: the exchange slots (dec_o, dec_ml, dec_cnt) are indexed by the unit inside the launch (0 for the workspace's area)
+    int32_t x_local;     // 1: the exchange slots (dec_o, dec_ml, dec_cnt) are indexed by the unit inside the launch
     int32_t x_stride;    // exchange slots per unit
 };
 struct DecodeSteps {

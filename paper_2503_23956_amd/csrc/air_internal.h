@@ -70,8 +70,8 @@ struct DevTables {
 
 // Where the workgroups of a decode launch exchange their split-K partials: per unit `stride` slots of
 // (16 x head_dim partial outputs, (max, sum) per head) and one arrival counter.  The workspace's area is
-// indexed by the context-wide unit (calls on different layers may overlap); an area shared between
-// contexts would be indexed by the unit inside the launch.
+// indexed by the context-wide unit (calls on different layers may overlap), the static one by the unit
+// inside the launch.
 struct DecodeExchange {
     float *o;
     float2 *ml;
@@ -79,6 +79,7 @@ struct DecodeExchange {
     int32_t local;   // 1: slots indexed by the unit inside the launch
     int32_t stride;  // slots per unit
 };
+constexpr size_t kStaticSlots = 1024;  // (unit, split) pairs per launch that the static exchange area holds
 
 WsLayout make_layout(const air_config &cfg);
 
@@ -104,7 +105,9 @@ hipError_t launch_gather(hipStream_t s, const Dims &dm, const DevTables &t, int 
 hipError_t launch_decode(hipStream_t s, const Dims &dm, const DevTables &t, const DecodeExchange &x, int dtype, int l0,
                          int nl, int lbase, const LaunchLayers &ll, const void *q_new, const void *k_new,
                          const void *v_new, void *out, int splits, int waves, int tiles, int uniform_appended);
-
+// the exchange area inside the library's static device array, for the device that is current (looked up once per device)
+hipError_t static_exchange(DecodeExchange *x);
+hipError_t launch_zero_counters(hipStream_t s, int32_t *p, int n);
 
 // The bf16 / head_dim 128 cache is laid out so that the decode kernel can feed it to MFMA straight
 // from global memory, every load instruction of a wave reading 1 KB of consecutive memory, and so
