@@ -128,9 +128,12 @@ def _run_case(w, retention, *, alpha=None, steps=2, layer_chunk=None, token_majo
         assert np.array_equal(vv, hv[b, h][rows]), f"{tag} V' rows differ at layer {l} b={b} kv={h}"
         caches[(l, b, h)] = (synth.storage_to_f64(kk), synth.storage_to_f64(vv))
 
-    # ---- air_decode_attn
+    # ---- air_decode_attn: every step runs on the GPU; the oracle is consulted on `oracle_steps` (default: all),
+    # its cache rebuilt from the compacted rows plus every token appended so far (Eq.2)
     worst_dec = 0.0
     out = torch.empty((L, B, w.n_q_heads, d), dtype=q_dev[0].dtype, device=dev)
+    check_at = set(range(steps)) if oracle_steps is None else set(oracle_steps)
+    assert all(0 <= t < steps for t in check_at)
     for step in range(steps):
         qs, ks, vs = zip(*[synth.decode_inputs(w, l, step) for l in range(L)])
         qn, kn, vn = np.stack(qs), np.stack(ks), np.stack(vs)
@@ -138,18 +141,30 @@ def _run_case(w, retention, *, alpha=None, steps=2, layer_chunk=None, token_majo
         for l0 in range(0, L, chunk):
             l1 = min(L, l0 + chunk)
             ac.air_decode_attn(l0, l1, dq[l0:l1], dk[l0:l1], dv[l0:l1], out[l0:l1])
-        got = synth.storage_to_f64(to_host(out))
-        assert not np.any(np.isnan(got))
-        q64, k64, v64 = synth.storage_to_f64(qn), synth.storage_to_f64(kn), synth.storage_to_f64(vn)
+        k64, v64 = synth.storage_to_f64(kn), synth.storage_to_f64(vn)
         for (l, b, h) in units:
             kc, vc = caches[(l, b, h)]
-            kc = np.concatenate([kc, k64[l, b, h][None]])  # Eq.2
-            vc = np.concatenate([vc, v64[l, b, h][None]])
+            if isinstance(kc, np.ndarray):  # compacted rows first, appended rows after them, joined when needed
+                kc, vc = [kc], [vc]
+            kc.append(k64[l, b, h][None])  # Eq.2
+            vc.append(v64[l, b, h][None])
             caches[(l, b, h)] = (kc, vc)
-            want = O.decode_attn(q64[l, b, h * G:(h + 1) * G], kc, vc)
+        if step not in check_at:
+            continue
+        got = synth.storage_to_f64(to_host(out))
+        assert not np.any(np.isnan(got))
+        q64 = synth.storage_to_f64(qn)
+        for (l, b, h) in units:
+            kc, vc = caches[(l, b, h)]
+            kc, vc = [np.concatenate(kc)], [np.concatenate(vc)]
+            caches[(l, b, h)] = (kc, vc)
+            want = O.decode_attn(q64[l, b, h * G:(h + 1) * G], kc[0], vc[0])
             err = np.abs(got[l, b, h * G:(h + 1) * G] - want).max()
             worst_dec = max(worst_dec, float(err))
             assert err <= P.DECODE_ATOL[w.dtype], f"{tag} decode step {step} layer {l} b={b} kv={h}: abs err {err:.3g}"
+    for key, (kc, vc) in caches.items():
+        if not isinstance(kc, np.ndarray):
+            caches[key] = (np.concatenate(kc), np.concatenate(vc))
     if steps:
         lens2 = ac.air_get_lengths()
         assert np.array_equal(lens2, lens + steps)
@@ -164,7 +179,8 @@ def _run_case(w, retention, *, alpha=None, steps=2, layer_chunk=None, token_majo
     del ac, q_dev, k_dev, v_dev
     gc.collect()
     torch.cuda.empty_cache()
-    return dict(score_err=worst, budget_moves=budget_moves, swaps=swaps, decode_err=worst_dec)
+    return dict(score_err=worst, budget_moves=budget_moves, swaps=swaps, decode_err=worst_dec, budgets=bud,
+                vis_len=[s.vis_len for s in seqs])
 
 
 def test_config1_tiny_fp32_elite_window():
@@ -507,6 +523,7 @@ def test_budget_allocation_random_configurations():
     at high retention, the floor at low retention with a large min_keep, both in one allocation): the budgets
     must be the oracle's allocation of the same statistics in every case."""
     rng = np.random.default_rng(4242)
+    both_clamps = 0
     for it in range(24):
         base = int(rng.choice([1, 2]))
         n_vis, n_text, L = int(rng.integers(8, 700)), int(rng.integers(2, 40)), int(rng.integers(1, 20))
@@ -515,7 +532,10 @@ def test_budget_allocation_random_configurations():
         B = int(rng.integers(1, 4))
         w = synth.get_workload(base).scaled(cfg_id=500 + it, batch=B, n_layers=L, n_vis=n_vis, n_text=n_text, window=0,
                                             decode_steps=1, jitter=0.2 if B > 1 else 0.0)
-        _run_case(w, ret, steps=1, budget_mode=mode, min_keep=min_keep, verbose=False)
+        r = _run_case(w, ret, steps=1, budget_mode=mode, min_keep=min_keep, verbose=False)
+        for b, n in enumerate(r["vis_len"]):  # allocations in which some layers sit at N_v and others at the floor
+            both_clamps += int(min_keep < n and np.any(r["budgets"][b] == n) and np.any(r["budgets"][b] == min(min_keep, n)))
+    assert both_clamps >= 1
     # deeper than one wave has lanes: the workgroup-wide form of the allocation
     for L, ret, min_keep in ((70, 0.1, 1), (100, 0.97, 0), (129, 0.02, 5)):
         w = synth.get_workload(1).scaled(cfg_id=600 + L, n_layers=L, n_vis=96, n_text=6, window=0, decode_steps=1)
@@ -534,28 +554,92 @@ def _sample_units(w, n, seed):
     return sorted(units)
 
 
-@pytest.mark.parametrize("retention", [0.05, 0.25])
+def _spaced_steps(n):
+    """First, last and six evenly spaced decode steps in between."""
+    return sorted(set(int(round(i * (n - 1) / 7)) for i in range(8)))
+
+
+@pytest.mark.parametrize("retention", [0.05, 0.10, 0.25])
 def test_config3_batched_ragged_full_size(retention):
-    # 16 ragged sequences; scores, budgets and index sets of every unit, compaction and decode on a sample
+    # 16 ragged sequences; scores, budgets and index sets of every unit; compaction and decode on a sample of
+    # units: all 256 steps run on the GPU, the oracle checks the first, the last and six spaced ones
     w = synth.get_workload(3)
-    _run_case(w, retention, steps=2, check_decode_units=_sample_units(w, 64, 3))
+    _run_case(w, retention, steps=w.decode_steps, oracle_steps=_spaced_steps(w.decode_steps),
+              check_decode_units=_sample_units(w, 64, 3))
 
 
 def test_config4_video_full_size():
-    w = synth.get_workload(4)
-    _run_case(w, 0.10, steps=2, check_decode_units=_sample_units(w, 48, 4))
+    w = synth.get_workload(4)  # 512 decode steps
+    _run_case(w, 0.10, steps=w.decode_steps, oracle_steps=_spaced_steps(w.decode_steps),
+              check_decode_units=_sample_units(w, 48, 4))
 
 
 def test_config5_72b_stress_full_size():
-    # 80 layers (three launches per stage), G = 8, 16384 visual tokens (one full select sweep)
+    # 80 layers (three launches per stage), G = 8, 16384 visual tokens (one full select sweep), 256 decode steps
     w = synth.get_workload(5)
-    _run_case(w, 0.10, steps=2, check_decode_units=_sample_units(w, 48, 5))
+    _run_case(w, 0.10, steps=w.decode_steps, oracle_steps=_spaced_steps(w.decode_steps),
+              check_decode_units=_sample_units(w, 48, 5))
 
 
-@pytest.mark.parametrize("retention", [0.01, 0.50])
-def test_config5_shape_retention_extremes(retention):
-    w = synth.get_workload(5).scaled(n_layers=6)
-    _run_case(w, retention, steps=2, check_decode_units=_sample_units(w, 24, 6))
+@pytest.mark.parametrize("retention", [0.01, 0.02, 0.05, 0.25, 0.50])
+def test_config5_shape_retention_sweep(retention):
+    # the other retentions of the 72B-shaped workload's sweep, on 6 of its layers at full width
+    w = synth.get_workload(5).scaled(n_layers=6, decode_steps=40)
+    _run_case(w, retention, steps=40, oracle_steps=[0, 1, 20, 39], check_decode_units=_sample_units(w, 24, 6))
+
+
+def test_two_runs_give_bitwise_equal_results():
+    """Same inputs, same outputs, bit for bit: scores, statistics, budgets, kept indices, cache rows and decode
+    outputs of two independent contexts (the selection kernel counts with LDS atomics, whose order varies from
+    run to run; nothing may depend on it).  A ragged batch, so that several launch paths take part."""
+    import torch
+
+    import paper_2503_23956_amd as A
+    from paper_2503_23956_amd.device_inputs import config_for, to_device, to_host
+
+    dev = torch.device("cuda:0")
+    w = synth.get_workload(3).scaled(batch=3, n_layers=4, n_vis=2600, n_text=60, decode_steps=5)
+    seqs = w.seqs()
+    L, B, Hkv = w.n_layers, w.batch, w.n_kv_heads
+    layers = [synth.layer_inputs(w, l, seqs) for l in range(L)]
+    q = [to_device(li.q_text, dev) for li in layers]
+    k = [to_device(li.k, dev) for li in layers]
+    v = [to_device(li.v, dev) for li in layers]
+    dec = []
+    for step in range(5):
+        qs, ks, vs = zip(*[synth.decode_inputs(w, l, step) for l in range(L)])
+        dec.append(tuple(to_device(np.stack(x), dev) for x in (qs, ks, vs)))
+
+    def one_run(tuning):
+        ac = A.AirCache(config_for(w, 0.10, seqs=seqs, max_decode_steps=5), dev)
+        ac.air_set_tuning(**tuning)
+        ac.air_score(0, L, q, k, v, seqs)
+        ac.air_budget()
+        ac.air_select_compact(0, L, k, v)
+        res = dict(scores=[ac.air_get_scores(l) for l in range(L)], stats=ac.air_get_stats(), budgets=ac.air_get_budgets(),
+                   indices=[], outs=[])
+        bud = res["budgets"]
+        for l in range(L):
+            idx = ac.air_get_indices(l)
+            res["indices"].append([idx[b, :, : bud[b, l]].copy() for b in range(B)])
+        out = torch.empty((L, B, w.n_q_heads, w.head_dim), dtype=torch.bfloat16, device=dev)
+        for step in range(5):
+            ac.air_decode_attn(0, L, *dec[step], out)
+            res["outs"].append(to_host(out).copy())
+        lens = ac.air_get_lengths()
+        res["cache"] = [ac.air_get_cache(l, b, h, int(lens[b, l])) for l in (0, L - 1) for b in range(B) for h in (0, Hkv - 1)]
+        ac.close()
+        return res
+
+    def same(a, b):
+        if isinstance(a, (list, tuple)):
+            return len(a) == len(b) and all(same(x, y) for x, y in zip(a, b))
+        return np.array_equal(a.view(np.uint8) if a.dtype != np.uint8 else a, b.view(np.uint8) if b.dtype != np.uint8 else b)
+
+    for tuning in (dict(), dict(decode_splits=4, decode_waves=4, decode_tiles=2), dict(select_direct_max=0, select_threads=256)):
+        r1, r2 = one_run(tuning), one_run(tuning)
+        for key in r1:
+            assert same(r1[key], r2[key]), f"{key} differs between two runs ({tuning})"
 
 
 # ---------------------------------------------------------------------------------------

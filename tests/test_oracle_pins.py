@@ -380,7 +380,7 @@ def test_budget_hand_worked_fixture():
                               O.BUDGET_STRENGTH_SKEW, int(min_keep))
         assert got == [int(x) for x in want.split(",")], line
         n += 1
-    assert n == 8
+    assert n == 10
 
 
 def test_budget_modes():
