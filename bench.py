@@ -119,6 +119,8 @@ def cpu_baseline(w, seqs, retention, host_layers, dec_inputs, decode_steps):
     except Exception:
         pass
     return dict(value=w.batch * decode_steps / total, unit="tokens/s", cores=int(cores), kind="oracle",
+                cores_note=f"threads of the BLAS pool inside numpy's matmul (the oracle's only parallel part; its own "
+                           f"loops run on one thread); the host shows {os.cpu_count()} cores",
                 sample=f"full compression pass of all {w.n_layers} layers ({t_compress:.2f} s) + {len(sample)} of "
                        f"{decode_steps} decode steps at their true cache lengths ({t_step * 1e3:.1f} ms/step), "
                        f"numpy fp64",
@@ -144,6 +146,109 @@ def device_copy_reference(result, dev, dec_gbs):
     result["device_copy"] = {"gbs_read_plus_write": copy_gbs, "bytes": src.numel() * 4}
     result["roofline"]["frac_of_device_copy"] = dec_gbs / copy_gbs
     result["roofline_compress"]["frac_of_device_copy"] = result["roofline_compress"]["achieved"] / copy_gbs
+
+
+def cold_decode(A, w, seqs, q, k, v, dq, dk, dv, out, n_dec, retention, dev):
+    """Decode steps rotating over `n_ctx` separately compressed copies of the prompt: between two visits of one
+    copy's cache the other copies' caches pass through, more than the memory-side cache holds."""
+    import numpy as np
+    import torch
+
+    from paper_2503_23956_amd.device_inputs import config_for
+
+    L = w.n_layers
+    probe = A.AirCache(config_for(w, retention, max_decode_steps=n_dec, seqs=seqs), dev)
+    probe.air_score(0, L, prepared=probe.prepare(q, k, v, seqs))
+    probe.air_budget()
+    budgets = probe.air_get_budgets()
+    del probe
+    per_ctx = algorithmic_bytes(w, seqs, budgets, 1)["decode_first"]
+    n_ctx = max(3, int(np.ceil(2.5 * 256e6 / per_ctx)))  # 2.5 x the memory-side cache between two visits
+    n_ctx = min(n_ctx, 24)
+    ctxs = []
+    for _ in range(n_ctx):
+        ac = A.AirCache(config_for(w, retention, max_decode_steps=n_dec, seqs=seqs), dev)
+        ac.air_score(0, L, prepared=ac.prepare(q, k, v, seqs))
+        ac.air_budget()
+        ac.air_select_compact(0, L, prepared=ac.prepare(None, k, v))
+        ctxs.append(ac)
+    esz = dq.element_size()
+    step_q, step_kv = dq[0].numel() * esz, dk[0].numel() * esz
+    pq, pk, pv, po = dq.data_ptr(), dk.data_ptr(), dv.data_ptr(), out.data_ptr()
+    per_visit = n_dec // n_ctx  # steps every copy takes per timed pass (each copy has room for n_dec appends)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    nonvis = [s.seq_len - s.vis_len for s in seqs]
+    base_rows = sum((nonvis[b] + int(budgets[b][l])) for b in range(w.batch) for l in range(L))
+    row_bytes = 2 * w.n_kv_heads * w.head_dim * (2 if w.dtype == "bf16" else 4)
+    times, byts = [], 0
+    torch.cuda.synchronize()
+    for rep in range(3):  # the first pass warms the code path, not the caches
+        total = 0
+        e0.record()
+        for t in range(per_visit):
+            for ac in ctxs:
+                i = rep * per_visit + t
+                ac.air_decode_attn(0, L, pq + i * step_q, pk + i * step_kv, pv + i * step_kv, po)
+                total += (base_rows + (i + 1) * w.batch * L) * row_bytes
+        e1.record()
+        torch.cuda.synchronize()
+        if rep:
+            times.append(e0.elapsed_time(e1))
+            byts = total
+        if (rep + 2) * per_visit > n_dec:
+            break
+    n_calls = per_visit * n_ctx
+    us = float(np.mean(times)) * 1e3 / n_calls
+    gbs = byts / (float(np.mean(times)) * 1e-3) / 1e9
+    for ac in ctxs:
+        ac.close()
+    return {"us_per_step": us, "achieved": gbs, "frac": gbs / HBM_PEAK_GBS, "contexts": n_ctx,
+            "bytes_between_two_visits_of_a_cache": int(per_ctx * (n_ctx - 1)),
+            "note": "each step reads a cache that was last read n_ctx - 1 steps ago; the warm figure (roofline) re-reads one cache every step"}
+
+
+def measure_config(A, cfg_id, dev, timed_passes):
+    """Compression and decode timings of another workload at its 10 % retention, inputs drawn on the device."""
+    import numpy as np
+    import torch
+
+    import synth
+    from paper_2503_23956_amd.device_inputs import device_layer_inputs
+
+    w = synth.get_workload(cfg_id)
+    seqs = w.seqs()
+    L, n_dec, retention = w.n_layers, w.decode_steps, 0.10
+    q, k, v = [], [], []
+    for l in range(L):
+        a, b, c = device_layer_inputs(w, l, seqs, dev)
+        q.append(a), k.append(b), v.append(c)
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(77 + cfg_id)
+    dt = q[0].dtype
+    dq = torch.randn((n_dec, L, w.batch, w.n_q_heads, w.head_dim), generator=gen, device=dev, dtype=torch.float32).to(dt)
+    dk = torch.randn((n_dec, L, w.batch, w.n_kv_heads, w.head_dim), generator=gen, device=dev, dtype=torch.float32).to(dt)
+    dv = torch.randn((n_dec, L, w.batch, w.n_kv_heads, w.head_dim), generator=gen, device=dev, dtype=torch.float32).to(dt)
+    out = torch.empty((L, w.batch, w.n_q_heads, w.head_dim), dtype=dt, device=dev)
+    stage, wall, budgets, _, ws_bytes = timed_passes(w, seqs, q, k, v, dq, dk, dv, out, n_dec, retention, 3, 1)
+    sc, bu, se, de = stage.mean(axis=0)
+    ab = algorithmic_bytes(w, seqs, budgets, n_dec)
+    comp_ms = sc + bu + se
+    res = {
+        "workload": f"config{w.cfg_id}:{w.name}", "retention": retention, "batch": w.batch, "layers": L,
+        "tokens": f"{w.n_sys}+{w.n_vis}+{w.n_text}", "decode_steps": n_dec, "data": "synthetic, drawn on the device",
+        "units_per_decode_launch": L * w.batch * w.n_kv_heads,
+        "compress_us_per_layer": comp_ms * 1e3 / L, "compress_frac": ab["compress"] / (comp_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
+        "score_frac": ab["score"] / (sc * 1e-3) / 1e9 / HBM_PEAK_GBS,
+        "stage_us": {"score": sc * 1e3, "budget": bu * 1e3, "select_compact": se * 1e3, "decode_per_step": de * 1e3 / n_dec},
+        "decode_us_per_step": de * 1e3 / n_dec, "decode_tokens_per_s": w.batch * n_dec / (de * 1e-3),
+        "decode_frac": ab["decode_total"] / (de * 1e-3) / 1e9 / HBM_PEAK_GBS,
+        "decode_bytes_per_step_first_last": [ab["decode_first"], ab["decode_last"]],
+        "compress_bytes": ab["compress"], "workspace_bytes": int(ws_bytes),
+        "budgets_min_mean_max": [int(np.min(budgets)), float(np.mean(budgets)), int(np.max(budgets))],
+    }
+    del q, k, v, dq, dk, dv, out
+    torch.cuda.empty_cache()
+    return res
 
 
 def main():
@@ -195,7 +300,7 @@ def main():
     import paper_2503_23956_amd as A
     import synth
     from paper_2503_23956_amd import binding
-    from paper_2503_23956_amd.device_inputs import config_for, to_device
+    from paper_2503_23956_amd.device_inputs import config_for, device_layer_inputs, to_device
 
     if not os.path.exists(binding.LIB_PATH):
         from paper_2503_23956_amd.build import build
@@ -222,8 +327,11 @@ def main():
     dv = to_device(np.stack([d[2] for d in dec_inputs]), dev)
     out = torch.empty((L, w.batch, w.n_q_heads, w.head_dim), dtype=q[0].dtype, device=dev)
 
-    def run(retention, steps, warmup, per_layer=args.per_layer, want_stats=False):
-        """One context at this retention: `warmup` untimed passes, then `steps` timed ones."""
+    def timed_passes(w, seqs, q, k, v, dq, dk, dv, out, n_dec, retention, steps, warmup, per_layer=False,
+                     want_stats=False):
+        """One context at this retention: `warmup` untimed passes of the whole hot path, then `steps` timed ones.
+        Returns per-pass stage times in ms [steps][score, budget, select_compact, decode], wall seconds, budgets, stats."""
+        L = w.n_layers
         ac = A.AirCache(config_for(w, retention, max_decode_steps=n_dec, seqs=seqs), dev)
         ev = lambda: torch.cuda.Event(enable_timing=True)  # noqa: E731
         # host-side marshalling is done once, outside the timed region: descriptor arrays and raw addresses
@@ -273,8 +381,12 @@ def main():
         wall = time.perf_counter() - t0
 
         stage = np.array([[e[i].elapsed_time(e[i + 1]) for i in range(4)] for e in all_events])  # ms
+        ws_bytes = ac.workspace_bytes
         del ac
-        return stage, wall, budgets, stats
+        return stage, wall, budgets, stats, ws_bytes
+
+    def run(retention, steps, warmup, per_layer=args.per_layer, want_stats=False):
+        return timed_passes(w, seqs, q, k, v, dq, dk, dv, out, n_dec, retention, steps, warmup, per_layer, want_stats)[:4]
 
     stage, wall, budgets, stats = run(retention, args.steps, args.warmup, want_stats=True)
     score_ms, budget_ms, select_ms, decode_ms = stage.mean(axis=0)
@@ -331,15 +443,33 @@ def main():
     # what a plain kernel reaches on this machine: a device-to-device copy of 512 MiB
     if not args.no_extras:
         device_copy_reference(result, dev, dec_gbs)
-    # measured HBM traffic of the dominant kernel (rocprofv3 byte counters, committed summary), when one
-    # exists for this workload and launch shape
+    # HBM traffic of the dominant kernel: NOT measured in this run.  It is the per-launch sum of the rocprofv3
+    # FETCH_SIZE / WRITE_SIZE counters of this kernel from the committed summary named below, which is remade
+    # whenever the kernel changes (the summary states its command and the counter scaling).
     try:
         with open(os.path.join(ROOT, "profiles", "hbm_traffic_config2.txt")) as f:
             tr = json.load(f).get(result["config"]["workload"], {}).get("air_decode_attn")
         if tr and not args.per_layer:
             result["roofline"]["traffic"] = tr["fetch_bytes"] + tr["write_bytes"]
+            result["roofline"]["traffic_source"] = ("profiles/hbm_traffic_config2.txt: rocprofv3 --pmc byte counters of "
+                                                    "this kernel, a committed summary, not measured in this run")
     except (OSError, ValueError):
         pass
+    # ---- decode with a cold memory-side cache: the steps rotate over several compressed copies of the prompt, so
+    # that more than the 256 MB of the memory-side cache is read between two visits of one copy
+    if not args.no_extras and not args.per_layer:
+        result["decode_cold_cache"] = cold_decode(A, w, seqs, q, k, v, dq, dk, dv, out, n_dec, retention, dev)
+    # ---- the quantity of the paper's efficiency table (Tab.3), for attention alone: the same workload with the
+    # full cache and at 50 % / 10 % / 1 % retention
+    if args.retention_sweep or not args.no_extras:
+        sweep = []
+        for r in (1.0, 0.5, 0.1, 0.01):
+            sc, bu, se, de = run(r, 3, 1)[0].mean(axis=0)
+            sweep.append({"retention": r, "compress_us_per_layer": (sc + bu + se) * 1e3 / L,
+                          "decode_us_per_step": de * 1e3 / n_dec})
+        for e in sweep:
+            e["decode_speedup_vs_full_cache"] = sweep[0]["decode_us_per_step"] / e["decode_us_per_step"]
+        result["retention_sweep"] = sweep
     if args.score_per_layer:
         ac = A.AirCache(config_for(w, retention, max_decode_steps=n_dec, seqs=seqs), dev)
         preps = [ac.prepare(q[l:l + 1], k[l:l + 1], v[l:l + 1], seqs) for l in range(L)]
@@ -438,15 +568,13 @@ def main():
                     times.append(e0.elapsed_time(e1))
             result["window_sweep_score_us_per_layer"][name] = float(np.mean(times)) * 1e3 / L
             del ac
-    if args.retention_sweep:
-        sweep = []
-        for r in (1.0, 0.5, 0.1, 0.01):
-            sc, bu, se, de = run(r, 3, 1)[0].mean(axis=0)
-            sweep.append({"retention": r, "compress_us_per_layer": (sc + bu + se) * 1e3 / L,
-                          "decode_us_per_step": de * 1e3 / n_dec})
-        for e in sweep:
-            e["decode_speedup_vs_full_cache"] = sweep[0]["decode_us_per_step"] / e["decode_us_per_step"]
-        result["retention_sweep"] = sweep
+    # ---- the other workloads the target names (GPU timing only; inputs drawn on the device)
+    if not args.no_extras and not args.per_layer and args.config == 2:
+        del q, k, v, dq, dk, dv, out
+        torch.cuda.empty_cache()
+        result["per_config"] = {}
+        for cfg_id in (3, 4, 5):
+            result["per_config"][f"config{cfg_id}"] = measure_config(A, cfg_id, dev, timed_passes)
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(w, seqs, retention, host_layers, dec_inputs, n_dec)
     print(json.dumps(result))
