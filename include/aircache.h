@@ -92,6 +92,15 @@ typedef struct {
                                  count with every launch.  1 (bf16, head_dim 128 only): the count lives in
                                  device memory and advances with every decode launch that RUNS, so that a
                                  decode step captured in a HIP graph can be replayed; see air_decode_attn */
+    int32_t cache_in_place;   /* 0: the compacted cache lives in the workspace.  1 (bf16, head_dim 128 only):
+                                 air_select_compact compacts every layer INSIDE the prompt's own K / V tensors
+                                 (App. A names the full-size cache kept until every layer is scored as the
+                                 method's memory cost; this mode at least adds no second copy to it): the
+                                 workspace then holds no cache pool, the layer's K / V tensors become its cache
+                                 (the caller keeps them alive and no longer reads them), and decode appends
+                                 into them.  Needs token stride == head_dim (each (sequence, KV head) a
+                                 contiguous run of rows) and, per head, rows for the prompt plus
+                                 max_decode_steps rounded up to a multiple of 32 (head stride / head_dim)    */
 } air_config;
 
 /* One prompt.  system = [0, vis_start), visual = [vis_start, vis_start+vis_len),
@@ -163,7 +172,10 @@ air_status air_budget(air_ctx *ctx, void *stream);
 /* Alg.1, second loop for layers [l0, l1): top-k_l visual tokens per (sequence, KV head)
  * by importance (ties to the lower token index), then K' = [K_sys ; K_v[idx] ; K_t] and
  * V' likewise into the compacted cache inside the workspace.  Needs air_budget (or
- * air_set_budgets).  After the enqueued work has run the caller may free the prompt K/V. */
+ * air_set_budgets).  After the enqueued work has run the caller may free the prompt K/V.
+ * With cfg.cache_in_place the rows are instead compacted inside layers[].k / layers[].v themselves (see
+ * air_config): those tensors ARE the cache afterwards and must stay alive; AIR_ERR_SHAPE if their strides or
+ * rows per head do not allow it (checked for the largest budget there can be, without waiting for the device). */
 air_status air_select_compact(air_ctx *ctx, void *stream, int32_t l0, int32_t l1, const air_layer *layers,
                               const air_strides *strides);
 

@@ -25,6 +25,8 @@ static bool config_ok(const air_config &c) {
     if (c.window_kind != AIR_WINDOW_TEXT && c.window_kind != AIR_WINDOW_VISUAL) return false;
     if (c.device_steps != 0 && c.device_steps != 1) return false;
     if (c.device_steps && !(c.dtype == AIR_BF16 && c.head_dim == 128)) return false;
+    if (c.cache_in_place != 0 && c.cache_in_place != 1) return false;
+    if (c.cache_in_place && !(c.dtype == AIR_BF16 && c.head_dim == 128)) return false;
     const bool vis_window = c.window_kind == AIR_WINDOW_VISUAL;
     if (c.max_window < 1 || c.max_window > AIR_MAX_TEXT) return false;
     if (c.max_window > (vis_window ? c.max_vis_len : c.max_nonvis_len)) return false;
@@ -82,8 +84,10 @@ WsLayout make_layout(const air_config &c) {
     w.dec_steps = take((L * B * Hkv + 1) * 4);
     w.moments = take(L * B * Hkv * (size_t)((w.n_chunks + kFinishChunks - 1) / kFinishChunks) * 4 * 8);
     w.indices = take(L * B * Hkv * NV * 4);
-    w.kcache = take(B * Hkv * (size_t)w.pool_rows * D * esz);
-    w.vcache = take(B * Hkv * (size_t)w.pool_rows * D * esz);
+    // the cache pool, unless the cache is kept inside the prompt's own tensors
+    w.kcache = take(c.cache_in_place ? 0 : B * Hkv * (size_t)w.pool_rows * D * esz);
+    w.vcache = take(c.cache_in_place ? 0 : B * Hkv * (size_t)w.pool_rows * D * esz);
+    w.cache_ptrs = take(L * sizeof(CachePtrs));
     w.dec_o = take(L * B * Hkv * kMaxSplits * 16 * D * 4);  // per (unit, split): 16 head rows x D
     w.dec_ml = take(L * B * Hq * kMaxSplits * 8);
     w.stash = v_transposed(c.dtype, c.head_dim) ? take(L * B * Hkv * (size_t)w.n_chunks * kStashRows * kChunkKeys * 4) : off;
@@ -111,6 +115,7 @@ struct air_ctx {
     std::vector<char> scored, compacted, fixed_idx;  // fixed_idx: the layer's kept indices were set by the caller
     std::vector<int32_t> appended;
     air_tuning tune;  // launch-shape overrides (air_set_tuning); all automatic after air_create
+    std::vector<CachePtrs> ip_layers;  // in-place cache: the K / V tensor each compacted layer lives in
     std::string err;
 };
 
@@ -186,6 +191,9 @@ air_status air_create(const air_config *cfg, void *workspace, size_t workspace_b
     t.unit_R = (int32_t *)(w + lay.unit_R);
     t.len_off = (int2 *)(w + lay.len_off);
     t.dec_steps = cfg->device_steps ? (int32_t *)(w + lay.dec_steps) : nullptr;
+    t.cache_ptrs = cfg->cache_in_place ? (CachePtrs *)(w + lay.cache_ptrs) : nullptr;
+    t.ip_kv_b = t.ip_kv_h = 0;
+    c->ip_layers.assign(d.L, CachePtrs{nullptr, nullptr});
     c->have_seqs = false;
     c->budgets_ready = false;
     memset(&c->tune, 0, sizeof(c->tune));
@@ -377,6 +385,30 @@ air_status air_select_compact(air_ctx *ctx, void *stream, int32_t l0, int32_t l1
     }
     air_status st = check_strides(ctx, strides, layers, l1 - l0, false);
     if (st != AIR_OK) return st;
+    const bool in_place = ctx->cfg.cache_in_place != 0;
+    if (in_place) {
+        // Every (sequence, KV head) must be a contiguous run of rows with room for the prompt and every token
+        // decode may append, rounded up to whole 32-token blocks.  The budgets are on the device (no wait for
+        // them here), so the room is checked for the largest budget there can be, the whole visual span.
+        const int64_t D = ctx->cfg.head_dim;
+        if (strides->kv_t != D || strides->kv_h % D)
+            return fail(ctx, AIR_ERR_SHAPE, "air_select_compact (in place): token stride must equal head_dim and the head stride be whole rows");
+        const int64_t rows_per_head = strides->kv_h / D;
+        for (int b = 0; b < ctx->cfg.batch; ++b) {
+            const int64_t need = ((int64_t)ctx->seqs[b].seq_len + ctx->cfg.max_decode_steps + kCacheRowAlign - 1) / kCacheRowAlign * kCacheRowAlign;
+            if (rows_per_head < need)
+                return fail(ctx, AIR_ERR_SHAPE, "air_select_compact (in place): a KV head of the prompt's tensors has " +
+                                                    std::to_string(rows_per_head) + " rows, prompt + max_decode_steps need " + std::to_string(need));
+        }
+        if (ctx->cfg.batch > 1 && strides->kv_b < strides->kv_h * (ctx->cfg.n_kv_heads - 1) + rows_per_head * D)
+            return fail(ctx, AIR_ERR_SHAPE, "air_select_compact (in place): sequences overlap in the prompt's tensors");
+        bool any = false;
+        for (int l = 0; l < ctx->cfg.n_layers; ++l) any = any || ctx->compacted[l];
+        if (any && (ctx->tab.ip_kv_b != strides->kv_b || ctx->tab.ip_kv_h != strides->kv_h))
+            return fail(ctx, AIR_ERR_STATE, "air_select_compact (in place): every layer must use the same strides");
+        ctx->tab.ip_kv_b = strides->kv_b;
+        ctx->tab.ip_kv_h = strides->kv_h;
+    }
     hipStream_t s = (hipStream_t)stream;
     const int lpl = layers_per_launch(ctx);
     for (int c0 = l0; c0 < l1; c0 += lpl) {
@@ -386,6 +418,7 @@ air_status air_select_compact(air_ctx *ctx, void *stream, int32_t l0, int32_t l1
         for (int i = 0; i < nl; ++i) {
             ll.p[i].k = layers[c0 - l0 + i].k;
             ll.p[i].v = layers[c0 - l0 + i].v;
+            if (in_place) ctx->ip_layers[c0 + i] = CachePtrs{const_cast<void *>(ll.p[i].k), const_cast<void *>(ll.p[i].v)};
         }
         // selection over each run of layers whose indices the caller has not fixed
         hipError_t e = hipSuccess;
@@ -399,7 +432,9 @@ air_status air_select_compact(air_ctx *ctx, void *stream, int32_t l0, int32_t l1
             e = launch_select(s, ctx->dm, ctx->tab, c0 + a, z - a, ctx->tune.select_threads, ctx->tune.select_direct_max);
             a = z;
         }
-        if (e == hipSuccess) e = launch_gather(s, ctx->dm, ctx->tab, ctx->cfg.dtype, c0, nl, ll, *strides, ctx->tune.gather_wgs);
+        if (e == hipSuccess)
+            e = in_place ? launch_gather_in_place(s, ctx->dm, ctx->tab, c0, nl, ll, *strides)
+                         : launch_gather(s, ctx->dm, ctx->tab, ctx->cfg.dtype, c0, nl, ll, *strides, ctx->tune.gather_wgs);
         if (e != hipSuccess) return hip_fail(ctx, e, "air_select_compact launch");
     }
     for (int l = l0; l < l1; ++l) ctx->compacted[l] = 1;
@@ -627,7 +662,8 @@ air_status air_set_budgets(air_ctx *ctx, const int32_t *host) {
             const int64_t cap = (int64_t)(s.seq_len - s.vis_len) + k + ctx->dm.max_steps;
             rows += (cap + kCacheRowAlign - 1) / kCacheRowAlign * kCacheRowAlign;
         }
-        if (rows > ctx->dm.pool_rows) return fail(ctx, AIR_ERR_SHAPE, "air_set_budgets: budgets exceed the cache pool");
+        if (!ctx->cfg.cache_in_place && rows > ctx->dm.pool_rows)
+            return fail(ctx, AIR_ERR_SHAPE, "air_set_budgets: budgets exceed the cache pool");
     }
     SeqArgs sa;
     memset(&sa, 0, sizeof(sa));
@@ -712,23 +748,30 @@ air_status air_get_cache(air_ctx *ctx, int32_t l, int32_t b, int32_t h, void *k_
     const int32_t len = base + app;
     if (len > max_rows) return fail(ctx, AIR_ERR_SHAPE, "air_get_cache: max_rows too small");
     const size_t esz = ctx->cfg.dtype == AIR_BF16 ? 2 : 4;
-    const size_t row0 = ((size_t)b * ctx->dm.Hkv + h) * (size_t)ctx->dm.pool_rows + off;
     const size_t rb = (size_t)ctx->dm.D * esz;
+    // row of the unit's first cache row, in units of rows from the base the cache is read from
+    const char *kbase = (const char *)ctx->tab.kcache, *vbase = (const char *)ctx->tab.vcache;
+    size_t row0 = ((size_t)b * ctx->dm.Hkv + h) * (size_t)ctx->dm.pool_rows + off;
+    if (ctx->cfg.cache_in_place) {
+        kbase = (const char *)ctx->ip_layers[l].k;
+        vbase = (const char *)ctx->ip_layers[l].v;
+        row0 = ((size_t)b * ctx->tab.ip_kv_b + (size_t)h * ctx->tab.ip_kv_h) / ctx->dm.D;
+    }
     if (!v_transposed(ctx->cfg.dtype, ctx->dm.D)) {
-        st = d2h(ctx, k_host, (char *)ctx->tab.kcache + row0 * rb, (size_t)len * rb);
+        st = d2h(ctx, k_host, kbase + row0 * rb, (size_t)len * rb);
         if (st != AIR_OK) return st;
-        return d2h(ctx, v_host, (char *)ctx->tab.vcache + row0 * rb, (size_t)len * rb);
+        return d2h(ctx, v_host, vbase + row0 * rb, (size_t)len * rb);
     }
     // tiled K' and block-transposed V': fetch whole 32-token blocks and put the tokens back in row order
     const int D = ctx->dm.D;
     const size_t n_blk = ((size_t)len + 31) / 32;
     std::vector<uint16_t> raw(n_blk * 32 * D);
-    st = d2h(ctx, raw.data(), (char *)ctx->tab.kcache + row0 * rb, raw.size() * 2);
+    st = d2h(ctx, raw.data(), kbase + row0 * rb, raw.size() * 2);
     if (st != AIR_OK) return st;
     uint16_t *kh = (uint16_t *)k_host;
     for (int r = 0; r < len; ++r)
         for (int col = 0; col < D; ++col) kh[(size_t)r * D + col] = raw[k_tiled(r, col)];
-    st = d2h(ctx, raw.data(), (char *)ctx->tab.vcache + row0 * rb, raw.size() * 2);
+    st = d2h(ctx, raw.data(), vbase + row0 * rb, raw.size() * 2);
     if (st != AIR_OK) return st;
     uint16_t *vh = (uint16_t *)v_host;
     for (int r = 0; r < len; ++r)

@@ -138,6 +138,8 @@ struct DecodeTabs {
     int32_t *dec_cnt;
     int32_t *dec_steps;  // null: the host passes the count of appended tokens (DecodeSteps)
     int32_t n_units;     // units of the whole context: dec_steps[n_units] is the cache-full flag
+    const CachePtrs *cache_ptrs;  // in-place cache: the K / V tensor of every layer (else null: the cache is the workspace's pool)
+    int64_t kv_b, kv_h;           // in-place cache: element strides between sequences / KV heads of those tensors
     int32_t x_local;     // 1: the exchange slots (dec_o, dec_ml, dec_cnt) are indexed by the unit inside the launch
     int32_t x_stride;    // exchange slots per unit
 };
@@ -146,7 +148,8 @@ struct DecodeSteps {
     int32_t appended[kMaxLayersPerLaunch];
 };
 
-template <int NW, int KT, bool SPLIT>
+// INPLACE: the cache is kept inside the layers' own K / V tensors (their addresses come from a table)
+template <int NW, int KT, bool SPLIT, bool INPLACE>
 __global__ __launch_bounds__(64 * NW) void decode_mfma_kernel(Dims dm, DecodeTabs t, int l0, int lbase,
                                                               DecodeSteps ll, const bf16_t *q_new,
                                                               const bf16_t *k_new, const bf16_t *v_new, bf16_t *out,
@@ -165,6 +168,8 @@ __global__ __launch_bounds__(64 * NW) void decode_mfma_kernel(Dims dm, DecodeTab
     const int G = dm.G;
     // the unit's cache length and offset first: everything that touches the cache waits for them
     const int2 len_off = t.len_off[(int64_t)b * dm.L + l];
+    CachePtrs cp = {nullptr, nullptr};
+    if (INPLACE) cp = t.cache_ptrs[l];  // requested together with the table entry
     // The token this call appends (Eq.2): every wave fetches its k_new / v_new values first thing (the
     // addresses depend on the block index only), so they are long there when the wave that owns the
     // token needs them.
@@ -199,9 +204,11 @@ __global__ __launch_bounds__(64 * NW) void decode_mfma_kernel(Dims dm, DecodeTab
         k1 = min(len, k0 + cs);
     }
     const int kend = min(k1, newrow);  // the split's keys that are in the cache: [k0, kend)
-    const int64_t row0 = ((int64_t)b * dm.Hkv + kvh) * dm.pool_rows + len_off.y;
-    bf16_t *kc = (bf16_t *)t.kcache + row0 * D;
-    bf16_t *vc = (bf16_t *)t.vcache + row0 * D;
+    // the unit's cache: its region of the workspace pool, or (kept in place) its rows of the layer's own K / V tensors
+    const int64_t row0 = INPLACE ? 0 : ((int64_t)b * dm.Hkv + kvh) * dm.pool_rows + len_off.y;
+    const int64_t ip0 = INPLACE ? (int64_t)b * t.kv_b + (int64_t)kvh * t.kv_h : 0;
+    bf16_t *kc = INPLACE ? (bf16_t *)cp.k + ip0 : (bf16_t *)t.kcache + row0 * D;
+    bf16_t *vc = INPLACE ? (bf16_t *)cp.v + ip0 : (bf16_t *)t.vcache + row0 * D;
     bf16_t *o_unit = out + (((int64_t)(lbase + li) * dm.B + b) * dm.Hq + (int64_t)kvh * G) * D;
 
     bf16x8 qb[4];
@@ -747,20 +754,23 @@ hipError_t launch_decode(hipStream_t s, const Dims &dm, const DevTables &t, cons
         dt.x_local = x.local;
         dt.x_stride = x.stride;
         dt.dec_steps = t.dec_steps;
+        dt.cache_ptrs = t.cache_ptrs;
+        dt.kv_b = t.ip_kv_b;
+        dt.kv_h = t.ip_kv_h;
         dt.n_units = dm.L * dm.B * dm.Hkv;
         DecodeSteps ds;
         ds.uniform = uniform_appended;
         for (int i = 0; i < kMaxLayersPerLaunch; ++i) ds.appended[i] = ll.appended[i];
-#define AIR_LAUNCH_DECODE(NW, KT)                                                                                  \
-    do {                                                                                                           \
-        if (splits == 1)                                                                                           \
-            hipLaunchKernelGGL((decode_mfma_kernel<NW, KT, false>), grid, dim3(64 * NW), 0, s, dm, dt, l0, lbase,  \
-                               ds, (const bf16_t *)q_new, (const bf16_t *)k_new, (const bf16_t *)v_new,            \
-                               (bf16_t *)out, splits, lg_splits);                                                  \
-        else                                                                                                       \
-            hipLaunchKernelGGL((decode_mfma_kernel<NW, KT, true>), grid, dim3(64 * NW), 0, s, dm, dt, l0, lbase,   \
-                               ds, (const bf16_t *)q_new, (const bf16_t *)k_new, (const bf16_t *)v_new,            \
-                               (bf16_t *)out, splits, lg_splits);                                                  \
+#define AIR_LAUNCH_DECODE_(NW, KT, SP, IP)                                                                          \
+    hipLaunchKernelGGL((decode_mfma_kernel<NW, KT, SP, IP>), grid, dim3(64 * NW), 0, s, dm, dt, l0, lbase, ds,      \
+                       (const bf16_t *)q_new, (const bf16_t *)k_new, (const bf16_t *)v_new, (bf16_t *)out, splits,  \
+                       lg_splits)
+#define AIR_LAUNCH_DECODE(NW, KT)                                                       \
+    do {                                                                                \
+        if (splits == 1 && !t.cache_ptrs) AIR_LAUNCH_DECODE_(NW, KT, false, false);     \
+        else if (splits == 1) AIR_LAUNCH_DECODE_(NW, KT, false, true);                  \
+        else if (!t.cache_ptrs) AIR_LAUNCH_DECODE_(NW, KT, true, false);                \
+        else AIR_LAUNCH_DECODE_(NW, KT, true, true);                                    \
     } while (0)
         if (waves == 8 && tiles == 4) AIR_LAUNCH_DECODE(8, 4);
         else if (waves == 4 && tiles == 4) AIR_LAUNCH_DECODE(4, 4);
@@ -774,6 +784,7 @@ hipError_t launch_decode(hipStream_t s, const Dims &dm, const DevTables &t, cons
         else if (waves == 2) AIR_LAUNCH_DECODE(2, 8);
         else AIR_LAUNCH_DECODE(1, 8);
 #undef AIR_LAUNCH_DECODE
+#undef AIR_LAUNCH_DECODE_
         return hipGetLastError();
     }
     hipError_t e = launch_append(s, dm, t, dtype, l0, nl, lbase, ll, k_new, v_new);

@@ -28,6 +28,11 @@ struct LaunchLayers {
     int32_t appended[kMaxLayersPerLaunch];
 };
 
+// K and V tensor of one layer (the compacted cache itself when it is kept in place)
+struct CachePtrs {
+    void *k, *v;
+};
+
 struct SeqArgs {
     air_seq s[AIR_MAX_BATCH];
 };
@@ -36,7 +41,7 @@ struct SeqArgs {
 struct WsLayout {
     size_t seq_tab, elite_cnt, elite_idx, row_mtext, row_ztext, row_M, row_w, part, scores;
     size_t unit_st, unit_sk, s_t, s_k, budgets, base_len, layer_off, dec_cnt, moments, indices;
-    size_t kcache, vcache, dec_o, dec_ml, stash, row_f, unit_R, len_off, dec_steps;
+    size_t kcache, vcache, dec_o, dec_ml, stash, row_f, unit_R, len_off, dec_steps, cache_ptrs;
     size_t total;
     int32_t n_chunks;     // ceil(max_vis_len / kChunkKeys)
     int64_t pool_rows;    // rows of one (sequence, KV head) cache pool
@@ -66,6 +71,8 @@ struct DevTables {
     int32_t *unit_R;  // window rows of a unit (all heads of the group), left by the row-parameter kernel
     float2 *dec_ml;
     int32_t *dec_steps;  // tokens appended so far per unit when the device counts them (else null); one overflow flag after the last unit
+    CachePtrs *cache_ptrs;  // in-place cache: K / V tensor of every layer, written by the compaction gather (else null)
+    int64_t ip_kv_b, ip_kv_h;  // in-place cache: element strides between sequences and between KV heads of those tensors
 };
 
 // Where the workgroups of a decode launch exchange their split-K partials: per unit `stride` slots of
@@ -102,6 +109,8 @@ hipError_t launch_budget(hipStream_t s, const Dims &dm, const DevTables &t, doub
 hipError_t launch_select(hipStream_t s, const Dims &dm, const DevTables &t, int l0, int nl, int threads, int direct_max);
 hipError_t launch_gather(hipStream_t s, const Dims &dm, const DevTables &t, int dtype, int l0, int nl,
                          const LaunchLayers &ll, const air_strides &st, int wgs_per_unit);
+hipError_t launch_gather_in_place(hipStream_t s, const Dims &dm, const DevTables &t, int l0, int nl, const LaunchLayers &ll,
+                                  const air_strides &st);
 hipError_t launch_decode(hipStream_t s, const Dims &dm, const DevTables &t, const DecodeExchange &x, int dtype, int l0,
                          int nl, int lbase, const LaunchLayers &ll, const void *q_new, const void *k_new,
                          const void *v_new, void *out, int splits, int waves, int tiles, int uniform_appended);

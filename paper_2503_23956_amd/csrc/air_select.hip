@@ -311,6 +311,94 @@ __global__ __launch_bounds__(256) void gather_vt_kernel(Dims dm, DevTables t, in
     }
 }
 
+// The same compaction INSIDE the prompt's own K / V tensors (token stride == head_dim, so a unit is a contiguous
+// run of rows): block j of the compacted cache (rows 32 j .. 32 j + 31, K' tiled, V' block-transposed) lands on
+// the 8 KB that source rows 32 j .. 32 j + 31 occupy.  A kept token never moves backwards (compact row <= source
+// row), so the sources of block j lie at rows >= 32 j and the rows a block overwrites are needed by that block
+// and earlier ones only: ONE workgroup per unit walks the blocks front to back and reads a block's sources
+// (into registers, then LDS) before it stores the block.  Reading the NEXT block's sources ahead of the current
+// block's stores is safe as well (they lie behind the rows being overwritten), which keeps the index and row
+// reads of block j + 1 in flight under the stores of block j.
+__global__ __launch_bounds__(256) void gather_in_place_kernel(Dims dm, DevTables t, int l0, LaunchLayers ll, air_strides st) {
+    constexpr int D = 128;
+    typedef bf16_t T;
+    const int kvh = blockIdx.x;  // grid (KV head, sequence + B * layer)
+    int b, li;
+    seq_layer_of(dm, (int)blockIdx.y, b, li);
+    const int l = l0 + li;
+    const air_seq sq = t.seq_tab[b];
+    const int kl = t.budgets[(int64_t)b * dm.L + l];
+    const int n_rows = sq.seq_len - sq.vis_len + kl;
+    const int64_t unit = ((int64_t)l * dm.B + b) * dm.Hkv + kvh;
+    const int32_t *idx = t.indices + unit * dm.max_vis;
+    T *kbase = (T *)const_cast<void *>(ll.p[li].k) + (int64_t)b * st.kv_b + (int64_t)kvh * st.kv_h;
+    T *vbase = (T *)const_cast<void *>(ll.p[li].v) + (int64_t)b * st.kv_b + (int64_t)kvh * st.kv_h;
+    if (threadIdx.x == 0) {
+        if (kvh == 0 && b == 0) {  // where the decode kernel finds this layer's cache from now on
+            t.cache_ptrs[l].k = const_cast<void *>(ll.p[li].k);
+            t.cache_ptrs[l].v = const_cast<void *>(ll.p[li].v);
+        }
+        if (t.dec_steps) {  // a fresh cache: nothing appended yet, cache-full flag down
+            t.dec_steps[unit] = 0;
+            if (blockIdx.x == 0 && blockIdx.y == 0) t.dec_steps[(int64_t)dm.L * dm.B * dm.Hkv] = 0;
+        }
+    }
+    __shared__ bf16_t tile[32][D + 8];   // V rows, indexed [slot][column]
+    __shared__ bf16_t ktile[32][D + 8];  // K rows, indexed [row][column]
+    uint4 kx[2], vx[2];
+    auto fetch = [&](int r0) __attribute__((always_inline)) {
+#pragma unroll
+        for (int it = 0; it < 2; ++it) {
+            const int v = threadIdx.x + 256 * it;
+            const int row = v >> 4, c = (v & 15) * 8;
+            const int j = r0 + row;
+            kx[it] = make_uint4(0, 0, 0, 0);
+            vx[it] = kx[it];
+            if (j < n_rows) {
+                int tok;
+                if (j < sq.vis_start) tok = j;
+                else if (j < sq.vis_start + kl) tok = sq.vis_start + idx[j - sq.vis_start];
+                else tok = sq.vis_start + sq.vis_len + (j - sq.vis_start - kl);
+                kx[it] = *reinterpret_cast<const uint4 *>(kbase + (int64_t)tok * D + c);
+                vx[it] = *reinterpret_cast<const uint4 *>(vbase + (int64_t)tok * D + c);
+            }
+        }
+    };
+    if (n_rows > 0) fetch(0);
+    for (int r0 = 0; r0 < n_rows; r0 += 32) {
+        // the wait for this block's rows (a use of kx / vx) comes before any store of this block
+#pragma unroll
+        for (int it = 0; it < 2; ++it) {
+            const int v = threadIdx.x + 256 * it;
+            const int row = v >> 4, c = (v & 15) * 8;
+            *reinterpret_cast<uint4 *>(&ktile[row][c]) = kx[it];
+            *reinterpret_cast<uint4 *>(&tile[v_slot(row)][c]) = vx[it];
+        }
+        if (r0 + 32 < n_rows) fetch(r0 + 32);  // rows >= r0 + 32: untouched by the stores below
+        __syncthreads();  // every thread's rows of this block are in LDS (and therefore read) before the block is overwritten
+        for (int v = threadIdx.x; v < 32 * 16; v += 256) {
+            const int sl = (v >> 6) & 3, tl = v >> 8, n = (v >> 2) & 15, c = v & 3;
+            *reinterpret_cast<uint4 *>(kbase + (int64_t)r0 * D + (int64_t)v * 8) =
+                *reinterpret_cast<const uint4 *>(&ktile[16 * tl + n][32 * sl + 8 * c]);
+        }
+        for (int v = threadIdx.x; v < D * 4; v += 256) {
+            const int j = v >> 6, c = (v >> 4) & 3, col = 16 * j + (v & 15);
+            uint32_t w[4];
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+                w[i] = (uint32_t)tile[8 * c + 2 * i][col] | ((uint32_t)tile[8 * c + 2 * i + 1][col] << 16);
+            *reinterpret_cast<uint4 *>(vbase + (int64_t)r0 * D + (int64_t)v * 8) = make_uint4(w[0], w[1], w[2], w[3]);
+        }
+        __syncthreads();  // LDS is free for the next block; the next block's rows were requested above, before these stores
+    }
+}
+
+hipError_t launch_gather_in_place(hipStream_t s, const Dims &dm, const DevTables &t, int l0, int nl, const LaunchLayers &ll,
+                                  const air_strides &st) {
+    hipLaunchKernelGGL(gather_in_place_kernel, dim3(dm.Hkv, nl * dm.B), dim3(256), 0, s, dm, t, l0, ll, st);
+    return hipGetLastError();
+}
+
 // threads: 256 | 512, 0 = chosen here; direct_max: largest deciding bin that is ranked directly (0 = always the radix
 // passes), negative = kSelCand
 hipError_t launch_select(hipStream_t s, const Dims &dm, const DevTables &t, int l0, int nl, int threads, int direct_max) {
