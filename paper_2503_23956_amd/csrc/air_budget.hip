@@ -5,61 +5,221 @@
 // contraction off): per-layer strength / skewness as the left-to-right mean over KV heads,
 // layer shares by left-to-right sums, proportional allocation clamped to [min_keep, N_v] by
 // repeatedly pinning the side with the larger total violation, floor + largest remainder
-// (ties to the lower layer).  Up to 64 layers are done by one wave, a layer per lane, whose lanes
-// read each other's registers: no LDS, no barriers.  Beyond that the per-layer work is spread over
-// the threads of the workgroup and the order-dependent sums stay serial in thread 0; the threads
-// exchange data through LDS only, so the barriers order LDS traffic and do not wait for the
+// (ties to the lower layer).  Thread l owns layer l.  The order-dependent sums over the layers are
+// formed by EVERY thread for itself, left to right, from a copy of the addends in LDS: all lanes
+// read the same address (a broadcast), the reads of several addends are in flight together, and no
+// thread waits for another one's serial loop (a wave that handed values from lane to lane through
+// scalar registers spent 35-40 ns per addend; here an addend costs one dependent fp64 add).  The
+// threads exchange data through LDS only, so the barriers order LDS traffic and do not wait for the
 // global stores of the statistics and budgets.
 #include "air_device.h"
 #include "air_internal.h"
+#include <type_traits>
 
 namespace air {
 
 constexpr int kBT = 256;  // threads; also the largest layer count (AIR_MAX_LAYERS)
 
-// Value that lane `l` (the same for every lane of the wave) holds, handed to all lanes through a scalar register.
-__device__ __forceinline__ double lane_value(double v, int l) {
-    const unsigned long long u = __builtin_bit_cast(unsigned long long, v);
-    const unsigned lo = (unsigned)__builtin_amdgcn_readlane((int)(unsigned)u, l);
-    const unsigned hi = (unsigned)__builtin_amdgcn_readlane((int)(unsigned)(u >> 32), l);
-    return __builtin_bit_cast(double, ((unsigned long long)hi << 32) | lo);
+// left-to-right sum of a[0 .. n), the same in every thread that calls it.  The entries from n up to the next
+// multiple of 8 hold exact zeros (every thread writes its slot, threads past the last layer write zero), so the
+// sum runs over whole groups of 8 whose reads are in flight together: adding +0.0 changes nothing.
+__device__ __forceinline__ double ordered_sum(const double *a, int n) {
+    double sum = 0.0;
+    for (int l = 0; l < n; l += 8) {
+        double v[8];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) v[j] = a[l + j];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) sum += v[j];
+    }
+    return sum;
+}
+__device__ __forceinline__ int int_sum(const int *a, int n) {  // n a multiple of 8, zeros past the last layer
+    int sum = 0;
+    for (int l = 0; l < n; l += 8) {
+        int v[8];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) v[j] = a[l + j];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) sum += v[j];
+    }
+    return sum;
 }
 
-// Eq.11 and the cache layout for up to 64 layers by ONE wave, a layer per lane.  The order-dependent
-// sums run left to right over the lanes (every lane forms the same sum from scalar reads of the other
-// lanes' registers), so the wave needs neither LDS nor barriers; the arithmetic and its order are
-// those of the many-layer path below.
-__device__ __forceinline__ void allocate_one_wave(const Dims &dm, const DevTables &t, double retention, int mode, int min_keep,
-                                                  int skip_allocation, bool stats_in_lds, const air_seq &sq, int b,
-                                                  const double *u_st, const double *u_sk) {
-    const int lane = threadIdx.x, L = dm.L, n_vis = sq.vis_len;
-    const bool mine = lane < L;
+// ONE_WAVE (up to 64 layers, the usual depth): after the statistics the first wave does the rest alone; the
+// exchanges through LDS then need no workgroup barrier (a wave's LDS accesses complete in program order), only
+// the compiler kept from moving them.
+template <bool ONE_WAVE>
+__global__ __launch_bounds__(kBT) void budget_kernel(Dims dm, DevTables t, double retention, int mode, int min_keep,
+                                                     int skip_allocation, int use_moments, SeqArgs seqs) {
+    const int tid = threadIdx.x;
+    const int b = blockIdx.x;
+    const int L = dm.L;
+    const air_seq sq = seqs.s[b];  // from the kernel arguments: no table read in front of the moment entries
+    const int n_vis = sq.vis_len;
+    const bool mine = tid < L;
+    const int L8 = (L + 7) & ~7;  // the sums over the layers run over whole groups of 8 (zeros past the last layer)
+    __shared__ double a0[kBT], a1[kBT];  // addends of the ordered sums (one per layer)
+    __shared__ double frac[kBT];
+    __shared__ int i0[kBT], i1[kBT];
+    __shared__ double u_st[AIR_MAX_LAYERS * 16], u_sk[AIR_MAX_LAYERS * 16];  // per (layer, KV head), H_kv <= 16 staged
+
+    auto sync = [&]() __attribute__((always_inline)) {
+        if (ONE_WAVE) {
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+        } else {
+            lds_barrier();
+        }
+    };
     int32_t *budgets = t.budgets + (int64_t)b * L;
     int kk = 0;
+    if (ONE_WAVE && skip_allocation && tid >= 64) return;
     if (skip_allocation) {
-        if (mine) kk = budgets[lane];
+        if (mine) kk = budgets[tid];  // the budgets were set by the caller: only the layout is left
     } else {
+        const bool stage = use_moments && L * dm.Hkv <= AIR_MAX_LAYERS * 16;  // unit statistics fit the LDS staging arrays
+        if (use_moments) {
+            // Eq.9-10 of every (layer, KV head) from the moment entries of its importance row: entry c holds
+            // the sum S1_c, the mean m_c and the moments M2_c, M3_c about m_c of the n_c scores of kFinishChunks
+            // chunks.  With d_c = m_c - mu the central moments of the row are
+            //   sum (x - mu)^2 = sum_c M2_c + n_c d_c^2,   sum (x - mu)^3 = sum_c M3_c + 3 d_c M2_c + n_c d_c^3,
+            // sums of terms no larger than their result (raw power sums would cancel on rows of little spread).
+            // Sixteen lanes per (layer, KV head), lane g taking the entries g, g + 16, ...; the entries of a batch
+            // of rows are requested together (one trip to memory per batch), the sums over a row's entries are
+            // butterflies over the sixteen lanes (a fixed order, the same on every run), and the divisions and
+            // the square root of the rows of a batch are done side by side, lane r of a group finishing row r.
+            constexpr int kEntryKeys = kFinishChunks * kChunkKeys;
+            const int nch = (n_vis + kEntryKeys - 1) / kEntryKeys;  // entries per unit
+            const int grp = tid >> 4, gl = tid & 15, n_grp = kBT >> 4;
+            const double n = (double)n_vis;
+            const int n_units = L * dm.Hkv;
+            auto stats_batches = [&](auto per_tag, auto units_tag) __attribute__((always_inline)) {
+                constexpr int PER = decltype(per_tag)::value, UNITS = decltype(units_tag)::value;
+                for (int p0 = 0; p0 < n_units; p0 += n_grp * UNITS) {  // uniform over the workgroup
+                    double e[UNITS][PER][4];
+#pragma unroll
+                    for (int r = 0; r < UNITS; ++r) {
+                        const int p = min(p0 + r * n_grp + grp, n_units - 1);  // groups past the end repeat the last unit and store nothing
+                        const int l = p / dm.Hkv, h = p % dm.Hkv;
+                        const double *mo = t.moments + (((int64_t)l * dm.B + b) * dm.Hkv + h) * dm.n_entries * 4;
+#pragma unroll
+                        for (int j = 0; j < PER; ++j) {
+                            const int c = gl + 16 * j;
+                            const double2 lo2 = *reinterpret_cast<const double2 *>(mo + 4 * min(c, nch - 1));
+                            const double2 hi2 = *reinterpret_cast<const double2 *>(mo + 4 * min(c, nch - 1) + 2);
+                            const bool have = c < nch;
+                            e[r][j][0] = have ? lo2.x : 0.0;
+                            e[r][j][1] = have ? lo2.y : 0.0;
+                            e[r][j][2] = have ? hi2.x : 0.0;
+                            e[r][j][3] = have ? hi2.y : 0.0;
+                        }
+                    }
+                    double S1_mine = 0.0, c2_mine = 0.0, c3_mine = 0.0;  // of row gl of the batch
+#pragma unroll
+                    for (int r = 0; r < UNITS; ++r) {
+                        double s1 = 0.0;
+#pragma unroll
+                        for (int j = 0; j < PER; ++j) s1 += e[r][j][0];
+                        const double S1 = sum16(s1);
+                        const double mu = S1 / n;
+                        double c2 = 0.0, c3 = 0.0;
+#pragma unroll
+                        for (int j = 0; j < PER; ++j) {
+                            const int c = gl + 16 * j;
+                            if (c < nch) {
+                                const double nc = (double)min(kEntryKeys, n_vis - c * kEntryKeys);
+                                const double dl = e[r][j][1] - mu, M2 = e[r][j][2], M3 = e[r][j][3];
+                                c2 += M2 + nc * (dl * dl);
+                                c3 += (M3 + 3.0 * dl * M2) + nc * (dl * dl * dl);
+                            }
+                        }
+                        c2 = sum16(c2);
+                        c3 = sum16(c3);
+                        if (gl == r) {
+                            S1_mine = S1;
+                            c2_mine = c2;
+                            c3_mine = c3;
+                        }
+                    }
+                    const int p = p0 + gl * n_grp + grp;
+                    if (gl < UNITS && p < n_units) {
+                        double sk = 0.0;
+                        if (n_vis >= 3) {
+                            const double mu = S1_mine / n;
+                            const double sigma = sqrt(c2_mine / (n - 1.0));
+                            // zero spread (Eq.10 undefined; taken as 0): a standard deviation at most 1e-6 of the mean
+                            if (sigma > 1e-6 * fabs(mu)) sk = n / ((n - 1.0) * (n - 2.0)) * (c3_mine / (sigma * sigma * sigma));
+                        }
+                        const int l = p / dm.Hkv, h = p % dm.Hkv;
+                        const int64_t unit = ((int64_t)l * dm.B + b) * dm.Hkv + h;
+                        t.unit_st[unit] = S1_mine;
+                        t.unit_sk[unit] = sk;
+                        if (stage) {
+                            u_st[p] = S1_mine;
+                            u_sk[p] = sk;
+                        }
+                    }
+                }
+            };
+            if (nch <= 16) stats_batches(std::integral_constant<int, 1>(), std::integral_constant<int, 8>());
+            else if (nch <= 32) stats_batches(std::integral_constant<int, 2>(), std::integral_constant<int, 4>());
+            else {
+                // rows of more than 32 entries (beyond 32768 visual tokens): a thread per row, two passes over its entries
+                for (int p = tid; p < n_units; p += kBT) {
+                    const int l = p / dm.Hkv, h = p % dm.Hkv;
+                    const int64_t unit = ((int64_t)l * dm.B + b) * dm.Hkv + h;
+                    const double *mo = t.moments + unit * dm.n_entries * 4;
+                    double S1 = 0.0;
+#pragma unroll 4
+                    for (int c = 0; c < nch; ++c) S1 += mo[4 * c];
+                    double sk = 0.0;
+                    if (n_vis >= 3) {
+                        const double mu = S1 / n;
+                        double c2 = 0.0, c3 = 0.0;
+#pragma unroll 4
+                        for (int c = 0; c < nch; ++c) {
+                            const double nc = (double)min(kEntryKeys, n_vis - c * kEntryKeys);
+                            const double dl = mo[4 * c + 1] - mu, M2 = mo[4 * c + 2], M3 = mo[4 * c + 3];
+                            c2 += M2 + nc * (dl * dl);
+                            c3 += (M3 + 3.0 * dl * M2) + nc * (dl * dl * dl);
+                        }
+                        const double sigma = sqrt(c2 / (n - 1.0));
+                        if (sigma > 1e-6 * fabs(mu)) sk = n / ((n - 1.0) * (n - 2.0)) * (c3 / (sigma * sigma * sigma));
+                    }
+                    t.unit_st[unit] = S1;
+                    t.unit_sk[unit] = sk;
+                    if (stage) {
+                        u_st[p] = S1;
+                        u_sk[p] = sk;
+                    }
+                }
+            }
+            if (stage) lds_barrier();  // the statistics cross in LDS: no wait for the global stores above
+            else __syncthreads();
+        }
+        if (ONE_WAVE && tid >= 64) return;  // one wave takes it from here
         double st = 0.0, sk = 0.0;
         if (mine) {  // mean over the KV heads, left to right
             double a = 0.0, c = 0.0;
             for (int h = 0; h < dm.Hkv; ++h) {
-                const int64_t unit = ((int64_t)lane * dm.B + b) * dm.Hkv + h;
-                a += stats_in_lds ? u_st[lane * dm.Hkv + h] : t.unit_st[unit];
-                c += stats_in_lds ? u_sk[lane * dm.Hkv + h] : t.unit_sk[unit];
+                const int64_t unit = ((int64_t)tid * dm.B + b) * dm.Hkv + h;
+                a += stage ? u_st[tid * dm.Hkv + h] : t.unit_st[unit];
+                c += stage ? u_sk[tid * dm.Hkv + h] : t.unit_sk[unit];
             }
             st = a / (double)dm.Hkv;
             sk = c / (double)dm.Hkv;
-            t.s_t[(int64_t)b * L + lane] = st;
-            t.s_k[(int64_t)b * L + lane] = sk;
+            t.s_t[(int64_t)b * L + tid] = st;
+            t.s_k[(int64_t)b * L + tid] = sk;
         }
         const int lo_i = min(min_keep, n_vis);
         const double lo = (double)lo_i, hi = (double)n_vis;
         const double skp = fmax(sk, 0.0);
-        double sum_t = 0.0, sum_k = 0.0;
-        for (int l = 0; l < L; ++l) {
-            sum_t += lane_value(st, l);
-            sum_k += lane_value(skp, l);
-        }
+        a0[tid] = st;   // threads past the last layer hold exact zeros
+        a1[tid] = skp;
+        sync();
+        const double sum_t = ordered_sum(a0, L8), sum_k = ordered_sum(a1, L8);
         long long k_tot = (long long)floor(retention * (double)n_vis * (double)L + 0.5);
         const long long k_lo = (long long)L * lo_i, k_hi = (long long)L * n_vis;
         k_tot = k_tot < k_lo ? k_lo : (k_tot > k_hi ? k_hi : k_tot);
@@ -70,26 +230,29 @@ __device__ __forceinline__ void allocate_one_wave(const Dims &dm, const DevTable
         else if (mode == AIR_BUDGET_STRENGTH) wl = a;
         else if (mode == AIR_BUDGET_SKEW) wl = c;
         else wl = 0.5 * (a + c);
-        // proportional allocation with clamping: pin the side with the larger total violation, repeat
+        // proportional allocation with clamping: pin the side with the larger total violation, repeat.  Every
+        // thread carries the same k_free, n_free and pin decision, formed from the same LDS copies.
         bool is_free = mine;
         double x = 0.0, k_free = (double)k_tot;
         for (int it = 0; it < L + 1; ++it) {
-            const int n_free = __popcll(__ballot(is_free));
+            sync();  // the sums of the round before (or of the shares) have been read
+            a0[tid] = is_free ? wl : 0.0;  // a pinned layer adds an exact zero
+            i0[tid] = is_free ? 1 : 0;
+            sync();
+            const int n_free = int_sum(i0, L8);
             if (n_free == 0) break;
-            const double w_mine = is_free ? wl : 0.0;  // a pinned layer adds an exact zero
-            double w_free = 0.0;
-            for (int l = 0; l < L; ++l) w_free += lane_value(w_mine, l);
+            const double w_free = ordered_sum(a0, L8);
             double vo = 0.0, vu = 0.0;
             if (is_free) {
                 x = w_free > 0.0 ? (wl / w_free) * k_free : k_free / (double)n_free;
                 if (x > hi) vo = x - hi;
                 else if (x < lo) vu = lo - x;
             }
-            double over = 0.0, under = 0.0;
-            for (int l = 0; l < L; ++l) {
-                over += lane_value(vo, l);
-                under += lane_value(vu, l);
-            }
+            sync();
+            a0[tid] = vo;
+            a1[tid] = vu;
+            sync();
+            const double over = ordered_sum(a0, L8), under = ordered_sum(a1, L8);
             const int pin = (over == 0.0 && under == 0.0) ? 0 : (over >= under ? 1 : 2);
             if (pin == 0) break;
             bool pinned = false;
@@ -101,314 +264,83 @@ __device__ __forceinline__ void allocate_one_wave(const Dims &dm, const DevTable
                 pinned = true;
             }
             is_free = is_free && !pinned;
+            i1[tid] = pinned ? 1 : 0;
+            sync();
             // k_free stays an integer-valued double: the bound is subtracted once per pinned layer
-            const int n_pin = __popcll(__ballot(pinned));
+            const int n_pin = int_sum(i1, L8);
             const double bound = pin == 1 ? hi : lo;
             for (int q = 0; q < n_pin; ++q) k_free -= bound;
         }
-        double frac = -1.0;
+        sync();
+        double fr = -1.0;
         if (mine) {
             kk = max(lo_i, min((int)floor(x), n_vis));
-            frac = x - (double)kk;
+            fr = x - (double)kk;
         }
-        int tot = 0;
-        for (int l = 0; l < L; ++l) tot += __builtin_amdgcn_readlane(kk, l);
-        unsigned long long elig = __ballot(mine && kk < n_vis);
-        const long long left = k_tot - (long long)tot;
-        if (left > 0 && left <= (long long)__popcll(elig)) {
+        frac[tid] = fr;
+        i0[tid] = mine ? kk : 0;
+        i1[tid] = (mine && kk < n_vis) ? 1 : 0;  // eligible for a leftover token
+        sync();
+        const long long left = k_tot - (long long)int_sum(i0, L8);
+        const int n_elig = int_sum(i1, L8);
+        if (left > 0 && left <= (long long)n_elig) {
             // largest remainder: the `left` eligible layers that come first by (fraction descending, layer ascending)
-            int rank = 0;
-            for (int j = 0; j < L; ++j) {
-                const double fj = lane_value(frac, j);
-                rank += (int)((elig >> j) & 1ull) & ((int)(fj > frac) | ((int)(fj == frac) & (int)(j < lane)));
-            }
-            if (((elig >> lane) & 1ull) && rank < (int)left) kk += 1;
-        } else if (left > 0) {
-            // more leftovers than eligible layers: hand them out one by one, each to the eligible layer
-            // with the largest fraction (the lowest such layer), which then counts as served
-            for (long long rem = left; rem > 0 && elig != 0ull; --rem) {
-                int best = -1;
-                double fbest = 0.0;
-                for (int l = 0; l < L; ++l) {
-                    const double fl = lane_value(frac, l);
-                    if (((elig >> l) & 1ull) && (best < 0 || fl > fbest)) {
-                        best = l;
-                        fbest = fl;
+            if (mine && kk < n_vis) {
+                int rank = 0;
+                for (int j0 = 0; j0 < L8; j0 += 8) {  // branch-free groups of 8: their LDS reads are in flight together
+#pragma unroll
+                    for (int j = j0; j < j0 + 8; ++j) {
+                        const double fj = frac[j];
+                        rank += i1[j] & ((int)(fj > fr) | ((int)(fj == fr) & (int)(j < tid)));
                     }
                 }
-                if (lane == best) {
-                    kk += 1;
-                    frac = -1.0;
-                }
-                elig = __ballot(mine && kk < n_vis);
+                if (rank < (int)left) kk += 1;
             }
+        } else if (left > 0) {
+            // more leftovers than eligible layers: hand them out one by one, each to the eligible layer with the
+            // largest fraction (the lowest such layer), which then counts as served
+            sync();
+            if (tid == 0) {
+                for (long long rem = left; rem > 0; --rem) {
+                    int best = -1;
+                    for (int l = 0; l < L; ++l)
+                        if (i0[l] < n_vis && (best < 0 || frac[l] > frac[best])) best = l;
+                    if (best < 0) break;
+                    i0[best] += 1;
+                    frac[best] = -1.0;
+                }
+            }
+            sync();
+            if (mine) kk = i0[tid];
         }
-        if (mine) budgets[lane] = kk;
+        if (mine) budgets[tid] = kk;
+        sync();  // i0 is reused below
     }
     // cache layout: each layer's region holds system + kept + text rows and room for the decode
     // appends, and starts on a multiple of kCacheRowAlign rows
     const int nonvis = sq.seq_len - sq.vis_len;
-    const int cap = (nonvis + kk + dm.max_steps + kCacheRowAlign - 1) / kCacheRowAlign * kCacheRowAlign;
-    int off = 0;
-    for (int l = 0; l < L; ++l) {
-        const int cl = __builtin_amdgcn_readlane(cap, l);
-        off += l < lane ? cl : 0;
-    }
+    i0[tid] = mine ? (nonvis + kk + dm.max_steps + kCacheRowAlign - 1) / kCacheRowAlign * kCacheRowAlign : 0;
+    sync();
     if (mine) {
-        t.base_len[(int64_t)b * L + lane] = nonvis + kk;
-        t.layer_off[(int64_t)b * L + lane] = off;
-        t.len_off[(int64_t)b * L + lane] = make_int2(nonvis + kk, off);
-    }
-}
-
-__global__ __launch_bounds__(kBT) void budget_kernel(Dims dm, DevTables t, double retention, int mode, int min_keep,
-                                                     int skip_allocation, int use_moments, SeqArgs seqs) {
-    const int tid = threadIdx.x;
-    const int b = blockIdx.x;
-    const int L = dm.L;
-    const air_seq sq = seqs.s[b];  // from the kernel arguments: no table read in front of the moment entries
-    const int n_vis = sq.vis_len;
-    __shared__ double w[kBT], x[kBT], frac[kBT], sh_t[kBT], sh_k[kBT];
-    __shared__ int kk[kBT];
-    __shared__ unsigned char is_free[kBT];
-    __shared__ double s_sum_t, s_sum_k;
-    __shared__ long long s_ktot;
-    __shared__ int s_tot, s_elig, s_nfree, s_pin, s_npin;
-    __shared__ double s_wfree, s_kfree, v_over[kBT], v_under[kBT];
-    __shared__ double u_st[AIR_MAX_LAYERS * 16], u_sk[AIR_MAX_LAYERS * 16];  // per (layer, KV head), H_kv <= 16 staged
-
-    double *s_t = t.s_t + (int64_t)b * L;
-    double *s_k = t.s_k + (int64_t)b * L;
-    int32_t *budgets = t.budgets + (int64_t)b * L;
-
-    const bool stage = L * dm.Hkv <= AIR_MAX_LAYERS * 16;  // unit statistics fit the LDS staging arrays
-    if (!skip_allocation) {
-        if (use_moments) {
-            // Eq.9-10 of every (layer, KV head) from the moment entries of its importance row: entry c holds
-            // the sum S1_c, the mean m_c and the moments M2_c, M3_c about m_c of the n_c scores of kFinishChunks
-            // chunks.  With d_c = m_c - mu the central moments of the row are
-            //   sum (x - mu)^2 = sum_c M2_c + n_c d_c^2,   sum (x - mu)^3 = sum_c M3_c + 3 d_c M2_c + n_c d_c^3,
-            // sums of terms no larger than their result (raw power sums would cancel on rows of little spread).
-            constexpr int kEntryKeys = kFinishChunks * kChunkKeys;
-            const int nch = (n_vis + kEntryKeys - 1) / kEntryKeys;  // entries per unit
-            for (int p = tid; p < L * dm.Hkv; p += kBT) {
-                const int l = p / dm.Hkv, h = p % dm.Hkv;
-                const int64_t unit = ((int64_t)l * dm.B + b) * dm.Hkv + h;
-                const double *mo = t.moments + unit * dm.n_entries * 4;
-                double S1 = 0.0;
-#pragma unroll 4
-                for (int c = 0; c < nch; ++c) S1 += mo[4 * c];  // ordered sum; unrolled so that the loads of 4 entries are in flight together
-                double sk = 0.0;
-                if (n_vis >= 3) {
-                    const double n = (double)n_vis;
-                    const double mu = S1 / n;
-                    double c2 = 0.0, c3 = 0.0;
-#pragma unroll 4
-                    for (int c = 0; c < nch; ++c) {
-                        const double nc = (double)min(kEntryKeys, n_vis - c * kEntryKeys);
-                        const double dl = mo[4 * c + 1] - mu, M2 = mo[4 * c + 2], M3 = mo[4 * c + 3];
-                        c2 += M2 + nc * (dl * dl);
-                        c3 += (M3 + 3.0 * dl * M2) + nc * (dl * dl * dl);
-                    }
-                    const double sigma = sqrt(c2 / (n - 1.0));
-                    // zero spread (Eq.10 undefined; taken as 0): a standard deviation at most 1e-6 of the mean
-                    if (sigma > 1e-6 * fabs(mu)) sk = n / ((n - 1.0) * (n - 2.0)) * (c3 / (sigma * sigma * sigma));
-                }
-                t.unit_st[unit] = S1;
-                t.unit_sk[unit] = sk;
-                if (stage) {
-                    u_st[p] = S1;
-                    u_sk[p] = sk;
-                }
-            }
-            if (stage) lds_barrier();  // the statistics cross in LDS: no wait for the global stores above
-            else __syncthreads();
-        }
-        if (L <= 64) {  // the usual depth: one wave takes it from here
-            if (tid < 64) allocate_one_wave(dm, t, retention, mode, min_keep, 0, use_moments && stage, sq, b, u_st, u_sk);
-            return;
-        }
-        if (tid < L) {  // mean over the KV heads, left to right
-            double a = 0.0, c = 0.0;
-            for (int h = 0; h < dm.Hkv; ++h) {
-                const int64_t unit = ((int64_t)tid * dm.B + b) * dm.Hkv + h;
-                const bool lds = use_moments && stage;
-                a += lds ? u_st[tid * dm.Hkv + h] : t.unit_st[unit];
-                c += lds ? u_sk[tid * dm.Hkv + h] : t.unit_sk[unit];
-            }
-            sh_t[tid] = a / (double)dm.Hkv;
-            sh_k[tid] = c / (double)dm.Hkv;
-            s_t[tid] = sh_t[tid];
-            s_k[tid] = sh_k[tid];
-        }
-        lds_barrier();
-        const int lo_i = min(min_keep, n_vis);
-        const double lo = (double)lo_i, hi = (double)n_vis;
-        if (tid == 0) {
-            double sum_t = 0.0, sum_k = 0.0;
-            for (int l = 0; l < L; ++l) {
-                sum_t += sh_t[l];
-                sum_k += fmax(sh_k[l], 0.0);
-            }
-            s_sum_t = sum_t;
-            s_sum_k = sum_k;
-            long long k_tot = (long long)floor(retention * (double)n_vis * (double)L + 0.5);
-            const long long k_lo = (long long)L * lo_i, k_hi = (long long)L * n_vis;
-            s_ktot = k_tot < k_lo ? k_lo : (k_tot > k_hi ? k_hi : k_tot);
-            s_tot = 0;
-            s_elig = 0;
-            s_npin = 0;
-        }
-        lds_barrier();
-        if (tid < L) {
-            const double a = s_sum_t > 0.0 ? sh_t[tid] / s_sum_t : 1.0 / (double)L;
-            const double c = s_sum_k > 0.0 ? fmax(sh_k[tid], 0.0) / s_sum_k : 1.0 / (double)L;
-            double wl;
-            if (mode == AIR_BUDGET_UNIFORM) wl = 1.0 / (double)L;
-            else if (mode == AIR_BUDGET_STRENGTH) wl = a;
-            else if (mode == AIR_BUDGET_SKEW) wl = c;
-            else wl = 0.5 * (a + c);
-            w[tid] = wl;
-            x[tid] = 0.0;
-            is_free[tid] = 1;
-        }
-        lds_barrier();
-        // proportional allocation with clamping.  Per round: thread 0 sums the free weights in layer
-        // order, every layer forms its own x_l (the divisions run in parallel), thread 0 sums the
-        // violations in layer order and picks the side to pin.
-        if (tid == 0) s_kfree = (double)s_ktot;
-        for (int it = 0; it < L + 1; ++it) {
-            lds_barrier();
-            if (tid == 0) {
-                double w_free = 0.0;
-                int n_free = 0;
-#pragma unroll 8
-                for (int l = 0; l < L; ++l) {  // branch-free: a pinned layer adds an exact zero
-                    w_free += is_free[l] ? w[l] : 0.0;
-                    n_free += is_free[l];
-                }
-                s_wfree = w_free;
-                s_nfree = n_free;
-            }
-            lds_barrier();
-            if (s_nfree == 0) break;
-            if (tid < L) {
-                double vo = 0.0, vu = 0.0;
-                if (is_free[tid]) {
-                    const double xl = s_wfree > 0.0 ? (w[tid] / s_wfree) * s_kfree : s_kfree / (double)s_nfree;
-                    x[tid] = xl;
-                    if (xl > hi) vo = xl - hi;
-                    else if (xl < lo) vu = lo - xl;
-                }
-                v_over[tid] = vo;
-                v_under[tid] = vu;
-            }
-            lds_barrier();
-            if (tid == 0) {
-                double over = 0.0, under = 0.0;
-#pragma unroll 4
-                for (int l = 0; l < L; ++l) {  // pinned layers contribute exact zeros
-                    over += v_over[l];
-                    under += v_under[l];
-                }
-                s_pin = (over == 0.0 && under == 0.0) ? 0 : (over >= under ? 1 : 2);
-            }
-            lds_barrier();
-            const int pin = s_pin;
-            if (pin == 0) break;
-            int pinned = 0;
-            if (tid < L && is_free[tid]) {
-                if (pin == 1 && x[tid] > hi) {
-                    x[tid] = hi;
-                    is_free[tid] = 0;
-                    pinned = 1;
-                } else if (pin == 2 && x[tid] < lo) {
-                    x[tid] = lo;
-                    is_free[tid] = 0;
-                    pinned = 1;
-                }
-            }
-            // k_free stays an integer-valued double: subtracting the bound once per pinned layer is exact in any order
-            const unsigned long long any = __ballot(pinned);
-            if (any && (tid & 63) == 0) atomicAdd(&s_npin, __popcll(any));
-            lds_barrier();
-            if (tid == 0) {
-                const double bound = pin == 1 ? hi : lo;
-                for (int q = 0; q < s_npin; ++q) s_kfree -= bound;
-                s_npin = 0;
-            }
-        }
-        lds_barrier();
-        if (tid < L) {
-            int fl = (int)floor(x[tid]);
-            fl = max(lo_i, min(fl, n_vis));
-            kk[tid] = fl;
-            frac[tid] = x[tid] - (double)fl;
-            atomicAdd(&s_tot, fl);
-            if (fl < n_vis) atomicAdd(&s_elig, 1);
-        }
-        lds_barrier();
-        const long long left = s_ktot - (long long)s_tot;
-        if (left > 0 && left <= (long long)s_elig) {
-            // largest remainder: the `left` eligible layers that come first by (fraction descending, layer ascending)
-            int add = 0;
-            if (tid < L && kk[tid] < n_vis) {
-                int rank = 0;
-                const double mine = frac[tid];
-#pragma unroll 8
-                for (int j = 0; j < L; ++j) {  // branch-free, so that the LDS reads of several layers are in flight together
-                    const double fj = frac[j];
-                    rank += (int)(kk[j] < n_vis) & ((int)(fj > mine) | ((int)(fj == mine) & (int)(j < tid)));
-                }
-                add = rank < (int)left ? 1 : 0;
-            }
-            lds_barrier();
-            if (tid < L) kk[tid] += add;
-        } else if (left > 0) {
-            if (tid == 0) {  // more leftovers than eligible layers: hand them out one by one
-                long long rem = left;
-                while (rem > 0) {
-                    int best = -1;
-                    for (int l = 0; l < L; ++l)
-                        if (kk[l] < n_vis && (best < 0 || frac[l] > frac[best])) best = l;
-                    if (best < 0) break;
-                    kk[best] += 1;
-                    frac[best] = -1.0;
-                    --rem;
-                }
-            }
-        }
-        lds_barrier();
-        if (tid < L) budgets[tid] = kk[tid];
-        lds_barrier();
-    }
-
-    if (L <= 64) {  // only the layout is left (the budgets were set by the caller)
-        if (tid < 64) allocate_one_wave(dm, t, retention, mode, min_keep, 1, false, sq, b, u_st, u_sk);
-        return;
-    }
-    // cache layout: each layer's region holds system + kept + text rows and room for the
-    // decode appends, and starts on a multiple of kCacheRowAlign rows
-    if (skip_allocation && tid < L) kk[tid] = budgets[tid];  // otherwise kk still holds what was just written
-    lds_barrier();
-    const int nonvis = sq.seq_len - sq.vis_len;
-    if (tid < L) {
         int off = 0;
-#pragma unroll 8
-        for (int l = 0; l < tid; ++l) {
-            const int cap = nonvis + kk[l] + dm.max_steps;
-            off += (cap + kCacheRowAlign - 1) / kCacheRowAlign * kCacheRowAlign;
+        for (int l0 = 0; l0 < tid; l0 += 8) {
+#pragma unroll
+            for (int j = 0; j < 8; ++j) off += l0 + j < tid ? i0[l0 + j] : 0;
         }
-        t.base_len[(int64_t)b * L + tid] = nonvis + kk[tid];
+        t.base_len[(int64_t)b * L + tid] = nonvis + kk;
         t.layer_off[(int64_t)b * L + tid] = off;
-        t.len_off[(int64_t)b * L + tid] = make_int2(nonvis + kk[tid], off);
+        t.len_off[(int64_t)b * L + tid] = make_int2(nonvis + kk, off);
     }
 }
 
 hipError_t launch_budget(hipStream_t s, const Dims &dm, const DevTables &t, double retention, int mode,
                          int min_keep, int skip_allocation, int use_moments, const SeqArgs &seqs) {
-    hipLaunchKernelGGL(budget_kernel, dim3(dm.B), dim3(kBT), 0, s, dm, t, retention, mode, min_keep, skip_allocation,
-                       use_moments, seqs);
+    if (dm.L <= 64)
+        hipLaunchKernelGGL(budget_kernel<true>, dim3(dm.B), dim3(kBT), 0, s, dm, t, retention, mode, min_keep,
+                           skip_allocation, use_moments, seqs);
+    else
+        hipLaunchKernelGGL(budget_kernel<false>, dim3(dm.B), dim3(kBT), 0, s, dm, t, retention, mode, min_keep,
+                           skip_allocation, use_moments, seqs);
     return hipGetLastError();
 }
 
