@@ -442,15 +442,18 @@ air_status air_select_compact(air_ctx *ctx, void *stream, int32_t l0, int32_t l1
 }
 
 // Shape of one decode launch: `splits` workgroups of `waves` wavefronts per (layer, sequence, KV
-// head); a wave works in iterations of 16 * tiles keys.  Eight waves of 64-key iterations keep
-// every load of an iteration in flight within the 256 registers a lane has at that occupancy.
-// The waves of a workgroup merge through LDS, which is cheap; further splits exchange partials
-// through memory (merged by the last workgroup to finish), which costs about as much as two
-// more iterations per wave, so they are added only while a wave would otherwise run more than
-// kItersPerWave iterations at the average cache length and the launch is short of workgroups.
+// head); a wave works in iterations of 16 * tiles keys.  Measured on this machine: one workgroup streams
+// about 100 GB/s (what one CU's vector memory path takes in), the launch as a whole about 6 TB/s, and a
+// split costs about 3.7 us (partials written through to memory, an arrival counter, the last
+// workgroup reading them back: four dependent trips).  So a unit is split only when the launch is so small
+// that its time is one workgroup's streaming time and the split saves more of that than it costs.
+// Four waves per workgroup beat eight at every cache length tried (112 units, 215 to 7400 keys: 10.4
+// against 10.8 us at 10 % retention, 34.9 against 36.0 at 50 %, 75.3 against 78.2 with the full cache):
+// the merge of the waves through LDS is shorter and the streaming is bound by the CU, not by the number of waves.
 // air_set_tuning overrides the choice (tests, tuning).
 static void decode_shape(const air_ctx *ctx, int n_layers_in_launch, int appended, int *splits, int *waves, int *tiles) {
-    constexpr int kItersPerWave = 3, kEnoughWorkgroups = 256, kEnoughWaves = 1536;
+    constexpr int kEnoughWorkgroups = 256, kEnoughWaves = 1536;
+    constexpr double kWorkgroupGBs = 100.0, kLaunchGBs = 6000.0, kSplitUs = 3.7;
     const air_config &c = ctx->cfg;
     double avg_len = 0.0;
     for (int b = 0; b < c.batch; ++b) {
@@ -459,26 +462,30 @@ static void decode_shape(const air_ctx *ctx, int n_layers_in_launch, int appende
     }
     avg_len /= c.batch;
     const int64_t units = (int64_t)n_layers_in_launch * c.batch * c.n_kv_heads;
-    // A launch of a handful of units (one layer of one sequence) is bound by what one CU can stream
-    // (about 100 GB/s): the unit is cut into splits of about one 32-key chunk per wave, which beats the
-    // exchange of the partials (4 units of ~900 keys: 8.4 us against 9.9 us as single workgroups).
+    // A launch of a handful of units (one layer of one sequence) is bound by what one CU can stream: the unit
+    // is cut into splits of about one 32-key chunk per wave, which beats the exchange of the partials (4 units
+    // of ~900 keys: 8.4 us against 9.9 us as single workgroups).
     const bool tiny_launch = units <= 16;
     int kt = tiny_launch ? 2 : 4;
     if (ctx->tune.decode_tiles > 0) kt = ctx->tune.decode_tiles;
     const int64_t iters = (int64_t)((avg_len + 16.0 * kt - 1.0) / (16.0 * kt));
-    // Waves per workgroup: enough for the launch to hold about 1536 waves, and beyond that one wave per 8
-    // iterations of the unit.  Many short units run fastest with one wave each (no merge, no barrier:
-    // 1792 units of ~600 keys 85 us against 97 us with four waves); few units need all 8 to have
-    // enough loads in flight.
+    // Waves per workgroup: enough for the launch to hold about 1536 waves, and beyond that one wave per 16
+    // iterations of the unit, four at most (eight in a tiny launch).  Many short units run fastest with one wave
+    // each (no merge, no barrier: 1792 units of ~600 keys 85 us against 97 us with four waves).
+    const int w_max = tiny_launch ? 8 : 4;
     int w = 1;
-    while (w < 8 && (units * w < kEnoughWaves || iters >= 16 * w)) w *= 2;
+    while (w < w_max && (units * w < kEnoughWaves || iters >= 16 * w)) w *= 2;
     if (ctx->tune.decode_waves > 0) w = ctx->tune.decode_waves;
     if (kt == 8 && w == 8) w = 4;
     int64_t s = 1;
     if (tiny_launch) {
         while (s < kMaxSplits && iters > 4 * s && units * s * 2 <= kEnoughWorkgroups) s *= 2;
     } else {
-        while (s < kMaxSplits && iters > (int64_t)kItersPerWave * w * s && units * s < kEnoughWorkgroups) s *= 2;
+        const double unit_bytes = avg_len * 2.0 * c.head_dim * (c.dtype == AIR_BF16 ? 2.0 : 4.0);
+        const double launch_us = (double)units * unit_bytes / (kLaunchGBs * 1e3);
+        auto cost = [&](int64_t n) { return fmax(launch_us, unit_bytes / n / (kWorkgroupGBs * 1e3)) + (n > 1 ? kSplitUs : 0.0); };
+        for (int64_t n = 2; n <= kMaxSplits && units * n <= kEnoughWorkgroups; n *= 2)
+            if (cost(n) < cost(s)) s = n;
     }
     if (ctx->tune.decode_splits > 0) s = ctx->tune.decode_splits;
     *splits = (int)s;
