@@ -306,7 +306,8 @@ air_status air_score(air_ctx *ctx, void *stream, int32_t l0, int32_t l1, const a
     const int inline_rows = ctx->cfg.alpha > 0.0 && !ctx->dm.vis_window && ctx->tune.score_rows_kernel != 1;
     // Windows that are known to exceed the stash (alpha = 0 turns the whole candidate span into rows)
     // read K_v twice: run the two kernels over groups of layers whose keys fit the memory-side cache.
-    if (mfma && ctx->cfg.alpha == 0.0 && (int64_t)ctx->dm.G * ctx->cfg.max_window > kStashRows) {
+    const int many_rows = mfma && ctx->cfg.alpha == 0.0 && (int64_t)ctx->dm.G * ctx->cfg.max_window > kStashRows;
+    if (many_rows) {
         double layer_bytes = 0.0;
         for (int b = 0; b < ctx->cfg.batch; ++b) layer_bytes += (double)seqs[b].vis_len * ctx->cfg.n_kv_heads * 128 * 2;
         const double block = (double)(ctx->tune.score_block_mb > 0 ? ctx->tune.score_block_mb : 160) * 1048576.0;
@@ -340,8 +341,8 @@ air_status air_score(air_ctx *ctx, void *stream, int32_t l0, int32_t l1, const a
             LaunchLayers lg;
             memset(&lg, 0, sizeof(lg));
             for (int i = 0; i < gn; ++i) lg.p[i] = ll.p[g0 + i];
-            e = launch_score_mfma(s, ctx->dm, ctx->tab, 1, c0 + g0, gn, lg, *strides, sa, inline_rows);
-            if (e == hipSuccess) e = launch_score_mfma(s, ctx->dm, ctx->tab, 2, c0 + g0, gn, lg, *strides, sa, inline_rows);
+            e = launch_score_mfma(s, ctx->dm, ctx->tab, 1, c0 + g0, gn, lg, *strides, sa, inline_rows, many_rows);
+            if (e == hipSuccess) e = launch_score_mfma(s, ctx->dm, ctx->tab, 2, c0 + g0, gn, lg, *strides, sa, inline_rows, many_rows);
         }
         if (e != hipSuccess) return hip_fail(ctx, e, "air_score launch");
     }

@@ -103,7 +103,7 @@ hipError_t launch_stats(hipStream_t s, const Dims &dm, const DevTables &t, int l
 hipError_t launch_elite_mfma(hipStream_t s, const Dims &dm, const DevTables &t, int l0, int nl, const LaunchLayers &ll,
                              const air_strides &st, const SeqArgs &seqs, double alpha);
 hipError_t launch_score_mfma(hipStream_t s, const Dims &dm, const DevTables &t, int pass, int l0, int nl,
-                             const LaunchLayers &ll, const air_strides &st, const SeqArgs &seqs, int inline_rows);
+                             const LaunchLayers &ll, const air_strides &st, const SeqArgs &seqs, int inline_rows, int many_rows);
 hipError_t launch_budget(hipStream_t s, const Dims &dm, const DevTables &t, double retention, int mode,
                          int min_keep, int skip_allocation, int use_moments, const SeqArgs &seqs);
 hipError_t launch_select(hipStream_t s, const Dims &dm, const DevTables &t, int l0, int nl, int threads, int direct_max);

@@ -33,7 +33,7 @@ namespace air {
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(4))) float f32x4;
 
-constexpr int kRowsLds = 1024;  // rows whose (M, w) are staged in LDS at a time (recompute path)
+constexpr int kRowsLds = 512;  // rows whose (M, w) are staged in LDS at a time (recompute path)
 
 struct UnitCtx {
     int kvh, b, li, l, chunk, t0, G, W, R_total;
@@ -123,6 +123,36 @@ __device__ __forceinline__ void block_logits(const DevTables &t, const UnitCtx &
     logits_of(qa, kreg, s);
 }
 
+// Windows with many rows per unit (a continuous or all-text window: every span token of every head is a row) keep
+// the query rows of up to kLdsRows rows in LDS, so that a block of 16 rows costs four LDS reads per lane instead
+// of two dependent trips to memory (row token, then row).  Rows are padded to 272 bytes: the sixteen rows a
+// load touches then fall into different banks.
+constexpr int kLdsRows = 128;
+constexpr int kLdsRowElems = 128 + 8;
+typedef bf16_t QRows[kLdsRowElems];
+
+// rows [r0, r0 + count) of the unit's row list into s_q[0 .. count); sixteen threads per row, 16 bytes each
+__device__ __forceinline__ void stage_query_rows(const DevTables &t, const UnitCtx &u, const air_strides &st, const int *s_pref,
+                                                 int r0, int count, QRows *s_q) {
+    for (int p = threadIdx.x; p < count * 16; p += blockDim.x) {
+        const int rr = p >> 4, piece = p & 15;
+        const int rho = r0 + rr;
+        const int g = head_of_row(s_pref, u.G, rho);
+        const int tok = t.elite_idx[(u.hrow0 + g) * u.W + (rho - s_pref[g])];
+        const bf16_t *qr = u.q + (int64_t)(u.kvh * u.G + g) * st.q_h + (int64_t)(tok - u.qbase) * st.q_t;
+        *reinterpret_cast<uint4 *>(&s_q[rr][8 * piece]) = *reinterpret_cast<const uint4 *>(qr + 8 * piece);
+    }
+}
+// A operand of the block of 16 rows that starts at staged row rb (see load_rows for the row order); rows past `count` are zero
+__device__ __forceinline__ void load_rows_lds(const QRows *s_q, int rb, int count, int n, int c, uint4 (&qa)[4]) {
+    const int rr = rb + 4 * (n & 3) + (n >> 2);
+#pragma unroll
+    for (int sl = 0; sl < 4; ++sl) {
+        qa[sl] = make_uint4(0, 0, 0, 0);
+        if (rr < count) qa[sl] = *reinterpret_cast<const uint4 *>(&s_q[rr][32 * sl + 8 * c]);
+    }
+}
+
 __device__ __forceinline__ bool unit_setup(const Dims &dm, const SeqArgs &seqs, int l0, const LaunchLayers &ll,
                                            const air_strides &st, UnitCtx &u, int chunks_per_wg) {
     u.chunk = blockIdx.x * chunks_per_wg;  // first chunk of this workgroup
@@ -157,7 +187,9 @@ __device__ __forceinline__ int stash_pos(int key_in_chunk) {
 // VIS: the rows are the tokens of a visual window (all heads have the same win_len rows); row rho sits at
 // visual index prow0 + rho % win_len and sees the keys up to itself.  A (row, chunk) pair that lies wholly
 // behind the row leaves the partial (-inf, 0) and zeros in the stash.
-template <bool VIS>
+// MANY: launches whose window turns its whole span into rows (dozens to hundreds of rows per unit): the query rows are
+// staged in LDS, kLdsRows at a time.
+template <bool VIS, bool MANY>
 __global__ __launch_bounds__(256, 4) void score_stream_kernel(Dims dm, DevTables t, int l0, LaunchLayers ll,
                                                               air_strides st, SeqArgs seqs) {
     const int tid = threadIdx.x, wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63, n = lane & 15, c = lane >> 4;
@@ -175,7 +207,7 @@ __global__ __launch_bounds__(256, 4) void score_stream_kernel(Dims dm, DevTables
     u.R_total = s_pref[u.G];
     const bool stash = u.R_total <= kStashRows;
     uint4 qa0[4];
-    load_rows(t, u, st, s_pref, 0, n, c, qa0);
+    if (!MANY) load_rows(t, u, st, s_pref, 0, n, c, qa0);
 
 #pragma unroll
     for (int ci = 0; ci < kStreamChunks; ++ci) {
@@ -183,10 +215,8 @@ __global__ __launch_bounds__(256, 4) void score_stream_kernel(Dims dm, DevTables
         if (chunk >= last) break;
         if (chunk + 1 < last) load_keys(u, st, (chunk + 1) * kChunkKeys + wave * 64, n, c, knext, vnext);
         float *stash_base = t.stash + ((u.unit * dm.n_chunks + chunk) * (int64_t)kStashRows) * kChunkKeys;
-        for (int rb = 0; rb < u.R_total; rb += 16) {
-            f32x4 s[4];
-            if (rb == 0) logits_of(qa0, kreg, s);
-            else block_logits(t, u, st, s_pref, rb, n, c, kreg, s);
+        // per (row, chunk) maximum and sum-exp of the block of 16 rows that starts at list row rb, from its logits
+        auto reduce_block = [&](int rb, f32x4 (&s)[4]) __attribute__((always_inline)) {
             const int n_i = min(4, (u.R_total - rb + 3) >> 2);  // live values of i (uniform over the workgroup)
             int lim[4];  // VIS: last key of the lane's tiles that row i sees, relative to the lane's key of tile 0
 #pragma unroll
@@ -241,6 +271,29 @@ __global__ __launch_bounds__(256, 4) void score_stream_kernel(Dims dm, DevTables
                 const int g = head_of_row(s_pref, u.G, rho);
                 const int64_t slot = (u.hrow0 + g) * u.W + (rho - s_pref[g]);
                 t.part[slot * dm.n_chunks + chunk] = make_float2(s_mw[tid], Z);
+            }
+        };
+        if constexpr (!MANY) {
+            for (int rb = 0; rb < u.R_total; rb += 16) {
+                f32x4 s[4];
+                if (rb == 0) logits_of(qa0, kreg, s);
+                else block_logits(t, u, st, s_pref, rb, n, c, kreg, s);
+                reduce_block(rb, s);
+            }
+        } else {
+            __shared__ QRows s_q[kLdsRows];
+            for (int rs = 0; rs < u.R_total; rs += kLdsRows) {
+                const int cnt = min(kLdsRows, u.R_total - rs);
+                if (rs) lds_barrier();  // the blocks of the rows staged before have been read
+                stage_query_rows(t, u, st, s_pref, rs, cnt, s_q);
+                lds_barrier();
+                for (int rb = 0; rb < cnt; rb += 16) {
+                    uint4 qa[4];
+                    load_rows_lds(s_q, rb, cnt, n, c, qa);
+                    f32x4 s[4];
+                    logits_of(qa, kreg, s);
+                    reduce_block(rs + rb, s);
+                }
             }
         }
 #pragma unroll
@@ -321,7 +374,8 @@ __global__ __launch_bounds__(64 * kRowWaves) void score_rows_mfma_kernel(Dims dm
 // INLINE: no row-parameter kernel has run; every workgroup forms the parameters of the unit's rows
 // itself from the chunk partials (the elite window's handful of rows: cheaper than a launch).
 
-template <bool VIS, bool INLINE>
+// MANY: as in the stream kernel, the query rows of the recompute path are staged in LDS.
+template <bool VIS, bool INLINE, bool MANY>
 __global__ __launch_bounds__(256, 4) void score_finish_kernel(Dims dm, DevTables t, int l0, LaunchLayers ll,
                                                            air_strides st, SeqArgs seqs) {
     const int tid = threadIdx.x, wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63, n = lane & 15, c = lane >> 4;
@@ -522,7 +576,22 @@ __global__ __launch_bounds__(256, 4) void score_finish_kernel(Dims dm, DevTables
             if (chunk == first || u.R_total > kRowsLds) stage_rows(rs, rows_here);
             for (int rb = 0; rb < rows_here; rb += 16) {
                 f32x4 s[4];
-                block_logits(t, u, st, s_pref, rs + rb, n, c, kreg, s);
+                if constexpr (MANY) {
+                    // the query rows of rows rs + [qs, qs + kLdsRows) are in LDS; they are staged once per workgroup when the
+                    // unit has no more rows than that, else again for every chunk
+                    __shared__ QRows s_q[kLdsRows];
+                    const int qs = rb / kLdsRows * kLdsRows, cnt = min(kLdsRows, rows_here - qs);
+                    if (rb == qs && (chunk == first || u.R_total > kLdsRows)) {
+                        lds_barrier();  // the blocks of the rows staged before have been read
+                        stage_query_rows(t, u, st, s_pref, rs + qs, cnt, s_q);
+                        lds_barrier();
+                    }
+                    uint4 qa[4];
+                    load_rows_lds(s_q, rb - qs, cnt, n, c, qa);
+                    logits_of(qa, kreg, s);
+                } else {
+                    block_logits(t, u, st, s_pref, rs + rb, n, c, kreg, s);
+                }
                 const int n_i = min(4, (rows_here - rb + 3) >> 2);
 #pragma unroll
                 for (int i = 0; i < 4; ++i) {
@@ -740,15 +809,20 @@ hipError_t launch_elite_mfma(hipStream_t s, const Dims &dm, const DevTables &t, 
 }
 
 hipError_t launch_score_mfma(hipStream_t s, const Dims &dm, const DevTables &t, int pass, int l0, int nl,
-                             const LaunchLayers &ll, const air_strides &st, const SeqArgs &seqs, int inline_rows) {
-    if (pass == 1)
-        hipLaunchKernelGGL(dm.vis_window ? score_stream_kernel<true> : score_stream_kernel<false>,
-                           dim3((dm.n_chunks + kStreamChunks - 1) / kStreamChunks, dm.Hkv, nl * dm.B), dim3(256), 0, s, dm, t, l0,
-                           ll, st, seqs);
-    else {
+                             const LaunchLayers &ll, const air_strides &st, const SeqArgs &seqs, int inline_rows, int many_rows) {
+    if (pass == 1) {
+        const dim3 grid((dm.n_chunks + kStreamChunks - 1) / kStreamChunks, dm.Hkv, nl * dm.B);
+        if (dm.vis_window) {
+            if (many_rows) hipLaunchKernelGGL((score_stream_kernel<true, true>), grid, dim3(256), 0, s, dm, t, l0, ll, st, seqs);
+            else hipLaunchKernelGGL((score_stream_kernel<true, false>), grid, dim3(256), 0, s, dm, t, l0, ll, st, seqs);
+        } else {
+            if (many_rows) hipLaunchKernelGGL((score_stream_kernel<false, true>), grid, dim3(256), 0, s, dm, t, l0, ll, st, seqs);
+            else hipLaunchKernelGGL((score_stream_kernel<false, false>), grid, dim3(256), 0, s, dm, t, l0, ll, st, seqs);
+        }
+    } else {
         const dim3 grid((dm.n_chunks + kFinishChunks - 1) / kFinishChunks, dm.Hkv, nl * dm.B);
         if (inline_rows && !dm.vis_window) {
-            hipLaunchKernelGGL((score_finish_kernel<false, true>), grid, dim3(256), 0, s, dm, t, l0, ll, st, seqs);
+            hipLaunchKernelGGL((score_finish_kernel<false, true, false>), grid, dim3(256), 0, s, dm, t, l0, ll, st, seqs);
             return hipGetLastError();
         }
         // a wave per row when the launch has few units; with many units, 4 waves walk the rows
@@ -756,10 +830,13 @@ hipError_t launch_score_mfma(hipStream_t s, const Dims &dm, const DevTables &t, 
                            dim3(nl * dm.B * dm.Hkv >= 512 ? 256 : 64 * kRowWaves), 0, s, dm, t, l0, seqs);
         hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;
-        if (dm.vis_window)
-            hipLaunchKernelGGL((score_finish_kernel<true, false>), grid, dim3(256), 0, s, dm, t, l0, ll, st, seqs);
-        else
-            hipLaunchKernelGGL((score_finish_kernel<false, false>), grid, dim3(256), 0, s, dm, t, l0, ll, st, seqs);
+        if (dm.vis_window) {
+            if (many_rows) hipLaunchKernelGGL((score_finish_kernel<true, false, true>), grid, dim3(256), 0, s, dm, t, l0, ll, st, seqs);
+            else hipLaunchKernelGGL((score_finish_kernel<true, false, false>), grid, dim3(256), 0, s, dm, t, l0, ll, st, seqs);
+        } else {
+            if (many_rows) hipLaunchKernelGGL((score_finish_kernel<false, false, true>), grid, dim3(256), 0, s, dm, t, l0, ll, st, seqs);
+            else hipLaunchKernelGGL((score_finish_kernel<false, false, false>), grid, dim3(256), 0, s, dm, t, l0, ll, st, seqs);
+        }
     }
     return hipGetLastError();
 }

@@ -332,7 +332,7 @@ def test_generic_path_other_storage_combinations():
 
 def test_all_text_window_with_more_rows_than_one_staging_round():
     # 7 heads x 160 text tokens = 1120 window rows per unit: the finish kernel stages its row parameters
-    # in rounds of 1024, and the elite-text block of Eq.7 is 160 x 160 per head
+    # in rounds of 512, and the elite-text block of Eq.7 is 160 x 160 per head
     w = synth.get_workload(2).scaled(n_layers=1, n_vis=600, n_text=160, decode_steps=1)
     _run_case(w, 0.10, alpha=0.0, steps=1)
 
