@@ -494,11 +494,11 @@ def main():
     # FETCH_SIZE / WRITE_SIZE counters of this kernel from the committed summary named below, which is remade
     # whenever the kernel changes (the summary states its command and the counter scaling).
     try:
-        with open(os.path.join(ROOT, "profiles", "hbm_traffic_config2.txt")) as f:
+        with open(os.path.join(ROOT, "profiles", "hbm_traffic_per_kernel_config2_config5.txt")) as f:
             tr = json.load(f).get(result["config"]["workload"], {}).get("air_decode_attn")
         if tr and not args.per_layer:
             result["roofline"]["traffic"] = tr["fetch_bytes"] + tr["write_bytes"]
-            result["roofline"]["traffic_source"] = ("profiles/hbm_traffic_config2.txt: rocprofv3 --pmc byte counters of "
+            result["roofline"]["traffic_source"] = ("profiles/hbm_traffic_per_kernel_config2_config5.txt: rocprofv3 --pmc byte counters of "
                                                     "this kernel, a committed summary, not measured in this run")
     except (OSError, ValueError):
         pass
