@@ -71,6 +71,14 @@ def test_invalid_configs_are_rejected_on_the_host():
     assert not h.value
     assert lib.air_destroy(None) == A.binding.AIR_ERR_INVALID_ARG
     assert lib.air_budget(None, None) == A.binding.AIR_ERR_INVALID_ARG
+    assert lib.air_set_tuning(None, None) == A.binding.AIR_ERR_INVALID_ARG
+    assert lib.air_decode_attn_static(None, None, 0, 1, None, None, None, None) == A.binding.AIR_ERR_INVALID_ARG
+    # the in-place cache exists for the bf16 / head_dim 128 kernels only
+    assert lib.air_workspace_bytes(C.byref(A.make_config(**good, cache_in_place=1))) == 0
+    big = dict(good, head_dim=128, dtype=A.AIR_BF16)
+    with_pool = lib.air_workspace_bytes(C.byref(A.make_config(**big)))
+    without = lib.air_workspace_bytes(C.byref(A.make_config(**big, cache_in_place=1)))
+    assert 0 < without < with_pool
 
 
 def test_missing_library_fails_loudly(tmp_path):

@@ -23,9 +23,13 @@ def _roomy(x_host, extra_rows, dev):
     return big
 
 
-@pytest.mark.parametrize("base,batch,n_vis,retention,steps", [(2, 1, 1500, 0.10, 40), (2, 1, 700, 1.00, 35), (2, 1, 3000, 0.01, 3),
-                                                              (3, 3, 900, 0.25, 34)])
-def test_in_place_compaction_equals_the_pool_path(base, batch, n_vis, retention, steps):
+@pytest.mark.parametrize("base,batch,n_vis,retention,steps,tuning",
+                         [(2, 1, 1500, 0.10, 40, None), (2, 1, 700, 1.00, 35, None), (2, 1, 3000, 0.01, 3, None),
+                          (3, 3, 900, 0.25, 34, None),
+                          # the split-K instance of the in-place decode kernel, and through the entry point with the static exchange area
+                          (2, 1, 1500, 0.10, 36, dict(decode_splits=4, decode_waves=4, decode_tiles=4)),
+                          (2, 1, 1500, 0.10, 36, dict(decode_splits=2, decode_waves=8, decode_tiles=2, static=True))])
+def test_in_place_compaction_equals_the_pool_path(base, batch, n_vis, retention, steps, tuning):
     import torch
 
     import paper_2503_23956_amd as A
@@ -45,6 +49,10 @@ def test_in_place_compaction_equals_the_pool_path(base, batch, n_vis, retention,
     v2 = [_roomy(li.v, extra, dev) for li in layers]
     pool = A.AirCache(config_for(w, retention, seqs=seqs, max_decode_steps=steps), dev)
     inpl = A.AirCache(config_for(w, retention, seqs=seqs, max_decode_steps=steps, cache_in_place=1), dev)
+    use_static = bool(tuning and tuning.get("static"))
+    if tuning:
+        for ac in (pool, inpl):
+            ac.air_set_tuning(**{k_: v_ for k_, v_ in tuning.items() if k_ != "static"})
     # the workspace of the in-place context holds no cache pool
     max_nonvis = max(s.seq_len - s.vis_len for s in seqs)
     kept = int(np.floor(retention * max(s.vis_len for s in seqs) * L + 0.5))
@@ -76,7 +84,7 @@ def test_in_place_compaction_equals_the_pool_path(base, batch, n_vis, retention,
         qs, ks, vs = zip(*[synth.decode_inputs(w, l, step) for l in range(L)])
         qn, kn, vn = (to_device(np.stack(x), dev) for x in (qs, ks, vs))
         pool.air_decode_attn(0, L, qn, kn, vn, out_a)
-        inpl.air_decode_attn(0, L, qn, kn, vn, out_b)
+        (inpl.air_decode_attn_static if use_static else inpl.air_decode_attn)(0, L, qn, kn, vn, out_b)
         torch.cuda.synchronize()
         assert not torch.isnan(out_b.float()).any()
         assert torch.equal(out_a, out_b), f"decode step {step}"
