@@ -14,7 +14,8 @@ Eq.10 skewness, Eq.11 layer budget; Alg.1 is the two-loop procedure).
 Readings taken where the paper leaves a choice (all listed in the design notes):
 heads are scored per query head and averaged over the query heads that share a
 KV head; the scale is 1/sqrt(head_dim); Eq.7's softmax runs over the visual
-keys plus that head's elite text keys with no mask; system-prompt tokens are
+keys plus that head's elite text keys with no mask (a causal mask over the elite
+text keys is an option, off by default); system-prompt tokens are
 never scored and always kept; Eq.10 uses the sample standard deviation; the
 a row whose
 standard deviation is at most 1e-6 of its mean has zero spread (skewness 0); the
@@ -85,11 +86,14 @@ def elite_set(logits: np.ndarray, alpha: float) -> np.ndarray:
 # Eq.6-8: cross-modal attention of the elite window and importance scores
 # ---------------------------------------------------------------------------
 def head_importance(q_text_h: np.ndarray, k_h: np.ndarray, seg: Segments, alpha: float,
-                    return_attn: bool = False):
+                    return_attn: bool = False, causal_text: bool = False):
     """Importance of the visual tokens seen by one query head (Eq.4-8).
 
     q_text_h: [n_text][d] queries of the text span of this query head.
     k_h     : [seq_len][d] keys of the KV head this query head reads.
+    causal_text: Eq.7 as printed has no mask (the default).  With this flag an elite row sees only the
+        elite text keys at or before its own position, as it did in the model's causal prefill; the
+        visual keys all precede every text token and are never masked.
     Returns (I_h [vis_len], elite positions as absolute token indices
     [, A_vtk [R][vis_len + R]]).
     """
@@ -102,6 +106,9 @@ def head_importance(q_text_h: np.ndarray, k_h: np.ndarray, seg: Segments, alpha:
     q_e = q_text_h[elite - t0]                                  # Q_tk   (Eq.6)
     k_ve = np.concatenate([k_h[seg.vis_start:t0], k_h[elite]])  # K_vtk  (Eq.6)
     s = (q_e @ k_ve.T) / math.sqrt(d)
+    if causal_text:  # elite key j (a text token) is visible to elite row r only if it does not come after it
+        later = elite[None, :] > elite[:, None]
+        s[:, seg.vis_len:] = np.where(later, -np.inf, s[:, seg.vis_len:])
     s = s - s.max(axis=1, keepdims=True)
     p = np.exp(s)
     a = p / p.sum(axis=1, keepdims=True)                        # A_vtk  (Eq.7)
@@ -155,7 +162,7 @@ def layer_importance_visual_window(q_win: np.ndarray, k: np.ndarray, seg: Segmen
     return imp, [rows.copy() for _ in range(hq)]
 
 
-def layer_importance(q_text: np.ndarray, k: np.ndarray, seg: Segments, alpha: float):
+def layer_importance(q_text: np.ndarray, k: np.ndarray, seg: Segments, alpha: float, causal_text: bool = False):
     """Per-KV-head importance of one layer of one sequence.
 
     q_text: [H_q][n_text][d], k: [H_kv][seq_len][d] (fp64 values of the stored tensors).
@@ -168,7 +175,7 @@ def layer_importance(q_text: np.ndarray, k: np.ndarray, seg: Segments, alpha: fl
     imp = np.zeros((hkv, seg.vis_len), dtype=np.float64)
     elites = []
     for h in range(hq):
-        i_h, e_h = head_importance(q_text[h], k[h // g], seg, alpha)
+        i_h, e_h = head_importance(q_text[h], k[h // g], seg, alpha, causal_text=causal_text)
         imp[h // g] += i_h
         elites.append(e_h)
     imp /= g

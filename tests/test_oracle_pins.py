@@ -271,6 +271,37 @@ def test_visual_window_layer_is_mean_over_the_group_and_reads_the_right_kv_head(
         np.testing.assert_allclose(imp[kv], (heads[0] + heads[1]) / 2.0, rtol=1e-13)
 
 
+def test_causal_text_option_masks_later_elite_keys_only():
+    # Eq.7 with the optional causal mask over the elite text keys: every row equals causal scaled-dot-product attention
+    # of that text token over [visual keys ; elite text keys] (torch, fp64, explicit mask); the last elite row sees every
+    # key either way; with a single elite row the option changes nothing; visual columns are never masked
+    import torch
+
+    rng = np.random.default_rng(26)
+    d, n_vis, n_text, ns = 16, 40, 12, 2
+    seg = O.Segments(ns + n_vis + n_text, ns, n_vis, ns + n_vis, n_text)
+    k = rng.standard_normal((seg.seq_len, d))
+    q = rng.standard_normal((n_text, d)) * 0.3  # mild logits: several tokens pass the threshold
+    imp_c, elite, a_c = O.head_importance(q, k, seg, 0.2, return_attn=True, causal_text=True)
+    imp_u, elite_u, a_u = O.head_importance(q, k, seg, 0.2, return_attn=True)
+    assert np.array_equal(elite, elite_u) and len(elite) >= 3
+    keys = np.concatenate([k[seg.vis_start:seg.text_start], k[elite]])
+    mask = np.ones((len(elite), n_vis + len(elite)), dtype=bool)
+    mask[:, n_vis:] = elite[None, :] <= elite[:, None]
+    want = torch.nn.functional.scaled_dot_product_attention(
+        torch.from_numpy(q[elite - seg.text_start])[None], torch.from_numpy(keys)[None], torch.eye(n_vis + len(elite), dtype=torch.float64)[None],
+        attn_mask=torch.from_numpy(mask)[None]).numpy()[0]  # V = identity: the output is the attention matrix itself
+    np.testing.assert_allclose(a_c, want, rtol=1e-12, atol=1e-15)
+    np.testing.assert_allclose(a_c.sum(axis=1), 1.0, rtol=1e-13)
+    np.testing.assert_allclose(a_c[-1], a_u[-1], rtol=1e-13)       # the last elite row sees every elite key
+    assert np.all(a_c[:, n_vis:][~mask[:, n_vis:]] == 0.0) and np.all(a_c[:, :n_vis] > 0.0)
+    assert np.all(a_c[:-1, :n_vis] >= a_u[:-1, :n_vis])            # mass taken from masked keys goes to the visible ones
+    np.testing.assert_allclose(imp_c, a_c[:, :n_vis].mean(axis=0), rtol=1e-13)
+    one_c = O.head_importance(q, k, seg, 1.0, causal_text=True)[0]  # alpha = 1: a single elite row
+    one_u = O.head_importance(q, k, seg, 1.0)[0]
+    assert np.array_equal(one_c, one_u)
+
+
 # ---------------------------------------------------------------------------
 # Eq.9-10
 # ---------------------------------------------------------------------------
