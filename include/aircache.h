@@ -101,6 +101,9 @@ typedef struct {
                                  into them.  Needs token stride == head_dim (each (sequence, KV head) a
                                  contiguous run of rows) and, per head, rows for the prompt plus
                                  max_decode_steps rounded up to a multiple of 32 (head stride / head_dim)    */
+    int32_t causal_text;      /* 0: Eq.7 as printed, every elite row sees every elite text key.  1: an elite row
+                                 sees only the elite text keys at or before its own position (what it saw in
+                                 the model's causal prefill); visual keys are never masked.  Text windows only */
 } air_config;
 
 /* One prompt.  system = [0, vis_start), visual = [vis_start, vis_start+vis_len),

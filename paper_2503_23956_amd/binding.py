@@ -34,7 +34,7 @@ class air_config(C.Structure):
         "n_layers", "n_q_heads", "n_kv_heads", "head_dim", "batch", "max_vis_len", "max_nonvis_len",
         "max_window", "max_decode_steps", "dtype", "budget_mode", "min_keep")] + [
         ("alpha", C.c_double), ("retention", C.c_double), ("window_kind", C.c_int32), ("device_steps", C.c_int32),
-        ("cache_in_place", C.c_int32)]
+        ("cache_in_place", C.c_int32), ("causal_text", C.c_int32)]
 
 
 class air_seq(C.Structure):
@@ -112,9 +112,10 @@ def load_library(path: Optional[str] = None):
 
 def make_config(*, n_layers, n_q_heads, n_kv_heads, head_dim, batch, max_vis_len, max_nonvis_len, max_window,
                 max_decode_steps, dtype, alpha=0.9, retention=0.1, budget_mode=AIR_BUDGET_STRENGTH_SKEW,
-                min_keep=1, window_kind=AIR_WINDOW_TEXT, device_steps=0, cache_in_place=0) -> air_config:
+                min_keep=1, window_kind=AIR_WINDOW_TEXT, device_steps=0, cache_in_place=0, causal_text=0) -> air_config:
     return air_config(n_layers, n_q_heads, n_kv_heads, head_dim, batch, max_vis_len, max_nonvis_len, max_window,
-                      max_decode_steps, dtype, budget_mode, min_keep, alpha, retention, window_kind, device_steps, cache_in_place)
+                      max_decode_steps, dtype, budget_mode, min_keep, alpha, retention, window_kind, device_steps, cache_in_place,
+                      causal_text)
 
 
 def _ptr(t) -> int:

@@ -26,6 +26,8 @@ static bool config_ok(const air_config &c) {
     if (c.device_steps != 0 && c.device_steps != 1) return false;
     if (c.device_steps && !(c.dtype == AIR_BF16 && c.head_dim == 128)) return false;
     if (c.cache_in_place != 0 && c.cache_in_place != 1) return false;
+    if (c.causal_text != 0 && c.causal_text != 1) return false;
+    if (c.causal_text && c.window_kind == AIR_WINDOW_VISUAL) return false;  // a visual window has no text columns
     if (c.cache_in_place && !(c.dtype == AIR_BF16 && c.head_dim == 128)) return false;
     const bool vis_window = c.window_kind == AIR_WINDOW_VISUAL;
     if (c.max_window < 1 || c.max_window > AIR_MAX_TEXT) return false;
@@ -159,6 +161,7 @@ air_status air_create(const air_config *cfg, void *workspace, size_t workspace_b
     d.n_entries = (lay.n_chunks + kFinishChunks - 1) / kFinishChunks;
     d.max_steps = cfg->max_decode_steps;
     d.vis_window = cfg->window_kind == AIR_WINDOW_VISUAL ? 1 : 0;
+    d.causal_text = cfg->causal_text;
     d.inv_B = cfg->batch > 1 ? (uint32_t)(0x100000000ull / (uint64_t)cfg->batch) + 1u : 0u;
     d.pool_rows = lay.pool_rows;
     DevTables &t = c->tab;

@@ -53,6 +53,7 @@ struct Dims {
     int32_t max_vis, max_window, n_chunks, max_steps;
     int32_t n_entries;   // moment entries per unit: one per workgroup of air_score's last kernel, ceil(n_chunks / kFinishChunks)
     int32_t vis_window;  // 1: the window rows are visual tokens (causal over the visual keys, no text columns)
+    int32_t causal_text; // 1: an elite row sees only the elite text keys at or before its own position (Eq.7 with a causal mask)
     uint32_t inv_B;      // floor(2^32 / B) + 1 (unused for B = 1): division of a 16-bit index by B as one multiply
     int64_t pool_rows;
 };

@@ -143,12 +143,13 @@ __global__ __launch_bounds__(256) void elite_kernel(Dims dm, DevTables t, int l0
 #pragma unroll
                 for (int e = 0; e < kPer; ++e) qv[e] = ldf(qr + lane * kPer + e);
                 float m = -INFINITY, z = 0.f;
+                const int Rr = dm.causal_text ? r + 1 : R;  // keys this row sees: the list is in position order
                 if (R <= 8) {
                     float a[8];
 #pragma unroll
                     for (int j = 0; j < 8; ++j) {
                         a[j] = 0.f;
-                        if (j < R) {
+                        if (j < Rr) {
                             const T *kj = k + (int64_t)elite[j] * st.kv_t;
 #pragma unroll
                             for (int e = 0; e < kPer; ++e) a[j] = fmaf(qv[e], ldf(kj + lane * kPer + e), a[j]);
@@ -156,22 +157,22 @@ __global__ __launch_bounds__(256) void elite_kernel(Dims dm, DevTables t, int l0
                     }
 #pragma unroll
                     for (int j = 0; j < 8; ++j)
-                        if (j < R) {
+                        if (j < Rr) {
                             a[j] = wave_sum(a[j]);
                             m = fmaxf(m, a[j]);
                         }
 #pragma unroll
                     for (int j = 0; j < 8; ++j)
-                        if (j < R) z += expf((a[j] - m) * scale);
+                        if (j < Rr) z += expf((a[j] - m) * scale);
                 } else {
-                    for (int j = 0; j < R; ++j) {
+                    for (int j = 0; j < Rr; ++j) {
                         const T *kj = k + (int64_t)elite[j] * st.kv_t;
                         float a = 0.f;
 #pragma unroll
                         for (int e = 0; e < kPer; ++e) a = fmaf(qv[e], ldf(kj + lane * kPer + e), a);
                         m = fmaxf(m, wave_sum(a));
                     }
-                    for (int j = 0; j < R; ++j) {
+                    for (int j = 0; j < Rr; ++j) {
                         const T *kj = k + (int64_t)elite[j] * st.kv_t;
                         float a = 0.f;
 #pragma unroll

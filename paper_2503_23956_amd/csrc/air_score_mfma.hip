@@ -771,9 +771,11 @@ __global__ __launch_bounds__(64 * kEliteWaves) void elite_mfma_kernel(Dims dm, D
                                                                              __builtin_bit_cast(bf16x8, kb2), a4, 0, 0, 0);
                             }
                         }
-                        const bool live = jb + n < R;
 #pragma unroll
                         for (int i = 0; i < 4; ++i) {
+                            // key jb + n of the elite list against row rb + 4c + i; the list is in position order, so
+                            // with the causal option a row sees the keys up to its own place in it
+                            const bool live = jb + n < R && (!dm.causal_text || jb + n <= rb + 4 * c + i);
                             if (pass == 0) m4[i] = fmaxf(m4[i], live ? a4[i] : -INFINITY);
                             else z4[i] += live ? expf((a4[i] - m4[i]) * scale) : 0.f;
                         }

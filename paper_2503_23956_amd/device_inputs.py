@@ -9,7 +9,7 @@ from .binding import AIR_BF16, AIR_F32, make_config
 
 
 def config_for(w, retention: float, *, alpha=None, budget_mode=0, min_keep=1, max_decode_steps=None, seqs=None,
-               window_kind=0, device_steps=0, cache_in_place=0):
+               window_kind=0, device_steps=0, cache_in_place=0, causal_text=0):
     seqs = w.seqs() if seqs is None else seqs
     return make_config(
         n_layers=w.n_layers, n_q_heads=w.n_q_heads, n_kv_heads=w.n_kv_heads, head_dim=w.head_dim, batch=w.batch,
@@ -19,7 +19,7 @@ def config_for(w, retention: float, *, alpha=None, budget_mode=0, min_keep=1, ma
         max_decode_steps=w.decode_steps if max_decode_steps is None else max_decode_steps,
         dtype=AIR_BF16 if w.dtype == "bf16" else AIR_F32,
         alpha=w.alpha if alpha is None else alpha, retention=retention, budget_mode=budget_mode, min_keep=min_keep,
-        window_kind=window_kind, device_steps=device_steps, cache_in_place=cache_in_place)
+        window_kind=window_kind, device_steps=device_steps, cache_in_place=cache_in_place, causal_text=causal_text)
 
 
 def to_device(x: np.ndarray, device):

@@ -37,13 +37,13 @@ class OracleRun:
     budgets: Optional[np.ndarray] = None  # [B][L]
 
 
-def oracle_score_layer(w, li, seqs, alpha):
+def oracle_score_layer(w, li, seqs, alpha, causal_text=False):
     """Oracle importance + stats of one generated layer for every sequence."""
     out_scores, out_elites, st, sk = [], [], [], []
     for b, s in enumerate(seqs):
         q = synth.storage_to_f64(li.q_text[b][:, : s.n_text])
         k = synth.storage_to_f64(li.k[b][:, : s.seq_len])
-        imp, el = O.layer_importance(q, k, seg_of(s), alpha)
+        imp, el = O.layer_importance(q, k, seg_of(s), alpha, causal_text)
         a, c = O.layer_stats(imp)
         out_scores.append(imp)
         out_elites.append(el)

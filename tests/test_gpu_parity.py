@@ -12,7 +12,8 @@ pytestmark = pytest.mark.gpu
 
 
 def _run_case(w, retention, *, alpha=None, steps=2, layer_chunk=None, token_major=False, budget_mode=0,
-              min_keep=1, check_decode_units=None, verbose=True, visual_window=None, tuning=None, oracle_steps=None):
+              min_keep=1, check_decode_units=None, verbose=True, visual_window=None, tuning=None, oracle_steps=None,
+              causal_text=False):
     """Full pipeline on the GPU, checked stage by stage against the oracle.
 
     Stages after the budget are fed the oracle's budgets when the GPU's differ from them (the
@@ -39,7 +40,7 @@ def _run_case(w, retention, *, alpha=None, steps=2, layer_chunk=None, token_majo
         alpha = 0.0
     L, B, Hkv, G, d = w.n_layers, w.batch, w.n_kv_heads, w.group, w.head_dim
     cfg = config_for(w, retention, alpha=alpha, budget_mode=budget_mode, min_keep=min_keep, max_decode_steps=max(steps, 1),
-                     seqs=seqs, window_kind=0 if visual_window is None else A.AIR_WINDOW_VISUAL)
+                     seqs=seqs, window_kind=0 if visual_window is None else A.AIR_WINDOW_VISUAL, causal_text=int(causal_text))
     ac = A.AirCache(cfg, dev)
     if tuning:
         ac.air_set_tuning(**tuning)  # launch shapes the library would not pick for this size by itself
@@ -61,7 +62,7 @@ def _run_case(w, retention, *, alpha=None, steps=2, layer_chunk=None, token_majo
             k_dev.append(to_device(li.k, dev))
             v_dev.append(to_device(li.v, dev))
         if visual_window is None:
-            sc, el, a, c = P.oracle_score_layer(w, li, seqs, alpha)
+            sc, el, a, c = P.oracle_score_layer(w, li, seqs, alpha, causal_text)
         else:
             sc, el, a, c = P.oracle_score_layer_visual_window(w, li.q_text, li, seqs)
         orc.scores.append(sc)
@@ -351,6 +352,26 @@ def test_elite_window_with_more_rows_than_the_stash_holds():
     # parameters of several hundred rows itself
     w = synth.get_workload(2).scaled(n_layers=2, n_vis=1100, n_text=48, decode_steps=1)
     _run_case(w, 0.10, alpha=0.05, steps=1)
+
+
+@pytest.mark.parametrize("case", ["elite_few_rows", "low_threshold", "continuous_16", "all_text", "fp32_elite", "fp32_continuous"])
+def test_causal_mask_over_the_elite_text_keys(case):
+    """Eq.7 with the optional causal mask (an elite row sees the elite text keys at or before its position only):
+    one tile of rows, rows beyond the stash, more than 16 rows per head (two passes over the key tiles), and the
+    generic kernels with up to 8 and with more elite rows per head."""
+    if case in ("fp32_elite", "fp32_continuous"):
+        _run_case(synth.get_workload(1), 0.10, alpha=0.9 if case == "fp32_elite" else 0.0, steps=1, causal_text=True)
+        return
+    w = synth.get_workload(2).scaled(n_layers=2, n_vis=1100, n_text=48, decode_steps=1)
+    if case == "elite_few_rows":
+        _run_case(w, 0.10, alpha=0.5, steps=1, causal_text=True)
+    elif case == "low_threshold":
+        _run_case(w, 0.10, alpha=0.05, steps=1, causal_text=True)
+    elif case == "continuous_16":
+        import dataclasses
+        _run_case(dataclasses.replace(w, window=16), 0.10, alpha=0.0, steps=1, causal_text=True)
+    else:
+        _run_case(w, 0.10, alpha=0.0, steps=1, causal_text=True)
 
 
 def test_unified_span_without_a_modality_distinction():
