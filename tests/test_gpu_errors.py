@@ -91,3 +91,34 @@ def test_stage_order_shapes_and_capacity_are_enforced():
     assert status(ac.air_set_tuning, select_threads=128) == B.AIR_ERR_INVALID_ARG
     ac.air_set_tuning(decode_splits=2, decode_waves=4)
     ac.close()
+
+
+def test_device_side_generator_follows_the_recipe():
+    """The benchmark draws the larger workloads on the device (device_layer_inputs): same shapes, padding and
+    structure as the seeded host generator (the salient sets, directions and text shift ARE the host generator's),
+    only the N(0, 1) base tensors differ."""
+    import torch
+
+    from paper_2503_23956_amd.device_inputs import device_layer_inputs, to_host
+
+    dev = torch.device("cuda:0")
+    w = synth.get_workload(3).scaled(batch=3, n_layers=2, n_vis=900, n_text=40)
+    seqs = w.seqs()
+    host = synth.layer_inputs(w, 1, seqs)
+    q, k, v = device_layer_inputs(w, 1, seqs, dev)
+    for a, b in ((q, host.q_text), (k, host.k), (v, host.v)):
+        assert tuple(a.shape) == b.shape and a.dtype == torch.bfloat16
+        ah = synth.storage_to_f64(to_host(a))
+        assert np.array_equal(np.isnan(ah), np.isnan(synth.storage_to_f64(b)))  # the same padding rows hold NaN
+    kd = synth.storage_to_f64(to_host(k))
+    kh = synth.storage_to_f64(host.k)
+    for b, s in enumerate(seqs):
+        sal = synth.salient_mask(w, 1, b, s)
+        vis = slice(s.vis_start, s.vis_start + s.vis_len)
+        for h in range(w.n_kv_heads):
+            # the salient keys are shifted by 2 along the same unit direction on both sides: project on the host's shift
+            shift = kh[b, h, vis][sal].mean(axis=0) - kh[b, h, vis][~sal].mean(axis=0)
+            u = shift / np.linalg.norm(shift)
+            proj = (kd[b, h, vis][sal] @ u).mean() - (kd[b, h, vis][~sal] @ u).mean()
+            assert abs(proj - 2.0) < 0.6, proj
+        assert abs(kd[b, :, vis].std() - 1.0) < 0.1
