@@ -154,6 +154,8 @@ typedef struct {
     int32_t select_direct_max; /* largest deciding bin that is ranked directly, 0..1024 (0: always the radix
                                   passes); -1: the library's default                                            */
     int32_t gather_wgs;        /* workgroups per unit of the compaction gather: 1..64                            */
+    int32_t decode_order;      /* order of the units of a decode launch over all layers: 1 by layer, 2 longest
+                                  cache first (where the launch shape has that variant)                         */
 } air_tuning;
 /* AIR_ERR_INVALID_ARG (and no change) if a field holds a value outside its list. */
 air_status air_set_tuning(air_ctx *ctx, const air_tuning *tuning);

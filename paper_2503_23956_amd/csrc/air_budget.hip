@@ -320,16 +320,23 @@ __global__ __launch_bounds__(kBT) void budget_kernel(Dims dm, DevTables t, doubl
     // appends, and starts on a multiple of kCacheRowAlign rows
     const int nonvis = sq.seq_len - sq.vis_len;
     i0[tid] = mine ? (nonvis + kk + dm.max_steps + kCacheRowAlign - 1) / kCacheRowAlign * kCacheRowAlign : 0;
+    i1[tid] = mine ? kk : -1;
     sync();
     if (mine) {
-        int off = 0;
-        for (int l0 = 0; l0 < tid; l0 += 8) {
+        // one pass over the layers gives the layer's row offset and its rank by falling cache length (ties: the
+        // lower layer first); the table by rank serves decode launches that take their longest units first
+        int off = 0, rank = 0;
+        for (int l0 = 0; l0 < L8; l0 += 8) {
 #pragma unroll
-            for (int j = 0; j < 8; ++j) off += l0 + j < tid ? i0[l0 + j] : 0;
+            for (int j = 0; j < 8; ++j) {
+                off += l0 + j < tid ? i0[l0 + j] : 0;
+                rank += (int)(i1[l0 + j] > kk) | ((int)(i1[l0 + j] == kk) & (int)(l0 + j < tid));
+            }
         }
         t.base_len[(int64_t)b * L + tid] = nonvis + kk;
         t.layer_off[(int64_t)b * L + tid] = off;
         t.len_off[(int64_t)b * L + tid] = make_int2(nonvis + kk, off);
+        t.by_length[(int64_t)b * L + rank] = make_int4(nonvis + kk, off, tid, 0);
     }
 }
 

@@ -132,6 +132,7 @@ __global__ __launch_bounds__(128) void append_kernel(Dims dm, DevTables t, int l
 // argument block (the kernel starts with the loads of its arguments).
 struct DecodeTabs {
     const int2 *len_off;
+    const int4 *by_length;  // per sequence, (length, offset, layer) of the layers by falling cache length
     void *kcache, *vcache;
     float *dec_o;
     float2 *dec_ml;
@@ -149,7 +150,9 @@ struct DecodeSteps {
 };
 
 // INPLACE: the cache is kept inside the layers' own K / V tensors (their addresses come from a table)
-template <int NW, int KT, bool SPLIT, bool INPLACE>
+// SORTED: a launch over all layers whose grid index z is not the layer but its rank by cache length within the
+// sequence (longest first); the layer comes with the table entry that carries the length
+template <int NW, int KT, bool SPLIT, bool INPLACE, bool SORTED = false>
 __global__ __launch_bounds__(64 * NW) void decode_mfma_kernel(Dims dm, DecodeTabs t, int l0, int lbase,
                                                               DecodeSteps ll, const bf16_t *q_new,
                                                               const bf16_t *k_new, const bf16_t *v_new, bf16_t *out,
@@ -163,11 +166,18 @@ __global__ __launch_bounds__(64 * NW) void decode_mfma_kernel(Dims dm, DecodeTab
     // no index needs a division (the number of splits is a power of two)
     const int split = SPLIT ? (int)blockIdx.x & (splits - 1) : 0;
     const int kvh = SPLIT ? (int)blockIdx.x >> lg_splits : (int)blockIdx.x;
-    const int b = blockIdx.y, li = blockIdx.z;
+    const int b = blockIdx.y;
+    int li = blockIdx.z;
+    int2 len_off;
+    if (SORTED) {
+        const int4 e = t.by_length[(int64_t)b * dm.L + blockIdx.z];
+        len_off = make_int2(e.x, e.y);
+        li = e.z - l0;
+    }
     const int l = l0 + li;
     const int G = dm.G;
     // the unit's cache length and offset first: everything that touches the cache waits for them
-    const int2 len_off = t.len_off[(int64_t)b * dm.L + l];
+    if (!SORTED) len_off = t.len_off[(int64_t)b * dm.L + l];
     CachePtrs cp = {nullptr, nullptr};
     if (INPLACE) cp = t.cache_ptrs[l];  // requested together with the table entry
     // The token this call appends (Eq.2): every wave fetches its k_new / v_new values first thing (the
@@ -738,7 +748,8 @@ static hipError_t decode_launch(hipStream_t s, const Dims &dm, const DevTables &
 // Generic path: append, split-K attention, combine (three launches).
 hipError_t launch_decode(hipStream_t s, const Dims &dm, const DevTables &t, const DecodeExchange &x, int dtype, int l0,
                          int nl, int lbase, const LaunchLayers &ll, const void *q_new, const void *k_new,
-                         const void *v_new, void *out, int splits, int waves, int tiles, int uniform_appended) {
+                         const void *v_new, void *out, int splits, int waves, int tiles, int uniform_appended,
+                         bool longest_first) {
     if (v_transposed(dtype, dm.D)) {  // one launch: append, attention and merge of the partials
         if (splits < 1 || (splits & (splits - 1)) != 0) return hipErrorInvalidValue;  // the kernel shifts by log2(splits)
         int lg_splits = 0;
@@ -746,6 +757,7 @@ hipError_t launch_decode(hipStream_t s, const Dims &dm, const DevTables &t, cons
         const dim3 grid(splits * dm.Hkv, dm.B, nl);
         DecodeTabs dt;
         dt.len_off = t.len_off;
+        dt.by_length = t.by_length;
         dt.kcache = t.kcache;
         dt.vcache = t.vcache;
         dt.dec_o = x.o;
@@ -772,6 +784,15 @@ hipError_t launch_decode(hipStream_t s, const Dims &dm, const DevTables &t, cons
         else if (!t.cache_ptrs) AIR_LAUNCH_DECODE_(NW, KT, true, false);                \
         else AIR_LAUNCH_DECODE_(NW, KT, true, true);                                    \
     } while (0)
+        if (longest_first && splits == 1 && !t.cache_ptrs && tiles == 4 && (waves == 1 || waves == 4)) {
+            if (waves == 4)
+                hipLaunchKernelGGL((decode_mfma_kernel<4, 4, false, false, true>), grid, dim3(256), 0, s, dm, dt, l0, lbase, ds,
+                                   (const bf16_t *)q_new, (const bf16_t *)k_new, (const bf16_t *)v_new, (bf16_t *)out, splits, lg_splits);
+            else
+                hipLaunchKernelGGL((decode_mfma_kernel<1, 4, false, false, true>), grid, dim3(64), 0, s, dm, dt, l0, lbase, ds,
+                                   (const bf16_t *)q_new, (const bf16_t *)k_new, (const bf16_t *)v_new, (bf16_t *)out, splits, lg_splits);
+            return hipGetLastError();
+        }
         if (waves == 8 && tiles == 4) AIR_LAUNCH_DECODE(8, 4);
         else if (waves == 4 && tiles == 4) AIR_LAUNCH_DECODE(4, 4);
         else if (waves == 2 && tiles == 4) AIR_LAUNCH_DECODE(2, 4);

@@ -41,7 +41,7 @@ struct SeqArgs {
 struct WsLayout {
     size_t seq_tab, elite_cnt, elite_idx, row_mtext, row_ztext, row_M, row_w, part, scores;
     size_t unit_st, unit_sk, s_t, s_k, budgets, base_len, layer_off, dec_cnt, moments, indices;
-    size_t kcache, vcache, dec_o, dec_ml, stash, row_f, unit_R, len_off, dec_steps, cache_ptrs;
+    size_t kcache, vcache, dec_o, dec_ml, stash, row_f, unit_R, len_off, dec_steps, cache_ptrs, by_length;
     size_t total;
     int32_t n_chunks;     // ceil(max_vis_len / kChunkKeys)
     int64_t pool_rows;    // rows of one (sequence, KV head) cache pool
@@ -69,6 +69,7 @@ struct DevTables {
     void *kcache, *vcache;
     float *dec_o, *stash, *row_f;
     int2 *len_off;    // (base_len, layer_off) of a (sequence, layer) side by side: one read for the decode kernel
+    int4 *by_length;  // per sequence, the layers in order of falling cache length: (base_len, layer_off, layer, 0)
     int32_t *unit_R;  // window rows of a unit (all heads of the group), left by the row-parameter kernel
     float2 *dec_ml;
     int32_t *dec_steps;  // tokens appended so far per unit when the device counts them (else null); one overflow flag after the last unit
@@ -114,7 +115,8 @@ hipError_t launch_gather_in_place(hipStream_t s, const Dims &dm, const DevTables
                                   const air_strides &st);
 hipError_t launch_decode(hipStream_t s, const Dims &dm, const DevTables &t, const DecodeExchange &x, int dtype, int l0,
                          int nl, int lbase, const LaunchLayers &ll, const void *q_new, const void *k_new,
-                         const void *v_new, void *out, int splits, int waves, int tiles, int uniform_appended);
+                         const void *v_new, void *out, int splits, int waves, int tiles, int uniform_appended,
+                         bool longest_first);
 // the exchange area inside the library's static device array, for the device that is current (looked up once per device)
 hipError_t static_exchange(DecodeExchange *x);
 hipError_t launch_zero_counters(hipStream_t s, int32_t *p, int n);

@@ -422,6 +422,15 @@ def test_decode_forced_launch_shapes(splits, waves, tiles):
     _run_case(w, 0.25, steps=36, tuning=dict(decode_splits=splits, decode_waves=waves, decode_tiles=tiles))
 
 
+@pytest.mark.parametrize("waves", [1, 4])
+def test_decode_longest_cache_first(waves):
+    # a launch over all layers that takes its units by falling cache length (the table the budget kernel leaves,
+    # also after caller-set budgets): ragged batch, layers of clearly different budgets, against the oracle
+    w = synth.get_workload(3).scaled(batch=3, n_layers=5, n_vis=1500, n_text=40, decode_steps=34)
+    _run_case(w, 0.20, steps=34, oracle_steps=[0, 1, 33],
+              tuning=dict(decode_splits=1, decode_waves=waves, decode_tiles=4, decode_order=2))
+
+
 @pytest.mark.parametrize("side", [+1, -1])
 def test_elite_threshold_within_fp32_resolution_of_a_candidate(side):
     # Eq.5 with alpha placed a relative 1e-9 above / below exp(s_j - s_max) of a real candidate: fp32
@@ -661,6 +670,12 @@ def test_two_runs_give_bitwise_equal_results():
         r1, r2 = one_run(tuning), one_run(tuning)
         for key in r1:
             assert same(r1[key], r2[key]), f"{key} differs between two runs ({tuning})"
+    # the order in which a decode launch takes its units (by layer, or longest cache first) changes no bit either
+    for waves in (1, 4):
+        shape = dict(decode_splits=1, decode_waves=waves, decode_tiles=4)
+        r1, r2 = one_run(dict(shape, decode_order=1)), one_run(dict(shape, decode_order=2))
+        for key in r1:
+            assert same(r1[key], r2[key]), f"{key} differs between the two unit orders ({waves} waves)"
 
 
 # ---------------------------------------------------------------------------------------
