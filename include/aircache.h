@@ -156,6 +156,8 @@ typedef struct {
     int32_t gather_wgs;        /* workgroups per unit of the compaction gather: 1..64                            */
     int32_t decode_order;      /* order of the units of a decode launch over all layers: 1 by layer, 2 longest
                                   cache first (where the launch shape has that variant)                         */
+    int32_t decode_halves;     /* decode of one sequence, two workgroups per unit with one half of the columns of
+                                  V' each (taken wherever the launch shape has that variant): 1 never           */
 } air_tuning;
 /* AIR_ERR_INVALID_ARG (and no change) if a field holds a value outside its list. */
 air_status air_set_tuning(air_ctx *ctx, const air_tuning *tuning);

@@ -536,6 +536,16 @@ static air_status decode_attn(air_ctx *ctx, void *stream, int32_t l0, int32_t l1
         // a recorded launch is replayed at every cache length: its shape is chosen for the middle of the decode
         decode_shape(ctx, nl, ctx->cfg.device_steps ? ctx->cfg.max_decode_steps / 2 : ctx->appended[c0], splits, waves, tiles);
     };
+    // Two workgroups per unit, each with all of K' and one half of the columns of V' (air_decode.hip), wherever one
+    // sequence's launch of four-wave workgroups leaves half the CUs idle.  112 units, warm / cold cache: 215 keys per
+    // unit 6.4 / 8.7 us against 6.5 / 8.4 with one workgroup per unit, 870 keys 9.6 / 11.6 against 10.7 / 13.3,
+    // 3800 keys 33 / 45 against 35 / 55, 7400 keys 64 / 73 against 76 / 89.
+    auto halves_of = [&](int nl, int splits, int waves, int tiles) {
+        const int hkv = ctx->dm.Hkv;
+        const bool can = in_step && ctx->dm.B == 1 && (hkv & (hkv - 1)) == 0 && splits == 1 && waves == 4 && tiles == 4 &&
+                         2 * ((nl * hkv + 7) & ~7) <= 256;
+        return can && ctx->tune.decode_halves != 1;
+    };
     for (int c0 = l0; use_static && c0 < l1; c0 += max_nl) {
         const int nl = (l1 - c0 < max_nl) ? l1 - c0 : max_nl;
         int splits = 1, waves = 1, tiles = 4;
@@ -567,9 +577,13 @@ static air_status decode_attn(air_ctx *ctx, void *stream, int32_t l0, int32_t l1
                            v_transposed(ctx->cfg.dtype, ctx->cfg.head_dim) && !ctx->cfg.cache_in_place;
         const bool longest_first = whole && ctx->tune.decode_order != 1 &&
                                    (ctx->tune.decode_order == 2 || (int64_t)nl * units_per_layer >= 512);
+        const bool column_halves = halves_of(nl, splits, waves, tiles);
+        // with device-counted steps the two workgroups of a unit meet at the unit's arrival counter
+        if (e == hipSuccess && use_static && column_halves && ctx->cfg.device_steps && splits == 1)
+            e = launch_zero_counters(s, xch.cnt, (int)(nl * units_per_layer));
         if (e == hipSuccess)
             e = launch_decode(s, ctx->dm, ctx->tab, xch, ctx->cfg.dtype, c0, nl, c0 - l0, ll, q_new, k_new, v_new, out,
-                              splits, waves, tiles, in_step ? ctx->appended[l0] : -1, longest_first);
+                              splits, waves, tiles, in_step ? ctx->appended[l0] : -1, longest_first, column_halves);
         if (e != hipSuccess) return hip_fail(ctx, e, "air_decode_attn launch");
     }
     for (int l = l0; l < l1; ++l) {
@@ -598,7 +612,7 @@ air_status air_set_tuning(air_ctx *ctx, const air_tuning *tn) {
     };
     if (!one_of(tn->decode_splits, {0, 1, 2, 4, 8, 16}) || !one_of(tn->decode_waves, {0, 1, 2, 4, 8}) ||
         !one_of(tn->decode_tiles, {0, 2, 4, 8}) || tn->score_block_mb < 0 || tn->score_block_mb > 65536 ||
-        !one_of(tn->score_rows_kernel, {0, 1}) || !one_of(tn->decode_order, {0, 1, 2}) || !one_of(tn->select_threads, {0, 256, 512}) ||
+        !one_of(tn->score_rows_kernel, {0, 1}) || !one_of(tn->decode_order, {0, 1, 2}) || !one_of(tn->decode_halves, {0, 1, 2}) || !one_of(tn->select_threads, {0, 256, 512}) ||
         tn->select_direct_max < -1 || tn->select_direct_max > 1024 || tn->gather_wgs < 0 || tn->gather_wgs > 64)
         return fail(ctx, AIR_ERR_INVALID_ARG, "air_set_tuning: a field holds a value outside its list");
     ctx->tune = *tn;

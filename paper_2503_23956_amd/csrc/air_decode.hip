@@ -152,7 +152,7 @@ struct DecodeSteps {
 // INPLACE: the cache is kept inside the layers' own K / V tensors (their addresses come from a table)
 // SORTED: a launch over all layers whose grid index z is not the layer but its rank by cache length within the
 // sequence (longest first); the layer comes with the table entry that carries the length
-template <int NW, int KT, bool SPLIT, bool INPLACE, bool SORTED = false>
+template <int NW, int KT, bool SPLIT, bool INPLACE, bool SORTED = false, int VH = 1>
 __global__ __launch_bounds__(64 * NW) void decode_mfma_kernel(Dims dm, DecodeTabs t, int l0, int lbase,
                                                               DecodeSteps ll, const bf16_t *q_new,
                                                               const bf16_t *k_new, const bf16_t *v_new, bf16_t *out,
@@ -160,14 +160,35 @@ __global__ __launch_bounds__(64 * NW) void decode_mfma_kernel(Dims dm, DecodeTab
     constexpr int D = 128;
     constexpr int kIter = 16 * KT;  // keys per loop iteration of one wave (KT score tiles, KT/2 token blocks)
     constexpr int TB = KT / 2;
+    constexpr int NJ = 8 / VH;  // output tiles (16 columns each) of the workgroup
+    static_assert(VH == 1 || (!SPLIT && !SORTED && NJ % NW == 0), "column halves: one workgroup pair per unit");
     const int lane = threadIdx.x & 63, n = lane & 15, c = lane >> 4;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);  // a scalar: the wave's chunk walk and its branches stay off the vector unit
     // grid (split + splits * KV head, sequence, layer): the linear order of the workgroups is (split, unit) and
     // no index needs a division (the number of splits is a power of two)
     const int split = SPLIT ? (int)blockIdx.x & (splits - 1) : 0;
-    const int kvh = SPLIT ? (int)blockIdx.x >> lg_splits : (int)blockIdx.x;
-    const int b = blockIdx.y;
+    int kvh = SPLIT ? (int)blockIdx.x >> lg_splits : (int)blockIdx.x;
+    int b = blockIdx.y;
     int li = blockIdx.z;
+    int vh = 0;
+    bool live = true;
+    if (VH == 2) {
+        // Two workgroups per unit, each with all of K' and one half of the columns of V' and of the output: no partials to
+        // exchange, and a workgroup moves three quarters of the unit's bytes (a CU takes in about 140 GB/s, which is what
+        // bounds a launch of few units).  A 1-D grid: the two workgroups of a unit get ids 16 p + x and 16 p + 8 + x, the
+        // same XCD (ids are dealt round-robin over the 8 XCDs) at neighbouring dispatch slots, so that the K' tiles both
+        // stream come through that XCD's L2 once.  `splits` carries the units of the launch (the grid is rounded up to
+        // whole groups of 16: the workgroups past the end redo the last unit and store nothing), `lg_splits` log2 of
+        // the KV heads; one sequence.
+        const int wid = blockIdx.x, slot = wid >> 3;
+        int pair = ((slot >> 1) << 3) | (wid & 7);
+        vh = slot & 1;
+        live = pair < splits;
+        pair = min(pair, splits - 1);
+        kvh = pair & (dm.Hkv - 1);
+        li = pair >> lg_splits;
+        b = 0;
+    }
     int2 len_off;
     if (SORTED) {
         const int4 e = t.by_length[(int64_t)b * dm.L + blockIdx.z];
@@ -185,14 +206,14 @@ __global__ __launch_bounds__(64 * NW) void decode_mfma_kernel(Dims dm, DecodeTab
     // token needs them.
     const int64_t new_src = (((int64_t)(lbase + li) * dm.B + b) * dm.Hkv + kvh) * D;
     uint4 knew[4], krow;
-    bf16_t vnew[8], vcol[2];
+    bf16_t vnew[NJ], vcol[2];
 #pragma unroll
     for (int sl = 0; sl < 4; ++sl) knew[sl] = *reinterpret_cast<const uint4 *>(k_new + new_src + 32 * sl + 8 * c);
     krow = *reinterpret_cast<const uint4 *>(k_new + new_src + 8 * n);
 #pragma unroll
-    for (int j = 0; j < 8; ++j) vnew[j] = v_new[new_src + 16 * j + n];
-    vcol[0] = v_new[new_src + lane];
-    vcol[1] = v_new[new_src + 64 + lane];
+    for (int j = 0; j < NJ; ++j) vnew[j] = v_new[new_src + 16 * (j + NJ * vh) + n];
+    vcol[0] = v_new[new_src + 64 * vh + lane];
+    if (VH == 1) vcol[1] = v_new[new_src + 64 + lane];
     const int64_t unit = ((int64_t)l * dm.B + b) * dm.Hkv + kvh;
     // tokens appended so far: from the host with the launch, or counted on the device (a recorded launch
     // that is replayed): the workgroup that finishes the unit advances the count, after every workgroup
@@ -205,6 +226,7 @@ __global__ __launch_bounds__(64 * NW) void decode_mfma_kernel(Dims dm, DecodeTab
             return;
         }
     }
+    if (VH == 2 && !live) return;
     const int len = len_off.x + appended + 1;
     const int newrow = len - 1;  // the token appended by this call (Eq.2): scored from k_new / v_new, stored to the cache
     int k0 = 0, k1 = len;
@@ -230,9 +252,9 @@ __global__ __launch_bounds__(64 * NW) void decode_mfma_kernel(Dims dm, DecodeTab
     }
     constexpr float kScale2 = 0.08838834764831845f * 1.4426950408889634f;  // log2(e) / sqrt(128)
     float m_run = -INFINITY, l_run = 0.f;
-    f32x4 acc[8];
+    f32x4 acc[NJ];
 #pragma unroll
-    for (int j = 0; j < 8; ++j) acc[j] = (f32x4){0.f, 0.f, 0.f, 0.f};
+    for (int j = 0; j < NJ; ++j) acc[j] = (f32x4){0.f, 0.f, 0.f, 0.f};
 
     // ---- the appended token belongs to the wave of the owning split that would take the next
     // chunk.  The row goes into the cache at once, so that the stores complete behind the cache
@@ -243,12 +265,12 @@ __global__ __launch_bounds__(64 * NW) void decode_mfma_kernel(Dims dm, DecodeTab
     // accumulator = v_new for every head.
     const bool owns_new = newrow >= k0 && newrow < k1 && wave == ((kend - k0 + kIter - 1) / kIter) % NW;
     if (owns_new) {
-        if (lane < 16)  // the new K' row: 16 lanes x 16 bytes
+        if (lane < 16 && vh == 0)  // the new K' row: 16 lanes x 16 bytes
             *reinterpret_cast<uint4 *>(kc + k_tiled(newrow, 8 * lane)) = krow;
         const int tok = newrow & 31;
 #pragma unroll
-        for (int h2 = 0; h2 < 2; ++h2) {
-            const int col = lane + 64 * h2;
+        for (int h2 = 0; h2 < 2 / VH; ++h2) {
+            const int col = lane + 64 * (h2 + vh);
             if (tok == 0) {  // a new block: the column's other slots are written as zeros
                 bf16_t *vcolp = vc + (int64_t)newrow * D + (col >> 4) * 512 + (col & 15) * 8;  // slot group 0; +128 per group
                 const uint4 z = make_uint4(0, 0, 0, 0);
@@ -277,7 +299,7 @@ __global__ __launch_bounds__(64 * NW) void decode_mfma_kernel(Dims dm, DecodeTab
         m_run = sn * kScale2;
         l_run = c == 0 ? 1.f : 0.f;  // l_run is a per-lane partial of the head's sum: the token counts once
 #pragma unroll
-        for (int j = 0; j < 8; ++j) {
+        for (int j = 0; j < NJ; ++j) {
             const float v = bf16_bits_to_float(vnew[j]);
             acc[j] = (f32x4){v, v, v, v};
         }
@@ -295,7 +317,7 @@ __global__ __launch_bounds__(64 * NW) void decode_mfma_kernel(Dims dm, DecodeTab
     auto has = [&](int kb) { return kb >= k0 && kb < kend; };
 
     // all loads of a chunk: the KT score tiles of K' and the V' operands of the TB token blocks
-    auto load_chunk = [&](uint4(&a)[KT][4], uint4(&vb)[TB][8], int kb) {
+    auto load_chunk = [&](uint4(&a)[KT][4], uint4(&vb)[TB][NJ], int kb) {
 #pragma unroll
         for (int tile = 0; tile < KT; ++tile) {
             const bf16_t *src = kc + (int64_t)min(kb + 16 * tile, last16) * D + 32 * n + 8 * c;
@@ -306,10 +328,10 @@ __global__ __launch_bounds__(64 * NW) void decode_mfma_kernel(Dims dm, DecodeTab
         for (int tb = 0; tb < TB; ++tb) {
             const bf16_t *src = vc + (int64_t)min(kb + 32 * tb, last32) * D + 128 * c + 8 * n;
 #pragma unroll
-            for (int j = 0; j < 8; ++j) vb[tb][j] = *reinterpret_cast<const uint4 *>(src + 512 * j);
+            for (int j = 0; j < NJ; ++j) vb[tb][j] = *reinterpret_cast<const uint4 *>(src + 512 * (j + NJ * vh));
         }
     };
-    auto compute_chunk = [&](const uint4(&a)[KT][4], const uint4(&vb)[TB][8], int kb) {
+    auto compute_chunk = [&](const uint4(&a)[KT][4], const uint4(&vb)[TB][NJ], int kb) {
         // ---- scores^T
         f32x4 s[KT];
 #pragma unroll
@@ -351,7 +373,7 @@ __global__ __launch_bounds__(64 * NW) void decode_mfma_kernel(Dims dm, DecodeTab
                 for (int i = 0; i < 4; ++i) {
                     const float f = __shfl(corr, 4 * c + i, 64);
 #pragma unroll
-                    for (int j = 0; j < 8; ++j) acc[j][i] *= f;
+                    for (int j = 0; j < NJ; ++j) acc[j][i] *= f;
                 }
             }
         }
@@ -375,21 +397,21 @@ __global__ __launch_bounds__(64 * NW) void decode_mfma_kernel(Dims dm, DecodeTab
                 pa[4 + i] = (__bf16)s[2 * tb + 1][i];
             }
 #pragma unroll
-            for (int j = 0; j < 8; ++j)
+            for (int j = 0; j < NJ; ++j)
                 acc[j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(pa, __builtin_bit_cast(bf16x8, vb[tb][j]), acc[j], 0, 0, 0);
         }
     };
     // Two chunk buffers: while one chunk is multiplied the loads of the wave's next chunk are in
     // flight.  Loads are issued only for chunks that exist, and the loop is laid out so that every
     // path reaches a compute step with the same loads behind it (the wait counts stay exact).
-    if constexpr (KT > 2) {  // two buffers of this size do not fit the registers: load, then multiply
+    if constexpr (KT > 2 && VH == 1) {  // two buffers of this size do not fit the registers: load, then multiply
         for (int kb = kb_first; has(kb); kb += kStep) {
-            uint4 a0[KT][4], v0[TB][8];
+            uint4 a0[KT][4], v0[TB][NJ];
             load_chunk(a0, v0, kb);
             compute_chunk(a0, v0, kb);
         }
     } else if (has(kb_first)) {
-        uint4 a0[KT][4], v0[TB][8], a1[KT][4], v1[TB][8];
+        uint4 a0[KT][4], v0[TB][NJ], a1[KT][4], v1[TB][NJ];
         int kb = kb_first;
         load_chunk(a0, v0, kb);
         if (!has(kb + kStep)) {
@@ -421,7 +443,7 @@ __global__ __launch_bounds__(64 * NW) void decode_mfma_kernel(Dims dm, DecodeTab
     // ---- merge the NW waves of the workgroup through LDS.  Every wave first rescales its partial
     // to the workgroup's maximum, so that the merge is a plain sum: wave w ends up with output
     // tiles w, w+NW, ... (heads 4c..4c+3, column 16j+n), plus the merged (max, sum) of those heads.
-    __shared__ f32x4 s_acc[NW][8][64];
+    __shared__ f32x4 s_acc[NW][NJ][64];
     __shared__ float s_mw[kMaxGroup][NW], s_lw[kMaxGroup][NW];
     __shared__ int s_prev;
     float mrg_m[4], mrg_l[4];  // merged max / sum of heads 4c+i
@@ -438,13 +460,13 @@ __global__ __launch_bounds__(64 * NW) void decode_mfma_kernel(Dims dm, DecodeTab
             const float fi = __shfl(f, 4 * c + i, 64);
             mrg_m[i] = __shfl(M, 4 * c + i, 64);
 #pragma unroll
-            for (int j = 0; j < 8; ++j) acc[j][i] *= fi;
+            for (int j = 0; j < NJ; ++j) acc[j][i] *= fi;
         }
 #pragma unroll
-        for (int j = 0; j < 8; ++j) s_acc[wave][j][lane] = acc[j];
+        for (int j = 0; j < NJ; ++j) s_acc[wave][j][lane] = acc[j];
         __syncthreads();
 #pragma unroll
-        for (int jj = 0; jj < 8 / NW; ++jj) {
+        for (int jj = 0; jj < NJ / NW; ++jj) {
             const int j = wave + NW * jj;
             f32x4 sum = s_acc[0][j][lane];
 #pragma unroll
@@ -469,7 +491,7 @@ __global__ __launch_bounds__(64 * NW) void decode_mfma_kernel(Dims dm, DecodeTab
             mrg_l[i] = __shfl(l_run, 4 * c + i, 64);
         }
     }
-    constexpr int kTiles = 8 / NW;  // output tiles this wave owns after the merge: j = wave + NW*jj
+    constexpr int kTiles = NJ / NW;  // output tiles this wave owns after the merge: j = wave + NW*jj (of the workgroup's NJ)
 
     if (!SPLIT || splits == 1) {  // no partials: normalise and store
 #pragma unroll
@@ -479,10 +501,21 @@ __global__ __launch_bounds__(64 * NW) void decode_mfma_kernel(Dims dm, DecodeTab
                 const float inv = __builtin_amdgcn_rcpf(mrg_l[i]);
 #pragma unroll
                 for (int jj = 0; jj < kTiles; ++jj)
-                    o_unit[g * D + 16 * (wave + NW * jj) + n] = float_to_bf16_bits(acc[jj][i] * inv);
+                    o_unit[g * D + 16 * (NJ * vh + wave + NW * jj) + n] = float_to_bf16_bits(acc[jj][i] * inv);
             }
         }
-        if (t.dec_steps && threadIdx.x == 0) t.dec_steps[unit] = appended + 1;
+        if (t.dec_steps && threadIdx.x == 0) {
+            if (VH == 1) {
+                t.dec_steps[unit] = appended + 1;
+            } else {
+                // the workgroup of the pair that finishes second advances the count: the other one has read it by then
+                const int64_t xu = t.x_local ? ((int64_t)li * dm.B + b) * dm.Hkv + kvh : unit;
+                if (__hip_atomic_fetch_add(&t.dec_cnt[xu], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == 1) {
+                    __hip_atomic_store(&t.dec_cnt[xu], 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);  // next launch
+                    t.dec_steps[unit] = appended + 1;
+                }
+            }
+        }
         return;
     }
     if (!SPLIT) return;  // the instance for one workgroup per unit carries none of what follows
@@ -749,7 +782,7 @@ static hipError_t decode_launch(hipStream_t s, const Dims &dm, const DevTables &
 hipError_t launch_decode(hipStream_t s, const Dims &dm, const DevTables &t, const DecodeExchange &x, int dtype, int l0,
                          int nl, int lbase, const LaunchLayers &ll, const void *q_new, const void *k_new,
                          const void *v_new, void *out, int splits, int waves, int tiles, int uniform_appended,
-                         bool longest_first) {
+                         bool longest_first, bool column_halves) {
     if (v_transposed(dtype, dm.D)) {  // one launch: append, attention and merge of the partials
         if (splits < 1 || (splits & (splits - 1)) != 0) return hipErrorInvalidValue;  // the kernel shifts by log2(splits)
         int lg_splits = 0;
@@ -784,6 +817,19 @@ hipError_t launch_decode(hipStream_t s, const Dims &dm, const DevTables &t, cons
         else if (!t.cache_ptrs) AIR_LAUNCH_DECODE_(NW, KT, true, false);                \
         else AIR_LAUNCH_DECODE_(NW, KT, true, true);                                    \
     } while (0)
+        if (column_halves) {  // the caller has checked what this variant asks for
+            const int units = nl * dm.Hkv;
+            int lg_h = 0;
+            while ((1 << lg_h) < dm.Hkv) ++lg_h;
+            const dim3 grid2(2 * ((units + 7) & ~7));
+            if (t.cache_ptrs)
+                hipLaunchKernelGGL((decode_mfma_kernel<4, 4, false, true, false, 2>), grid2, dim3(256), 0, s, dm, dt, l0, lbase, ds,
+                                   (const bf16_t *)q_new, (const bf16_t *)k_new, (const bf16_t *)v_new, (bf16_t *)out, units, lg_h);
+            else
+                hipLaunchKernelGGL((decode_mfma_kernel<4, 4, false, false, false, 2>), grid2, dim3(256), 0, s, dm, dt, l0, lbase, ds,
+                                   (const bf16_t *)q_new, (const bf16_t *)k_new, (const bf16_t *)v_new, (bf16_t *)out, units, lg_h);
+            return hipGetLastError();
+        }
         if (longest_first && splits == 1 && !t.cache_ptrs && tiles == 4 && (waves == 1 || waves == 4)) {
             if (waves == 4)
                 hipLaunchKernelGGL((decode_mfma_kernel<4, 4, false, false, true>), grid, dim3(256), 0, s, dm, dt, l0, lbase, ds,

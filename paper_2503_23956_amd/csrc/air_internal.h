@@ -116,7 +116,7 @@ hipError_t launch_gather_in_place(hipStream_t s, const Dims &dm, const DevTables
 hipError_t launch_decode(hipStream_t s, const Dims &dm, const DevTables &t, const DecodeExchange &x, int dtype, int l0,
                          int nl, int lbase, const LaunchLayers &ll, const void *q_new, const void *k_new,
                          const void *v_new, void *out, int splits, int waves, int tiles, int uniform_appended,
-                         bool longest_first);
+                         bool longest_first, bool column_halves);
 // the exchange area inside the library's static device array, for the device that is current (looked up once per device)
 hipError_t static_exchange(DecodeExchange *x);
 hipError_t launch_zero_counters(hipStream_t s, int32_t *p, int n);

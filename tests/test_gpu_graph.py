@@ -35,7 +35,7 @@ def _contexts(w, steps, dev):
     return A, eager, counted, compress, seqs, layers
 
 
-@pytest.mark.parametrize("shape", [(1, 8, 4), (4, 4, 4), None])
+@pytest.mark.parametrize("shape", [(1, 8, 4, 0), (4, 4, 4, 0), (1, 4, 4, 2), None])
 def test_replayed_decode_step_matches_eager_calls(shape):
     import torch
 
@@ -47,7 +47,8 @@ def test_replayed_decode_step_matches_eager_calls(shape):
     A, eager, counted, compress, seqs, layers = _contexts(w, steps, dev)
     if shape is not None:  # the same launch shape on both sides makes the outputs bitwise comparable
         for ac in (eager, counted):
-            ac.air_set_tuning(decode_splits=shape[0], decode_waves=shape[1], decode_tiles=shape[2])
+            # shape[3] = 2: two workgroups per unit that meet at the unit's arrival counter to advance the device-side count
+            ac.air_set_tuning(decode_splits=shape[0], decode_waves=shape[1], decode_tiles=shape[2], decode_halves=shape[3])
     L, B, Hkv, G, d = w.n_layers, w.batch, w.n_kv_heads, w.group, w.head_dim
     ins = []
     for step in range(steps):

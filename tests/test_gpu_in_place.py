@@ -28,7 +28,9 @@ def _roomy(x_host, extra_rows, dev):
                           (3, 3, 900, 0.25, 34, None),
                           # the split-K instance of the in-place decode kernel, and through the entry point with the static exchange area
                           (2, 1, 1500, 0.10, 36, dict(decode_splits=4, decode_waves=4, decode_tiles=4)),
-                          (2, 1, 1500, 0.10, 36, dict(decode_splits=2, decode_waves=8, decode_tiles=2, static=True))])
+                          (2, 1, 1500, 0.10, 36, dict(decode_splits=2, decode_waves=8, decode_tiles=2, static=True)),
+                          # two workgroups per unit, one half of the columns of V' each
+                          (2, 1, 1500, 0.10, 36, dict(decode_splits=1, decode_waves=4, decode_tiles=4, decode_halves=2))])
 def test_in_place_compaction_equals_the_pool_path(base, batch, n_vis, retention, steps, tuning):
     import torch
 

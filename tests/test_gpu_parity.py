@@ -422,6 +422,48 @@ def test_decode_forced_launch_shapes(splits, waves, tiles):
     _run_case(w, 0.25, steps=36, tuning=dict(decode_splits=splits, decode_waves=waves, decode_tiles=tiles))
 
 
+@pytest.mark.parametrize("n_layers,n_vis,retention", [(3, 900, 0.25), (2, 2600, 1.00), (5, 300, 0.05)])
+def test_decode_column_halves(n_layers, n_vis, retention):
+    # two workgroups per unit, each with all of K' and one half of the columns of V' and of the output: against the
+    # oracle (12 and 20 units: a grid rounded up to whole groups of 16 workgroups; 8 units: an exact one), with appends
+    # that cross token blocks, and bit for bit against one workgroup per unit (same arithmetic per output column)
+    import torch
+
+    import paper_2503_23956_amd as A
+    from paper_2503_23956_amd.device_inputs import config_for, to_device, to_host
+
+    steps = 36
+    w = synth.get_workload(2).scaled(n_layers=n_layers, n_vis=n_vis, n_text=37, decode_steps=steps)
+    shape = dict(decode_splits=1, decode_waves=4, decode_tiles=4)
+    _run_case(w, retention, steps=steps, oracle_steps=[0, 1, 31, 32, 35], tuning=dict(shape, decode_halves=2))
+    dev = torch.device("cuda:0")
+    seqs = w.seqs()
+    L = w.n_layers
+    layers = [synth.layer_inputs(w, l, seqs) for l in range(L)]
+    q, k, v = ([to_device(getattr(li, name), dev) for li in layers] for name in ("q_text", "k", "v"))
+    outs = []
+    for halves in (1, 2):
+        ac = A.AirCache(config_for(w, retention, seqs=seqs, max_decode_steps=steps), dev)
+        ac.air_set_tuning(**shape, decode_halves=halves)
+        ac.air_score(0, L, q, k, v, seqs)
+        ac.air_budget()
+        ac.air_select_compact(0, L, k, v)
+        out = torch.empty((L, 1, w.n_q_heads, w.head_dim), dtype=torch.bfloat16, device=dev)
+        res = []
+        for step in range(steps):
+            qs, ks, vs = zip(*[synth.decode_inputs(w, l, step) for l in range(L)])
+            ac.air_decode_attn(0, L, *(to_device(np.stack(x), dev) for x in (qs, ks, vs)), out)
+            res.append(to_host(out).copy())
+        lens = ac.air_get_lengths()
+        res.append([ac.air_get_cache(l, 0, h, int(lens[0, l])) for l in range(L) for h in range(w.n_kv_heads)])
+        outs.append(res)
+        ac.close()
+    for step in range(steps):
+        assert np.array_equal(outs[0][step].view(np.uint16), outs[1][step].view(np.uint16)), f"step {step}"
+    for (k1, v1), (k2, v2) in zip(outs[0][steps], outs[1][steps]):
+        assert np.array_equal(k1, k2) and np.array_equal(v1, v2)
+
+
 @pytest.mark.parametrize("waves", [1, 4])
 def test_decode_longest_cache_first(waves):
     # a launch over all layers that takes its units by falling cache length (the table the budget kernel leaves,

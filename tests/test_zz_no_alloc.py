@@ -45,6 +45,7 @@ def _raw_decode(ac, fn_name, L, qn, kn, vn, out):
 
 @pytest.mark.parametrize("base,tuning", [(2, dict(decode_splits=4, decode_waves=4, decode_tiles=4)),
                                          (2, dict(decode_splits=16, decode_waves=1, decode_tiles=2)),
+                                         (2, dict(decode_splits=1, decode_waves=4, decode_tiles=4, decode_halves=2)),
                                          (1, dict(decode_splits=4))])
 def test_static_entry_point_matches_the_workspace_one(base, tuning):
     import torch
