@@ -83,6 +83,7 @@ WsLayout make_layout(const air_config &c) {
     w.base_len = take(B * L * 4);
     w.layer_off = take(B * L * 4);
     w.dec_cnt = take(L * B * Hkv * 4);
+    w.unit_cnt = take(L * B * Hkv * 4);
     w.dec_steps = take((L * B * Hkv + 1) * 4);
     w.moments = take(L * B * Hkv * (size_t)((w.n_chunks + kFinishChunks - 1) / kFinishChunks) * 4 * 8);
     w.indices = take(L * B * Hkv * NV * 4);
@@ -184,6 +185,7 @@ air_status air_create(const air_config *cfg, void *workspace, size_t workspace_b
     t.base_len = (int32_t *)(w + lay.base_len);
     t.layer_off = (int32_t *)(w + lay.layer_off);
     t.dec_cnt = (int32_t *)(w + lay.dec_cnt);
+    t.unit_cnt = (int32_t *)(w + lay.unit_cnt);
     t.moments = (double *)(w + lay.moments);
     t.indices = (int32_t *)(w + lay.indices);
     t.kcache = (void *)(w + lay.kcache);
@@ -370,7 +372,7 @@ air_status air_budget(air_ctx *ctx, void *stream) {
     memset(&sa, 0, sizeof(sa));
     memcpy(sa.s, ctx->seqs.data(), sizeof(air_seq) * ctx->cfg.batch);
     hipError_t e = launch_budget((hipStream_t)stream, ctx->dm, ctx->tab, ctx->cfg.retention, ctx->cfg.budget_mode,
-                                 ctx->cfg.min_keep, 0, v_transposed(ctx->cfg.dtype, ctx->cfg.head_dim) ? 1 : 0, sa);
+                                 ctx->cfg.min_keep, 0, sa);
     if (e != hipSuccess) return hip_fail(ctx, e, "air_budget launch");
     ctx->fixed_idx.assign(ctx->dm.L, 0);
     ctx->budgets_ready = true;
@@ -705,7 +707,7 @@ air_status air_set_budgets(air_ctx *ctx, const int32_t *host) {
     hipError_t e = hipDeviceSynchronize();
     if (e == hipSuccess) e = hipMemcpy(ctx->tab.budgets, host, (size_t)ctx->dm.B * L * 4, hipMemcpyHostToDevice);
     if (e == hipSuccess) e = launch_budget(nullptr, ctx->dm, ctx->tab, ctx->cfg.retention, ctx->cfg.budget_mode,
-                                           ctx->cfg.min_keep, 1, 0, sa);
+                                           ctx->cfg.min_keep, 1, sa);
     if (e == hipSuccess) e = hipDeviceSynchronize();
     if (e != hipSuccess) return hip_fail(ctx, e, "air_set_budgets");
     ctx->fixed_idx.assign(ctx->dm.L, 0);

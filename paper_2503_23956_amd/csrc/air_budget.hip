@@ -14,7 +14,6 @@
 // global stores of the statistics and budgets.
 #include "air_device.h"
 #include "air_internal.h"
-#include <type_traits>
 
 namespace air {
 
@@ -51,11 +50,11 @@ __device__ __forceinline__ int int_sum(const int *a, int n) {  // n a multiple o
 // the compiler kept from moving them.
 template <bool ONE_WAVE>
 __global__ __launch_bounds__(kBT) void budget_kernel(Dims dm, DevTables t, double retention, int mode, int min_keep,
-                                                     int skip_allocation, int use_moments, SeqArgs seqs) {
+                                                     int skip_allocation, SeqArgs seqs) {
     const int tid = threadIdx.x;
     const int b = blockIdx.x;
     const int L = dm.L;
-    const air_seq sq = seqs.s[b];  // from the kernel arguments: no table read in front of the moment entries
+    const air_seq sq = seqs.s[b];  // from the kernel arguments: no table read in front of the statistics
     const int n_vis = sq.vis_len;
     const bool mine = tid < L;
     const int L8 = (L + 7) & ~7;  // the sums over the layers run over whole groups of 8 (zeros past the last layer)
@@ -79,125 +78,18 @@ __global__ __launch_bounds__(kBT) void budget_kernel(Dims dm, DevTables t, doubl
     if (skip_allocation) {
         if (mine) kk = budgets[tid];  // the budgets were set by the caller: only the layout is left
     } else {
-        const bool stage = use_moments && L * dm.Hkv <= AIR_MAX_LAYERS * 16;  // unit statistics fit the LDS staging arrays
-        if (use_moments) {
-            // Eq.9-10 of every (layer, KV head) from the moment entries of its importance row: entry c holds
-            // the sum S1_c, the mean m_c and the moments M2_c, M3_c about m_c of the n_c scores of kFinishChunks
-            // chunks.  With d_c = m_c - mu the central moments of the row are
-            //   sum (x - mu)^2 = sum_c M2_c + n_c d_c^2,   sum (x - mu)^3 = sum_c M3_c + 3 d_c M2_c + n_c d_c^3,
-            // sums of terms no larger than their result (raw power sums would cancel on rows of little spread).
-            // Sixteen lanes per (layer, KV head), lane g taking the entries g, g + 16, ...; the entries of a batch
-            // of rows are requested together (one trip to memory per batch), the sums over a row's entries are
-            // butterflies over the sixteen lanes (a fixed order, the same on every run), and the divisions and
-            // the square root of the rows of a batch are done side by side, lane r of a group finishing row r.
-            constexpr int kEntryKeys = kFinishChunks * kChunkKeys;
-            const int nch = (n_vis + kEntryKeys - 1) / kEntryKeys;  // entries per unit
-            const int grp = tid >> 4, gl = tid & 15, n_grp = kBT >> 4;
-            const double n = (double)n_vis;
-            const int n_units = L * dm.Hkv;
-            auto stats_batches = [&](auto per_tag, auto units_tag) __attribute__((always_inline)) {
-                constexpr int PER = decltype(per_tag)::value, UNITS = decltype(units_tag)::value;
-                for (int p0 = 0; p0 < n_units; p0 += n_grp * UNITS) {  // uniform over the workgroup
-                    double e[UNITS][PER][4];
-#pragma unroll
-                    for (int r = 0; r < UNITS; ++r) {
-                        const int p = min(p0 + r * n_grp + grp, n_units - 1);  // groups past the end repeat the last unit and store nothing
-                        const int l = p / dm.Hkv, h = p % dm.Hkv;
-                        const double *mo = t.moments + (((int64_t)l * dm.B + b) * dm.Hkv + h) * dm.n_entries * 4;
-#pragma unroll
-                        for (int j = 0; j < PER; ++j) {
-                            const int c = gl + 16 * j;
-                            const double2 lo2 = *reinterpret_cast<const double2 *>(mo + 4 * min(c, nch - 1));
-                            const double2 hi2 = *reinterpret_cast<const double2 *>(mo + 4 * min(c, nch - 1) + 2);
-                            const bool have = c < nch;
-                            e[r][j][0] = have ? lo2.x : 0.0;
-                            e[r][j][1] = have ? lo2.y : 0.0;
-                            e[r][j][2] = have ? hi2.x : 0.0;
-                            e[r][j][3] = have ? hi2.y : 0.0;
-                        }
-                    }
-                    double S1_mine = 0.0, c2_mine = 0.0, c3_mine = 0.0;  // of row gl of the batch
-#pragma unroll
-                    for (int r = 0; r < UNITS; ++r) {
-                        double s1 = 0.0;
-#pragma unroll
-                        for (int j = 0; j < PER; ++j) s1 += e[r][j][0];
-                        const double S1 = sum16(s1);
-                        const double mu = S1 / n;
-                        double c2 = 0.0, c3 = 0.0;
-#pragma unroll
-                        for (int j = 0; j < PER; ++j) {
-                            const int c = gl + 16 * j;
-                            if (c < nch) {
-                                const double nc = (double)min(kEntryKeys, n_vis - c * kEntryKeys);
-                                const double dl = e[r][j][1] - mu, M2 = e[r][j][2], M3 = e[r][j][3];
-                                c2 += M2 + nc * (dl * dl);
-                                c3 += (M3 + 3.0 * dl * M2) + nc * (dl * dl * dl);
-                            }
-                        }
-                        c2 = sum16(c2);
-                        c3 = sum16(c3);
-                        if (gl == r) {
-                            S1_mine = S1;
-                            c2_mine = c2;
-                            c3_mine = c3;
-                        }
-                    }
-                    const int p = p0 + gl * n_grp + grp;
-                    if (gl < UNITS && p < n_units) {
-                        double sk = 0.0;
-                        if (n_vis >= 3) {
-                            const double mu = S1_mine / n;
-                            const double sigma = sqrt(c2_mine / (n - 1.0));
-                            // zero spread (Eq.10 undefined; taken as 0): a standard deviation at most 1e-6 of the mean
-                            if (sigma > 1e-6 * fabs(mu)) sk = n / ((n - 1.0) * (n - 2.0)) * (c3_mine / (sigma * sigma * sigma));
-                        }
-                        const int l = p / dm.Hkv, h = p % dm.Hkv;
-                        const int64_t unit = ((int64_t)l * dm.B + b) * dm.Hkv + h;
-                        t.unit_st[unit] = S1_mine;
-                        t.unit_sk[unit] = sk;
-                        if (stage) {
-                            u_st[p] = S1_mine;
-                            u_sk[p] = sk;
-                        }
-                    }
-                }
-            };
-            if (nch <= 16) stats_batches(std::integral_constant<int, 1>(), std::integral_constant<int, 8>());
-            else if (nch <= 32) stats_batches(std::integral_constant<int, 2>(), std::integral_constant<int, 4>());
-            else {
-                // rows of more than 32 entries (beyond 32768 visual tokens): a thread per row, two passes over its entries
-                for (int p = tid; p < n_units; p += kBT) {
-                    const int l = p / dm.Hkv, h = p % dm.Hkv;
-                    const int64_t unit = ((int64_t)l * dm.B + b) * dm.Hkv + h;
-                    const double *mo = t.moments + unit * dm.n_entries * 4;
-                    double S1 = 0.0;
-#pragma unroll 4
-                    for (int c = 0; c < nch; ++c) S1 += mo[4 * c];
-                    double sk = 0.0;
-                    if (n_vis >= 3) {
-                        const double mu = S1 / n;
-                        double c2 = 0.0, c3 = 0.0;
-#pragma unroll 4
-                        for (int c = 0; c < nch; ++c) {
-                            const double nc = (double)min(kEntryKeys, n_vis - c * kEntryKeys);
-                            const double dl = mo[4 * c + 1] - mu, M2 = mo[4 * c + 2], M3 = mo[4 * c + 3];
-                            c2 += M2 + nc * (dl * dl);
-                            c3 += (M3 + 3.0 * dl * M2) + nc * (dl * dl * dl);
-                        }
-                        const double sigma = sqrt(c2 / (n - 1.0));
-                        if (sigma > 1e-6 * fabs(mu)) sk = n / ((n - 1.0) * (n - 2.0)) * (c3 / (sigma * sigma * sigma));
-                    }
-                    t.unit_st[unit] = S1;
-                    t.unit_sk[unit] = sk;
-                    if (stage) {
-                        u_st[p] = S1;
-                        u_sk[p] = sk;
-                    }
-                }
+        // Eq.9-10 of every (layer, KV head) are there (air_score's last kernel leaves them per unit): staged through
+        // LDS in one round of loads where they fit
+        const int n_units = L * dm.Hkv;
+        const bool stage = n_units <= AIR_MAX_LAYERS * 16;
+        if (stage) {
+            for (int p = tid; p < n_units; p += kBT) {
+                const int l = p / dm.Hkv, h = p % dm.Hkv;
+                const int64_t unit = ((int64_t)l * dm.B + b) * dm.Hkv + h;
+                u_st[p] = t.unit_st[unit];
+                u_sk[p] = t.unit_sk[unit];
             }
-            if (stage) lds_barrier();  // the statistics cross in LDS: no wait for the global stores above
-            else __syncthreads();
+            __syncthreads();
         }
         if (ONE_WAVE && tid >= 64) return;  // one wave takes it from here
         double st = 0.0, sk = 0.0;
@@ -341,13 +233,13 @@ __global__ __launch_bounds__(kBT) void budget_kernel(Dims dm, DevTables t, doubl
 }
 
 hipError_t launch_budget(hipStream_t s, const Dims &dm, const DevTables &t, double retention, int mode,
-                         int min_keep, int skip_allocation, int use_moments, const SeqArgs &seqs) {
+                         int min_keep, int skip_allocation, const SeqArgs &seqs) {
     if (dm.L <= 64)
         hipLaunchKernelGGL(budget_kernel<true>, dim3(dm.B), dim3(kBT), 0, s, dm, t, retention, mode, min_keep,
-                           skip_allocation, use_moments, seqs);
+                           skip_allocation, seqs);
     else
         hipLaunchKernelGGL(budget_kernel<false>, dim3(dm.B), dim3(kBT), 0, s, dm, t, retention, mode, min_keep,
-                           skip_allocation, use_moments, seqs);
+                           skip_allocation, seqs);
     return hipGetLastError();
 }
 

@@ -75,8 +75,6 @@ hipError_t launch_zero_counters(hipStream_t s, int32_t *p, int n) {
 
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(4))) float f32x4;
-typedef __attribute__((ext_vector_type(4))) unsigned int u32x4;
-constexpr int kSysScope = 17;  // buffer cache policy sc0 | sc1: write through / read past the L2 of this XCD
 
 // key range of one split: ceil(len / splits) rounded up to whole 32-token blocks
 __device__ __forceinline__ void split_range(int len, int splits, int split, int &k0, int &k1) {

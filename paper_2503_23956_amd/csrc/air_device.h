@@ -7,6 +7,11 @@
 namespace air {
 
 typedef uint16_t bf16_t;  // bf16 bit pattern
+typedef __attribute__((ext_vector_type(4))) unsigned int u32x4;
+typedef __attribute__((ext_vector_type(2))) unsigned int u32x2;
+// Buffer cache policy sc0 | sc1 of the raw buffer loads / stores that exchange data between workgroups of one launch
+// (they may run on XCDs whose L2s are not kept coherent): written through to memory / read past the L2 of this XCD.
+constexpr int kSysScope = 17;
 
 __device__ __forceinline__ float bf16_bits_to_float(uint32_t b) { return __uint_as_float(b << 16); }
 

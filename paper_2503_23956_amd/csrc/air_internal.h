@@ -40,7 +40,7 @@ struct SeqArgs {
 // Byte offsets of every table inside the workspace.
 struct WsLayout {
     size_t seq_tab, elite_cnt, elite_idx, row_mtext, row_ztext, row_M, row_w, part, scores;
-    size_t unit_st, unit_sk, s_t, s_k, budgets, base_len, layer_off, dec_cnt, moments, indices;
+    size_t unit_st, unit_sk, s_t, s_k, budgets, base_len, layer_off, dec_cnt, unit_cnt, moments, indices;
     size_t kcache, vcache, dec_o, dec_ml, stash, row_f, unit_R, len_off, dec_steps, cache_ptrs, by_length;
     size_t total;
     int32_t n_chunks;     // ceil(max_vis_len / kChunkKeys)
@@ -70,6 +70,7 @@ struct DevTables {
     float *dec_o, *stash, *row_f;
     int2 *len_off;    // (base_len, layer_off) of a (sequence, layer) side by side: one read for the decode kernel
     int4 *by_length;  // per sequence, the layers in order of falling cache length: (base_len, layer_off, layer, 0)
+    int32_t *unit_cnt;  // per unit: workgroups of air_score's last kernel that have left their moment entry (zero between launches)
     int32_t *unit_R;  // window rows of a unit (all heads of the group), left by the row-parameter kernel
     float2 *dec_ml;
     int32_t *dec_steps;  // tokens appended so far per unit when the device counts them (else null); one overflow flag after the last unit
@@ -107,7 +108,7 @@ hipError_t launch_elite_mfma(hipStream_t s, const Dims &dm, const DevTables &t, 
 hipError_t launch_score_mfma(hipStream_t s, const Dims &dm, const DevTables &t, int pass, int l0, int nl,
                              const LaunchLayers &ll, const air_strides &st, const SeqArgs &seqs, int inline_rows, int many_rows);
 hipError_t launch_budget(hipStream_t s, const Dims &dm, const DevTables &t, double retention, int mode,
-                         int min_keep, int skip_allocation, int use_moments, const SeqArgs &seqs);
+                         int min_keep, int skip_allocation, const SeqArgs &seqs);
 hipError_t launch_select(hipStream_t s, const Dims &dm, const DevTables &t, int l0, int nl, int threads, int direct_max);
 hipError_t launch_gather(hipStream_t s, const Dims &dm, const DevTables &t, int dtype, int l0, int nl,
                          const LaunchLayers &ll, const air_strides &st, int wgs_per_unit);

@@ -374,6 +374,71 @@ __global__ __launch_bounds__(64 * kRowWaves) void score_rows_mfma_kernel(Dims dm
 // INLINE: no row-parameter kernel has run; every workgroup forms the parameters of the unit's rows
 // itself from the chunk partials (the elite window's handful of rows: cheaper than a launch).
 
+// Eq.9-10 of one (layer, sequence, KV head) from the moment entries of its importance row, by one wave.  Entry c holds
+// the sum S1_c, the mean m_c and the moments M2_c, M3_c about m_c of the n_c scores of kFinishChunks chunks.  With
+// d_c = m_c - mu the central moments of the row are
+//   sum (x - mu)^2 = sum_c M2_c + n_c d_c^2,   sum (x - mu)^3 = sum_c M3_c + 3 d_c M2_c + n_c d_c^3,
+// sums of terms no larger than their result (raw power sums would cancel on rows of little spread).  Lane g of each row
+// of sixteen lanes takes the entries g, g + 16, ... (the first two stay in registers), the sums over the entries are
+// butterflies over the sixteen lanes: a fixed order, the same on every run; every operation is rounded once (no
+// contraction: the budgets that follow from these numbers must not depend on how the compiler fuses them).
+__device__ __forceinline__ void unit_statistics(const DevTables &t, __amdgpu_buffer_rsrc_t ers, int64_t unit, int n_ent,
+                                                int n_vis, int lane) {
+#pragma clang fp contract(off)
+    constexpr int kEntryKeys = kFinishChunks * kChunkKeys;
+    const int gl = lane & 15;
+    auto entry = [&](int c, double (&e)[4]) __attribute__((always_inline)) {
+        const int cc = min(c, n_ent - 1);
+        const u32x4 lo = __builtin_amdgcn_raw_buffer_load_b128(ers, cc * 32, 0, kSysScope);
+        const u32x4 hi = __builtin_amdgcn_raw_buffer_load_b128(ers, cc * 32 + 16, 0, kSysScope);
+        const bool have = c < n_ent;
+        e[0] = have ? __builtin_bit_cast(double, (u32x2){lo[0], lo[1]}) : 0.0;
+        e[1] = have ? __builtin_bit_cast(double, (u32x2){lo[2], lo[3]}) : 0.0;
+        e[2] = have ? __builtin_bit_cast(double, (u32x2){hi[0], hi[1]}) : 0.0;
+        e[3] = have ? __builtin_bit_cast(double, (u32x2){hi[2], hi[3]}) : 0.0;
+    };
+    double e0[4], e1[4];
+    entry(gl, e0);
+    entry(gl + 16, e1);
+    const double n = (double)n_vis;
+    double s1 = e0[0] + e1[0];
+    for (int c = gl + 32; c < n_ent; c += 16) {  // beyond 32768 visual tokens
+        double ex[4];
+        entry(c, ex);
+        s1 += ex[0];
+    }
+    const double S1 = sum16(s1);
+    const double mu = S1 / n;
+    double c2 = 0.0, c3 = 0.0;
+    auto add = [&](int c, const double (&e)[4]) __attribute__((always_inline)) {
+        if (c < n_ent) {
+            const double nc = (double)min(kEntryKeys, n_vis - c * kEntryKeys);
+            const double dl = e[1] - mu, M2 = e[2], M3 = e[3];
+            c2 += M2 + nc * (dl * dl);
+            c3 += (M3 + 3.0 * dl * M2) + nc * (dl * dl * dl);
+        }
+    };
+    add(gl, e0);
+    add(gl + 16, e1);
+    for (int c = gl + 32; c < n_ent; c += 16) {
+        double ex[4];
+        entry(c, ex);
+        add(c, ex);
+    }
+    c2 = sum16(c2);
+    c3 = sum16(c3);
+    double sk = 0.0;
+    if (n_vis >= 3) {
+        const double sigma = sqrt(c2 / (n - 1.0));
+        // zero spread (Eq.10 undefined; taken as 0): a standard deviation at most 1e-6 of the mean
+        if (sigma > 1e-6 * fabs(mu)) sk = n / ((n - 1.0) * (n - 2.0)) * (c3 / (sigma * sigma * sigma));
+    }
+    if (lane == 0) {
+        t.unit_st[unit] = S1;
+        t.unit_sk[unit] = sk;
+    }
+}
+
 // MANY: as in the stream kernel, the query rows of the recompute path are staged in LDS.
 template <bool VIS, bool INLINE, bool MANY>
 __global__ __launch_bounds__(256, 4) void score_finish_kernel(Dims dm, DevTables t, int l0, LaunchLayers ll,
@@ -431,11 +496,26 @@ __global__ __launch_bounds__(256, 4) void score_finish_kernel(Dims dm, DevTables
             s_mom[wave][2] = m3;
         }
         lds_barrier();
-        if (tid < 4) {
-            double *mo = t.moments + (u.unit * dm.n_entries + blockIdx.x) * 4;
-            const double r = tid == 0 ? S1 : (tid == 1 ? mean : ((s_mom[0][tid - 1] + s_mom[1][tid - 1]) + s_mom[2][tid - 1]) + s_mom[3][tid - 1]);
-            mo[tid] = r;
+        if (wave != 0) return;
+        // The entry goes out written through to memory, and the workgroup then counts itself at the unit's arrival
+        // counter; the one that counts last (every entry of the unit is in memory by then: each writer waited for its
+        // stores before it counted) turns the entries into the unit's strength and skewness.  The ordering is that of
+        // the decode kernel's exchange of partials: write-through stores, s_waitcnt, a relaxed device-scope
+        // read-modify-write, loads that bypass the caches.
+        double *mo_unit = t.moments + u.unit * dm.n_entries * 4;
+        const __amdgpu_buffer_rsrc_t ers = __builtin_amdgcn_make_buffer_rsrc(mo_unit, 0, dm.n_entries * 32, 0x00020000);
+        if (lane < 4) {
+            const double r = lane == 0 ? S1 : (lane == 1 ? mean : ((s_mom[0][lane - 1] + s_mom[1][lane - 1]) + s_mom[2][lane - 1]) + s_mom[3][lane - 1]);
+            __builtin_amdgcn_raw_buffer_store_b64(__builtin_bit_cast(u32x2, r), ers, (int)blockIdx.x * 32 + lane * 8, 0, kSysScope);
         }
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        int prev = 0;
+        if (lane == 0) prev = __hip_atomic_fetch_add(&t.unit_cnt[u.unit], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        prev = __builtin_amdgcn_readfirstlane(prev);
+        const int n_ent = (nch + kFinishChunks - 1) / kFinishChunks;  // workgroups of this unit
+        if (prev != n_ent - 1) return;
+        if (lane == 0) __hip_atomic_store(&t.unit_cnt[u.unit], 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);  // next launch
+        unit_statistics(t, ers, u.unit, n_ent, u.sq.vis_len, lane);
     };
 
     if (stash) {
