@@ -276,9 +276,8 @@ def measure_config(A, cfg_id, dev, timed_passes):
     dv = torch.randn((n_dec, L, w.batch, w.n_kv_heads, w.head_dim), generator=gen, device=dev, dtype=torch.float32).to(dt)
     out = torch.empty((L, w.batch, w.n_q_heads, w.head_dim), dtype=dt, device=dev)
     stage, wall, budgets, _, ws_bytes = timed_passes(w, seqs, q, k, v, dq, dk, dv, out, n_dec, retention, 3, 1)
-    sc, bu, se, de = stage.mean(axis=0)
+    sc, bu, se, de, comp_ms = stage.mean(axis=0)
     ab = algorithmic_bytes(w, seqs, budgets, n_dec)
-    comp_ms = sc + bu + se
     res = {
         "workload": f"config{w.cfg_id}:{w.name}", "retention": retention, "batch": w.batch, "layers": L,
         "tokens": f"{w.n_sys}+{w.n_vis}+{w.n_text}", "decode_steps": n_dec, "data": "synthetic, drawn on the device",
@@ -307,6 +306,8 @@ def main():
     ap.add_argument("--decode-steps", type=int, default=None)
     ap.add_argument("--per-layer", action="store_true", help="one air_decode_attn call per layer instead of one per step")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--tuning", default="", metavar="K=V,...",
+                    help="launch-shape overrides passed to air_set_tuning for every context of the run (A/B measurements)")
     ap.add_argument("--no-extras", action="store_true",
                     help="skip the one-launch-per-layer passes and the device-copy reference (profiling runs)")
     ap.add_argument("--score-per-layer", action="store_true",
@@ -373,12 +374,20 @@ def main():
     dv = to_device(np.stack([d[2] for d in dec_inputs]), dev)
     out = torch.empty((L, w.batch, w.n_q_heads, w.head_dim), dtype=q[0].dtype, device=dev)
 
+    tuning = {kv.split("=")[0]: int(kv.split("=")[1]) for kv in args.tuning.split(",") if kv}
+
     def timed_passes(w, seqs, q, k, v, dq, dk, dv, out, n_dec, retention, steps, warmup, per_layer=False,
                      want_stats=False):
-        """One context at this retention: `warmup` untimed passes of the whole hot path, then `steps` timed ones.
-        Returns per-pass stage times in ms [steps][score, budget, select_compact, decode], wall seconds, budgets, stats."""
+        """One context at this retention: `warmup` untimed passes of the whole hot path, then `steps` timed ones with
+        three events each (in front of air_score, behind air_select_compact, behind the last decode step), then a few
+        more passes with an event at every stage boundary for the breakdown.  An event costs the stream a few
+        microseconds, so the stage times carry that overhead and the compression figure is the region timed as a whole.
+        Returns times in ms [steps][score, budget, select_compact (means of the breakdown passes), decode, compression
+        (of the timed pass)], wall seconds, budgets, stats."""
         L = w.n_layers
         ac = A.AirCache(config_for(w, retention, max_decode_steps=n_dec, seqs=seqs), dev)
+        if tuning:
+            ac.air_set_tuning(**tuning)
         ev = lambda: torch.cuda.Event(enable_timing=True)  # noqa: E731
         # host-side marshalling is done once, outside the timed region: descriptor arrays and raw addresses
         prep_score = ac.prepare(q, k, v, seqs)
@@ -390,15 +399,15 @@ def main():
         lay_kv = dk[0, 0].numel() * esz
         pq, pk, pv, po = dq.data_ptr(), dk.data_ptr(), dv.data_ptr(), out.data_ptr()
 
-        def one_step(events=None):
+        def one_step(events=None, boundaries=False):
             ac.air_reset()
             if events is not None:
                 events[0].record()
             ac.air_score(0, L, prepared=prep_score)
-            if events is not None:
+            if boundaries:
                 events[1].record()
             ac.air_budget()
-            if events is not None:
+            if boundaries:
                 events[2].record()
             ac.air_select_compact(0, L, prepared=prep_compact)
             if events is not None:
@@ -426,7 +435,13 @@ def main():
         torch.cuda.synchronize()
         wall = time.perf_counter() - t0
 
-        stage = np.array([[e[i].elapsed_time(e[i + 1]) for i in range(4)] for e in all_events])  # ms
+        timed = np.array([[e[3].elapsed_time(e[4]), e[0].elapsed_time(e[3])] for e in all_events])  # ms: decode, compression
+        bd_events = [[ev() for _ in range(5)] for _ in range(min(steps, 5))]
+        for e in bd_events:
+            one_step(e, boundaries=True)
+        torch.cuda.synchronize()
+        bd = np.array([[e[i].elapsed_time(e[i + 1]) for i in range(3)] for e in bd_events]).mean(axis=0)
+        stage = np.concatenate([np.tile(bd, (steps, 1)), timed], axis=1)
         ws_bytes = ac.workspace_bytes
         del ac
         return stage, wall, budgets, stats, ws_bytes
@@ -436,8 +451,7 @@ def main():
 
     stage, wall, budgets, stats, ws_bytes_main = timed_passes(w, seqs, q, k, v, dq, dk, dv, out, n_dec, retention, args.steps,
                                                               args.warmup, args.per_layer, True)
-    score_ms, budget_ms, select_ms, decode_ms = stage.mean(axis=0)
-    compress_ms = score_ms + budget_ms + select_ms
+    score_ms, budget_ms, select_ms, decode_ms, compress_ms = stage.mean(axis=0)
     ms_per_step = wall * 1e3 / args.steps
     ab = algorithmic_bytes(w, seqs, budgets, n_dec)
     n_launch = n_dec * (L if args.per_layer else 1)
@@ -464,7 +478,10 @@ def main():
         "decode_tokens_per_s": w.batch * n_dec / (decode_ms * 1e-3),
         "budgets_min_mean_max": [int(np.min(budgets)), float(np.mean(budgets)), int(np.max(budgets))],
         "stage_us": {"score": score_ms * 1e3, "budget": budget_ms * 1e3, "select_compact": select_ms * 1e3,
-                     "decode_per_step": decode_ms * 1e3 / n_dec},
+                     "decode_per_step": decode_ms * 1e3 / n_dec,
+                     "note": "score / budget / select_compact from separate passes with an event at every stage boundary "
+                             "(an event costs the stream a few us: their sum exceeds the compression pass timed as a "
+                             "whole; up to 64 layers air_score's last kernel does the allocation and air_budget launches nothing)"},
         "roofline": {"kernel": "air_decode_attn", "bound": "hbm", "achieved": dec_gbs, "peak": HBM_PEAK_GBS,
                      "unit": "GB/s", "frac": dec_gbs / HBM_PEAK_GBS, "traffic": None,
                      "bytes_per_launch": ab["decode_total"] / n_launch, "launch_us": dec_launch_us},
@@ -475,7 +492,7 @@ def main():
                               "bytes": ab["compress"]},
     }
     # median and minimum over the timed passes
-    comp_iter = stage[:, :3].sum(axis=1)
+    comp_iter = stage[:, 4]
     result["compress_us_per_layer_median_min"] = [float(np.median(comp_iter)) * 1e3 / L, float(comp_iter.min()) * 1e3 / L]
     result["workspace_bytes"] = int(ws_bytes_main)
     result["decode_us_per_step_median_min"] = [float(np.median(stage[:, 3])) * 1e3 / n_dec, float(stage[:, 3].min()) * 1e3 / n_dec]
@@ -523,8 +540,8 @@ def main():
     if args.retention_sweep or not args.no_extras:
         sweep = []
         for r in (1.0, 0.5, 0.1, 0.01):
-            sc, bu, se, de = run(r, 3, 1)[0].mean(axis=0)
-            sweep.append({"retention": r, "compress_us_per_layer": (sc + bu + se) * 1e3 / L,
+            sc, bu, se, de, comp = run(r, 3, 1)[0].mean(axis=0)
+            sweep.append({"retention": r, "compress_us_per_layer": comp * 1e3 / L,
                           "decode_us_per_step": de * 1e3 / n_dec})
         for e in sweep:
             e["decode_speedup_vs_full_cache"] = sweep[0]["decode_us_per_step"] / e["decode_us_per_step"]

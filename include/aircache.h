@@ -158,6 +158,8 @@ typedef struct {
                                   cache first (where the launch shape has that variant)                         */
     int32_t decode_halves;     /* decode of one sequence, two workgroups per unit with one half of the columns of
                                   V' each (taken wherever the launch shape has that variant): 1 never           */
+    int32_t budget_in_score;   /* 1: air_score never does the allocation of Eq.11 in the tail of its last kernel
+                                  (air_budget then launches the budget kernel, as it does beyond 64 layers)       */
 } air_tuning;
 /* AIR_ERR_INVALID_ARG (and no change) if a field holds a value outside its list. */
 air_status air_set_tuning(air_ctx *ctx, const air_tuning *tuning);

@@ -47,7 +47,7 @@ class air_layer(C.Structure):
 
 class air_tuning(C.Structure):
     _fields_ = [(n, C.c_int32) for n in ("decode_splits", "decode_waves", "decode_tiles", "score_block_mb",
-                                         "score_rows_kernel", "select_threads", "select_direct_max", "gather_wgs", "decode_order", "decode_halves")]
+                                         "score_rows_kernel", "select_threads", "select_direct_max", "gather_wgs", "decode_order", "decode_halves", "budget_in_score")]
 
 
 class air_strides(C.Structure):
@@ -218,9 +218,9 @@ class AirCache:
         self._check(self.lib.air_reset(self.handle))
 
     def air_set_tuning(self, *, decode_splits=0, decode_waves=0, decode_tiles=0, score_block_mb=0, score_rows_kernel=0,
-                       select_threads=0, select_direct_max=-1, gather_wgs=0, decode_order=0, decode_halves=0):
+                       select_threads=0, select_direct_max=-1, gather_wgs=0, decode_order=0, decode_halves=0, budget_in_score=0):
         tn = air_tuning(decode_splits, decode_waves, decode_tiles, score_block_mb, score_rows_kernel, select_threads,
-                        select_direct_max, gather_wgs, decode_order, decode_halves)
+                        select_direct_max, gather_wgs, decode_order, decode_halves, budget_in_score)
         self._check(self.lib.air_set_tuning(self.handle, C.byref(tn)))
 
     def air_select_compact(self, l0: int, l1: int, k=None, v=None, strides=None, prepared=None):

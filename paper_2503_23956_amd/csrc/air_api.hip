@@ -84,6 +84,7 @@ WsLayout make_layout(const air_config &c) {
     w.layer_off = take(B * L * 4);
     w.dec_cnt = take(L * B * Hkv * 4);
     w.unit_cnt = take(L * B * Hkv * 4);
+    w.seq_cnt = take(B * 4);
     w.dec_steps = take((L * B * Hkv + 1) * 4);
     w.moments = take(L * B * Hkv * (size_t)((w.n_chunks + kFinishChunks - 1) / kFinishChunks) * 4 * 8);
     w.indices = take(L * B * Hkv * NV * 4);
@@ -106,6 +107,12 @@ WsLayout make_layout(const air_config &c) {
 
 using namespace air;
 
+// Eq.11 in the tail of air_score's last kernel: the MFMA score path, the layers within one wave, the KV heads of a layer
+// within one round of sixteen loads
+static bool can_fuse_budget(const air_config &c) {
+    return v_transposed(c.dtype, c.head_dim) && c.n_layers <= 64 && c.n_kv_heads <= 16;
+}
+
 struct air_ctx {
     air_config cfg;
     WsLayout lay;
@@ -119,7 +126,12 @@ struct air_ctx {
     std::vector<char> scored, compacted, fixed_idx;  // fixed_idx: the layer's kept indices were set by the caller
     std::vector<int32_t> appended;
     air_tuning tune;  // launch-shape overrides (air_set_tuning); all automatic after air_create
-    std::vector<CachePtrs> ip_layers;  // in-place cache: the K / V tensor each compacted layer lives in
+    std::vector<CachePtrs> ip_layers;
+    // Eq.11 done in the tail of air_score (Dims::fuse_budget): layers scored that way since the reset; broken: a layer was
+    // scored twice or with the fusion switched off, so air_budget launches its kernel; need_zero: the per-sequence
+    // arrival counters may hold a partial count and are cleared in front of the next air_score
+    int fused_count = 0;
+    bool fused_broken = false, need_zero = false;  // in-place cache: the K / V tensor each compacted layer lives in
     std::string err;
 };
 
@@ -166,6 +178,10 @@ air_status air_create(const air_config *cfg, void *workspace, size_t workspace_b
     d.causal_text = cfg->causal_text;
     d.inv_B = cfg->batch > 1 ? (uint32_t)(0x100000000ull / (uint64_t)cfg->batch) + 1u : 0u;
     d.pool_rows = lay.pool_rows;
+    d.fuse_budget = can_fuse_budget(*cfg) ? 1 : 0;
+    d.budget_mode = cfg->budget_mode;
+    d.min_keep = cfg->min_keep;
+    d.retention = cfg->retention;
     DevTables &t = c->tab;
     char *w = c->ws;
     t.seq_tab = (air_seq *)(w + lay.seq_tab);
@@ -186,6 +202,7 @@ air_status air_create(const air_config *cfg, void *workspace, size_t workspace_b
     t.layer_off = (int32_t *)(w + lay.layer_off);
     t.dec_cnt = (int32_t *)(w + lay.dec_cnt);
     t.unit_cnt = (int32_t *)(w + lay.unit_cnt);
+    t.seq_cnt = (int32_t *)(w + lay.seq_cnt);
     t.moments = (double *)(w + lay.moments);
     t.indices = (int32_t *)(w + lay.indices);
     t.kcache = (void *)(w + lay.kcache);
@@ -240,6 +257,9 @@ air_status air_reset(air_ctx *ctx) {
     ctx->fixed_idx.assign(ctx->dm.L, 0);
     ctx->appended.assign(ctx->dm.L, 0);
     ctx->decoded.assign(ctx->dm.L, 0);
+    if (ctx->fused_count > 0 && (ctx->fused_broken || ctx->fused_count != ctx->dm.L)) ctx->need_zero = true;
+    ctx->fused_count = 0;
+    ctx->fused_broken = false;
     return AIR_OK;
 }
 
@@ -306,6 +326,11 @@ air_status air_score(air_ctx *ctx, void *stream, int32_t l0, int32_t l1, const a
     memcpy(sa.s, seqs, sizeof(air_seq) * ctx->cfg.batch);
     const int dt = ctx->cfg.dtype;
     const bool mfma = v_transposed(dt, ctx->cfg.head_dim);  // bf16, head_dim 128
+    if (ctx->need_zero) {  // a prompt that was dropped half-way left partial counts of finished units
+        hipError_t e = launch_zero_counters(s, ctx->tab.seq_cnt, ctx->dm.B);
+        if (e != hipSuccess) return hip_fail(ctx, e, "air_score: clearing the arrival counters");
+        ctx->need_zero = false;
+    }
     const int lpl = layers_per_launch(ctx);
     int group = lpl;
     // The elite window (alpha > 0) leaves a unit a handful of rows: the finish kernel forms their
@@ -357,7 +382,11 @@ air_status air_score(air_ctx *ctx, void *stream, int32_t l0, int32_t l1, const a
         ctx->seqs.assign(seqs, seqs + ctx->cfg.batch);
         ctx->have_seqs = true;
     }
-    for (int l = l0; l < l1; ++l) ctx->scored[l] = 1;
+    for (int l = l0; l < l1; ++l) {
+        if (ctx->scored[l] || !ctx->dm.fuse_budget) ctx->fused_broken = true;
+        ctx->scored[l] = 1;
+    }
+    if (ctx->dm.fuse_budget) ctx->fused_count += l1 - l0;
     ctx->budgets_ready = false;
     return AIR_OK;
 }
@@ -368,12 +397,17 @@ air_status air_budget(air_ctx *ctx, void *stream) {
         if (!ctx->scored[l]) return fail(ctx, AIR_ERR_STATE, "air_budget: not every layer has been scored");
     for (int l = 0; l < ctx->cfg.n_layers; ++l)
         if (ctx->compacted[l]) return fail(ctx, AIR_ERR_STATE, "air_budget: layers already compacted");
-    SeqArgs sa;
-    memset(&sa, 0, sizeof(sa));
-    memcpy(sa.s, ctx->seqs.data(), sizeof(air_seq) * ctx->cfg.batch);
-    hipError_t e = launch_budget((hipStream_t)stream, ctx->dm, ctx->tab, ctx->cfg.retention, ctx->cfg.budget_mode,
-                                 ctx->cfg.min_keep, 0, sa);
-    if (e != hipSuccess) return hip_fail(ctx, e, "air_budget launch");
+    // Where every layer went through air_score's last kernel once, with the allocation of Eq.11 in its tail, the
+    // budgets and the layout tables are already on their way: nothing is launched here.
+    const bool done_in_score = ctx->dm.fuse_budget && !ctx->fused_broken && ctx->fused_count == ctx->dm.L;
+    if (!done_in_score) {
+        SeqArgs sa;
+        memset(&sa, 0, sizeof(sa));
+        memcpy(sa.s, ctx->seqs.data(), sizeof(air_seq) * ctx->cfg.batch);
+        hipError_t e = launch_budget((hipStream_t)stream, ctx->dm, ctx->tab, ctx->cfg.retention, ctx->cfg.budget_mode,
+                                     ctx->cfg.min_keep, 0, sa);
+        if (e != hipSuccess) return hip_fail(ctx, e, "air_budget launch");
+    }
     ctx->fixed_idx.assign(ctx->dm.L, 0);
     ctx->budgets_ready = true;
     return AIR_OK;
@@ -614,10 +648,18 @@ air_status air_set_tuning(air_ctx *ctx, const air_tuning *tn) {
     };
     if (!one_of(tn->decode_splits, {0, 1, 2, 4, 8, 16}) || !one_of(tn->decode_waves, {0, 1, 2, 4, 8}) ||
         !one_of(tn->decode_tiles, {0, 2, 4, 8}) || tn->score_block_mb < 0 || tn->score_block_mb > 65536 ||
-        !one_of(tn->score_rows_kernel, {0, 1}) || !one_of(tn->decode_order, {0, 1, 2}) || !one_of(tn->decode_halves, {0, 1, 2}) || !one_of(tn->select_threads, {0, 256, 512}) ||
+        !one_of(tn->score_rows_kernel, {0, 1}) || !one_of(tn->decode_order, {0, 1, 2}) || !one_of(tn->decode_halves, {0, 1, 2}) || !one_of(tn->budget_in_score, {0, 1}) || !one_of(tn->select_threads, {0, 256, 512}) ||
         tn->select_direct_max < -1 || tn->select_direct_max > 1024 || tn->gather_wgs < 0 || tn->gather_wgs > 64)
         return fail(ctx, AIR_ERR_INVALID_ARG, "air_set_tuning: a field holds a value outside its list");
     ctx->tune = *tn;
+    // the allocation in the tail of air_score can be switched off (then air_budget launches its kernel); a switch
+    // in the middle of a prompt leaves that prompt to the kernel as well
+    const int fuse = can_fuse_budget(ctx->cfg) && tn->budget_in_score != 1 ? 1 : 0;
+    if (fuse != ctx->dm.fuse_budget) {
+        for (int l = 0; l < ctx->dm.L; ++l)
+            if (ctx->scored[l]) ctx->fused_broken = true;
+        ctx->dm.fuse_budget = fuse;
+    }
     return AIR_OK;
 }
 

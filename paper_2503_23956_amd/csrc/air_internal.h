@@ -40,7 +40,7 @@ struct SeqArgs {
 // Byte offsets of every table inside the workspace.
 struct WsLayout {
     size_t seq_tab, elite_cnt, elite_idx, row_mtext, row_ztext, row_M, row_w, part, scores;
-    size_t unit_st, unit_sk, s_t, s_k, budgets, base_len, layer_off, dec_cnt, unit_cnt, moments, indices;
+    size_t unit_st, unit_sk, s_t, s_k, budgets, base_len, layer_off, dec_cnt, unit_cnt, seq_cnt, moments, indices;
     size_t kcache, vcache, dec_o, dec_ml, stash, row_f, unit_R, len_off, dec_steps, cache_ptrs, by_length;
     size_t total;
     int32_t n_chunks;     // ceil(max_vis_len / kChunkKeys)
@@ -56,6 +56,9 @@ struct Dims {
     int32_t causal_text; // 1: an elite row sees only the elite text keys at or before its own position (Eq.7 with a causal mask)
     uint32_t inv_B;      // floor(2^32 / B) + 1 (unused for B = 1): division of a 16-bit index by B as one multiply
     int64_t pool_rows;
+    // Eq.11 inside air_score: the last workgroup of a sequence to finish its unit does the allocation (the layers fit one wave)
+    int32_t fuse_budget, budget_mode, min_keep;
+    double retention;
 };
 
 struct DevTables {
@@ -71,6 +74,7 @@ struct DevTables {
     int2 *len_off;    // (base_len, layer_off) of a (sequence, layer) side by side: one read for the decode kernel
     int4 *by_length;  // per sequence, the layers in order of falling cache length: (base_len, layer_off, layer, 0)
     int32_t *unit_cnt;  // per unit: workgroups of air_score's last kernel that have left their moment entry (zero between launches)
+    int32_t *seq_cnt;   // per sequence: units whose statistics are complete (zero again once all L * H_kv have arrived)
     int32_t *unit_R;  // window rows of a unit (all heads of the group), left by the row-parameter kernel
     float2 *dec_ml;
     int32_t *dec_steps;  // tokens appended so far per unit when the device counts them (else null); one overflow flag after the last unit

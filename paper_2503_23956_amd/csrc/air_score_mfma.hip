@@ -26,6 +26,7 @@
 //       sums would cancel on rows of little spread: S2 - S1 mu loses (mu / sigma)^2 of its digits.
 #include "air_device.h"
 #include "air_internal.h"
+#include "air_budget_dev.h"
 #include <type_traits>
 
 namespace air {
@@ -382,8 +383,8 @@ __global__ __launch_bounds__(64 * kRowWaves) void score_rows_mfma_kernel(Dims dm
 // of sixteen lanes takes the entries g, g + 16, ... (the first two stay in registers), the sums over the entries are
 // butterflies over the sixteen lanes: a fixed order, the same on every run; every operation is rounded once (no
 // contraction: the budgets that follow from these numbers must not depend on how the compiler fuses them).
-__device__ __forceinline__ void unit_statistics(const DevTables &t, __amdgpu_buffer_rsrc_t ers, int64_t unit, int n_ent,
-                                                int n_vis, int lane) {
+__device__ __forceinline__ void unit_statistics(__amdgpu_buffer_rsrc_t ers, int n_ent, int n_vis, int lane, double &st_out,
+                                                double &sk_out) {
 #pragma clang fp contract(off)
     constexpr int kEntryKeys = kFinishChunks * kChunkKeys;
     const int gl = lane & 15;
@@ -433,10 +434,8 @@ __device__ __forceinline__ void unit_statistics(const DevTables &t, __amdgpu_buf
         // zero spread (Eq.10 undefined; taken as 0): a standard deviation at most 1e-6 of the mean
         if (sigma > 1e-6 * fabs(mu)) sk = n / ((n - 1.0) * (n - 2.0)) * (c3 / (sigma * sigma * sigma));
     }
-    if (lane == 0) {
-        t.unit_st[unit] = S1;
-        t.unit_sk[unit] = sk;
-    }
+    st_out = S1;
+    sk_out = sk;
 }
 
 // MANY: as in the stream kernel, the query rows of the recompute path are staged in LDS.
@@ -515,7 +514,51 @@ __global__ __launch_bounds__(256, 4) void score_finish_kernel(Dims dm, DevTables
         const int n_ent = (nch + kFinishChunks - 1) / kFinishChunks;  // workgroups of this unit
         if (prev != n_ent - 1) return;
         if (lane == 0) __hip_atomic_store(&t.unit_cnt[u.unit], 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);  // next launch
-        unit_statistics(t, ers, u.unit, n_ent, u.sq.vis_len, lane);
+        double unit_st, unit_sk;
+        unit_statistics(ers, n_ent, u.sq.vis_len, lane, unit_st, unit_sk);
+        if (!dm.fuse_budget) {
+            if (lane == 0) {
+                t.unit_st[u.unit] = unit_st;
+                t.unit_sk[u.unit] = unit_sk;
+            }
+            return;
+        }
+        // The same once more, one level up: the unit's statistics go out written through, the wave counts the unit at
+        // its sequence's arrival counter, and the wave that counts the last of the L * H_kv units does Eq.11 and the
+        // cache layout of the sequence (the layers fit one wave): air_budget has nothing left to launch.
+        const int64_t all_units = (int64_t)dm.L * dm.B * dm.Hkv;
+        const __amdgpu_buffer_rsrc_t srs = __builtin_amdgcn_make_buffer_rsrc(t.unit_st, 0, (int)(all_units * 8), 0x00020000);
+        const __amdgpu_buffer_rsrc_t krs = __builtin_amdgcn_make_buffer_rsrc(t.unit_sk, 0, (int)(all_units * 8), 0x00020000);
+        if (lane == 0) {
+            __builtin_amdgcn_raw_buffer_store_b64(__builtin_bit_cast(u32x2, unit_st), srs, (int)u.unit * 8, 0, kSysScope);
+            __builtin_amdgcn_raw_buffer_store_b64(__builtin_bit_cast(u32x2, unit_sk), krs, (int)u.unit * 8, 0, kSysScope);
+        }
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        prev = 0;
+        if (lane == 0) prev = __hip_atomic_fetch_add(&t.seq_cnt[u.b], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        prev = __builtin_amdgcn_readfirstlane(prev);
+        if (prev != dm.L * dm.Hkv - 1) return;
+        if (lane == 0) __hip_atomic_store(&t.seq_cnt[u.b], 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);  // next prompt
+        __shared__ double s_a0[64], s_a1[64], s_frac[64];
+        __shared__ int s_i0[64], s_i1[64];
+        allocate_and_lay_out<true>(dm, t, u.b, u.sq, dm.retention, dm.budget_mode, dm.min_keep, false, lane, s_a0, s_a1, s_frac,
+                                   s_i0, s_i1, [&](int l, double &a, double &c) __attribute__((always_inline)) {
+                                       // all heads' loads go out together; the sums run left to right over the live ones
+                                       u32x2 vs[16], vk[16];
+#pragma unroll
+                                       for (int h = 0; h < 16; ++h) {
+                                           const int off = (int)((((int64_t)l * dm.B + u.b) * dm.Hkv + min(h, dm.Hkv - 1)) * 8);
+                                           vs[h] = __builtin_amdgcn_raw_buffer_load_b64(srs, off, 0, kSysScope);
+                                           vk[h] = __builtin_amdgcn_raw_buffer_load_b64(krs, off, 0, kSysScope);
+                                       }
+#pragma unroll
+                                       for (int h = 0; h < 16; ++h) {
+                                           if (h < dm.Hkv) {
+                                               a += __builtin_bit_cast(double, vs[h]);
+                                               c += __builtin_bit_cast(double, vk[h]);
+                                           }
+                                       }
+                                   });
     };
 
     if (stash) {

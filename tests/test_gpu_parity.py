@@ -720,6 +720,68 @@ def test_two_runs_give_bitwise_equal_results():
             assert same(r1[key], r2[key]), f"{key} differs between the two unit orders ({waves} waves)"
 
 
+def test_allocation_in_the_tail_of_scoring_equals_the_budget_kernel():
+    """Up to 64 layers air_score's last kernel does Eq.11 itself (the last unit of a sequence to finish); beyond that,
+    or with the tuning switch, air_budget launches the budget kernel.  Both must leave the same statistics, budgets
+    and layout, also when the layers are scored in several calls, when a layer is scored twice (the kernel takes
+    over) and when a prompt is dropped half-way (its partial arrival counts must not leak into the next one)."""
+    import torch
+
+    import paper_2503_23956_amd as A
+    from paper_2503_23956_amd.device_inputs import config_for, to_device
+
+    dev = torch.device("cuda:0")
+    w = synth.get_workload(3).scaled(batch=3, n_layers=5, n_vis=1300, n_text=48, decode_steps=1)
+    seqs = w.seqs()
+    L = w.n_layers
+    layers = [synth.layer_inputs(w, l, seqs) for l in range(L)]
+    q, k, v = ([to_device(getattr(li, name), dev) for li in layers] for name in ("q_text", "k", "v"))
+
+    def state(ac):
+        ac.air_budget()
+        ac.air_select_compact(0, L, k, v)  # the layout tables are what the gather and the lengths follow
+        bud = ac.air_get_budgets()
+        idx = [ac.air_get_indices(l) for l in range(L)]
+        return dict(stats=ac.air_get_stats(), budgets=bud, lengths=ac.air_get_lengths(),
+                    idx=[[idx[l][b, :, : bud[b, l]] for b in range(w.batch)] for l in range(L)])
+
+    def same(a, b):
+        for key in a:
+            xs, ys = (a[key], b[key]) if isinstance(a[key], (list, tuple)) else ([a[key]], [b[key]])
+            for x, y in zip(xs, ys):
+                if isinstance(x, (list, tuple)):
+                    assert all(np.array_equal(p, r) for p, r in zip(x, y)), key
+                else:
+                    assert np.array_equal(x, y), key
+
+    ref = A.AirCache(config_for(w, 0.10, seqs=seqs, max_decode_steps=1), dev)
+    ref.air_set_tuning(budget_in_score=1)
+    ref.air_score(0, L, q, k, v, seqs)
+    want = state(ref)
+    ref.close()
+
+    ac = A.AirCache(config_for(w, 0.10, seqs=seqs, max_decode_steps=1), dev)
+    ac.air_score(0, L, q, k, v, seqs)  # all layers in one call
+    same(want, state(ac))
+    ac.air_reset()
+    for l0, l1 in ((3, 5), (0, 1), (1, 3)):  # in pieces, out of order
+        ac.air_score(l0, l1, q[l0:l1], k[l0:l1], v[l0:l1], seqs)
+    same(want, state(ac))
+    ac.air_reset()
+    ac.air_score(0, L, q, k, v, seqs)
+    ac.air_score(2, 3, q[2:3], k[2:3], v[2:3], seqs)  # a layer scored twice: the arrival count is off, the kernel takes over
+    same(want, state(ac))
+    ac.air_reset()
+    ac.air_score(0, 2, q[:2], k[:2], v[:2], seqs)  # a prompt dropped after two layers
+    ac.air_reset()
+    ac.air_score(0, L, q, k, v, seqs)
+    same(want, state(ac))
+    ac.air_reset()
+    ac.air_score(0, L, q, k, v, seqs)  # and the counters are back at zero after a complete pass
+    same(want, state(ac))
+    ac.close()
+
+
 # ---------------------------------------------------------------------------------------
 # Eq.10 on importance rows of little or no spread
 # ---------------------------------------------------------------------------------------
