@@ -175,7 +175,11 @@ air_status air_reset(air_ctx *ctx);
 air_status air_score(air_ctx *ctx, void *stream, int32_t l0, int32_t l1, const air_layer *layers,
                      const air_strides *strides, const air_seq *seqs);
 
-/* Eq.11 for every sequence.  All layers must have been scored (else AIR_ERR_STATE). */
+/* Eq.11 for every sequence.  All layers must have been scored (else AIR_ERR_STATE).  Where every layer went
+ * through air_score exactly once since the reset, on the bf16 / head_dim 128 path with at most 64 layers and 16 KV
+ * heads, the last kernel of air_score has done the allocation in its tail and this call launches nothing; it is
+ * still the call that makes the budgets available to air_select_compact.  Call it on the stream air_score ran on
+ * (or one ordered behind it). */
 air_status air_budget(air_ctx *ctx, void *stream);
 
 /* Alg.1, second loop for layers [l0, l1): top-k_l visual tokens per (sequence, KV head)
