@@ -493,7 +493,8 @@ air_status air_select_compact(air_ctx *ctx, void *stream, int32_t l0, int32_t l1
 // against 10.8 us at 10 % retention, 34.9 against 36.0 at 50 %, 75.3 against 78.2 with the full cache):
 // the merge of the waves through LDS is shorter and the streaming is bound by the CU, not by the number of waves.
 // air_set_tuning overrides the choice (tests, tuning).
-static void decode_shape(const air_ctx *ctx, int n_layers_in_launch, int appended, int *splits, int *waves, int *tiles) {
+static void decode_shape(const air_ctx *ctx, int n_layers_in_launch, int appended, bool halves_ok, int *splits, int *waves,
+                         int *tiles) {
     constexpr int kEnoughWorkgroups = 256, kEnoughWaves = 1536;
     constexpr double kWorkgroupGBs = 100.0, kLaunchGBs = 6000.0, kSplitUs = 3.7;
     const air_config &c = ctx->cfg;
@@ -507,7 +508,12 @@ static void decode_shape(const air_ctx *ctx, int n_layers_in_launch, int appende
     // A launch of a handful of units (one layer of one sequence) is bound by what one CU can stream: the unit
     // is cut into splits of about one 32-key chunk per wave, which beats the exchange of the partials (4 units
     // of ~900 keys: 8.4 us against 9.9 us as single workgroups).
-    const bool tiny_launch = units <= 16;
+    // Short units of such a launch do better still as two workgroups each with half of V' and no exchange (the column
+    // halves: four waves, 64-key chunks): 4 units, us per launch against the splits, 360 keys 5.8 / 7.7, 870 keys
+    // 8.1 / 8.4, 1600 keys 11.3 / 9.8, 3800 keys 20.7 / 10.8.
+    // (The rule goes by the prompt's own length, so that a decode run keeps one shape from its first step to its last.)
+    const bool short_halves = units <= 16 && halves_ok && avg_len - appended < 896.0;
+    const bool tiny_launch = units <= 16 && !short_halves;
     int kt = tiny_launch ? 2 : 4;
     if (ctx->tune.decode_tiles > 0) kt = ctx->tune.decode_tiles;
     const int64_t iters = (int64_t)((avg_len + 16.0 * kt - 1.0) / (16.0 * kt));
@@ -522,7 +528,7 @@ static void decode_shape(const air_ctx *ctx, int n_layers_in_launch, int appende
     int64_t s = 1;
     if (tiny_launch) {
         while (s < kMaxSplits && iters > 4 * s && units * s * 2 <= kEnoughWorkgroups) s *= 2;
-    } else {
+    } else if (!short_halves) {
         const double unit_bytes = avg_len * 2.0 * c.head_dim * (c.dtype == AIR_BF16 ? 2.0 : 4.0);
         const double launch_us = (double)units * unit_bytes / (kLaunchGBs * 1e3);
         auto cost = [&](int64_t n) { return fmax(launch_us, unit_bytes / n / (kWorkgroupGBs * 1e3)) + (n > 1 ? kSplitUs : 0.0); };
@@ -570,16 +576,19 @@ static air_status decode_attn(air_ctx *ctx, void *stream, int32_t l0, int32_t l1
     // launch shapes first: a static exchange area that is too small must be found before anything is launched
     auto shape_of = [&](int c0, int nl, int *splits, int *waves, int *tiles) {
         // a recorded launch is replayed at every cache length: its shape is chosen for the middle of the decode
-        decode_shape(ctx, nl, ctx->cfg.device_steps ? ctx->cfg.max_decode_steps / 2 : ctx->appended[c0], splits, waves, tiles);
+        const int hkv = ctx->dm.Hkv;
+        const bool halves_ok = in_step && (hkv & (hkv - 1)) == 0 && ctx->tune.decode_halves != 1;
+        decode_shape(ctx, nl, ctx->cfg.device_steps ? ctx->cfg.max_decode_steps / 2 : ctx->appended[c0], halves_ok, splits, waves,
+                     tiles);
     };
-    // Two workgroups per unit, each with all of K' and one half of the columns of V' (air_decode.hip), wherever one
-    // sequence's launch of four-wave workgroups leaves half the CUs idle.  112 units, warm / cold cache: 215 keys per
+    // Two workgroups per unit, each with all of K' and one half of the columns of V' (air_decode.hip), wherever a
+    // launch of four-wave workgroups leaves half the CUs idle.  112 units, warm / cold cache: 215 keys per
     // unit 6.4 / 8.7 us against 6.5 / 8.4 with one workgroup per unit, 870 keys 9.6 / 11.6 against 10.7 / 13.3,
     // 3800 keys 33 / 45 against 35 / 55, 7400 keys 64 / 73 against 76 / 89.
     auto halves_of = [&](int nl, int splits, int waves, int tiles) {
         const int hkv = ctx->dm.Hkv;
-        const bool can = in_step && ctx->dm.B == 1 && (hkv & (hkv - 1)) == 0 && splits == 1 && waves == 4 && tiles == 4 &&
-                         2 * ((nl * hkv + 7) & ~7) <= 256;
+        const bool can = in_step && (hkv & (hkv - 1)) == 0 && splits == 1 && waves == 4 && tiles == 4 &&
+                         2 * ((nl * units_per_layer + 7) & ~7) <= 256;
         return can && ctx->tune.decode_halves != 1;
     };
     for (int c0 = l0; use_static && c0 < l1; c0 += max_nl) {

@@ -177,15 +177,14 @@ __global__ __launch_bounds__(64 * NW) void decode_mfma_kernel(Dims dm, DecodeTab
         // same XCD (ids are dealt round-robin over the 8 XCDs) at neighbouring dispatch slots, so that the K' tiles both
         // stream come through that XCD's L2 once.  `splits` carries the units of the launch (the grid is rounded up to
         // whole groups of 16: the workgroups past the end redo the last unit and store nothing), `lg_splits` log2 of
-        // the KV heads; one sequence.
+        // the KV heads.
         const int wid = blockIdx.x, slot = wid >> 3;
         int pair = ((slot >> 1) << 3) | (wid & 7);
         vh = slot & 1;
         live = pair < splits;
         pair = min(pair, splits - 1);
         kvh = pair & (dm.Hkv - 1);
-        li = pair >> lg_splits;
-        b = 0;
+        seq_layer_of(dm, pair >> lg_splits, b, li);
     }
     int2 len_off;
     if (SORTED) {
@@ -816,7 +815,7 @@ hipError_t launch_decode(hipStream_t s, const Dims &dm, const DevTables &t, cons
         else AIR_LAUNCH_DECODE_(NW, KT, true, true);                                    \
     } while (0)
         if (column_halves) {  // the caller has checked what this variant asks for
-            const int units = nl * dm.Hkv;
+            const int units = nl * dm.B * dm.Hkv;
             int lg_h = 0;
             while ((1 << lg_h) < dm.Hkv) ++lg_h;
             const dim3 grid2(2 * ((units + 7) & ~7));

@@ -422,10 +422,12 @@ def test_decode_forced_launch_shapes(splits, waves, tiles):
     _run_case(w, 0.25, steps=36, tuning=dict(decode_splits=splits, decode_waves=waves, decode_tiles=tiles))
 
 
-@pytest.mark.parametrize("n_layers,n_vis,retention", [(3, 900, 0.25), (2, 2600, 1.00), (5, 300, 0.05)])
-def test_decode_column_halves(n_layers, n_vis, retention):
+@pytest.mark.parametrize("base,batch,n_layers,n_vis,retention", [(2, 1, 3, 900, 0.25), (2, 1, 2, 2600, 1.00), (2, 1, 5, 300, 0.05),
+                                                                 (3, 3, 2, 1100, 0.25)])
+def test_decode_column_halves(base, batch, n_layers, n_vis, retention):
     # two workgroups per unit, each with all of K' and one half of the columns of V' and of the output: against the
-    # oracle (12 and 20 units: a grid rounded up to whole groups of 16 workgroups; 8 units: an exact one), with appends
+    # oracle (12, 20 and 24 units: a grid rounded up to whole groups of 16 workgroups; 8 units: an exact one; one sequence
+    # and a ragged batch of three), with appends
     # that cross token blocks, and bit for bit against one workgroup per unit (same arithmetic per output column)
     import torch
 
@@ -433,7 +435,7 @@ def test_decode_column_halves(n_layers, n_vis, retention):
     from paper_2503_23956_amd.device_inputs import config_for, to_device, to_host
 
     steps = 36
-    w = synth.get_workload(2).scaled(n_layers=n_layers, n_vis=n_vis, n_text=37, decode_steps=steps)
+    w = synth.get_workload(base).scaled(batch=batch, n_layers=n_layers, n_vis=n_vis, n_text=37, decode_steps=steps)
     shape = dict(decode_splits=1, decode_waves=4, decode_tiles=4)
     _run_case(w, retention, steps=steps, oracle_steps=[0, 1, 31, 32, 35], tuning=dict(shape, decode_halves=2))
     dev = torch.device("cuda:0")
@@ -448,14 +450,14 @@ def test_decode_column_halves(n_layers, n_vis, retention):
         ac.air_score(0, L, q, k, v, seqs)
         ac.air_budget()
         ac.air_select_compact(0, L, k, v)
-        out = torch.empty((L, 1, w.n_q_heads, w.head_dim), dtype=torch.bfloat16, device=dev)
+        out = torch.empty((L, w.batch, w.n_q_heads, w.head_dim), dtype=torch.bfloat16, device=dev)
         res = []
         for step in range(steps):
             qs, ks, vs = zip(*[synth.decode_inputs(w, l, step) for l in range(L)])
             ac.air_decode_attn(0, L, *(to_device(np.stack(x), dev) for x in (qs, ks, vs)), out)
             res.append(to_host(out).copy())
         lens = ac.air_get_lengths()
-        res.append([ac.air_get_cache(l, 0, h, int(lens[0, l])) for l in range(L) for h in range(w.n_kv_heads)])
+        res.append([ac.air_get_cache(l, b, h, int(lens[b, l])) for l in range(L) for b in range(w.batch) for h in range(w.n_kv_heads)])
         outs.append(res)
         ac.close()
     for step in range(steps):
