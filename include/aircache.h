@@ -156,8 +156,9 @@ typedef struct {
     int32_t gather_wgs;        /* workgroups per unit of the compaction gather: 1..64                            */
     int32_t decode_order;      /* order of the units of a decode launch over all layers: 1 by layer, 2 longest
                                   cache first (where the launch shape has that variant)                         */
-    int32_t decode_halves;     /* decode launches of at most 128 units: two workgroups per unit with one half of
-                                  the columns of V' each (taken wherever the launch shape has that variant): 1 never */
+    int32_t decode_halves;     /* two workgroups per unit with one half of the columns of V' each, in decode launches
+                                  whose shape has that variant: 1 never, 2 whatever the number of units (the library
+                                  takes it up to 128 units per launch)                                               */
     int32_t budget_in_score;   /* 1: air_score never does the allocation of Eq.11 in the tail of its last kernel
                                   (air_budget then launches the budget kernel, as it does beyond 64 layers)       */
 } air_tuning;

@@ -582,14 +582,15 @@ static air_status decode_attn(air_ctx *ctx, void *stream, int32_t l0, int32_t l1
                      tiles);
     };
     // Two workgroups per unit, each with all of K' and one half of the columns of V' (air_decode.hip), wherever a
-    // launch of four-wave workgroups leaves half the CUs idle.  112 units, warm / cold cache: 215 keys per
+    // launch of four-wave workgroups leaves half the CUs idle (with more workgroups than CUs it loses: 448 units
+    // 47.8 against 42.4 us, 1280 units 256 against 250).  112 units, warm / cold cache: 215 keys per
     // unit 6.4 / 8.7 us against 6.5 / 8.4 with one workgroup per unit, 870 keys 9.6 / 11.6 against 10.7 / 13.3,
     // 3800 keys 33 / 45 against 35 / 55, 7400 keys 64 / 73 against 76 / 89.
     auto halves_of = [&](int nl, int splits, int waves, int tiles) {
         const int hkv = ctx->dm.Hkv;
-        const bool can = in_step && (hkv & (hkv - 1)) == 0 && splits == 1 && waves == 4 && tiles == 4 &&
-                         2 * ((nl * units_per_layer + 7) & ~7) <= 256;
-        return can && ctx->tune.decode_halves != 1;
+        const bool can = in_step && (hkv & (hkv - 1)) == 0 && splits == 1 && waves == 4 && tiles == 4;
+        const bool few = 2 * ((nl * units_per_layer + 7) & ~7) <= 256;
+        return can && ctx->tune.decode_halves != 1 && (few || ctx->tune.decode_halves == 2);
     };
     for (int c0 = l0; use_static && c0 < l1; c0 += max_nl) {
         const int nl = (l1 - c0 < max_nl) ? l1 - c0 : max_nl;
