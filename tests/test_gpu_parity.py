@@ -781,6 +781,15 @@ def test_allocation_in_the_tail_of_scoring_equals_the_budget_kernel():
     ac.air_reset()
     ac.air_score(0, L, q, k, v, seqs)  # and the counters are back at zero after a complete pass
     same(want, state(ac))
+    for _ in range(12):  # prompts back to back with no host wait in between: every pass finds its counters at zero
+        ac.air_reset()
+        ac.air_score(0, 2, q[:2], k[:2], v[:2], seqs)
+        ac.air_score(2, L, q[2:], k[2:], v[2:], seqs)
+        ac.air_budget()
+        ac.air_select_compact(0, L, k, v)
+    ac.air_reset()
+    ac.air_score(0, L, q, k, v, seqs)
+    same(want, state(ac))
     ac.close()
 
 
