@@ -466,6 +466,43 @@ def test_decode_column_halves(base, batch, n_layers, n_vis, retention):
         assert np.array_equal(k1, k2) and np.array_equal(v1, v2)
 
 
+def test_decode_longest_cache_first_after_caller_set_budgets():
+    # budgets handed in by the caller (reversed per sequence, so that the order by length is not the order by layer)
+    # go through the same layout code: the table by falling length must follow them
+    import torch
+
+    import paper_2503_23956_amd as A
+    from paper_2503_23956_amd.device_inputs import config_for, to_device, to_host
+
+    dev = torch.device("cuda:0")
+    w = synth.get_workload(3).scaled(batch=2, n_layers=6, n_vis=1200, n_text=40, decode_steps=3)
+    seqs = w.seqs()
+    L = w.n_layers
+    layers = [synth.layer_inputs(w, l, seqs) for l in range(L)]
+    q, k, v = ([to_device(getattr(li, name), dev) for li in layers] for name in ("q_text", "k", "v"))
+    outs = []
+    for order in (1, 2):
+        ac = A.AirCache(config_for(w, 0.20, seqs=seqs, max_decode_steps=3), dev)
+        ac.air_set_tuning(decode_splits=1, decode_waves=4, decode_tiles=4, decode_order=order, decode_halves=1)
+        ac.air_score(0, L, q, k, v, seqs)
+        ac.air_budget()
+        bud = ac.air_get_budgets()[:, ::-1].copy()
+        assert len(set(bud[0].tolist())) > 1
+        ac.air_set_budgets(bud)
+        ac.air_select_compact(0, L, k, v)
+        out = torch.empty((L, w.batch, w.n_q_heads, w.head_dim), dtype=torch.bfloat16, device=dev)
+        res = []
+        for step in range(3):
+            qs, ks, vs = zip(*[synth.decode_inputs(w, l, step) for l in range(L)])
+            ac.air_decode_attn(0, L, *(to_device(np.stack(x), dev) for x in (qs, ks, vs)), out)
+            res.append(to_host(out).copy())
+        assert np.array_equal(ac.air_get_lengths(), bud + np.array([[s.seq_len - s.vis_len] for s in seqs]) + 3)
+        outs.append(res)
+        ac.close()
+    for a, b in zip(*outs):
+        assert np.array_equal(a.view(np.uint16), b.view(np.uint16))
+
+
 @pytest.mark.parametrize("waves", [1, 4])
 def test_decode_longest_cache_first(waves):
     # a launch over all layers that takes its units by falling cache length (the table the budget kernel leaves,
