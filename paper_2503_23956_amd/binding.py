@@ -47,7 +47,8 @@ class air_layer(C.Structure):
 
 class air_tuning(C.Structure):
     _fields_ = [(n, C.c_int32) for n in ("decode_splits", "decode_waves", "decode_tiles", "score_block_mb",
-                                         "score_rows_kernel", "select_threads", "select_direct_max", "gather_wgs", "decode_order", "decode_halves", "budget_in_score")]
+                                         "score_rows_kernel", "select_threads", "select_direct_max", "gather_wgs",
+                                         "decode_order", "decode_halves", "budget_in_score")]
 
 
 class air_strides(C.Structure):

@@ -97,3 +97,28 @@ def test_index_division_by_batch_as_one_multiply():
     for B in range(2, 65):
         inv = np.uint64((1 << 32) // B + 1)
         assert np.array_equal((z * inv) >> np.uint64(32), z // np.uint64(B)), B
+
+
+def test_binding_structs_follow_the_header_field_by_field():
+    """The ctypes structures of the binding against the struct bodies of include/aircache.h: same fields, same order,
+    same C types (a field added on one side only would shift everything behind it without any error)."""
+    from paper_2503_23956_amd import binding
+
+    text = open(os.path.join(ROOT, "include", "aircache.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    ctype = {"int32_t": C.c_int32, "int64_t": C.c_int64, "double": C.c_double, "void": C.c_void_p}
+    for name in ("air_config", "air_seq", "air_layer", "air_strides", "air_tuning"):
+        m = re.search(r"typedef struct\s*\{([^}]*)\}\s*" + name + r"\s*;", text)
+        assert m, name
+        fields = []
+        for decl in m.group(1).split(";"):
+            decl = decl.strip()
+            if not decl:
+                continue
+            mm = re.match(r"(?:const\s+)?(\w+)\s+(.*)", decl)
+            base, rest = mm.group(1), mm.group(2)
+            for var in rest.split(","):
+                var = var.strip()
+                fields.append((var.lstrip("*").strip(), C.c_void_p if var.startswith("*") else ctype[base]))
+        got = [(n, t) for n, t in getattr(binding, name)._fields_]
+        assert got == fields, (name, got, fields)
