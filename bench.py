@@ -399,26 +399,28 @@ def main():
         lay_kv = dk[0, 0].numel() * esz
         pq, pk, pv, po = dq.data_ptr(), dk.data_ptr(), dv.data_ptr(), out.data_ptr()
 
+        hs = int(torch.cuda.current_stream(dev).cuda_stream)  # the launch stream's handle, taken once
+
         def one_step(events=None, boundaries=False):
             ac.air_reset()
             if events is not None:
                 events[0].record()
-            ac.air_score(0, L, prepared=prep_score)
+            ac.air_score(0, L, prepared=prep_score, stream=hs)
             if boundaries:
                 events[1].record()
-            ac.air_budget()
+            ac.air_budget(stream=hs)
             if boundaries:
                 events[2].record()
-            ac.air_select_compact(0, L, prepared=prep_compact)
+            ac.air_select_compact(0, L, prepared=prep_compact, stream=hs)
             if events is not None:
                 events[3].record()
             for t in range(n_dec):
                 if per_layer:
                     for l in range(L):
                         ac.air_decode_attn(l, l + 1, pq + t * step_q + l * lay_q, pk + t * step_kv + l * lay_kv,
-                                           pv + t * step_kv + l * lay_kv, po + l * lay_q)
+                                           pv + t * step_kv + l * lay_kv, po + l * lay_q, stream=hs)
                 else:
-                    ac.air_decode_attn(0, L, pq + t * step_q, pk + t * step_kv, pv + t * step_kv, po)
+                    ac.air_decode_attn(0, L, pq + t * step_q, pk + t * step_kv, pv + t * step_kv, po, stream=hs)
             if events is not None:
                 events[4].record()
 

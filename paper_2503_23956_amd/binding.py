@@ -205,15 +205,17 @@ class AirCache:
         return Prepared(self._layers(q_text, k, v), self.strides_of(q_text[0] if q_text is not None else None, k[0]),
                         self.seq_array(seqs) if seqs is not None else None, len(k), (q_text, k, v))
 
-    def air_score(self, l0: int, l1: int, q_text=None, k=None, v=None, seqs=None, strides=None, prepared=None):
-        """prepared: result of prepare() for exactly the layers [l0, l1) (skips the per-call marshalling)."""
+    def air_score(self, l0: int, l1: int, q_text=None, k=None, v=None, seqs=None, strides=None, prepared=None, stream=None):
+        """prepared: result of prepare() for exactly the layers [l0, l1) (skips the per-call marshalling).
+        stream (here and in the other stage calls): a raw HIP stream handle taken beforehand; default: torch's current stream."""
         p = prepared or self.prepare(q_text, k, v, seqs)
         st = strides or p.strides
         assert p.n == l1 - l0 and p.seqs is not None
-        self._check(self.lib.air_score(self.handle, self._stream(), l0, l1, p.layers, C.byref(st), p.seqs))
+        self._check(self.lib.air_score(self.handle, self._stream() if stream is None else stream, l0, l1, p.layers, C.byref(st),
+                                       p.seqs))
 
-    def air_budget(self):
-        self._check(self.lib.air_budget(self.handle, self._stream()))
+    def air_budget(self, stream=None):
+        self._check(self.lib.air_budget(self.handle, self._stream() if stream is None else stream))
 
     def air_reset(self):
         self._check(self.lib.air_reset(self.handle))
@@ -224,22 +226,28 @@ class AirCache:
                         select_direct_max, gather_wgs, decode_order, decode_halves, budget_in_score)
         self._check(self.lib.air_set_tuning(self.handle, C.byref(tn)))
 
-    def air_select_compact(self, l0: int, l1: int, k=None, v=None, strides=None, prepared=None):
+    def air_select_compact(self, l0: int, l1: int, k=None, v=None, strides=None, prepared=None, stream=None):
         p = prepared or self.prepare(None, k, v)
         st = strides or p.strides
         assert p.n == l1 - l0
-        self._check(self.lib.air_select_compact(self.handle, self._stream(), l0, l1, p.layers, C.byref(st)))
+        self._check(self.lib.air_select_compact(self.handle, self._stream() if stream is None else stream, l0, l1, p.layers,
+                                                C.byref(st)))
 
-    def air_decode_attn(self, l0: int, l1: int, q_new, k_new, v_new, out):
+    def air_decode_attn(self, l0: int, l1: int, q_new, k_new, v_new, out, stream=None):
         """Tensors, or raw device addresses (ints) when the caller has taken them beforehand."""
-        ptr = lambda x: x if isinstance(x, int) else _ptr(x)  # noqa: E731
-        self._check(self.lib.air_decode_attn(self.handle, self._stream(), l0, l1, ptr(q_new), ptr(k_new),
-                                             ptr(v_new), ptr(out)))
+        if type(q_new) is not int:
+            q_new, k_new, v_new, out = _ptr(q_new), _ptr(k_new), _ptr(v_new), _ptr(out)
+        st = self.lib.air_decode_attn(self.handle, self._stream() if stream is None else stream, l0, l1, q_new, k_new, v_new, out)
+        if st != AIR_OK:
+            self._check(st)
 
-    def air_decode_attn_static(self, l0: int, l1: int, q_new, k_new, v_new, out):
-        ptr = lambda x: x if isinstance(x, int) else _ptr(x)  # noqa: E731
-        self._check(self.lib.air_decode_attn_static(self.handle, self._stream(), l0, l1, ptr(q_new), ptr(k_new),
-                                                    ptr(v_new), ptr(out)))
+    def air_decode_attn_static(self, l0: int, l1: int, q_new, k_new, v_new, out, stream=None):
+        if type(q_new) is not int:
+            q_new, k_new, v_new, out = _ptr(q_new), _ptr(k_new), _ptr(v_new), _ptr(out)
+        st = self.lib.air_decode_attn_static(self.handle, self._stream() if stream is None else stream, l0, l1, q_new, k_new,
+                                             v_new, out)
+        if st != AIR_OK:
+            self._check(st)
 
     # -- inspection ------------------------------------------------------------------
     def air_get_scores(self, l: int) -> np.ndarray:
