@@ -22,8 +22,10 @@
 //       I[key] = sum_rows e[row][key] * (w exp(m_chunk - M)).  Units with more rows (continuous
 //       or all-text windows) recompute their logits from K_v: I[key] = sum_rows w exp(s - M).
 //       Epilogue: the workgroup's sum of I and its second and third moments about the workgroup's own
-//       mean (fp64), which the budget kernel shifts to the row mean and adds up for Eq.9-10.  Raw power
-//       sums would cancel on rows of little spread: S2 - S1 mu loses (mu / sigma)^2 of its digits.
+//       mean (fp64); the unit's last workgroup to finish shifts the entries to the row mean and adds them
+//       up for Eq.9-10 (raw power sums would cancel on rows of little spread: S2 - S1 mu loses
+//       (mu / sigma)^2 of its digits), and, where the layers fit one wave, the last unit of a sequence
+//       goes on to Eq.11 and the cache layout (air_budget_dev.h).
 #include "air_device.h"
 #include "air_internal.h"
 #include "air_budget_dev.h"
