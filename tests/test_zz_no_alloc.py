@@ -23,8 +23,10 @@ def _compressed_pair(w, dev, tuning):
     k = [to_device(li.k, dev) for li in layers]
     v = [to_device(li.v, dev) for li in layers]
     pair = []
+    tuning = dict(tuning)
+    device_steps = 1 if tuning.pop("device_steps", False) else 0  # the tokens appended so far counted on the device
     for _ in range(2):
-        ac = A.AirCache(config_for(w, 0.25, max_decode_steps=w.decode_steps, seqs=seqs), dev)
+        ac = A.AirCache(config_for(w, 0.25, max_decode_steps=w.decode_steps, seqs=seqs, device_steps=device_steps), dev)
         ac.air_set_tuning(**tuning)
         ac.air_score(0, L, q, k, v, seqs)
         ac.air_budget()
@@ -46,6 +48,8 @@ def _raw_decode(ac, fn_name, L, qn, kn, vn, out):
 @pytest.mark.parametrize("base,tuning", [(2, dict(decode_splits=4, decode_waves=4, decode_tiles=4)),
                                          (2, dict(decode_splits=16, decode_waves=1, decode_tiles=2)),
                                          (2, dict(decode_splits=1, decode_waves=4, decode_tiles=4, decode_halves=2)),
+                                         # two workgroups per unit that meet at an arrival counter of the static area
+                                         (2, dict(decode_splits=1, decode_waves=4, decode_tiles=4, decode_halves=2, device_steps=True)),
                                          (1, dict(decode_splits=4))])
 def test_static_entry_point_matches_the_workspace_one(base, tuning):
     import torch
