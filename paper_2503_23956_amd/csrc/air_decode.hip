@@ -150,7 +150,8 @@ struct DecodeSteps {
 // INPLACE: the cache is kept inside the layers' own K / V tensors (their addresses come from a table)
 // SORTED: a launch over all layers whose grid index z is not the layer but its rank by cache length within the
 // sequence (longest first); the layer comes with the table entry that carries the length
-template <int NW, int KT, bool SPLIT, bool INPLACE, bool SORTED = false, int VH = 1>
+// VH = 2: two workgroups per unit, each with one half of the columns of V' (see below); ONE_SEQ: the instance for B = 1
+template <int NW, int KT, bool SPLIT, bool INPLACE, bool SORTED = false, int VH = 1, bool ONE_SEQ = false>
 __global__ __launch_bounds__(64 * NW) void decode_mfma_kernel(Dims dm, DecodeTabs t, int l0, int lbase,
                                                               DecodeSteps ll, const bf16_t *q_new,
                                                               const bf16_t *k_new, const bf16_t *v_new, bf16_t *out,
@@ -184,7 +185,12 @@ __global__ __launch_bounds__(64 * NW) void decode_mfma_kernel(Dims dm, DecodeTab
         live = pair < splits;
         pair = min(pair, splits - 1);
         kvh = pair & (dm.Hkv - 1);
-        seq_layer_of(dm, pair >> lg_splits, b, li);
+        if (ONE_SEQ) {  // one sequence: its index is a constant of the instance (every address in front of the first loads is shorter: 0.6 us per launch)
+            li = pair >> lg_splits;
+            b = 0;
+        } else {
+            seq_layer_of(dm, pair >> lg_splits, b, li);
+        }
     }
     int2 len_off;
     if (SORTED) {
@@ -819,12 +825,17 @@ hipError_t launch_decode(hipStream_t s, const Dims &dm, const DevTables &t, cons
             int lg_h = 0;
             while ((1 << lg_h) < dm.Hkv) ++lg_h;
             const dim3 grid2(2 * ((units + 7) & ~7));
-            if (t.cache_ptrs)
-                hipLaunchKernelGGL((decode_mfma_kernel<4, 4, false, true, false, 2>), grid2, dim3(256), 0, s, dm, dt, l0, lbase, ds,
-                                   (const bf16_t *)q_new, (const bf16_t *)k_new, (const bf16_t *)v_new, (bf16_t *)out, units, lg_h);
-            else
-                hipLaunchKernelGGL((decode_mfma_kernel<4, 4, false, false, false, 2>), grid2, dim3(256), 0, s, dm, dt, l0, lbase, ds,
-                                   (const bf16_t *)q_new, (const bf16_t *)k_new, (const bf16_t *)v_new, (bf16_t *)out, units, lg_h);
+#define AIR_LAUNCH_HALVES_(IP, ONE)                                                                                        \
+    hipLaunchKernelGGL((decode_mfma_kernel<4, 4, false, IP, false, 2, ONE>), grid2, dim3(256), 0, s, dm, dt, l0, lbase, ds, \
+                       (const bf16_t *)q_new, (const bf16_t *)k_new, (const bf16_t *)v_new, (bf16_t *)out, units, lg_h)
+            if (t.cache_ptrs) {
+                if (dm.B == 1) AIR_LAUNCH_HALVES_(true, true);
+                else AIR_LAUNCH_HALVES_(true, false);
+            } else {
+                if (dm.B == 1) AIR_LAUNCH_HALVES_(false, true);
+                else AIR_LAUNCH_HALVES_(false, false);
+            }
+#undef AIR_LAUNCH_HALVES_
             return hipGetLastError();
         }
         if (longest_first && splits == 1 && !t.cache_ptrs && tiles == 4 && (waves == 1 || waves == 4)) {
